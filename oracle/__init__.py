@@ -1,0 +1,133 @@
+"""ctypes front end of the CPU oracle (test infrastructure only).
+
+Only tests, the smoke check and the benchmark's cpu-baseline leg import this
+package.  It knows nothing about the HIP library: arrays in, arrays out, all numpy.
+See lsrm_oracle.c for what each function computes and which passage of the paper
+it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lsrm_oracle.c")
+_LIB = os.path.join(_HERE, "liblsrm_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile lsrm_oracle.c with gcc (no fused multiply-add: routing is compared bit for bit)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def centroids(pos: np.ndarray) -> np.ndarray:
+    pos = _f32(pos)
+    n_obj = pos.shape[0]
+    out = np.empty((n_obj // 64, 3), dtype=np.float32)
+    _load().oracle_centroids(ctypes.c_int(n_obj), _p(pos, ctypes.c_float), _p(out, ctypes.c_float))
+    return out
+
+
+def route(pos: np.ndarray, cams: np.ndarray, grid: int, topk: int):
+    """-> (idx int32 [NB, K], dist2 float32 [NB, K])."""
+    pos, cams = _f32(pos), _f32(cams)
+    n_obj, m = pos.shape[0], cams.shape[0]
+    nb = n_obj // 64 + m * (grid // 8) ** 2
+    idx = np.empty((nb, topk), dtype=np.int32)
+    d2 = np.empty((nb, topk), dtype=np.float32)
+    _load().oracle_route(ctypes.c_int(n_obj), ctypes.c_int(m), ctypes.c_int(grid), ctypes.c_int(topk),
+                         _p(pos, ctypes.c_float), _p(cams, ctypes.c_float), _p(idx, ctypes.c_int32),
+                         _p(d2, ctypes.c_float))
+    return idx, d2
+
+
+def pool(x: np.ndarray) -> np.ndarray:
+    """x fp32 [N, H, d] -> block means fp32 [N/64, H, d]."""
+    x = _f32(x)
+    n, h, d = x.shape
+    out = np.empty((n // 64, h, d), dtype=np.float32)
+    _load().oracle_pool(ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), _p(x, ctypes.c_float),
+                        _p(out, ctypes.c_float))
+    return out
+
+
+def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qblocks=None,
+                want_lse=False, want_branches=False):
+    """NSA forward for the query blocks in `qblocks` (all blocks if None).
+
+    Returns out fp32 [nq*64, H, d] (compact over the listed blocks) and, on request,
+    lse fp32 [3, nq*64, H] and the three branch outputs fp32 [3, nq*64, H, d].
+    """
+    q, k, v, kc, vc, gates = map(_f32, (q, k, v, kc, vc, gates))
+    idx, seg = _i32(idx), _i32(seg_offsets)
+    n, h, d = q.shape
+    topk = idx.shape[1] if idx.ndim == 2 else 0
+    if qblocks is None:
+        qblocks = np.arange(n // 64, dtype=np.int32)
+    qblocks = _i32(qblocks)
+    nq = qblocks.shape[0]
+    out = np.empty((nq * 64, h, d), dtype=np.float32)
+    lse = np.empty((3, nq * 64, h), dtype=np.float32) if want_lse else None
+    ob = np.empty((3, nq * 64, h, d), dtype=np.float32) if want_branches else None
+    _load().oracle_nsa_forward(
+        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), ctypes.c_int(topk), ctypes.c_int(window),
+        ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
+        _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
+        _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
+        _p(qblocks, ctypes.c_int32), ctypes.c_int(nq), _p(out, ctypes.c_float),
+        _p(lse, ctypes.c_float), _p(ob, ctypes.c_float))
+    res = [out]
+    if want_lse:
+        res.append(lse)
+    if want_branches:
+        res.append(ob)
+    return res[0] if len(res) == 1 else tuple(res)
+
+
+def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0):
+    """-> (dq, dk, dv) fp32 [N, H, d]; single-threaded definition, small inputs only."""
+    q, k, v, kc, vc, gates, dout = map(_f32, (q, k, v, kc, vc, gates, dout))
+    idx, seg = _i32(idx), _i32(seg_offsets)
+    n, h, d = q.shape
+    topk = idx.shape[1] if idx.ndim == 2 else 0
+    dq, dk, dv = (np.empty_like(q) for _ in range(3))
+    _load().oracle_nsa_backward(
+        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), ctypes.c_int(topk), ctypes.c_int(window),
+        ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
+        _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
+        _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
+        _p(dout, ctypes.c_float), _p(dq, ctypes.c_float), _p(dk, ctypes.c_float), _p(dv, ctypes.c_float))
+    return dq, dk, dv

@@ -1,0 +1,354 @@
+/*
+ * CPU oracle for the NSA layer with 3D-aware block routing.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the GPU
+ * library is compared against.  Only the tests, the smoke check and the
+ * benchmark's cpu-baseline leg may call it; the product path never does, and this
+ * file shares no code, header, table or helper with the HIP sources.
+ *
+ * What is computed (section / equation of the paper in brackets):
+ *   - routing        [Sec. 3.3 "3D-Aware Block Routing"]: key blocks are chosen from
+ *                    geometry alone.  In the block-level reading used here an object
+ *                    block is represented by the centroid of its 64 token positions,
+ *                    the centroid is projected into every view with the known
+ *                    pinhole parameters, and blocks are ranked by the squared 2-D
+ *                    distance between that projection and the centres of the 8x8
+ *                    image-patch tiles.  Object query blocks keep the K nearest
+ *                    tiles (over all views); image query tiles keep the K object
+ *                    blocks whose projection falls nearest to them.  The result is
+ *                    defined as an exhaustive sort by (distance, block id).
+ *   - compression    [Sec. 3.2 "Block Partitioning and Compression"; App. A
+ *                    "Compressed"]: one key/value pair per block, the in-block
+ *                    average (the learned residual module is upstream of this layer).
+ *   - three branches [App. A, Eq. (nsa_1)]: CmpAttn over all compressed pairs,
+ *                    SelAttn over every token of the routed blocks, WinAttn over a
+ *                    local window, each its own softmax, combined by a gated sum.
+ *                    The window here is token level: keys j with
+ *                    -W/2 <= j - i < W/2, clipped to the query's segment
+ *                    (object tokens / each view).  No causal mask anywhere.
+ *   - backward       analytic gradients of the above with routing and gates fixed.
+ *
+ * Precision: inputs are fp32 (bf16 values widened).  Routing distances are
+ * evaluated in fp32 with a fixed operation order and no fused multiply-add (build
+ * with -ffp-contract=off) because the routed indices are compared bit for bit.
+ * Everything else accumulates in double.
+ *
+ * Parity with the authors' own implementation is unpinned: the paper prints no
+ * worked numeric example.  The functions here are pinned by the CPU tests against
+ * brute-force dense-mask attention, closed forms and hand-built routing cases.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define BLK 64
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ routing */
+
+/* Centroid of each object block: left-to-right fp32 sum of its 64 positions, times 1/64. */
+void oracle_centroids(int n_obj, const float *pos, float *cent) {
+    int nb = n_obj / BLK;
+    for (int b = 0; b < nb; ++b) {
+        for (int c = 0; c < 3; ++c) {
+            float s = pos[(size_t)(BLK * b) * 3 + c];
+            for (int t = 1; t < BLK; ++t) s = s + pos[(size_t)(BLK * b + t) * 3 + c];
+            cent[b * 3 + c] = s * (1.0f / 64.0f);
+        }
+    }
+}
+
+/*
+ * Squared 2-D distance (patch units) between the projection of centroid c into the
+ * camera cam = {R[9] row-major, t[3], fx, fy, cx, cy} and the centre of tile (ti, tj).
+ * Every product and sum is rounded to fp32, in exactly this order.  A centroid at or
+ * behind the image plane (z <= 1e-6) is infinitely far from every tile of that view.
+ */
+static float tile_dist2(const float *c, const float *cam, int ti, int tj) {
+    float x = ((cam[0] * c[0] + cam[1] * c[1]) + cam[2] * c[2]) + cam[9];
+    float y = ((cam[3] * c[0] + cam[4] * c[1]) + cam[5] * c[2]) + cam[10];
+    float z = ((cam[6] * c[0] + cam[7] * c[1]) + cam[8] * c[2]) + cam[11];
+    if (!(z > 1e-6f)) return INFINITY;
+    float u = cam[12] * (x / z) + cam[14];
+    float v = cam[13] * (y / z) + cam[15];
+    float ut = (float)(8 * tj + 4);
+    float vt = (float)(8 * ti + 4);
+    float du = u - ut;
+    float dv = v - vt;
+    float d2 = du * du + dv * dv;
+    if (d2 != d2) d2 = INFINITY;
+    return d2;
+}
+
+typedef struct { float d2; int32_t id; } cand_t;
+
+static int cand_cmp(const void *a, const void *b) {
+    const cand_t *x = (const cand_t *)a, *y = (const cand_t *)b;
+    if (x->d2 < y->d2) return -1;
+    if (x->d2 > y->d2) return 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+/*
+ * idx [NB, K] int32, dist2 [NB, K] fp32 (dist2 may be NULL), NB = n_obj/64 + M*(S/8)^2.
+ * Row b < NB_obj: the K image tiles nearest to block b, as global block ids
+ * NB_obj + tile, ascending by (d2, id).  Row NB_obj + t: the K object blocks nearest
+ * to tile t.  If fewer than K candidates exist the tail is -1 / +inf.
+ */
+void oracle_route(int n_obj, int n_views, int grid, int topk, const float *pos, const float *cams,
+                  int32_t *idx, float *dist2) {
+    int nbo = n_obj / BLK;
+    int tg = grid / 8;
+    int tpv = tg * tg;
+    int nt = n_views * tpv;
+    float *cent = (float *)malloc(sizeof(float) * 3 * (size_t)(nbo > 0 ? nbo : 1));
+    float *dm = (float *)malloc(sizeof(float) * (size_t)(nbo > 0 ? nbo : 1) * (size_t)(nt > 0 ? nt : 1));
+    oracle_centroids(n_obj, pos, cent);
+    for (int b = 0; b < nbo; ++b)
+        for (int m = 0; m < n_views; ++m)
+            for (int ti = 0; ti < tg; ++ti)
+                for (int tj = 0; tj < tg; ++tj)
+                    dm[(size_t)b * nt + m * tpv + ti * tg + tj] = tile_dist2(cent + 3 * b, cams + 16 * m, ti, tj);
+    int maxc = nbo > nt ? nbo : nt;
+    cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(maxc > 0 ? maxc : 1));
+    for (int b = 0; b < nbo; ++b) {
+        for (int t = 0; t < nt; ++t) { cand[t].d2 = dm[(size_t)b * nt + t]; cand[t].id = nbo + t; }
+        qsort(cand, nt, sizeof(cand_t), cand_cmp);
+        for (int k = 0; k < topk; ++k) {
+            idx[(size_t)b * topk + k] = k < nt ? cand[k].id : -1;
+            if (dist2) dist2[(size_t)b * topk + k] = k < nt ? cand[k].d2 : INFINITY;
+        }
+    }
+    for (int t = 0; t < nt; ++t) {
+        for (int b = 0; b < nbo; ++b) { cand[b].d2 = dm[(size_t)b * nt + t]; cand[b].id = b; }
+        qsort(cand, nbo, sizeof(cand_t), cand_cmp);
+        for (int k = 0; k < topk; ++k) {
+            idx[(size_t)(nbo + t) * topk + k] = k < nbo ? cand[k].id : -1;
+            if (dist2) dist2[(size_t)(nbo + t) * topk + k] = k < nbo ? cand[k].d2 : INFINITY;
+        }
+    }
+    free(cand); free(dm); free(cent);
+}
+
+/* ------------------------------------------------------------------ pooling */
+
+/* out[b, h, :] = (1/64) sum_t x[64 b + t, h, :];  x is [N, H, d], out is [N/64, H, d]. */
+void oracle_pool(int64_t n, int h, int d, const float *x, float *out) {
+    int64_t nb = n / BLK;
+    size_t row = (size_t)h * d;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < nb; ++b) {
+        for (size_t c = 0; c < row; ++c) {
+            double s = 0.0;
+            for (int t = 0; t < BLK; ++t) s += (double)x[((size_t)(BLK * b + t)) * row + c];
+            out[(size_t)b * row + c] = (float)(s / 64.0);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ forward */
+
+/*
+ * One softmax attention of a single query vector over an explicit list of key rows.
+ * s_j = scale * <q, K[rows[j]]>,  p = softmax(s),  o = sum_j p_j V[rows[j]].
+ * Returns log-sum-exp; an empty list gives o = 0 and lse = -inf.  p (optional, length
+ * n) receives the probabilities.
+ */
+static double attend(const float *qv, int d, double scale, const float *kbase, const float *vbase,
+                     size_t stride, const int64_t *rows, int n, double *s, double *o) {
+    for (int c = 0; c < d; ++c) o[c] = 0.0;
+    if (n == 0) return -INFINITY;
+    double m = -INFINITY;
+    for (int j = 0; j < n; ++j) {
+        const float *kr = kbase + (size_t)rows[j] * stride;
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) acc += (double)qv[c] * (double)kr[c];
+        s[j] = acc * scale;
+        if (s[j] > m) m = s[j];
+    }
+    double l = 0.0;
+    for (int j = 0; j < n; ++j) { s[j] = exp(s[j] - m); l += s[j]; }
+    for (int j = 0; j < n; ++j) {
+        const float *vr = vbase + (size_t)rows[j] * stride;
+        double p = s[j] / l;
+        s[j] = p;
+        for (int c = 0; c < d; ++c) o[c] += p * (double)vr[c];
+    }
+    return m + log(l);
+}
+
+static int segment_of(const int32_t *seg, int n_seg, int64_t i) {
+    for (int s = 0; s < n_seg; ++s)
+        if (i >= seg[s] && i < seg[s + 1]) return s;
+    return -1;
+}
+
+/* Key rows of the three branches for query token i (block qb = i / 64). Returns counts. */
+static void key_sets(int64_t i, int64_t nb, int topk, int window, int n_seg, const int32_t *seg,
+                     const int32_t *idx, int64_t *rc, int *nc, int64_t *rs, int *ns, int64_t *rw, int *nw) {
+    int64_t qb = i / BLK;
+    *nc = 0;
+    for (int64_t b = 0; b < nb; ++b) rc[(*nc)++] = b;
+    *ns = 0;
+    for (int k = 0; k < topk; ++k) {
+        int32_t kb = idx[qb * topk + k];
+        if (kb < 0) continue;
+        for (int t = 0; t < BLK; ++t) rs[(*ns)++] = (int64_t)kb * BLK + t;
+    }
+    *nw = 0;
+    int sg = segment_of(seg, n_seg, i);
+    if (sg >= 0) {
+        int64_t lo = i - window / 2, hi = i + window / 2;
+        if (lo < seg[sg]) lo = seg[sg];
+        if (hi > seg[sg + 1]) hi = seg[sg + 1];
+        for (int64_t j = lo; j < hi; ++j) rw[(*nw)++] = j;
+    }
+}
+
+/*
+ * NSA forward for the listed query blocks.
+ *   q, k, v  [N, H, d] fp32;  kc, vc [NB, H, d] fp32 (pooled);  idx [NB, K];
+ *   gates [N, H, 3];  seg [n_seg + 1] token offsets;  qblocks [nq] block ids.
+ * Outputs are compact over the listed blocks (row r = 64 * position-in-list + t):
+ *   out [nq*64, H, d];  lse [3, nq*64, H] (nullable);  ob [3, nq*64, H, d] (nullable).
+ */
+void oracle_nsa_forward(int64_t n, int h, int d, int topk, int window, float scale, int n_seg,
+                        const int32_t *seg, const float *q, const float *k, const float *v,
+                        const float *kc, const float *vc, const int32_t *idx, const float *gates,
+                        const int32_t *qblocks, int nq, float *out, float *lse, float *ob) {
+    int64_t nb = n / BLK;
+    size_t stride = (size_t)h * d;
+    double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
+    size_t maxkeys = (size_t)nb;
+    if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
+    if ((size_t)window + 1 > maxkeys) maxkeys = (size_t)window + 1;
+    int64_t rows_out = (int64_t)nq * BLK;
+#pragma omp parallel
+    {
+        int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
+        int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
+        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + 1));
+        double *s = (double *)malloc(sizeof(double) * maxkeys);
+        double *o = (double *)malloc(sizeof(double) * (size_t)d * 3);
+#pragma omp for schedule(dynamic, 1) collapse(2)
+        for (int iq = 0; iq < nq; ++iq) {
+            for (int hh = 0; hh < h; ++hh) {
+                for (int t = 0; t < BLK; ++t) {
+                    int64_t i = (int64_t)qblocks[iq] * BLK + t;
+                    int64_t r = (int64_t)iq * BLK + t;
+                    int nc, ns, nw;
+                    key_sets(i, nb, topk, window, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+                    const float *qv = q + (size_t)i * stride + (size_t)hh * d;
+                    double l0 = attend(qv, d, sc, kc + (size_t)hh * d, vc + (size_t)hh * d, stride, rc, nc, s, o);
+                    double l1 = attend(qv, d, sc, k + (size_t)hh * d, v + (size_t)hh * d, stride, rs, ns, s, o + d);
+                    double l2 = attend(qv, d, sc, k + (size_t)hh * d, v + (size_t)hh * d, stride, rw, nw, s, o + 2 * d);
+                    const float *g = gates + ((size_t)i * h + hh) * 3;
+                    for (int c = 0; c < d; ++c)
+                        out[((size_t)r * h + hh) * d + c] =
+                            (float)((double)g[0] * o[c] + (double)g[1] * o[d + c] + (double)g[2] * o[2 * d + c]);
+                    if (lse) {
+                        lse[((size_t)0 * rows_out + r) * h + hh] = (float)l0;
+                        lse[((size_t)1 * rows_out + r) * h + hh] = (float)l1;
+                        lse[((size_t)2 * rows_out + r) * h + hh] = (float)l2;
+                    }
+                    if (ob)
+                        for (int br = 0; br < 3; ++br)
+                            for (int c = 0; c < d; ++c)
+                                ob[(((size_t)br * rows_out + r) * h + hh) * d + c] = (float)o[br * d + c];
+                }
+            }
+        }
+        free(rc); free(rs); free(rw); free(s); free(o);
+    }
+}
+
+/* ------------------------------------------------------------------ backward */
+
+/*
+ * Gradients of  L = sum_i <dout_i, out_i>  with respect to q, k, v (all [N, H, d]),
+ * routing indices and gates held fixed, through the three branches and the pooling.
+ * For one softmax attention with probabilities p_j and output o:
+ *   dp_j = <do, v_j>,  ds_j = p_j (dp_j - <do, o>),
+ *   dq += scale * sum_j ds_j k_j,  dk_j += scale * ds_j q,  dv_j += p_j do,
+ * where do = gate * dout for that branch.  Pooled keys/values pass their gradient
+ * to the 64 tokens of their block, divided by 64.  Gradients are accumulated in
+ * double, single-threaded over queries (this is a definition, not a fast path).
+ * dq, dk, dv are fp32 outputs [N, H, d].
+ */
+void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, float scale, int n_seg,
+                         const int32_t *seg, const float *q, const float *k, const float *v,
+                         const float *kc, const float *vc, const int32_t *idx, const float *gates,
+                         const float *dout, float *dq, float *dk, float *dv) {
+    int64_t nb = n / BLK;
+    size_t stride = (size_t)h * d;
+    size_t total = (size_t)n * stride, totalc = (size_t)nb * stride;
+    double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
+    size_t maxkeys = (size_t)nb;
+    if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
+    if ((size_t)window + 1 > maxkeys) maxkeys = (size_t)window + 1;
+    double *gq = (double *)calloc(total, sizeof(double));
+    double *gk = (double *)calloc(total, sizeof(double));
+    double *gv = (double *)calloc(total, sizeof(double));
+    double *gkc = (double *)calloc(totalc > 0 ? totalc : 1, sizeof(double));
+    double *gvc = (double *)calloc(totalc > 0 ? totalc : 1, sizeof(double));
+    int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
+    int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
+    int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + 1));
+    double *p = (double *)malloc(sizeof(double) * maxkeys);
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int64_t i = 0; i < n; ++i) {
+        int nc, ns, nw;
+        key_sets(i, nb, topk, window, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+        for (int hh = 0; hh < h; ++hh) {
+            const float *qv = q + (size_t)i * stride + (size_t)hh * d;
+            const float *dor = dout + (size_t)i * stride + (size_t)hh * d;
+            const float *g = gates + ((size_t)i * h + hh) * 3;
+            double *gqr = gq + (size_t)i * stride + (size_t)hh * d;
+            for (int br = 0; br < 3; ++br) {
+                const float *kb = (br == 0 ? kc : k) + (size_t)hh * d;
+                const float *vb = (br == 0 ? vc : v) + (size_t)hh * d;
+                double *gkb = (br == 0 ? gkc : gk) + (size_t)hh * d;
+                double *gvb = (br == 0 ? gvc : gv) + (size_t)hh * d;
+                const int64_t *rows = br == 0 ? rc : (br == 1 ? rs : rw);
+                int cnt = br == 0 ? nc : (br == 1 ? ns : nw);
+                if (cnt == 0) continue;
+                attend(qv, d, sc, kb, vb, stride, rows, cnt, p, o);
+                double delta = 0.0;
+                for (int c = 0; c < d; ++c) delta += (double)g[br] * (double)dor[c] * o[c];
+                for (int j = 0; j < cnt; ++j) {
+                    const float *kr = kb + (size_t)rows[j] * stride;
+                    const float *vr = vb + (size_t)rows[j] * stride;
+                    double *gkr = gkb + (size_t)rows[j] * stride;
+                    double *gvr = gvb + (size_t)rows[j] * stride;
+                    double dp = 0.0;
+                    for (int c = 0; c < d; ++c) dp += (double)g[br] * (double)dor[c] * (double)vr[c];
+                    double ds = p[j] * (dp - delta) * sc;
+                    for (int c = 0; c < d; ++c) {
+                        gqr[c] += ds * (double)kr[c];
+                        gkr[c] += ds * (double)qv[c];
+                        gvr[c] += p[j] * (double)g[br] * (double)dor[c];
+                    }
+                }
+            }
+        }
+    }
+    for (int64_t j = 0; j < n; ++j)
+        for (size_t c = 0; c < stride; ++c) {
+            gk[(size_t)j * stride + c] += gkc[(size_t)(j / BLK) * stride + c] / 64.0;
+            gv[(size_t)j * stride + c] += gvc[(size_t)(j / BLK) * stride + c] / 64.0;
+        }
+    for (size_t e = 0; e < total; ++e) { dq[e] = (float)gq[e]; dk[e] = (float)gk[e]; dv[e] = (float)gv[e]; }
+    free(gq); free(gk); free(gv); free(gkc); free(gvc);
+    free(rc); free(rs); free(rw); free(p); free(o);
+}

@@ -1,0 +1,97 @@
+"""Dense-mask formulation of the NSA layer in float64 numpy / torch.
+
+An independent second formulation used to pin the CPU oracle: instead of gathering
+key lists per query, every branch is an ordinary masked softmax attention over a
+full score matrix (App. A, Eq. nsa_1: three separate softmaxes, gated sum).  Only
+usable for small N.
+"""
+import numpy as np
+
+
+def pooled(x):
+    n, h, d = x.shape
+    return x.reshape(n // 64, 64, h, d).mean(axis=1)
+
+
+def masks(n, idx, seg_offsets, window):
+    nb = n // 64
+    sel = np.zeros((n, n), dtype=bool)
+    for qb in range(nb):
+        for kb in idx[qb]:
+            if kb >= 0:
+                sel[qb * 64:(qb + 1) * 64, kb * 64:(kb + 1) * 64] = True
+    seg_id = np.full(n, -1)
+    for s, (a, b) in enumerate(zip(seg_offsets[:-1], seg_offsets[1:])):
+        seg_id[a:b] = s
+    i = np.arange(n)[:, None]
+    j = np.arange(n)[None, :]
+    win = (seg_id[:, None] == seg_id[None, :]) & (seg_id[:, None] >= 0) & (j - i >= -(window // 2)) & (j - i < window // 2)
+    return sel, win
+
+
+def masked_attention(q, k, v, mask, scale):
+    """q [n,d], k,v [m,d], mask [n,m] -> (o [n,d], lse [n], p [n,m])."""
+    s = (q @ k.T) * scale
+    s = np.where(mask, s, -np.inf)
+    m = s.max(axis=1, keepdims=True)
+    m = np.where(np.isfinite(m), m, 0.0)
+    e = np.exp(s - m)
+    l = e.sum(axis=1, keepdims=True)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        p = np.where(l > 0, e / l, 0.0)
+        lse = np.where(l[:, 0] > 0, m[:, 0] + np.log(l[:, 0]), -np.inf)
+    return p @ v, lse, p
+
+
+def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None):
+    """All float64.  Returns out [N,H,d], branches [3,N,H,d], lse [3,N,H]."""
+    q, k, v, gates = (np.asarray(a, dtype=np.float64) for a in (q, k, v, gates))
+    n, h, d = q.shape
+    scale = 1.0 / np.sqrt(d) if not scale else scale
+    kc, vc = pooled(k), pooled(v)
+    sel, win = masks(n, idx, seg_offsets, window)
+    allc = np.ones((n, n // 64), dtype=bool)
+    ob = np.zeros((3, n, h, d))
+    lse = np.zeros((3, n, h))
+    for hh in range(h):
+        ob[0, :, hh], lse[0, :, hh], _ = masked_attention(q[:, hh], kc[:, hh], vc[:, hh], allc, scale)
+        ob[1, :, hh], lse[1, :, hh], _ = masked_attention(q[:, hh], k[:, hh], v[:, hh], sel, scale)
+        ob[2, :, hh], lse[2, :, hh], _ = masked_attention(q[:, hh], k[:, hh], v[:, hh], win, scale)
+    out = sum(gates[:, :, b, None] * ob[b] for b in range(3))
+    return out, ob, lse
+
+
+def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None):
+    """Library autograd (float64) through the dense-mask formulation -> dq, dk, dv."""
+    import torch
+    tq, tk, tv = (torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True) for a in (q, k, v))
+    g = torch.tensor(np.asarray(gates, dtype=np.float64))
+    n, h, d = tq.shape
+    scale = 1.0 / np.sqrt(d) if not scale else scale
+    sel, win = masks(n, idx, seg_offsets, window)
+    sel, win = torch.tensor(sel), torch.tensor(win)
+    kc = tk.reshape(n // 64, 64, h, d).mean(1)
+    vc = tv.reshape(n // 64, 64, h, d).mean(1)
+
+    def att(qh, kh, vh, mask):
+        s = (qh @ kh.T) * scale
+        if mask is not None:
+            s = s.masked_fill(~mask, float("-inf"))
+            empty = ~mask.any(dim=1, keepdim=True)
+            s = torch.where(empty, torch.zeros_like(s), s)
+            p = torch.softmax(s, dim=1)
+            p = torch.where(empty, torch.zeros_like(p), p)
+        else:
+            p = torch.softmax(s, dim=1)
+        return p @ vh
+
+    out = torch.zeros_like(tq)
+    outs = []
+    for hh in range(h):
+        o = (g[:, hh, 0:1] * att(tq[:, hh], kc[:, hh], vc[:, hh], None)
+             + g[:, hh, 1:2] * att(tq[:, hh], tk[:, hh], tv[:, hh], sel)
+             + g[:, hh, 2:3] * att(tq[:, hh], tk[:, hh], tv[:, hh], win))
+        outs.append(o)
+    out = torch.stack(outs, dim=1)
+    (out * torch.tensor(np.asarray(dout, dtype=np.float64))).sum().backward()
+    return tq.grad.numpy(), tk.grad.numpy(), tv.grad.numpy()

@@ -1,0 +1,199 @@
+"""Pins for the pooling / three-branch attention / backward oracle (App. A, Eq. nsa_1;
+Sec. 3.2 block compression): an independent dense-mask formulation, a library routine
+(torch scaled_dot_product_attention with a boolean mask), closed forms and invariants."""
+import numpy as np
+import pytest
+
+from paper_2604_05182_amd import inputs as I
+import dense_ref as D
+
+
+def _case(seed=0, n_obj=256, n_views=2, grid=16, heads=2, d=16, topk=2, window=96, full_idx=False):
+    cfg = I.small_config(n_obj=n_obj, n_views=n_views, grid=grid, heads=heads, d=d, topk=topk,
+                         window=window, seed=seed)
+    q, k, v = (I.bf16_bits_to_f32(a) for a in I.make_qkv(cfg))
+    gates = I.make_gates(cfg)
+    rng = np.random.default_rng(seed)
+    # arbitrary routing table (the attention code must accept any), with some -1 holes
+    idx = np.stack([rng.choice(cfg.nb, size=topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.15] = -1
+    idx[1, :] = -1                       # a query block with no routed keys at all
+    return cfg, q, k, v, gates, idx
+
+
+def test_pool_matches_library_mean(oracle_lib):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((256, 3, 8)).astype(np.float32)
+    got = oracle_lib.pool(x)
+    ref = x.astype(np.float64).reshape(4, 64, 3, 8).mean(1)
+    assert np.allclose(got, ref, rtol=0, atol=1e-7)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_forward_matches_dense_mask_formulation(oracle_lib, seed):
+    cfg, q, k, v, gates, idx = _case(seed)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    out, lse, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window,
+                                          want_lse=True, want_branches=True)
+    rout, rob, rlse = D.dense_nsa(q, k, v, idx, gates, seg, cfg.window)
+    assert np.abs(out - rout).max() < 2e-6
+    assert np.abs(ob - rob).max() < 2e-6
+    fin = np.isfinite(rlse)
+    assert np.array_equal(np.isfinite(lse), fin)
+    assert np.abs(lse[fin] - rlse[fin]).max() < 2e-6
+    # the block with no routed keys has a zero selected branch
+    assert np.all(ob[1, 64:128] == 0) and np.all(np.isneginf(lse[1, 64:128]))
+
+
+def test_forward_subset_of_query_blocks(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(2)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    full = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window)
+    pick = np.array([5, 0, 3], dtype=np.int32)
+    part = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, qblocks=pick)
+    for p, b in enumerate(pick):
+        assert np.array_equal(part[p * 64:(p + 1) * 64], full[b * 64:(b + 1) * 64])
+
+
+def test_branches_match_torch_sdpa(oracle_lib):
+    import torch
+    cfg, q, k, v, gates, idx = _case(3)
+    idx[idx < 0] = 0                     # SDPA needs at least one key per row
+    idx[1] = [2, 4]
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    _, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, want_branches=True)
+    sel, win = D.masks(cfg.n, idx, seg, cfg.window)
+    tq, tk, tv = (torch.tensor(a, dtype=torch.float64).permute(1, 0, 2) for a in (q, k, v))
+    F = torch.nn.functional.scaled_dot_product_attention
+    o_sel = F(tq, tk, tv, attn_mask=torch.tensor(sel)).permute(1, 0, 2).numpy()
+    o_win = F(tq, tk, tv, attn_mask=torch.tensor(win)).permute(1, 0, 2).numpy()
+    tkc, tvc = (torch.tensor(a, dtype=torch.float64).permute(1, 0, 2) for a in (kc, vc))
+    o_cmp = F(tq, tkc, tvc).permute(1, 0, 2).numpy()
+    assert np.abs(ob[0] - o_cmp).max() < 2e-6
+    assert np.abs(ob[1] - o_sel).max() < 2e-6
+    assert np.abs(ob[2] - o_win).max() < 2e-6
+
+
+def test_dense_equivalence(oracle_lib):
+    """One segment, window covering everything and all blocks routed: the selected and
+    window branches are plain full attention; with K, V constant inside each block the
+    compressed branch equals it too (equal multiplicities cancel in the softmax)."""
+    n, h, d = 512, 2, 16
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal((n, h, d)).astype(np.float32)
+    kb = rng.standard_normal((n // 64, 1, h, d)).astype(np.float32)
+    vb = rng.standard_normal((n // 64, 1, h, d)).astype(np.float32)
+    k = np.broadcast_to(kb, (n // 64, 64, h, d)).reshape(n, h, d).copy()
+    v = np.broadcast_to(vb, (n // 64, 64, h, d)).reshape(n, h, d).copy()
+    idx = np.tile(np.arange(n // 64, dtype=np.int32), (n // 64, 1))
+    gates = np.ones((n, h, 3), dtype=np.float32)
+    seg = np.array([0, n], dtype=np.int32)
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    _, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, 2 * n, want_branches=True)
+    import torch
+    tq, tk, tv = (torch.tensor(a, dtype=torch.float64).permute(1, 0, 2) for a in (q, k, v))
+    full = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).permute(1, 0, 2).numpy()
+    for b in range(3):
+        assert np.abs(ob[b] - full).max() < 2e-6, b
+
+
+def test_constant_values_give_gate_sum(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(5)
+    idx[idx < 0] = 3
+    v = np.ones_like(v)
+    seg = cfg.seg_offsets()
+    out = oracle_lib.nsa_forward(q, k, v, oracle_lib.pool(k), oracle_lib.pool(v), idx, gates, seg, cfg.window)
+    expect = gates.astype(np.float64).sum(-1)[..., None]
+    assert np.abs(out - expect).max() < 1e-6
+
+
+def test_zero_queries_give_means(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(6)
+    q = np.zeros_like(q)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    _, lse, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window,
+                                        want_lse=True, want_branches=True)
+    v64 = v.astype(np.float64)
+    assert np.abs(ob[0] - v64.mean(0)[None]).max() < 1e-6          # mean of block means = global mean
+    assert np.allclose(lse[0], np.log(cfg.nb), atol=1e-6)
+    half = cfg.window // 2
+    for i in (0, 70, 255, 256, 300, cfg.n - 1):
+        s = np.searchsorted(seg, i, side="right") - 1
+        lo, hi = max(seg[s], i - half), min(seg[s + 1], i + half)
+        assert np.abs(ob[2, i] - v64[lo:hi].mean(0)).max() < 1e-6
+        assert np.allclose(lse[2, i], np.log(hi - lo), atol=1e-6)
+        blocks = [b for b in idx[i // 64] if b >= 0]
+        if blocks:
+            rows = np.concatenate([np.arange(b * 64, b * 64 + 64) for b in blocks])
+            assert np.abs(ob[1, i] - v64[rows].mean(0)).max() < 1e-6
+
+
+def test_gates_are_linear_and_isolate_branches(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(7)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    _, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, want_branches=True)
+    for b in range(3):
+        g = np.zeros_like(gates)
+        g[..., b] = 1.0
+        out = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, g, seg, cfg.window)
+        assert np.array_equal(out, ob[b])
+
+
+def test_lse_normalises_scores(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(8)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    _, lse, _ = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window,
+                                       want_lse=True, want_branches=True)
+    scale = 1.0 / np.sqrt(cfg.d)
+    i, hh = 77, 1
+    s = (kc[:, hh].astype(np.float64) @ q[i, hh].astype(np.float64)) * scale
+    assert abs(np.exp(s - lse[0, i, hh]).sum() - 1.0) < 1e-6
+
+
+def test_explicit_scale_is_used(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(9)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    out = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, scale=0.3)
+    ref, _, _ = D.dense_nsa(q, k, v, idx, gates, seg, cfg.window, scale=0.3)
+    assert np.abs(out - ref).max() < 2e-6
+
+
+def test_backward_matches_library_autograd(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(10, n_obj=128, grid=8, n_views=2, heads=2, d=8, topk=2, window=48)
+    seg = cfg.seg_offsets()
+    dout = I.bf16_bits_to_f32(I.make_dout(cfg))
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    dq, dk, dv = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout)
+    rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout)
+    for a, b in ((dq, rq), (dk, rk), (dv, rv)):
+        assert np.abs(a - b).max() < 1e-5 * max(1.0, np.abs(b).max())
+
+
+def test_backward_finite_difference_of_dense_formulation():
+    """Pins the autograd reference itself: central differences in float64."""
+    cfg, q, k, v, gates, idx = _case(11, n_obj=64, grid=8, n_views=1, heads=1, d=4, topk=1, window=32)
+    seg = cfg.seg_offsets()
+    rng = np.random.default_rng(0)
+    dout = rng.standard_normal(q.shape)
+    rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout)
+
+    def loss(qq, kk, vv):
+        return (D.dense_nsa(qq, kk, vv, idx, gates, seg, cfg.window)[0] * dout).sum()
+
+    eps = 1e-5
+    for arr, grad, which in ((q, rq, 0), (k, rk, 1), (v, rv, 2)):
+        for _ in range(6):
+            pos = tuple(rng.integers(0, s) for s in arr.shape)
+            args = [q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)]
+            args[which] = args[which].copy(); args[which][pos] += eps
+            up = loss(*args)
+            args[which][pos] -= 2 * eps
+            dn = loss(*args)
+            assert abs((up - dn) / (2 * eps) - grad[pos]) < 1e-6
