@@ -1,0 +1,146 @@
+/*
+ * lsrm.h -- C boundary of the MI355X (gfx950) native-sparse-attention layer with
+ * 3D-aware block routing.
+ *
+ * One layer call works on a joint sequence of N = n_obj + n_views * grid^2 tokens:
+ * first the object (volume) tokens, then the image-patch tokens of view 0, 1, ...
+ * Tokens are grouped in blocks of 64 consecutive tokens (block id = token / 64):
+ * object blocks are spatially coherent runs (the caller orders object tokens, e.g.
+ * along a Morton curve), image blocks are 8x8 patch tiles, tile-major inside a view
+ * (tile grid row-major, patches row-major inside a tile).  [Sec. 3.2, "Block
+ * Partitioning and Compression": 8x8 image blocks, spatial volume blocks.]
+ *
+ * Conventions for every entry point
+ *   - pointers named d_* are DEVICE pointers owned by the caller; everything else
+ *     (params, seg_offsets) is HOST memory read during the call;
+ *   - tensors are dense row-major with the shapes given; bf16 is the 16-bit
+ *     brain-float bit pattern (uint16_t here);
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and the call returns without synchronising;
+ *   - the library allocates no device memory: scratch comes from the caller
+ *     (d_ws / ws_bytes, size from lsrm_workspace_bytes, 256-byte aligned);
+ *   - nothing throws or aborts: the return value is LSRM_OK or a negative code,
+ *     and on error no kernel has been launched.
+ */
+#ifndef LSRM_H
+#define LSRM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t lsrm_status;
+enum {
+    LSRM_OK = 0,
+    LSRM_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, misaligned segment, ... */
+    LSRM_ERR_UNSUPPORTED = -2, /* block != 64, d not in {64,128}, h_kv != h_q, topk > 64    */
+    LSRM_ERR_WORKSPACE = -3,   /* d_ws null / too small / misaligned                        */
+    LSRM_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed                */
+};
+
+/* Human-readable text for a status code (static storage). */
+const char *lsrm_strerror(lsrm_status s);
+
+/*
+ * Pinhole camera, world -> camera: x_cam = R * p + t (R row-major).  Intrinsics are
+ * in PATCH units: (u, v) = (fx * x/z + cx, fy * y/z + cy) and the centre of patch
+ * (row r, column c) is (c + 0.5, r + 0.5); the centre of tile (ti, tj) is
+ * (8 tj + 4, 8 ti + 4).  16 floats, same order as the struct.
+ */
+typedef struct lsrm_camera {
+    float R[9];
+    float t[3];
+    float fx, fy, cx, cy;
+} lsrm_camera;
+
+/*
+ * Problem statement shared by all calls.  [App. A: q in R^{N x h_q x d_h},
+ * k, v in R^{N x h_kv x d_h}; Sec. 3.3: routing from token coordinates + cameras.]
+ */
+typedef struct lsrm_nsa_params {
+    int32_t n_obj;    /* object tokens, multiple of 64 (may be 0)                          */
+    int32_t n_views;  /* M, number of views (may be 0)                                     */
+    int32_t grid;     /* S, patches per image side, multiple of 8                          */
+    int32_t block;    /* tokens per block; must be 64                                      */
+    int32_t h_q;      /* query heads                                                       */
+    int32_t h_kv;     /* key/value heads; must equal h_q                                   */
+    int32_t d;        /* head dimension, 64 or 128                                         */
+    int32_t topk;     /* K routed key blocks per query block (<= 64)                       */
+    int32_t window;   /* W, even: query i sees keys j with -W/2 <= j - i < W/2             */
+    int32_t n_seg;    /* number of window segments                                         */
+    const int32_t *seg_offsets; /* HOST, n_seg + 1 ascending token offsets, multiples of 64,
+                                   first 0, last N; the window never crosses a boundary.
+                                   NULL means the default: [objects], [view 0], [view 1]... */
+    float scale;      /* softmax scale; 0 selects 1/sqrt(d)                                */
+} lsrm_nsa_params;
+
+enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2 };
+
+/* Bytes of scratch the given call needs for these params (0 on invalid params). */
+size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call);
+
+/*
+ * 3D-aware block routing.  [Sec. 3.3 "3D-Aware Block Routing": blocks are selected by
+ * geometry -- project the query's 3D position into each view with the known camera
+ * parameters and rank image blocks by distance of their 2D centres to the projection;
+ * rank volume blocks by distance to the query.  Block-level reading: an object block
+ * is represented by the centroid of its 64 token positions; the same projected
+ * distance serves both directions.]
+ *
+ *   d_pos   [n_obj, 3] fp32   object token positions in sequence order
+ *   d_cams  [n_views] lsrm_camera
+ *   d_idx   [NB, topk] int32  OUT.  Row b < n_obj/64: the topk image tiles nearest to
+ *           the projection of object block b's centroid, over all views, as global
+ *           block ids n_obj/64 + tile.  Row n_obj/64 + t: the topk object blocks whose
+ *           projected centroid is nearest to the centre of tile t.  Ascending by
+ *           (squared distance, block id); ties go to the lowest id; missing
+ *           candidates are -1.
+ *   d_dist2 [NB, topk] fp32   OUT, nullable: the squared distances (+inf for -1).
+ * Distances are evaluated in fp32 in a fixed operation order without fused
+ * multiply-add, so indices and distances are reproducible bit for bit:
+ *   centroid c = (((p0 + p1) + p2) + ... + p63) * (1/64) per component;
+ *   x = ((R0 c.x + R1 c.y) + R2 c.z) + t0 (likewise y, z);  z <= 1e-6 -> +inf;
+ *   u = fx (x / z) + cx;  v = fy (y / z) + cy;  d2 = (u - ut)^2 + (v - vt)^2.
+ */
+lsrm_status lsrm_route_blocks(const lsrm_nsa_params *p, const float *d_pos, const lsrm_camera *d_cams,
+                              int32_t *d_idx, float *d_dist2, void *d_ws, size_t ws_bytes, void *stream);
+
+/*
+ * Block compression.  [Sec. 3.2, k_cmp = AvgPool(.), v_cmp = AvgPool(.); App. A
+ * "Compressed".  The learned residual module applied before the average in the paper
+ * is upstream of this call.]
+ *   d_k, d_v   [N, h_kv, d] bf16
+ *   d_kc, d_vc [N/64, h_kv, d] bf16  OUT: mean over the 64 tokens of each block,
+ *              accumulated in fp32, rounded to nearest-even bf16.
+ */
+lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, const uint16_t *d_v,
+                              uint16_t *d_kc, uint16_t *d_vc, void *stream);
+
+/*
+ * NSA forward.  [App. A, Eq. (nsa_1): o_i = w_cmp CmpAttn(q_i, k_cmp, v_cmp)
+ * + w_sel SelAttn(q_i, k_sel, v_sel) + w_win WinAttn(q_i, k_win, v_win); three
+ * separate softmaxes, no causal mask.]
+ *   d_q [N, h_q, d], d_k, d_v [N, h_kv, d], d_kc, d_vc [N/64, h_kv, d]   bf16
+ *   d_idx   [NB, topk] int32  any routing table: block ids in [0, NB) or -1 (skipped);
+ *           all queries of block b attend every token of the listed blocks.  A row
+ *           of -1 gives a zero selected branch.
+ *   d_gates [N, h_q, 3] fp32  gate weights (cmp, sel, win), already passed through
+ *           the sigmoid of Eq. (nsa_2)
+ *   d_out   [N, h_q, d] bf16  OUT
+ *   d_lse   [3, N, h_q] fp32  OUT, nullable: natural-log sum-exp of the scaled scores
+ *           of each branch (-inf for an empty key set)
+ *   d_out_branch [3, N, h_q, d] bf16  OUT, nullable: the un-gated branch outputs
+ * bf16 MFMA contractions with fp32 accumulation; softmax in fp32.
+ */
+lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k,
+                             const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,
+                             const int32_t *d_idx, const float *d_gates, uint16_t *d_out, float *d_lse,
+                             uint16_t *d_out_branch, void *d_ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSRM_H */

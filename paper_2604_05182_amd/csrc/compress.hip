@@ -1,0 +1,72 @@
+// Block compression (Sec. 3.2 "Block Partitioning and Compression"; App. A "Compressed"):
+// one key/value pair per 64-token block, the in-block average.
+//
+// HBM-streaming kernel: every element of K and V is read exactly once (4 N h d bytes)
+// and 1/64 of that is written.  One thread owns 8 consecutive channels (one 16-byte
+// load per token row), consecutive threads own consecutive channels, so each row of a
+// block is read with fully coalesced 16-byte accesses; the 64 rows are independent
+// loads kept in flight by unrolling.  fp32 accumulation in token order, one rounding
+// to bf16 at the end.
+#include "lsrm_internal.h"
+
+namespace lsrm {
+
+namespace {
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// grid: (ceil(NB * row_chunks / 256), 2)   y = 0 -> K, y = 1 -> V
+__global__ __launch_bounds__(256) void pool_blocks(int nb, int row_chunks /* h*d/8 */, const uint4 *__restrict__ k,
+                                                   const uint4 *__restrict__ v, uint4 *__restrict__ kc,
+                                                   uint4 *__restrict__ vc) {
+    const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t b = g / row_chunks;
+    const int c = (int)(g % row_chunks);
+    if (b >= (size_t)nb) return;
+    const uint4 *src = (blockIdx.y == 0 ? k : v) + b * kBlock * (size_t)row_chunks + c;
+    uint4 *dst = (blockIdx.y == 0 ? kc : vc) + b * (size_t)row_chunks + c;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int t0 = 0; t0 < kBlock; t0 += 16) {
+        uint4 r[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) r[t] = src[(size_t)(t0 + t) * row_chunks];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            acc[0] += bf16_lo(r[t].x); acc[1] += bf16_hi(r[t].x);
+            acc[2] += bf16_lo(r[t].y); acc[3] += bf16_hi(r[t].y);
+            acc[4] += bf16_lo(r[t].z); acc[5] += bf16_hi(r[t].z);
+            acc[6] += bf16_lo(r[t].w); acc[7] += bf16_hi(r[t].w);
+        }
+    }
+    const float inv = 1.0f / 64.0f;
+    uint4 o;
+    o.x = f32_to_bf16_rne(acc[0] * inv) | (f32_to_bf16_rne(acc[1] * inv) << 16);
+    o.y = f32_to_bf16_rne(acc[2] * inv) | (f32_to_bf16_rne(acc[3] * inv) << 16);
+    o.z = f32_to_bf16_rne(acc[4] * inv) | (f32_to_bf16_rne(acc[5] * inv) << 16);
+    o.w = f32_to_bf16_rne(acc[6] * inv) | (f32_to_bf16_rne(acc[7] * inv) << 16);
+    *dst = o;
+}
+
+}  // namespace
+
+lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
+                            uint16_t *d_vc, hipStream_t st) {
+    if (s.nb == 0) return LSRM_OK;
+    int row_chunks = s.h * s.d / 8;
+    dim3 grid((unsigned)(((size_t)s.nb * row_chunks + 255) / 256), 2);
+    hipLaunchKernelGGL(pool_blocks, grid, dim3(256), 0, st, s.nb, row_chunks, reinterpret_cast<const uint4 *>(d_k),
+                       reinterpret_cast<const uint4 *>(d_v), reinterpret_cast<uint4 *>(d_kc),
+                       reinterpret_cast<uint4 *>(d_vc));
+    LSRM_HIP_CHECK(hipGetLastError());
+    return LSRM_OK;
+}
+
+}  // namespace lsrm

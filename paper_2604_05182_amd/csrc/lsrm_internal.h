@@ -1,0 +1,44 @@
+// Internal declarations shared by the HIP translation units of liblsrm (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lsrm.h"
+
+namespace lsrm {
+
+constexpr int kBlock = 64;
+
+struct Shape {
+    int n_obj, n_views, grid, h, d, topk, window;
+    int nb_obj, tiles_per_view, n_tiles, nb;
+    int64_t n;
+    float scale;
+};
+
+// Validates params; fills `s`.  Returns LSRM_OK or an error code.
+lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+#define LSRM_HIP_CHECK(expr)                         \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) return LSRM_ERR_HIP;   \
+    } while (0)
+
+// launchers (each validates nothing: callers in api.hip have done so)
+lsrm_status launch_route(const Shape &s, const float *d_pos, const lsrm_camera *d_cams, int32_t *d_idx,
+                         float *d_dist2, void *d_ws, hipStream_t st);
+size_t route_ws_bytes(const Shape &s);
+
+lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
+                            uint16_t *d_vc, hipStream_t st);
+
+lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
+                           const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc,
+                           const uint16_t *d_vc, const int32_t *d_idx, const float *d_gates, uint16_t *d_out,
+                           float *d_lse, uint16_t *d_out_branch, void *d_ws, hipStream_t st);
+size_t forward_ws_bytes(const Shape &s);
+
+}  // namespace lsrm

@@ -1,0 +1,44 @@
+"""The C boundary: the shared library loads and exports every symbol include/lsrm.h
+declares (no compute calls here: this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lsrm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lsrm_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_entry_points():
+    names = _declared()
+    for must in ("lsrm_route_blocks", "lsrm_nsa_compress", "lsrm_nsa_forward", "lsrm_workspace_bytes",
+                 "lsrm_strerror"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    path = os.path.join(ROOT, "paper_2604_05182_amd", "liblsrm.so")
+    assert os.path.exists(path), "build first: python -m paper_2604_05182_amd.build"
+    lib = ctypes.CDLL(path)
+    for name in _declared():
+        assert hasattr(lib, name), name
+
+
+def test_host_side_argument_checks():
+    """Validation happens on the host before any HIP call, so it can be exercised here."""
+    from paper_2604_05182_amd import binding as B
+    ok = B.make_params(512, 2, 16, 2, 64, 3, 128)
+    assert B.lsrm_workspace_bytes(ok, B.LSRM_WS_ROUTE) >= 8 * 2 * 8
+    assert B.lsrm_workspace_bytes(ok, B.LSRM_WS_FORWARD) >= 1024 * 2 * 64 * 2
+    for bad in (B.make_params(500, 2, 16, 2, 64, 3, 128), B.make_params(512, 2, 12, 2, 64, 3, 128),
+                B.make_params(512, 2, 16, 2, 64, 3, 127), B.make_params(512, 2, 16, 2, 96, 3, 128),
+                B.make_params(512, 2, 16, 2, 64, 65, 128), B.make_params(512, 2, 16, 2, 64, 3, 128, h_kv=1)):
+        assert B.lsrm_workspace_bytes(bad, B.LSRM_WS_FORWARD) == 0
+    assert B.strerror(B.LSRM_ERR_WORKSPACE).startswith("workspace")
+    # null pointers are rejected before anything is launched
+    rc = B._lib.lsrm_nsa_compress(__import__("ctypes").byref(ok), None, None, None, None, None)
+    assert rc == B.LSRM_ERR_INVALID_ARG

@@ -1,0 +1,199 @@
+"""GPU parity: the HIP library (through its C boundary) against the CPU oracle, element
+by element, on the same seeded inputs.
+
+Bars: routed indices and squared distances bit-exact; pooled keys/values within one
+bf16 rounding of the fp32 mean; attention outputs within max-abs 2e-2 and relative L2
+5e-3 of the oracle (bf16 inputs, fp32 oracle arithmetic in double accumulators).
+"""
+import numpy as np
+import pytest
+
+from paper_2604_05182_amd import inputs as I
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2604_05182_amd import binding
+    return binding
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+# ----------------------------------------------------------------------------- routing
+ROUTE_CASES = [
+    I.small_config(name="r-small", n_obj=512, n_views=2, grid=16, topk=3, seed=3),
+    I.small_config(name="r-ragged", n_obj=1088, n_views=3, grid=24, topk=7, seed=4, points="ellipsoids"),
+    I.small_config(name="r-fullk", n_obj=512, n_views=2, grid=16, topk=8, seed=5),
+    I.small_config(name="r-pad", n_obj=128, n_views=1, grid=8, topk=3, seed=5),
+    I.CONFIGS[1], I.CONFIGS[2], I.CONFIGS[3], I.CONFIGS[4],
+]
+
+
+@pytest.mark.parametrize("cfg", ROUTE_CASES, ids=lambda c: c.name)
+def test_route_bit_exact(B, oracle_lib, cfg):
+    _log(f"[route] {cfg.name} n_obj={cfg.n_obj} views={cfg.n_views} grid={cfg.grid} K={cfg.topk}")
+    pos, cams = I.make_points(cfg), I.make_cameras(cfg)
+    ref_idx, ref_d2 = oracle_lib.route(pos, cams, cfg.grid, cfg.topk)
+    idx, d2 = G.run_route(B, cfg, pos, cams)
+    assert np.array_equal(idx, ref_idx)
+    assert np.array_equal(d2.view(np.uint32), ref_d2.view(np.uint32))
+
+
+def test_route_ties_and_behind_camera(B, oracle_lib):
+    cfg = I.small_config(name="r-hand", n_obj=128, n_views=1, grid=16, topk=4)
+    pos = np.zeros((128, 3), dtype=np.float32)
+    pos[64:] = (0, 0, -5.0)
+    cams = np.zeros((1, 16), dtype=np.float32)
+    cams[0, :9] = np.eye(3).reshape(-1)
+    cams[0, 9:12] = (0, 0, 3)
+    cams[0, 12:] = (10, 10, 8, 8)
+    ref_idx, ref_d2 = oracle_lib.route(pos, cams, 16, 4)
+    idx, d2 = G.run_route(B, cfg, pos, cams)
+    assert idx[0].tolist() == [2, 3, 4, 5] and d2[0].tolist() == [32.0] * 4
+    assert np.array_equal(idx, ref_idx) and np.array_equal(d2.view(np.uint32), ref_d2.view(np.uint32))
+
+
+def test_route_without_distances(B, oracle_lib):
+    cfg = ROUTE_CASES[0]
+    pos, cams = I.make_points(cfg), I.make_cameras(cfg)
+    idx, _ = G.run_route(B, cfg, pos, cams, want_dist=False)
+    assert np.array_equal(idx, oracle_lib.route(pos, cams, cfg.grid, cfg.topk)[0])
+
+
+# ----------------------------------------------------------------------------- pooling
+@pytest.mark.parametrize("cfg", [I.small_config(name="p-small", heads=2, d=64),
+                                 I.small_config(name="p-d128", heads=3, d=128, n_obj=448, grid=24),
+                                 I.CONFIGS[1]], ids=lambda c: c.name)
+def test_compress(B, oracle_lib, cfg):
+    _log(f"[compress] {cfg.name}")
+    _, k_bits, v_bits = I.make_qkv(cfg)
+    _, _, kc, vc = G.run_compress(B, cfg, k_bits, v_bits)
+    for got, bits in ((kc, k_bits), (vc, v_bits)):
+        ref = oracle_lib.pool(I.bf16_bits_to_f32(bits))
+        got = G.bf16_host(got)
+        # one rounding to bf16 (relative 2^-9) plus fp32 summation noise
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-6)
+
+
+# ----------------------------------------------------------------------------- forward
+def _forward_case(B, oracle_lib, cfg, idx=None, seg="default", scale=0.0, qblocks=None, window=None):
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates = I.make_gates(cfg)
+    if idx is None:
+        idx, _ = oracle_lib.route(I.make_points(cfg), I.make_cameras(cfg), cfg.grid, cfg.topk)
+    seg_arr = cfg.seg_offsets() if isinstance(seg, str) else np.asarray(seg, dtype=np.int32)
+    window = cfg.window if window is None else window
+    res = G.run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets=seg, scale=scale,
+                        want_aux=True, window=window)
+    q, k, v = (I.bf16_bits_to_f32(a) for a in (q_bits, k_bits, v_bits))
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    ref_out, ref_lse, ref_ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg_arr, window, scale=scale,
+                                                      qblocks=qblocks, want_lse=True, want_branches=True)
+    if qblocks is not None:
+        rows = (np.asarray(qblocks)[:, None] * 64 + np.arange(64)[None]).reshape(-1)
+        res = {"out": res["out"][rows], "lse": res["lse"][:, rows], "ob": res["ob"][:, rows]}
+    return res, ref_out, ref_lse, ref_ob
+
+
+def _assert_forward(res, ref_out, ref_lse, ref_ob, tag):
+    ma, rl = G.attention_errors(res["out"], ref_out)
+    _log(f"[forward] {tag}: out max-abs {ma:.3e} rel-L2 {rl:.3e}")
+    assert ma <= G.MAX_ABS_TOL and rl <= G.REL_L2_TOL
+    for b, name in enumerate(("cmp", "sel", "win")):
+        ma, rl = G.attention_errors(res["ob"][b], ref_ob[b])
+        _log(f"           branch {name}: max-abs {ma:.3e} rel-L2 {rl:.3e}")
+        assert ma <= G.MAX_ABS_TOL and rl <= G.REL_L2_TOL
+    fin = np.isfinite(ref_lse)
+    assert np.array_equal(np.isfinite(res["lse"]), fin)
+    assert np.array_equal(np.isneginf(res["lse"]), np.isneginf(ref_lse))
+    assert np.abs(res["lse"][fin] - ref_lse[fin]).max() <= 2e-2
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_forward_small(B, oracle_lib, d):
+    cfg = I.small_config(name=f"f-small-d{d}", n_obj=512, n_views=2, grid=16, heads=2, d=d, topk=3, window=128)
+    _log(f"[forward] {cfg.name}")
+    _assert_forward(*_forward_case(B, oracle_lib, cfg), cfg.name)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_forward_ragged_and_holes(B, oracle_lib, d):
+    """NB not a multiple of 4 or 32, odd head count, -1 holes, an empty routed row, a window
+    that is not a multiple of the block, explicit scale."""
+    cfg = I.small_config(name=f"f-ragged-d{d}", n_obj=1088, n_views=3, grid=24, heads=3, d=d, topk=5,
+                         window=200, seed=21)
+    _log(f"[forward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(5)
+    idx = np.stack([rng.choice(cfg.nb, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.2] = -1
+    idx[2] = -1
+    _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx, scale=0.2), cfg.name)
+
+
+def test_forward_dense_equivalence(B, oracle_lib):
+    """Single segment, window covering the sequence, every block routed: the selected and
+    window branches both equal plain full attention (compared with the oracle's)."""
+    cfg = I.small_config(name="f-dense", n_obj=512, n_views=0, grid=0, heads=2, d=64, topk=8, window=1024)
+    idx = np.tile(np.arange(8, dtype=np.int32), (8, 1))
+    res, ref_out, ref_lse, ref_ob = _forward_case(B, oracle_lib, cfg, idx=idx, seg=[0, 512])
+    _assert_forward(res, ref_out, ref_lse, ref_ob, cfg.name)
+    ma, _ = G.attention_errors(res["ob"][1], res["ob"][2])
+    assert ma <= 2e-2
+
+
+def test_forward_zero_window_and_topk_one(B, oracle_lib):
+    cfg = I.small_config(name="f-w0", n_obj=256, n_views=1, grid=16, heads=1, d=64, topk=1, window=0)
+    _assert_forward(*_forward_case(B, oracle_lib, cfg), cfg.name)
+
+
+def test_forward_config1_full(B, oracle_lib):
+    cfg = I.CONFIGS[1]
+    _log(f"[forward] config 1 full ({cfg.n} tokens)")
+    _assert_forward(*_forward_case(B, oracle_lib, cfg), "config1")
+
+
+@pytest.mark.parametrize("cid,n_random", [(2, 24), (3, 12), (4, 4)])
+def test_forward_full_size_sampled(B, oracle_lib, cid, n_random):
+    """Full-size launch (the configuration the benchmark times), oracle on a stratified sample of
+    query blocks: first and last block of every segment plus random ones, all heads."""
+    cfg = I.CONFIGS[cid]
+    qblocks = I.sample_query_blocks(cfg, n_random)
+    _log(f"[forward] config {cid} full-size launch, oracle on {len(qblocks)} query blocks")
+    _assert_forward(*_forward_case(B, oracle_lib, cfg, qblocks=qblocks), f"config{cid}-sampled")
+
+
+def test_forward_is_deterministic(B, oracle_lib):
+    cfg = I.small_config(name="f-det", n_obj=512, n_views=2, grid=16, heads=2, d=64, topk=3, window=128)
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates = I.make_gates(cfg)
+    idx, _ = oracle_lib.route(I.make_points(cfg), I.make_cameras(cfg), cfg.grid, cfg.topk)
+    a = G.run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates)["out"]
+    b = G.run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates)["out"]
+    assert np.array_equal(a, b)
+
+
+# ----------------------------------------------------------------------------- error paths
+def test_error_codes(B):
+    import torch
+    cfg = I.small_config()
+    p = G.params_for(B, cfg)
+    bad = B.make_params(cfg.n_obj, cfg.n_views, cfg.grid, cfg.heads, 96, cfg.topk, cfg.window)
+    t = torch.empty(16, device="cuda")
+    with pytest.raises(B.LsrmError) as e:
+        B.lsrm_nsa_compress(bad, t, t, t, t)
+    assert e.value.status == B.LSRM_ERR_UNSUPPORTED
+    with pytest.raises(B.LsrmError) as e:
+        B.lsrm_route_blocks(p, t, t, t, None, None)
+    assert e.value.status == B.LSRM_ERR_WORKSPACE
+    odd = B.make_params(cfg.n_obj + 1, cfg.n_views, cfg.grid, cfg.heads, cfg.d, cfg.topk, cfg.window)
+    with pytest.raises(B.LsrmError) as e:
+        B.lsrm_nsa_compress(odd, t, t, t, t)
+    assert e.value.status == B.LSRM_ERR_INVALID_ARG
+    assert B.lsrm_workspace_bytes(bad, B.LSRM_WS_FORWARD) == 0
