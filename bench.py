@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the NSA layer hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: lsrm_route_blocks ->
+lsrm_nsa_compress -> lsrm_nsa_forward, inputs already resident in HBM.  The metric is
+effective attention TFLOP/s (4 d h x attended (query, key) pairs; masked or padded work
+does not count) and ms per layer.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..4] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def cpu_baseline(cfg, arrays, idx, target_seconds=20.0):
+    """Times the CPU oracle (as it stands) on a bounded sample of query blocks."""
+    import oracle
+    from paper_2604_05182_amd import inputs as I
+    q, k, v = (I.bf16_bits_to_f32(a) for a in arrays["qkv_bits"])
+    t0 = time.perf_counter()
+    kc, vc = oracle.pool(k), oracle.pool(v)
+    t_pool = time.perf_counter() - t0
+    seg = cfg.seg_offsets()
+    threads = oracle.num_threads()
+    # calibrate on a few blocks, then size the sample for about target_seconds
+    probe = I.sample_query_blocks(cfg, 0)[:max(2, threads // 4)]
+    t0 = time.perf_counter()
+    oracle.nsa_forward(q, k, v, kc, vc, idx, arrays["gates"], seg, cfg.window, qblocks=probe)
+    per_block = (time.perf_counter() - t0) / len(probe)
+    n_blocks = int(min(cfg.nb, max(threads, target_seconds / max(per_block, 1e-6))))
+    blocks = I.sample_query_blocks(cfg, n_blocks, seed=1)[:n_blocks] if n_blocks < cfg.nb else np.arange(cfg.nb, dtype=np.int32)
+    t0 = time.perf_counter()
+    oracle.nsa_forward(q, k, v, kc, vc, idx, arrays["gates"], seg, cfg.window, qblocks=blocks)
+    dt = time.perf_counter() - t0
+    flops_per_block = cfg.forward_flops(int((idx >= 0).sum())) / cfg.nb
+    return {
+        "value": round(flops_per_block * len(blocks) / dt / 1e12, 6),
+        "unit": "TFLOP/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"forward oracle on {len(blocks)} of {cfg.nb} query blocks (all heads), {dt:.1f} s; "
+                  f"pooling of all K,V {t_pool:.1f} s not included; extrapolated ms/layer "
+                  f"{dt / len(blocks) * cfg.nb * 1e3:.0f}",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="workload id 1..4 (default 4: the largest single-GPU config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2604_05182_amd import inputs as I
+    from paper_2604_05182_amd import binding as B  # raises if the HIP library is not built
+
+    cfg = I.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- seeded synthetic inputs, moved to HBM before anything is timed
+    pos, cams = I.make_points(cfg), I.make_cameras(cfg)
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates = I.make_gates(cfg)
+
+    def bf16_dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    d_pos, d_cams = torch.from_numpy(pos).to(dev), torch.from_numpy(cams).to(dev)
+    d_q, d_k, d_v = bf16_dev(q_bits), bf16_dev(k_bits), bf16_dev(v_bits)
+    d_gates = torch.from_numpy(gates).to(dev)
+    p = B.make_params(cfg.n_obj, cfg.n_views, cfg.grid, cfg.heads, cfg.d, cfg.topk, cfg.window)
+    d_idx = torch.empty((cfg.nb, cfg.topk), dtype=torch.int32, device=dev)
+    d_kc = torch.empty((cfg.nb, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
+    d_vc = torch.empty_like(d_kc)
+    d_out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
+    ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE)
+    ws_fwd = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
+
+    n_ev = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_ev)]
+    for row in ev:
+        for e in row:
+            e.record()  # creates the underlying hipEvent handles
+
+    def step(i=None):
+        e = ev[i] if i is not None else [None] * 6
+        if i is not None:
+            e[0].record()
+        B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route)
+        if i is not None:
+            e[1].record()
+        B.lsrm_nsa_compress(p, d_k, d_v, d_kc, d_vc)
+        if i is not None:
+            e[2].record()
+        B.lsrm_nsa_forward(p, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, None, None, ws_fwd,
+                           ev_attn_start=e[3], ev_attn_stop=e[4])
+        if i is not None:
+            e[5].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_step = wall * 1e3 / args.steps
+    ms_route = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    ms_compress = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    ms_fwd_call = float(np.mean([e[2].elapsed_time(e[5]) for e in ev]))
+    ms_attn = float(np.mean([e[3].elapsed_time(e[4]) for e in ev]))
+
+    idx = d_idx.cpu().numpy()
+    n_valid = int((idx >= 0).sum())
+    flops = cfg.forward_flops(n_valid)
+    value = flops / (ms_step * 1e-3) / 1e12
+    attn_tflops = flops / (ms_attn * 1e-3) / 1e12
+
+    result = {
+        "metric": "NSA layer effective TFLOP/s (route + compress + fused forward), 1 MI355X",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config {args.config} ({cfg.name}): {cfg.n_obj} object + {cfg.n_views}x{cfg.grid}x{cfg.grid} image "
+                        f"tokens = {cfg.n}, {cfg.heads} heads, d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}",
+            "effective_flops": flops,
+            "pct_of_bf16_mfma_peak": round(100.0 * value / BF16_MFMA_PEAK_TFLOPS, 2),
+        },
+        "breakdown_ms": {"route": round(ms_route, 4), "compress": round(ms_compress, 4),
+                         "forward_call": round(ms_fwd_call, 4), "attention_kernel": round(ms_attn, 4)},
+        "roofline": {
+            "kernel": "nsa_forward_kernel",
+            "bound": "mfma",
+            "achieved": round(attn_tflops, 3),
+            "peak": BF16_MFMA_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(attn_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, {"qkv_bits": (q_bits, k_bits, v_bits), "gates": gates}, idx)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

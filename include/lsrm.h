@@ -133,12 +133,17 @@ lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, con
  *   d_lse   [3, N, h_q] fp32  OUT, nullable: natural-log sum-exp of the scaled scores
  *           of each branch (-inf for an empty key set)
  *   d_out_branch [3, N, h_q, d] bf16  OUT, nullable: the un-gated branch outputs
+ *   ev_attn_start, ev_attn_stop  nullable hipEvent_t (as void*), created by the caller:
+ *           recorded on `stream` immediately before and after the fused attention
+ *           kernel alone (the call also runs a short repacking of V before it), so a
+ *           caller can time that kernel with hipEventElapsedTime.
  * bf16 MFMA contractions with fp32 accumulation; softmax in fp32.
  */
 lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k,
                              const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,
                              const int32_t *d_idx, const float *d_gates, uint16_t *d_out, float *d_lse,
-                             uint16_t *d_out_branch, void *d_ws, size_t ws_bytes, void *stream);
+                             uint16_t *d_out_branch, void *d_ws, size_t ws_bytes, void *stream,
+                             void *ev_attn_start, void *ev_attn_stop);
 
 #ifdef __cplusplus
 }

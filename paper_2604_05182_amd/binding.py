@@ -51,7 +51,7 @@ _lib.lsrm_route_blocks.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.lsrm_nsa_compress.restype = ctypes.c_int32
 _lib.lsrm_nsa_compress.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
 _lib.lsrm_nsa_forward.restype = ctypes.c_int32
-_lib.lsrm_nsa_forward.argtypes = [_pp] + [_vp] * 11 + [_sz, _vp]
+_lib.lsrm_nsa_forward.argtypes = [_pp] + [_vp] * 11 + [_sz, _vp, _vp, _vp]
 
 
 def strerror(status: int) -> str:
@@ -109,11 +109,21 @@ def lsrm_nsa_compress(p, k, v, kc, vc, stream=None):
            "lsrm_nsa_compress")
 
 
-def lsrm_nsa_forward(p, q, k, v, kc, vc, idx, gates, out, lse=None, out_branch=None, ws=None, stream=None):
+def _event(ev):
+    """torch.cuda.Event -> raw hipEvent_t handle (the event must have been created)."""
+    if ev is None:
+        return None
+    if not ev.cuda_event:
+        ev.record()  # torch creates the underlying event lazily
+    return ev.cuda_event
+
+
+def lsrm_nsa_forward(p, q, k, v, kc, vc, idx, gates, out, lse=None, out_branch=None, ws=None, stream=None,
+                     ev_attn_start=None, ev_attn_stop=None):
     nbytes = ws.numel() * ws.element_size() if ws is not None else 0
     _check(_lib.lsrm_nsa_forward(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kc), _ptr(vc), _ptr(idx),
                                  _ptr(gates), _ptr(out), _ptr(lse), _ptr(out_branch), _ptr(ws), nbytes,
-                                 _stream(stream)), "lsrm_nsa_forward")
+                                 _stream(stream), _event(ev_attn_start), _event(ev_attn_stop)), "lsrm_nsa_forward")
 
 
 def alloc_workspace(p, which: int, device="cuda") -> torch.Tensor:

@@ -112,7 +112,7 @@ lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, con
 lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k, const uint16_t *d_v,
                              const uint16_t *d_kc, const uint16_t *d_vc, const int32_t *d_idx, const float *d_gates,
                              uint16_t *d_out, float *d_lse, uint16_t *d_out_branch, void *d_ws, size_t ws_bytes,
-                             void *stream) {
+                             void *stream, void *ev_attn_start, void *ev_attn_stop) {
     Shape s;
     lsrm_status rc = make_shape(p, &s);
     if (rc != LSRM_OK) return rc;
@@ -129,7 +129,8 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
         return LSRM_ERR_INVALID_ARG;
     if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < forward_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
     return launch_forward(s, seg.data(), (int)seg.size() - 1, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_lse,
-                          d_out_branch, d_ws, static_cast<hipStream_t>(stream));
+                          d_out_branch, d_ws, static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(ev_attn_start),
+                          static_cast<hipEvent_t>(ev_attn_stop));
 }
 
 }  // extern "C"

@@ -493,7 +493,8 @@ WsLayout ws_layout(const Shape &s) {
 
 template <int D>
 lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg, FwdArgs a, const uint16_t *d_v,
-                             const uint16_t *d_vc, char *ws, const WsLayout &w, hipStream_t st) {
+                             const uint16_t *d_vc, char *ws, const WsLayout &w, hipStream_t st, hipEvent_t ev_start,
+                             hipEvent_t ev_stop) {
     using G = Geo<D>;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     hipLaunchKernelGGL(pack_transposed<D>, dim3(s.nb, s.h), dim3(256), 0, st, d_v, (uint16_t *)(ws + w.v_t), s.n, s.h);
@@ -513,8 +514,10 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
         attr_set = true;
     }
+    if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
     hipLaunchKernelGGL(nsa_forward_kernel<D>, dim3(a.units_per_xcd * 8), dim3(256), lds_bytes, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
+    if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;
 }
 
@@ -525,7 +528,8 @@ size_t forward_ws_bytes(const Shape &s) { return ws_layout(s).total; }
 lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
                            const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,
                            const int32_t *d_idx, const float *d_gates, uint16_t *d_out, float *d_lse,
-                           uint16_t *d_out_branch, void *d_ws, hipStream_t st) {
+                           uint16_t *d_out_branch, void *d_ws, hipStream_t st, hipEvent_t ev_start,
+                           hipEvent_t ev_stop) {
     if (s.nb == 0) return LSRM_OK;
     if (n_seg > kMaxSeg) return LSRM_ERR_UNSUPPORTED;
     FwdArgs a{};
@@ -547,8 +551,8 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.scale_log2e = s.scale * 1.4426950408889634f;
     WsLayout w = ws_layout(s);
     char *ws = reinterpret_cast<char *>(d_ws);
-    if (s.d == 64) return launch_forward_d<64>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st);
-    return launch_forward_d<128>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st);
+    if (s.d == 64) return launch_forward_d<64>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
+    return launch_forward_d<128>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
 }
 
 }  // namespace lsrm

@@ -38,7 +38,8 @@ lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t 
 lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
                            const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc,
                            const uint16_t *d_vc, const int32_t *d_idx, const float *d_gates, uint16_t *d_out,
-                           float *d_lse, uint16_t *d_out_branch, void *d_ws, hipStream_t st);
+                           float *d_lse, uint16_t *d_out_branch, void *d_ws, hipStream_t st, hipEvent_t ev_start,
+                           hipEvent_t ev_stop);
 size_t forward_ws_bytes(const Shape &s);
 
 }  // namespace lsrm

@@ -16,6 +16,7 @@ bf16 tensors are carried as numpy uint16 bit patterns.
 from __future__ import annotations
 
 import math
+import os
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -113,7 +114,37 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
-    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    if b.size < (1 << 22):
+        return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    out = np.empty(b.shape, dtype=np.float32)
+    src, dst = b.reshape(-1), out.reshape(-1).view(np.uint32)
+    step = 1 << 22
+
+    def work(i):
+        np.left_shift(src[i:i + step], np.uint32(16), out=dst[i:i + step], dtype=np.uint32, casting="unsafe")
+
+    _parallel_for(range(0, src.size, step), work)
+    return out
+
+
+def _n_workers() -> int:
+    try:
+        return max(1, min(16, len(os.sched_getaffinity(0))))
+    except AttributeError:
+        return max(1, min(16, os.cpu_count() or 1))
+
+
+def _parallel_for(items, fn):
+    """Runs fn over items on a few threads (numpy releases the GIL in its inner loops)."""
+    from concurrent.futures import ThreadPoolExecutor
+    items = list(items)
+    if len(items) <= 1:
+        for it in items:
+            fn(it)
+        return
+    with ThreadPoolExecutor(max_workers=_n_workers()) as pool:
+        list(pool.map(fn, items))
 
 
 # ----------------------------------------------------------------------------- geometry
@@ -224,20 +255,27 @@ def make_cameras(cfg: NSAConfig, radius: float = 2.5, fov_deg: float = 40.0) -> 
 
 
 # ----------------------------------------------------------------------------- tensors
-def _normal_bf16(shape, rng: np.random.Generator, chunk_rows: int = 1 << 14) -> np.ndarray:
+def _normal_bf16(shape, seed: int, stream: int, chunk_rows: int = 1 << 12) -> np.ndarray:
+    """N(0,1) rounded to bf16.  Chunk c of 4096 rows draws from its own counter-based Philox
+    stream keyed by (seed, stream, c), so the result does not depend on the thread count."""
     out = np.empty(shape, dtype=np.uint16)
     flat = out.reshape(shape[0], -1)
-    for r0 in range(0, shape[0], chunk_rows):
+
+    def work(c):
+        r0 = c * chunk_rows
         r1 = min(shape[0], r0 + chunk_rows)
+        rng = np.random.Generator(np.random.Philox(key=[seed, (stream << 32) + c]))
         x = rng.standard_normal((r1 - r0, flat.shape[1]), dtype=np.float32)
         flat[r0:r1] = f32_to_bf16_bits(x)
+
+    _parallel_for(range((shape[0] + chunk_rows - 1) // chunk_rows), work)
     return out
 
 
 def make_qkv(cfg: NSAConfig):
     """(q, k, v) bf16 bit patterns, each uint16 [N, H, d], values ~ N(0, 1) rounded to bf16."""
     shape = (cfg.n, cfg.heads, cfg.d)
-    return tuple(_normal_bf16(shape, _rng(cfg.seed, 10 + i)) for i in range(3))
+    return tuple(_normal_bf16(shape, cfg.seed, 10 + i) for i in range(3))
 
 
 def make_gates(cfg: NSAConfig) -> np.ndarray:
@@ -248,7 +286,7 @@ def make_gates(cfg: NSAConfig) -> np.ndarray:
 
 
 def make_dout(cfg: NSAConfig) -> np.ndarray:
-    return _normal_bf16((cfg.n, cfg.heads, cfg.d), _rng(cfg.seed, 30))
+    return _normal_bf16((cfg.n, cfg.heads, cfg.d), cfg.seed, 30)
 
 
 def sample_query_blocks(cfg: NSAConfig, n_random: int, seed: int = 0) -> np.ndarray:
