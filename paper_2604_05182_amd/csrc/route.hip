@@ -4,9 +4,9 @@
 //   project_blocks  one thread per object block: centroid of its 64 positions, then its
 //                   pinhole projection (u, v) into every view.
 //   select_topk     one 256-thread workgroup per query block (object block or image
-//                   tile): evaluates the squared 2-D distance to every candidate and
-//                   extracts the K smallest (distance, id) keys by K rounds of a
-//                   workgroup-wide minimum.
+//                   tile): evaluates the squared 2-D distance to every candidate once
+//                   (keys parked in LDS) and extracts the K smallest (distance, id)
+//                   keys by K rounds of a workgroup-wide minimum.
 // The whole file is built with floating-point contraction off: every product and sum
 // below is rounded to fp32 exactly as written, which is what makes the indices
 // reproducible bit for bit.  Plain ALU work, latency bound and tiny next to attention.
@@ -72,9 +72,15 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
     return v;
 }
 
-__global__ __launch_bounds__(256) void select_topk(int nb_obj, int n_views, int tg, int topk,
+// Keys of all candidates of one query block are computed once into LDS; every thread
+// remembers the smallest key of its own strided slice that is still unselected, a round
+// is one workgroup-wide minimum over those, and only the winning thread rescans its slice.
+// `cache_keys` is false when the candidate keys do not fit in LDS: keys are then
+// recomputed on every scan (same results, slower).
+__global__ __launch_bounds__(256) void select_topk(int nb_obj, int n_views, int tg, int topk, int cache_keys,
                                                    const float2 *__restrict__ uv, int32_t *__restrict__ idx,
                                                    float *__restrict__ dist2_out) {
+    extern __shared__ unsigned long long key_cache[];
     const int row = blockIdx.x;  // query block
     const int tpv = tg * tg;
     const int n_tiles = n_views * tpv;
@@ -89,24 +95,34 @@ __global__ __launch_bounds__(256) void select_topk(int nb_obj, int n_views, int 
         qi = r / tg;
         qj = r % tg;
     }
+    auto key_of = [&](int c) {
+        float d2;
+        if (obj_row) {
+            int m = c / tpv, r = c % tpv;
+            d2 = dist2(uv[(size_t)row * n_views + m], r / tg, r % tg);
+        } else {
+            d2 = dist2(uv[(size_t)c * n_views + qm], qi, qj);
+        }
+        return make_key(d2, (unsigned)c);
+    };
     __shared__ unsigned long long wmin[4];
     const unsigned long long kNone = ~0ull;
-    unsigned long long last = 0;
-    bool have_last = false;
-    for (int k = 0; k < topk; ++k) {
+    // smallest key of this thread's slice strictly above `floor_key` (any key if !have_floor)
+    auto scan = [&](bool have_floor, unsigned long long floor_key) {
         unsigned long long best = kNone;
         for (int c = threadIdx.x; c < n_cand; c += blockDim.x) {
-            float d2;
-            if (obj_row) {
-                int m = c / tpv, r = c % tpv;
-                d2 = dist2(uv[(size_t)row * n_views + m], r / tg, r % tg);
-            } else {
-                d2 = dist2(uv[(size_t)c * n_views + qm], qi, qj);
-            }
-            unsigned long long key = make_key(d2, (unsigned)c);
-            if ((!have_last || key > last) && key < best) best = key;
+            unsigned long long key = cache_keys ? key_cache[c] : key_of(c);
+            if ((!have_floor || key > floor_key) && key < best) best = key;
         }
-        best = wave_min_u64(best);
+        return best;
+    };
+    if (cache_keys) {
+        for (int c = threadIdx.x; c < n_cand; c += blockDim.x) key_cache[c] = key_of(c);
+        // each thread only ever reads back the entries it wrote itself: no barrier needed
+    }
+    unsigned long long mine = scan(false, 0);
+    for (int k = 0; k < topk; ++k) {
+        unsigned long long best = wave_min_u64(mine);
         if ((threadIdx.x & 63) == 0) wmin[threadIdx.x >> 6] = best;
         __syncthreads();
         unsigned long long b0 = wmin[0], b1 = wmin[1], b2 = wmin[2], b3 = wmin[3];
@@ -130,8 +146,7 @@ __global__ __launch_bounds__(256) void select_topk(int nb_obj, int n_views, int 
             }
             return;
         }
-        last = best;
-        have_last = true;
+        if (mine == best) mine = scan(true, best);  // keys are distinct: exactly one thread owns the winner
     }
 }
 
@@ -151,8 +166,11 @@ lsrm_status launch_route(const Shape &s, const float *d_pos, const lsrm_camera *
         LSRM_HIP_CHECK(hipGetLastError());
     }
     if (s.nb > 0 && s.topk > 0) {
-        hipLaunchKernelGGL(select_topk, dim3(s.nb), dim3(256), 0, st, s.nb_obj, s.n_views, s.grid / 8, s.topk, uv,
-                           d_idx, d_dist2);
+        const int max_cand = s.nb_obj > s.n_tiles ? s.nb_obj : s.n_tiles;
+        const size_t lds = (size_t)max_cand * sizeof(unsigned long long);
+        const int cache_keys = lds <= 60 * 1024 ? 1 : 0;  // default dynamic-LDS limit; beyond it keys are recomputed
+        hipLaunchKernelGGL(select_topk, dim3(s.nb), dim3(256), cache_keys ? lds : 0, st, s.nb_obj, s.n_views,
+                           s.grid / 8, s.topk, cache_keys, uv, d_idx, d_dist2);
         LSRM_HIP_CHECK(hipGetLastError());
     }
     return LSRM_OK;

@@ -32,6 +32,8 @@ ROUTE_CASES = [
     I.small_config(name="r-ragged", n_obj=1088, n_views=3, grid=24, topk=7, seed=4, points="ellipsoids"),
     I.small_config(name="r-fullk", n_obj=512, n_views=2, grid=16, topk=8, seed=5),
     I.small_config(name="r-pad", n_obj=128, n_views=1, grid=8, topk=3, seed=5),
+    # more object blocks than the routing kernel keeps in LDS: exercises its recompute path
+    I.small_config(name="r-nocache", n_obj=7744 * 64, n_views=2, grid=8, topk=6, seed=6),
     I.CONFIGS[1], I.CONFIGS[2], I.CONFIGS[3], I.CONFIGS[4],
 ]
 
