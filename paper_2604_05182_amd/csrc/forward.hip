@@ -2,17 +2,21 @@
 // each its own softmax, combined by the gated sum, in one kernel.
 //
 // Work decomposition
-//   One wavefront owns one (query block of 64 tokens, head) and carries it through all
-//   three branches; a 256-thread workgroup is four wavefronts on four consecutive query
-//   blocks of the same head.  Workgroups are numbered so that each of the 8 XCDs walks
-//   a contiguous range of (head, query block) units: the L2 of an XCD then holds one
-//   head's pooled keys/values and the neighbouring windows / routed blocks.
+//   One workgroup owns one (query block of 64 tokens, head) and carries it through all
+//   three branches.  A wavefront holds QT tiles of 32 query rows: QT = 1 means two
+//   wavefronts per workgroup that share every K/V tile through LDS (d = 128: the state
+//   of 32 rows fits 256 registers, so two wavefronts run per SIMD and one's softmax
+//   overlaps the other's MFMAs); QT = 2 means a single self-contained wavefront per
+//   workgroup with no barriers at all (d = 64).  Workgroups are numbered so that each
+//   of the 8 XCDs walks a contiguous range of (head, query block) units: the L2 of an
+//   XCD then holds one head's pooled keys/values and the neighbouring windows / routed
+//   blocks.
 //
-// Per 32-key step (the unit of the inner loop), per wavefront
+// Per 32-key step, per wavefront and query tile
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = 32 keys x 16 channels, B = Q^T.
 //                      With S transposed, each lane owns one query column, so the row
 //                      max / row sum of the softmax are in-lane reductions plus one
-//                      exchange between the two lane halves.
+//                      exchange between the two lane halves (v_permlane32_swap).
 //   P^T -> bf16        the accumulator layout of S^T is already the B-operand layout of
 //                      the next contraction once the key rows of the A operand are
 //                      loaded in a fixed permutation (bits 2 and 3 of the row swapped),
@@ -23,8 +27,11 @@
 //   K rows come straight from the caller's [N, H, d] tensor, V from a packed transposed
 //   copy made once per call ([block][head][half][d][32 keys], 16-byte chunks XOR-swizzled
 //   so that LDS reads are bank-conflict free).  Both are copied global -> LDS with
-//   global_load_lds_dwordx4 (no VGPR staging), double buffered per wavefront, and read
-//   back as ds_read_b128 MFMA fragments.
+//   global_load_lds_dwordx4 (no VGPR staging; scalar base + per-lane 32-bit offset),
+//   double buffered per workgroup, and read back as ds_read_b128 MFMA fragments.
+//   The gated sum of the branches is carried between branches in an fp32 scratch tile in
+//   MFMA-fragment order (fully coalesced) instead of in registers; the final tile goes
+//   through LDS so that the bf16 output rows are written as whole 16-byte chunks.
 #include "lsrm_internal.h"
 
 namespace lsrm {
@@ -34,6 +41,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxSeg = 63;
 constexpr float kMinusHuge = -1.0e30f;  // initial running maximum: finite, so no inf - inf
@@ -49,20 +57,26 @@ struct FwdArgs {
     uint16_t *out;
     float *lse;
     uint16_t *out_branch;
+    float *gsum;  // scratch: running gated sum, fragment order
     int64_t n;
     int nb, h, topk, window, n_seg;
-    int units, units_per_xcd, groups_per_head;
+    int units, units_per_xcd;
     float scale_log2e, scale;
 };
 
-template <int D>
+template <int D, int QT>
 struct Geo {
     static constexpr int NS = D / 16;           // 16-channel slabs of the QK^T contraction
     static constexpr int ND = D / 32;           // 32-channel tiles of the PV output
     static constexpr int K_BYTES = 32 * D * 2;  // 32 key rows
     static constexpr int V_BYTES = D * 64;      // D channel rows x 32 keys
     static constexpr int STAGE = K_BYTES + V_BYTES;
-    static constexpr int WAVE_LDS = 2 * STAGE;
+    static constexpr int NW = 2 / QT;           // wavefronts per workgroup
+    static constexpr int THREADS = 64 * NW;
+    static constexpr int K_INST = K_BYTES / 1024 / NW;  // copy instructions per wavefront and tile
+    static constexpr int V_INST = V_BYTES / 1024 / NW;
+    static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output transpose (bytes)
+    static constexpr int LDS_BYTES = 2 * STAGE > NW * 32 * OUT_ROW ? 2 * STAGE : NW * 32 * OUT_ROW;
 };
 
 // swizzle of the 16-byte chunk index inside a K row held in LDS
@@ -78,68 +92,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return *reinterpret_cast<uint32_t *>(&p);
 }
 
-struct TileSrc {
-    const uint16_t *k_rows;  // row 0 of the 32-key sub-tile, this head
-    int rows_valid;          // rows >= rows_valid are clamped (their scores get masked)
-    const uint16_t *v_t;     // packed transposed V sub-tile, contiguous V_BYTES
-    int j0;                  // index of key 0 of the sub-tile in mask coordinates
-    bool need_mask;
-};
-
-template <int D>
-__device__ __forceinline__ void issue_tile(const TileSrc &t, int64_t row_stride, char *lds_stage, int lane) {
-    using G = Geo<D>;
-    constexpr int ROWS_PER_INST = 1024 / (D * 2);
-    constexpr int CHUNKS = D / 8;
-#pragma unroll
-    for (int i = 0; i < G::K_BYTES / 1024; ++i) {
-        int row = i * ROWS_PER_INST + lane / CHUNKS;
-        int slot = lane % CHUNKS;
-        int c = slot ^ k_swz<D>(row);
-        int srow = row < t.rows_valid ? row : t.rows_valid - 1;
-        const uint16_t *src = t.k_rows + (int64_t)srow * row_stride + c * 8;
-        __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds_stage + i * 1024), 16, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < G::V_BYTES / 1024; ++i) {
-        const uint16_t *src = t.v_t + i * 512 + lane * 8;
-        __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds_stage + G::K_BYTES + i * 1024), 16, 0, 0);
-    }
-}
-
-template <int D>
-struct WaveCtx {
-    using G = Geo<D>;
-    bf16x8 qf[2][G::NS];
-    f32x16 o[2][G::ND];
-    f32x16 acc[2][G::ND];
-    float m[2], l[2];
-    int lo[2], hi[2];
-};
-
-template <int D>
-__device__ __forceinline__ void reset_branch(WaveCtx<D> &c) {
-    using G = Geo<D>;
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        c.m[qt] = kMinusHuge;
-        c.l[qt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) c.o[qt][dt][i] = 0.f;
-    }
-}
-
-// Keeps the O accumulators in accumulation registers across loop iterations (an empty
-// asm that only constrains the register class): without it the compiler copies them
-// to ordinary VGPRs and back every step because the rare rescale path multiplies them.
-template <int D>
-__device__ __forceinline__ void pin_acc(f32x16 (&o)[Geo<D>::ND]) {
-#pragma unroll
-    for (int dt = 0; dt < Geo<D>::ND; ++dt) asm volatile("" : "+a"(o[dt]));
-}
-
 // max / sum across the two lane halves (lanes i and i + 32 hold the same query)
 __device__ __forceinline__ float half_max(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -150,6 +102,70 @@ __device__ __forceinline__ float half_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+struct TileSrc {
+    const uint16_t *k_rows;  // row 0 of the 32-key sub-tile, this head
+    int rows_valid;          // rows >= rows_valid are clamped (their scores get masked)
+    const uint16_t *v_t;     // packed transposed V sub-tile, contiguous V_BYTES
+    int j0;                  // index of key 0 of the sub-tile in mask coordinates
+    bool need_mask;
+};
+
+template <int D, int QT>
+struct WaveCtx {
+    using G = Geo<D, QT>;
+    bf16x8 qf[QT][G::NS];
+    f32x16 o[QT][G::ND];
+    float m[QT], l[QT];
+    int lo[QT], hi[QT];
+    uint32_t koff[G::K_INST];  // per-lane byte offsets of this wavefront's K copy instructions
+    int krow[G::K_INST];       // and the tile row / 16-byte chunk each of them fetches
+    int kchunk[G::K_INST];
+};
+
+// Issues this wavefront's share of the global -> LDS copies of one 32-key sub-tile.
+template <int D, int QT>
+__device__ __forceinline__ void issue_tile(const WaveCtx<D, QT> &c, const TileSrc &t, uint32_t row_stride_bytes,
+                                           char *lds_stage, int wave, int lane) {
+    using G = Geo<D, QT>;
+    const char *kbase = reinterpret_cast<const char *>(t.k_rows);
+    if (__builtin_expect(t.rows_valid >= 32, 1)) {
+#pragma unroll
+        for (int j = 0; j < G::K_INST; ++j) {
+            const int i = wave + G::NW * j;
+            __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + c.koff[j]), LDS_PTR(lds_stage + i * 1024), 16, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < G::K_INST; ++j) {
+            const int i = wave + G::NW * j;
+            const int srow = c.krow[j] < t.rows_valid ? c.krow[j] : t.rows_valid - 1;
+            const uint32_t off = (uint32_t)srow * row_stride_bytes + (uint32_t)c.kchunk[j] * 16u;
+            __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + off), LDS_PTR(lds_stage + i * 1024), 16, 0, 0);
+        }
+    }
+    const char *vbase = reinterpret_cast<const char *>(t.v_t);
+#pragma unroll
+    for (int j = 0; j < G::V_INST; ++j) {
+        const int i = wave + G::NW * j;
+        __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + i * 1024 + (uint32_t)lane * 16u),
+                                         LDS_PTR(lds_stage + G::K_BYTES + i * 1024), 16, 0, 0);
+    }
+}
+
+template <int D, int QT>
+__device__ __forceinline__ void reset_branch(WaveCtx<D, QT> &c) {
+    using G = Geo<D, QT>;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        c.m[qt] = kMinusHuge;
+        c.l[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < G::ND; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c.o[qt][dt][i] = 0.f;
+    }
+}
+
 // One 32-key step: fragments are already in registers.
 //
 // The running maximum m is allowed to lag: it is raised (and O, l rescaled) only when a
@@ -158,13 +174,13 @@ __device__ __forceinline__ float half_sum(float x) {
 // the rescale of the O accumulators becomes a rare, wave-uniform branch.
 constexpr float kLag = 8.0f;
 
-template <int D>
-__device__ __forceinline__ void step_compute(WaveCtx<D> &c, const bf16x8 (&kf)[Geo<D>::NS],
-                                             const bf16x8 (&vf)[Geo<D>::ND][2], int j0, bool need_mask, int hh,
+template <int D, int QT>
+__device__ __forceinline__ void step_compute(WaveCtx<D, QT> &c, const bf16x8 (&kf)[Geo<D, QT>::NS],
+                                             const bf16x8 (&vf)[Geo<D, QT>::ND][2], int j0, bool need_mask, int hh,
                                              float sl2) {
-    using G = Geo<D>;
+    using G = Geo<D, QT>;
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < QT; ++qt) {
         f32x16 s;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[i] = 0.f;
@@ -189,12 +205,10 @@ __device__ __forceinline__ void step_compute(WaveCtx<D> &c, const bf16x8 (&kf)[G
             float alpha = raise ? __builtin_amdgcn_exp2f((c.m[qt] - m_new) * sl2) : 1.0f;
             c.m[qt] = m_new;
             c.l[qt] *= alpha;
-            pin_acc<D>(c.o[qt]);  // the copies out of / into the accumulation registers stay inside this block
 #pragma unroll
             for (int dt = 0; dt < G::ND; ++dt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) c.o[qt][dt][i] *= alpha;
-            pin_acc<D>(c.o[qt]);
         }
         const float mc = c.m[qt] * sl2;
         float psum = 0.f;
@@ -220,10 +234,10 @@ __device__ __forceinline__ void step_compute(WaveCtx<D> &c, const bf16x8 (&kf)[G
     }
 }
 
-template <int D>
+template <int D, int QT>
 __device__ __forceinline__ void read_frags(const char *lds_stage, int r_perm, int r, int hh,
-                                           bf16x8 (&kf)[Geo<D>::NS], bf16x8 (&vf)[Geo<D>::ND][2]) {
-    using G = Geo<D>;
+                                           bf16x8 (&kf)[Geo<D, QT>::NS], bf16x8 (&vf)[Geo<D, QT>::ND][2]) {
+    using G = Geo<D, QT>;
     const int ksw = k_swz<D>(r_perm);
 #pragma unroll
     for (int ks = 0; ks < G::NS; ++ks) {
@@ -242,55 +256,59 @@ __device__ __forceinline__ void read_frags(const char *lds_stage, int r_perm, in
     }
 }
 
-// Streams n_steps sub-tiles produced by src(t) through the two LDS stages of this wavefront.
-template <int D, typename SrcFn>
-__device__ __forceinline__ void run_steps(WaveCtx<D> &c, int n_steps, SrcFn src, int64_t row_stride, char *lds_wave,
-                                          int lane, float sl2) {
-    using G = Geo<D>;
+// Streams n_steps sub-tiles produced by src(t) through the two LDS stages of the workgroup.
+// n_steps and src are uniform over the workgroup, so every wavefront meets every barrier.
+template <int D, int QT, typename SrcFn>
+__device__ __forceinline__ void run_steps(WaveCtx<D, QT> &c, int n_steps, SrcFn src, uint32_t row_stride_bytes,
+                                          char *lds, int wave, int lane, float sl2) {
+    using G = Geo<D, QT>;
     const int r = lane & 31, hh = lane >> 5;
     const int r_perm = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
     if (n_steps <= 0) return;
     TileSrc cur = src(0);
-    issue_tile<D>(cur, row_stride, lds_wave, lane);
+    if (G::NW > 1) __syncthreads();  // every wavefront is done with both stages (previous branch)
+    issue_tile<D, QT>(c, cur, row_stride_bytes, lds, wave, lane);
     for (int t = 0; t < n_steps; ++t) {
-        char *stage = lds_wave + (t & 1) * G::STAGE;
+        char *stage = lds + (t & 1) * G::STAGE;
         bf16x8 kf[G::NS];
         bf16x8 vf[G::ND][2];
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this step's copies have landed in LDS
-        read_frags<D>(stage, r_perm, r, hh, kf, vf);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's copies of step t have landed
+        if (G::NW > 1) __syncthreads();      // ... and the partner's; also: everyone finished reading step t-1
+        read_frags<D, QT>(stage, r_perm, r, hh, kf, vf);
         TileSrc nxt = cur;
         if (t + 1 < n_steps) {
             nxt = src(t + 1);
-            issue_tile<D>(nxt, row_stride, lds_wave + ((t + 1) & 1) * G::STAGE, lane);
+            issue_tile<D, QT>(c, nxt, row_stride_bytes, lds + ((t + 1) & 1) * G::STAGE, wave, lane);
         }
-        step_compute<D>(c, kf, vf, cur.j0, cur.need_mask, hh, sl2);
+        step_compute<D, QT>(c, kf, vf, cur.j0, cur.need_mask, hh, sl2);
         cur = nxt;
     }
 }
 
-// Ends a branch: normalises, applies the gate, adds into the running output, and
-// optionally stores the branch output and its log-sum-exp.
-template <int D>
-__device__ __forceinline__ void finish_branch(WaveCtx<D> &c, const FwdArgs &a, int branch, int qb, int head,
-                                              int lane) {
-    using G = Geo<D>;
+// Ends a branch: normalises, applies the gate and folds the result into the running
+// gated sum kept in the fp32 scratch tile (written by branch 0, updated by branch 1,
+// consumed by branch 2, which converts to bf16 and stores the output rows through LDS).
+// Optionally stores the un-gated branch output and its log-sum-exp.
+template <int D, int QT>
+__device__ __forceinline__ void finish_branch(WaveCtx<D, QT> &c, const FwdArgs &a, int branch, int qb, int head,
+                                              int wave, int lane, char *lds) {
+    using G = Geo<D, QT>;
     const int r = lane & 31, hh = lane >> 5;
+    if (branch == 2 && G::NW > 1) __syncthreads();  // the copy stages are about to be reused for the output
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        int64_t row = (int64_t)qb * 64 + 32 * qt + r;
-        float l_tot = half_sum(c.l[qt]);
-        float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-        float g = a.gates[(row * a.h + head) * 3 + branch];
-        float w = g * inv;
+    for (int qt = 0; qt < QT; ++qt) {
+        const int64_t row0 = (int64_t)qb * 64 + 32 * (wave * QT + qt);
+        const int64_t row = row0 + r;
+        const float l_tot = half_sum(c.l[qt]);
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        const float w = a.gates[(row * a.h + head) * 3 + branch] * inv;
         if (a.lse != nullptr && hh == 0) {
             float v = l_tot > 0.f ? c.m[qt] * a.scale + __logf(l_tot) : -__builtin_inff();
             a.lse[((int64_t)branch * a.n + row) * a.h + head] = v;
         }
+        if (a.out_branch != nullptr) {
 #pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) c.acc[qt][dt][i] += w * c.o[qt][dt][i];
-            if (a.out_branch != nullptr) {
+            for (int dt = 0; dt < G::ND; ++dt) {
                 uint16_t *dst = a.out_branch + (((int64_t)branch * a.n + row) * a.h + head) * D + 32 * dt + 4 * hh;
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
@@ -301,48 +319,90 @@ __device__ __forceinline__ void finish_branch(WaveCtx<D> &c, const FwdArgs &a, i
                 }
             }
         }
+        // scratch tile of this (32-row tile, head): [ND][4][64 lanes] float4
+        f32x4 *gs = reinterpret_cast<f32x4 *>(a.gsum) + (((row0 >> 5) * a.h + head) * (G::ND * 4)) * 64 + lane;
+        char *tr = lds + wave * 32 * G::OUT_ROW;  // output transpose region of this wavefront
+#pragma unroll
+        for (int dt = 0; dt < G::ND; ++dt) {
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                f32x4 v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = w * c.o[qt][dt][4 * gq + j];
+                if (branch > 0) {
+                    f32x4 prev = gs[(dt * 4 + gq) * 64];
+                    v += prev;
+                }
+                if (branch < 2) {
+                    gs[(dt * 4 + gq) * 64] = v;
+                } else {
+                    uint2 w2;
+                    w2.x = pack_bf16(v[0], v[1]);
+                    w2.y = pack_bf16(v[2], v[3]);
+                    *reinterpret_cast<uint2 *>(tr + r * G::OUT_ROW + (32 * dt + 8 * gq + 4 * hh) * 2) = w2;
+                }
+            }
+        }
+        if (branch == 2) {
+            // rows of this tile back from LDS as whole 16-byte chunks: 4 (d=128) or 8 (d=64) rows per pass
+            constexpr int CH = D / 8;
+            constexpr int ROWS = 64 / CH;
+#pragma unroll
+            for (int it = 0; it < 32 / ROWS; ++it) {
+                const int rr = it * ROWS + lane / CH, ch = lane % CH;
+                uint4 val = *reinterpret_cast<const uint4 *>(tr + rr * G::OUT_ROW + ch * 16);
+                *reinterpret_cast<uint4 *>(a.out + ((row0 + rr) * a.h + head) * D + ch * 8) = val;
+            }
+        }
     }
 }
 
-// One wavefront per SIMD: each may use the whole 512-entry register file (O and the
-// gated sum live in accumulation registers, operands and scores in ordinary VGPRs).
-template <int D>
-__global__ __launch_bounds__(256, 1) void nsa_forward_kernel(FwdArgs a) {
-    using G = Geo<D>;
+template <int D, int QT>
+__global__ __launch_bounds__((Geo<D, QT>::THREADS), 2) void nsa_forward_kernel(FwdArgs a) {
+    using G = Geo<D, QT>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // XCD-aware numbering: hardware deals consecutive workgroups round-robin to the 8 XCDs
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     if (slot >= a.units_per_xcd) return;
     const int unit = xcd * a.units_per_xcd + slot;
     if (unit >= a.units) return;
-    const int head = unit / a.groups_per_head;
-    const int group = unit % a.groups_per_head;
+    const int head = unit / a.nb;
+    const int qb = unit % a.nb;
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int qb = group * 4 + wave;
-    if (qb >= a.nb) return;  // wavefronts are independent: no workgroup barrier below
-    char *lds_wave = lds + wave * G::WAVE_LDS;
+    const int wave = G::NW > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : 0;
     const int r = lane & 31, hh = lane >> 5;
-    const int64_t row_stride = (int64_t)a.h * D;
+    const uint32_t row_stride_bytes = (uint32_t)a.h * D * 2;
     const float sl2 = a.scale_log2e;
 
-    WaveCtx<D> c;
+    WaveCtx<D, QT> c;
+    {
+        constexpr int ROWS_PER_INST = 1024 / (D * 2);
+        constexpr int CHUNKS = D / 8;
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        const uint16_t *qrow = a.q + (((int64_t)qb * 64 + 32 * qt + r) * a.h + head) * D + 8 * hh;
+        for (int j = 0; j < G::K_INST; ++j) {
+            const int i = wave + G::NW * j;
+            const int row = i * ROWS_PER_INST + lane / CHUNKS;
+            const int chunk = (lane % CHUNKS) ^ k_swz<D>(row);
+            c.krow[j] = row;
+            c.kchunk[j] = chunk;
+            c.koff[j] = (uint32_t)row * row_stride_bytes + (uint32_t)chunk * 16u;
+        }
+    }
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const uint16_t *qrow = a.q + (((int64_t)qb * 64 + 32 * (wave * QT + qt) + r) * a.h + head) * D + 8 * hh;
 #pragma unroll
         for (int ks = 0; ks < G::NS; ++ks) c.qf[qt][ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
-#pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) c.acc[qt][dt][i] = 0.f;
     }
 
     // ---------------- compressed branch: all NB pooled pairs
     {
-        reset_branch<D>(c);
-        c.lo[0] = c.lo[1] = 0;
-        c.hi[0] = c.hi[1] = a.nb;
+        reset_branch<D, QT>(c);
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            c.lo[qt] = 0;
+            c.hi[qt] = a.nb;
+        }
         const int n_steps = (a.nb + 31) / 32;
         auto src = [&](int t) {
             TileSrc s;
@@ -353,13 +413,13 @@ __global__ __launch_bounds__(256, 1) void nsa_forward_kernel(FwdArgs a) {
             s.need_mask = 32 * t + 32 > a.nb;
             return s;
         };
-        run_steps<D>(c, n_steps, src, row_stride, lds_wave, lane, sl2);
-        finish_branch<D>(c, a, 0, qb, head, lane);
+        run_steps<D, QT>(c, n_steps, src, row_stride_bytes, lds, wave, lane, sl2);
+        finish_branch<D, QT>(c, a, 0, qb, head, wave, lane, lds);
     }
 
     // ---------------- selected branch: every token of the routed blocks
     {
-        reset_branch<D>(c);
+        reset_branch<D, QT>(c);
         int my = lane < a.topk ? a.idx[(int64_t)qb * a.topk + lane] : -1;
         if (my >= a.nb) my = -1;
         const unsigned long long valid = __ballot(my >= 0);
@@ -378,13 +438,13 @@ __global__ __launch_bounds__(256, 1) void nsa_forward_kernel(FwdArgs a) {
             s.need_mask = false;
             return s;
         };
-        run_steps<D>(c, 2 * n_valid, src, row_stride, lds_wave, lane, sl2);
-        finish_branch<D>(c, a, 1, qb, head, lane);
+        run_steps<D, QT>(c, 2 * n_valid, src, row_stride_bytes, lds, wave, lane, sl2);
+        finish_branch<D, QT>(c, a, 1, qb, head, wave, lane, lds);
     }
 
     // ---------------- window branch: keys j with -W/2 <= j - i < W/2 inside the segment
     {
-        reset_branch<D>(c);
+        reset_branch<D, QT>(c);
         const int q0 = qb * 64;
         int seg_lo = 0, seg_hi = 0;
         for (int s = 0; s < a.n_seg; ++s) {
@@ -396,11 +456,12 @@ __global__ __launch_bounds__(256, 1) void nsa_forward_kernel(FwdArgs a) {
         }
         const int half = a.window / 2;
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            int i = q0 + 32 * qt + r;
+        for (int qt = 0; qt < QT; ++qt) {
+            int i = q0 + 32 * (wave * QT + qt) + r;
             c.lo[qt] = max(seg_lo, i - half);
             c.hi[qt] = min(seg_hi, i + half);
         }
+        // tile range of the whole query block (uniform over the workgroup)
         const int k_start = max(seg_lo, q0 - half);
         const int k_end = min(seg_hi, q0 + 63 + half);  // exclusive
         const int full_lo = max(seg_lo, q0 + 63 - half);
@@ -417,25 +478,8 @@ __global__ __launch_bounds__(256, 1) void nsa_forward_kernel(FwdArgs a) {
             s.need_mask = (32 * st < full_lo) || (32 * st + 32 > full_hi);
             return s;
         };
-        run_steps<D>(c, n_steps, src, row_stride, lds_wave, lane, sl2);
-        finish_branch<D>(c, a, 2, qb, head, lane);
-    }
-
-    // ---------------- gated sum -> bf16
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        int64_t row = (int64_t)qb * 64 + 32 * qt + r;
-#pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt) {
-            uint16_t *dst = a.out + (row * a.h + head) * D + 32 * dt + 4 * hh;
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                uint2 w2;
-                w2.x = pack_bf16(c.acc[qt][dt][4 * gq + 0], c.acc[qt][dt][4 * gq + 1]);
-                w2.y = pack_bf16(c.acc[qt][dt][4 * gq + 2], c.acc[qt][dt][4 * gq + 3]);
-                *reinterpret_cast<uint2 *>(dst + 8 * gq) = w2;
-            }
-        }
+        run_steps<D, QT>(c, n_steps, src, row_stride_bytes, lds, wave, lane, sl2);
+        finish_branch<D, QT>(c, a, 2, qb, head, wave, lane, lds);
     }
 }
 
@@ -477,7 +521,7 @@ __global__ __launch_bounds__(256) void pack_transposed(const uint16_t *__restric
 }
 
 struct WsLayout {
-    size_t v_t, vc_t, total;
+    size_t v_t, vc_t, gsum, total;
 };
 
 WsLayout ws_layout(const Shape &s) {
@@ -487,15 +531,17 @@ WsLayout ws_layout(const Shape &s) {
     off += align_up((size_t)s.nb * 64 * s.h * s.d * 2, 256);
     w.vc_t = off;
     off += align_up((size_t)((s.nb + 63) / 64) * 64 * s.h * s.d * 2, 256);
+    w.gsum = off;
+    off += align_up((size_t)s.nb * 64 * s.h * s.d * 4, 256);
     w.total = off > 0 ? off : 256;
     return w;
 }
 
-template <int D>
+template <int D, int QT>
 lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg, FwdArgs a, const uint16_t *d_v,
                              const uint16_t *d_vc, char *ws, const WsLayout &w, hipStream_t st, hipEvent_t ev_start,
                              hipEvent_t ev_stop) {
-    using G = Geo<D>;
+    using G = Geo<D, QT>;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     hipLaunchKernelGGL(pack_transposed<D>, dim3(s.nb, s.h), dim3(256), 0, st, d_v, (uint16_t *)(ws + w.v_t), s.n, s.h);
     LSRM_HIP_CHECK(hipGetLastError());
@@ -504,18 +550,11 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     LSRM_HIP_CHECK(hipGetLastError());
     a.v_t = (const uint16_t *)(ws + w.v_t);
     a.vc_t = (const uint16_t *)(ws + w.vc_t);
-    a.groups_per_head = (s.nb + 3) / 4;
-    a.units = a.groups_per_head * s.h;
+    a.gsum = (float *)(ws + w.gsum);
+    a.units = s.nb * s.h;
     a.units_per_xcd = (a.units + 7) / 8;
-    const int lds_bytes = 4 * G::WAVE_LDS;
-    static bool attr_set = false;
-    if (!attr_set) {
-        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
-        attr_set = true;
-    }
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
-    hipLaunchKernelGGL(nsa_forward_kernel<D>, dim3(a.units_per_xcd * 8), dim3(256), lds_bytes, st, a);
+    hipLaunchKernelGGL((nsa_forward_kernel<D, QT>), dim3(a.units_per_xcd * 8), dim3(G::THREADS), G::LDS_BYTES, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;
@@ -551,8 +590,8 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.scale_log2e = s.scale * 1.4426950408889634f;
     WsLayout w = ws_layout(s);
     char *ws = reinterpret_cast<char *>(d_ws);
-    if (s.d == 64) return launch_forward_d<64>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
-    return launch_forward_d<128>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
+    if (s.d == 64) return launch_forward_d<64, 2>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
+    return launch_forward_d<128, 1>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
 }
 
 }  // namespace lsrm
