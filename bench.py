@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="workload id 1..4 (default 4: the largest single-GPU config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--topk", type=int, default=None, help="override the config's routed top-k (experiments)")
+    ap.add_argument("--window", type=int, default=None, help="override the config's window (experiments)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings against)")
@@ -76,6 +78,11 @@ def main():
     from paper_2604_05182_amd import binding as B  # raises if the HIP library is not built
 
     cfg = I.CONFIGS[args.config]
+    if args.topk is not None or args.window is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, topk=cfg.topk if args.topk is None else args.topk,
+                                  window=cfg.window if args.window is None else args.window,
+                                  name=cfg.name + "-override")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 

@@ -2,17 +2,17 @@
 // each its own softmax, combined by the gated sum, in one kernel.
 //
 // Work decomposition
-//   One workgroup owns one (query block of 64 tokens, head) and carries it through all
-//   three branches.  A wavefront holds QT tiles of 32 query rows: QT = 1 means two
-//   wavefronts per workgroup that share every K/V tile through LDS (d = 128: the state
-//   of 32 rows fits 256 registers, so two wavefronts run per SIMD and one's softmax
-//   overlaps the other's MFMAs); QT = 2 means a single self-contained wavefront per
-//   workgroup with no barriers at all (d = 64).  Workgroups are numbered so that each
-//   of the 8 XCDs walks a contiguous range of (head, query block) units: the L2 of an
-//   XCD then holds one head's pooled keys/values and the neighbouring windows / routed
-//   blocks.
+//   One 512-thread workgroup owns NP = 4 consecutive query blocks of one head and carries
+//   them through all three branches.  A wavefront holds 32 query rows (two wavefronts per
+//   query block); its state fits 256 registers, so two wavefronts run per SIMD.  In the
+//   compressed and window branches every K/V tile is copied to LDS once and used by all
+//   four query blocks (a ring of 2 NP tile slots, refilled as soon as a slot is free); in
+//   the selected branch each query block streams its own routed blocks (two stages of NP
+//   slots).  Workgroups are numbered so that each of the 8 XCDs walks a contiguous range
+//   of (head, query block) units: the L2 of an XCD then holds one head's pooled
+//   keys/values and the neighbouring windows / routed blocks.
 //
-// Per 32-key step, per wavefront and query tile
+// Per 32-key step, per wavefront
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = 32 keys x 16 channels, B = Q^T.
 //                      With S transposed, each lane owns one query column, so the row
 //                      max / row sum of the softmax are in-lane reductions plus one
@@ -22,13 +22,19 @@
 //                      loaded in a fixed permutation (bits 2 and 3 of the row swapped),
 //                      so P never leaves registers.
 //   O^T += V^T P^T     A = 32 channels x 16 keys from a pre-transposed copy of V.
+//   A wavefront issues in order and the matrix pipe takes one MFMA at a time, so MFMA and
+//   VALU work only overlap if they alternate in program order.  The shared phases are
+//   therefore software pipelined by hand: the QK^T MFMAs of tile t+1 are interleaved, one
+//   by one, with the exponentials of tile t, and the PV MFMAs of tile t with the row max
+//   of tile t+1 (scheduling barriers keep the compiler from regrouping them).
 //
 // Data movement
 //   K rows come straight from the caller's [N, H, d] tensor, V from a packed transposed
 //   copy made once per call ([block][head][half][d][32 keys], 16-byte chunks XOR-swizzled
 //   so that LDS reads are bank-conflict free).  Both are copied global -> LDS with
 //   global_load_lds_dwordx4 (no VGPR staging; scalar base + per-lane 32-bit offset),
-//   double buffered per workgroup, and read back as ds_read_b128 MFMA fragments.
+//   the copy instructions of a tile split over the wavefronts that share it, s_waitcnt
+//   vmcnt placed by hand, and read back as ds_read_b128 MFMA fragments.
 //   The gated sum of the branches is carried between branches in an fp32 scratch tile in
 //   MFMA-fragment order (fully coalesced) instead of in registers; the final tile goes
 //   through LDS so that the bf16 output rows are written as whole 16-byte chunks.
@@ -60,23 +66,33 @@ struct FwdArgs {
     float *gsum;  // scratch: running gated sum, fragment order
     int64_t n;
     int nb, h, topk, window, n_seg;
-    int units, units_per_xcd;
+    int units, units_per_xcd, groups_per_head;
     float scale_log2e, scale;
 };
 
-template <int D, int QT>
+// NP = query blocks per workgroup (two wavefronts each).
+// LDS is a ring of 2 NP tile slots of 32 keys each (K rows, then the V^T slab).  The shared
+// phases use it as one ring; the pair phase as two stages of NP slots.
+template <int D, int NP>
 struct Geo {
     static constexpr int NS = D / 16;           // 16-channel slabs of the QK^T contraction
     static constexpr int ND = D / 32;           // 32-channel tiles of the PV output
     static constexpr int K_BYTES = 32 * D * 2;  // 32 key rows
     static constexpr int V_BYTES = D * 64;      // D channel rows x 32 keys
-    static constexpr int STAGE = K_BYTES + V_BYTES;
-    static constexpr int NW = 2 / QT;           // wavefronts per workgroup
-    static constexpr int THREADS = 64 * NW;
-    static constexpr int K_INST = K_BYTES / 1024 / NW;  // copy instructions per wavefront and tile
-    static constexpr int V_INST = V_BYTES / 1024 / NW;
-    static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output transpose (bytes)
-    static constexpr int LDS_BYTES = 2 * STAGE > NW * 32 * OUT_ROW ? 2 * STAGE : NW * 32 * OUT_ROW;
+    static constexpr int TILE = K_BYTES + V_BYTES;
+    static constexpr int WAVES = 2 * NP;
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int NSLOT = 2 * NP;        // tile slots in LDS
+    static constexpr int K_INST = K_BYTES / 1024;  // 1 KB copy instructions per tile
+    static constexpr int V_INST = V_BYTES / 1024;
+    static constexpr int SH_IPT = (K_INST + V_INST) / WAVES;  // shared phases: copy instructions per wavefront and tile
+    static constexpr int SH_K = K_INST % WAVES == 0 ? K_INST / WAVES : 1;  // of which key instructions (at most)
+    static constexpr int PR_K = K_INST / 2;     // pair phase: a wavefront copies half of its pair's tile
+    static constexpr int PR_V = V_INST / 2;
+    static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output staging (bytes)
+    static constexpr int LDS_BYTES = NSLOT * TILE;
+    static_assert(WAVES * 32 * OUT_ROW <= LDS_BYTES, "output staging must fit in the tile slots");
+    static_assert(SH_IPT >= 1 && (K_INST + V_INST) % WAVES == 0 && NSLOT >= 4, "");
 };
 
 // swizzle of the 16-byte chunk index inside a K row held in LDS
@@ -102,186 +118,369 @@ __device__ __forceinline__ float half_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// s_waitcnt immediates (vmcnt is split over bits [3:0] and [15:14], expcnt is bits [6:4],
+// lgkmcnt bits [11:8]; counters that are not waited for are left at their maxima)
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }            // vmcnt <= n
+constexpr int vm_lgkm_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }          // vmcnt <= n, lgkmcnt == 0
+
+// Workgroup barrier without the memory fence that __syncthreads() implies: the fence
+// would wait for every outstanding copy (vmcnt(0)) and defeat the prefetch ring.  What
+// must be visible is ordered by hand: a wavefront waits for its own copies (s_waitcnt
+// vmcnt) and its own LDS reads (lgkmcnt) before the barrier and reads LDS only after it.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Results of an MFMA become readable by VALU instructions only a fixed number of cycles
+// after issue, and the hardware does not interlock that dependency: the compiler pads
+// with s_nop, but it has been seen to misplace the padding when a branch separates the
+// MFMA from its first VALU reader.  Every such (rare) path starts with this explicit
+// settle instead; 32 wait states cover the longest MFMA used here.
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 struct TileSrc {
-    const uint16_t *k_rows;  // row 0 of the 32-key sub-tile, this head
+    const uint16_t *k_rows;  // row 0 of the 32-key tile, this head
     int rows_valid;          // rows >= rows_valid are clamped (their scores get masked)
-    const uint16_t *v_t;     // packed transposed V sub-tile, contiguous V_BYTES
-    int j0;                  // index of key 0 of the sub-tile in mask coordinates
-    bool need_mask;
+    const uint16_t *v_t;     // packed transposed V tile, contiguous V_BYTES
 };
 
-template <int D, int QT>
+template <int D, int NP>
 struct WaveCtx {
-    using G = Geo<D, QT>;
-    bf16x8 qf[QT][G::NS];
-    f32x16 o[QT][G::ND];
-    float m[QT], l[QT];
-    int lo[QT], hi[QT];
-    uint32_t koff[G::K_INST];  // per-lane byte offsets of this wavefront's K copy instructions
-    int krow[G::K_INST];       // and the tile row / 16-byte chunk each of them fetches
-    int kchunk[G::K_INST];
+    using G = Geo<D, NP>;
+    bf16x8 qf[G::NS];
+    f32x16 o[G::ND];
+    float m, l;
+    int lo, hi;                 // valid key range of this lane's query in mask coordinates
+    uint32_t sh_koff[G::SH_K];  // shared phases: per-lane byte offsets of this wavefront's K copy instructions
+    int sh_krow[G::SH_K], sh_kchunk[G::SH_K];
+    uint32_t pr_koff[G::PR_K];  // pair phase: offsets of this wavefront's K copy instructions
+    uint32_t kf_off[G::NS];     // per-lane LDS byte offsets (inside a tile slot) of the K and V^T fragments
+    uint32_t vf_off[G::ND][2];
 };
 
-// Issues this wavefront's share of the global -> LDS copies of one 32-key sub-tile.
-template <int D, int QT>
-__device__ __forceinline__ void issue_tile(const WaveCtx<D, QT> &c, const TileSrc &t, uint32_t row_stride_bytes,
-                                           char *lds_stage, int wave, int lane) {
-    using G = Geo<D, QT>;
+template <int D>
+__device__ __forceinline__ void k_copy_geometry(int inst, int lane, uint32_t row_stride_bytes, int *row, int *chunk,
+                                                uint32_t *off) {
+    constexpr int ROWS_PER_INST = 1024 / (D * 2);
+    constexpr int CHUNKS = D / 8;
+    *row = inst * ROWS_PER_INST + lane / CHUNKS;
+    *chunk = (lane % CHUNKS) ^ k_swz<D>(*row);
+    *off = (uint32_t)(*row) * row_stride_bytes + (uint32_t)(*chunk) * 16u;
+}
+
+// Shared phases: the wavefronts of the workgroup split the K_INST + V_INST copy instructions
+// of one tile evenly (SH_IPT each).
+template <int D, int NP>
+__device__ __forceinline__ void issue_shared(const WaveCtx<D, NP> &c, const TileSrc &t, uint32_t row_stride_bytes,
+                                             char *slot, int wave, int lane) {
+    using G = Geo<D, NP>;
     const char *kbase = reinterpret_cast<const char *>(t.k_rows);
-    if (__builtin_expect(t.rows_valid >= 32, 1)) {
-#pragma unroll
-        for (int j = 0; j < G::K_INST; ++j) {
-            const int i = wave + G::NW * j;
-            __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + c.koff[j]), LDS_PTR(lds_stage + i * 1024), 16, 0, 0);
+    const char *vbase = reinterpret_cast<const char *>(t.v_t);
+    auto copy_k = [&](int j, int inst) {
+        uint32_t off = c.sh_koff[j];
+        if (__builtin_expect(t.rows_valid < 32, 0)) {
+            const int srow = c.sh_krow[j] < t.rows_valid ? c.sh_krow[j] : t.rows_valid - 1;
+            off = (uint32_t)srow * row_stride_bytes + (uint32_t)c.sh_kchunk[j] * 16u;
         }
+        __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + off), LDS_PTR(slot + inst * 1024), 16, 0, 0);
+    };
+    auto copy_v = [&](int inst) {
+        __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + inst * 1024 + (uint32_t)lane * 16u),
+                                         LDS_PTR(slot + G::K_BYTES + inst * 1024), 16, 0, 0);
+    };
+    if constexpr (G::K_INST % G::WAVES == 0) {
+        // every wavefront copies K_INST / WAVES key instructions and as many value instructions
+#pragma unroll
+        for (int j = 0; j < G::SH_K; ++j) copy_k(j, wave + G::WAVES * j);
+#pragma unroll
+        for (int j = 0; j < G::V_INST / G::WAVES; ++j) copy_v(wave + G::WAVES * j);
     } else {
-#pragma unroll
-        for (int j = 0; j < G::K_INST; ++j) {
-            const int i = wave + G::NW * j;
-            const int srow = c.krow[j] < t.rows_valid ? c.krow[j] : t.rows_valid - 1;
-            const uint32_t off = (uint32_t)srow * row_stride_bytes + (uint32_t)c.kchunk[j] * 16u;
-            __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + off), LDS_PTR(lds_stage + i * 1024), 16, 0, 0);
-        }
+        // fewer key instructions than wavefronts: the first K_INST wavefronts copy keys, the rest values
+        static_assert(G::K_INST % G::WAVES == 0 || (G::SH_IPT == 1 && G::K_INST + G::V_INST == G::WAVES), "");
+        if (wave < G::K_INST)
+            copy_k(0, wave);
+        else
+            copy_v(wave - G::K_INST);
     }
+}
+
+// Pair phase: the two wavefronts of a query block split the copies of their own tile.
+template <int D, int NP>
+__device__ __forceinline__ void issue_pair(const WaveCtx<D, NP> &c, const TileSrc &t, char *slot, int half, int lane) {
+    using G = Geo<D, NP>;
+    const char *kbase = reinterpret_cast<const char *>(t.k_rows);
     const char *vbase = reinterpret_cast<const char *>(t.v_t);
 #pragma unroll
-    for (int j = 0; j < G::V_INST; ++j) {
-        const int i = wave + G::NW * j;
+    for (int j = 0; j < G::PR_K; ++j) {
+        const int i = half + 2 * j;
+        __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + c.pr_koff[j]), LDS_PTR(slot + i * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < G::PR_V; ++j) {
+        const int i = half + 2 * j;
         __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + i * 1024 + (uint32_t)lane * 16u),
-                                         LDS_PTR(lds_stage + G::K_BYTES + i * 1024), 16, 0, 0);
+                                         LDS_PTR(slot + G::K_BYTES + i * 1024), 16, 0, 0);
     }
 }
 
-template <int D, int QT>
-__device__ __forceinline__ void reset_branch(WaveCtx<D, QT> &c) {
-    using G = Geo<D, QT>;
+template <int D, int NP>
+__device__ __forceinline__ void reset_branch(WaveCtx<D, NP> &c) {
+    c.m = kMinusHuge;
+    c.l = 0.f;
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        c.m[qt] = kMinusHuge;
-        c.l[qt] = 0.f;
+    for (int dt = 0; dt < Geo<D, NP>::ND; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt)
+        for (int i = 0; i < 16; ++i) c.o[dt][i] = 0.f;
+}
+
+// ---- pieces of one 32-key step of one wavefront (32 query rows) -------------------------
+template <int D, int NP>
+__device__ __forceinline__ void read_k(const WaveCtx<D, NP> &c, const char *slot, bf16x8 (&kf)[Geo<D, NP>::NS]) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) c.o[qt][dt][i] = 0.f;
+    for (int ks = 0; ks < Geo<D, NP>::NS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(slot + c.kf_off[ks]);
+}
+template <int D, int NP>
+__device__ __forceinline__ void read_v(const WaveCtx<D, NP> &c, const char *slot, bf16x8 (&vf)[Geo<D, NP>::ND][2]) {
+#pragma unroll
+    for (int dt = 0; dt < Geo<D, NP>::ND; ++dt)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = *reinterpret_cast<const bf16x8 *>(slot + c.vf_off[dt][ks]);
+}
+
+// S^T = K Q^T for 32 keys x 32 queries
+template <int D, int NP>
+__device__ __forceinline__ f32x16 qk_scores(const WaveCtx<D, NP> &c, const bf16x8 (&kf)[Geo<D, NP>::NS]) {
+    f32x16 s;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < Geo<D, NP>::NS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], c.qf[ks], s, 0, 0, 0);
+    return s;
+}
+
+// Keys outside [lo, hi) of this lane's query get a score of -inf.
+template <int D, int NP>
+__device__ __forceinline__ void mask_scores(const WaveCtx<D, NP> &c, f32x16 &s, int j0, int lane) {
+    const int hh = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
+        if (j < c.lo || j >= c.hi) s[i] = -__builtin_inff();
     }
 }
 
-// One 32-key step: fragments are already in registers.
+__device__ __forceinline__ float lane_max(const f32x16 &s) {
+    float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[i], s[i + 1]));
+    return mx;
+}
+
+// Folds the maximum of a new score tile into the running maximum.
 //
 // The running maximum m is allowed to lag: it is raised (and O, l rescaled) only when a
 // new score exceeds it by more than kLag in the log2 domain, so probabilities stay
 // below 2^kLag -- harmless in fp32 and bf16, whose exponent ranges are the same -- and
-// the rescale of the O accumulators becomes a rare, wave-uniform branch.
+// the rescale of the O accumulators becomes a rare, wave-uniform branch.  m starts at
+// kMinusHuge (finite), so the first real score always raises it and no inf - inf ever
+// appears; a fully masked tile (maximum -inf) never does.
 constexpr float kLag = 8.0f;
 
-template <int D, int QT>
-__device__ __forceinline__ void step_compute(WaveCtx<D, QT> &c, const bf16x8 (&kf)[Geo<D, QT>::NS],
-                                             const bf16x8 (&vf)[Geo<D, QT>::ND][2], int j0, bool need_mask, int hh,
-                                             float sl2) {
-    using G = Geo<D, QT>;
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        f32x16 s;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < G::NS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], c.qf[qt][ks], s, 0, 0, 0);
-        if (need_mask) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
-                if (j < c.lo[qt] || j >= c.hi[qt]) s[i] = -__builtin_inff();
-            }
-        }
-        float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-        for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[i], s[i + 1]));
-        mx = half_max(mx);
-        // m starts at kMinusHuge (finite), so the first real score always raises it and no
-        // inf - inf ever appears; a fully masked step (mx = -inf) never does.
-        const bool raise = (mx - c.m[qt]) * sl2 > kLag;
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(raise) != 0, 0)) {
-            float m_new = raise ? mx : c.m[qt];
-            float alpha = raise ? __builtin_amdgcn_exp2f((c.m[qt] - m_new) * sl2) : 1.0f;
-            c.m[qt] = m_new;
-            c.l[qt] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < G::ND; ++dt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) c.o[qt][dt][i] *= alpha;
-        }
-        const float mc = c.m[qt] * sl2;
-        float psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            s[i] = __builtin_amdgcn_exp2f(s[i] * sl2 - mc);
-            psum += s[i];
-        }
-        c.l[qt] += psum;
-        union {
-            bf16x8 v;
-            uint32_t u[4];
-        } pb[2];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) pb[ks].u[j] = pack_bf16(s[8 * ks + 2 * j], s[8 * ks + 2 * j + 1]);
+template <int D, int NP>
+__device__ __forceinline__ void update_max(WaveCtx<D, NP> &c, float mx_lane, float sl2) {
+    using G = Geo<D, NP>;
+    const float mx = half_max(mx_lane);
+    const bool raise = (mx - c.m) * sl2 > kLag;
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(raise) != 0, 0)) {
+        mfma_settle();  // the O accumulators may still be in flight
+        float m_new = raise ? mx : c.m;
+        float alpha = raise ? __builtin_amdgcn_exp2f((c.m - m_new) * sl2) : 1.0f;
+        c.m = m_new;
+        c.l *= alpha;
 #pragma unroll
         for (int dt = 0; dt < G::ND; ++dt)
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                c.o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb[ks].v, c.o[qt][dt], 0, 0, 0);
+            for (int i = 0; i < 16; ++i) c.o[dt][i] *= alpha;
     }
 }
 
-template <int D, int QT>
-__device__ __forceinline__ void read_frags(const char *lds_stage, int r_perm, int r, int hh,
-                                           bf16x8 (&kf)[Geo<D, QT>::NS], bf16x8 (&vf)[Geo<D, QT>::ND][2]) {
-    using G = Geo<D, QT>;
-    const int ksw = k_swz<D>(r_perm);
+// Exponentials of the current tile (scores s, already masked, maximum already folded into
+// c.m) -> bf16 probabilities pu[k] = (p[2k], p[2k+1]).  When NEXT is set, the QK^T MFMAs of
+// the next tile (fragments kf) are issued one by one between groups of these VALU
+// instructions, so both pipes stay busy from within one wavefront.
+template <int D, int NP, bool NEXT>
+__device__ __forceinline__ void exp_block(WaveCtx<D, NP> &c, const f32x16 &s, const bf16x8 (&kf)[Geo<D, NP>::NS],
+                                          f32x16 &s_next, uint32_t (&pu)[8], float sl2) {
+    using G = Geo<D, NP>;
+    constexpr int EPG = 16 / G::NS;  // score elements handled per MFMA of the next tile
+    const float mc = c.m * sl2;
+    float psum = 0.f;
+    if (NEXT) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_next[i] = 0.f;
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < G::NS; ++ks) {
-        int slot = (2 * ks + hh) ^ ksw;
-        kf[ks] = *reinterpret_cast<const bf16x8 *>(lds_stage + r_perm * (2 * D) + slot * 16);
-    }
-#pragma unroll
-    for (int dt = 0; dt < G::ND; ++dt) {
-        int row = 32 * dt + r;
-        int vsw = (row >> 2) & 3;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            int slot = (2 * ks + hh) ^ vsw;
-            vf[dt][ks] = *reinterpret_cast<const bf16x8 *>(lds_stage + G::K_BYTES + row * 64 + slot * 16);
+        // The empty asm statements pin each result to this point of the program: without
+        // them the compiler sinks the arithmetic to its first use and regroups the MFMAs.
+        if (NEXT) {
+            s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], c.qf[ks], s_next, 0, 0, 0);
+            asm volatile("" : "+v"(s_next));
         }
+        float p[EPG];
+#pragma unroll
+        for (int e = 0; e < EPG; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(s[ks * EPG + e] * sl2 - mc);
+            psum += p[e];
+        }
+#pragma unroll
+        for (int e = 0; e < EPG; e += 2) {
+            pu[(ks * EPG + e) / 2] = pack_bf16(p[e], p[e + 1]);
+            asm volatile("" : "+v"(pu[(ks * EPG + e) / 2]));
+        }
+        asm volatile("" : "+v"(psum));
+        __builtin_amdgcn_sched_barrier(0);
     }
+    c.l += psum;
 }
 
-// Streams n_steps sub-tiles produced by src(t) through the two LDS stages of the workgroup.
-// n_steps and src are uniform over the workgroup, so every wavefront meets every barrier.
-template <int D, int QT, typename SrcFn>
-__device__ __forceinline__ void run_steps(WaveCtx<D, QT> &c, int n_steps, SrcFn src, uint32_t row_stride_bytes,
-                                          char *lds, int wave, int lane, float sl2) {
-    using G = Geo<D, QT>;
-    const int r = lane & 31, hh = lane >> 5;
-    const int r_perm = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
-    if (n_steps <= 0) return;
-    TileSrc cur = src(0);
-    if (G::NW > 1) __syncthreads();  // every wavefront is done with both stages (previous branch)
-    issue_tile<D, QT>(c, cur, row_stride_bytes, lds, wave, lane);
-    for (int t = 0; t < n_steps; ++t) {
-        char *stage = lds + (t & 1) * G::STAGE;
-        bf16x8 kf[G::NS];
-        bf16x8 vf[G::ND][2];
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's copies of step t have landed
-        if (G::NW > 1) __syncthreads();      // ... and the partner's; also: everyone finished reading step t-1
-        read_frags<D, QT>(stage, r_perm, r, hh, kf, vf);
-        TileSrc nxt = cur;
-        if (t + 1 < n_steps) {
-            nxt = src(t + 1);
-            issue_tile<D, QT>(c, nxt, row_stride_bytes, lds + ((t + 1) & 1) * G::STAGE, wave, lane);
+// O^T += V^T P^T for the current tile; when NEXT is set the in-lane maximum of the next
+// tile's scores is folded in between the MFMAs and returned.
+template <int D, int NP, bool NEXT>
+__device__ __forceinline__ float pv_block(WaveCtx<D, NP> &c, const bf16x8 (&vf)[Geo<D, NP>::ND][2],
+                                          const uint32_t (&pu)[8], const f32x16 &s_next) {
+    using G = Geo<D, NP>;
+    constexpr int EPM = 16 / (2 * G::ND);  // score elements folded per PV MFMA
+    float mx = -__builtin_inff();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        union {
+            bf16x8 v;
+            uint32_t u[4];
+        } pb;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pb.u[j] = pu[4 * ks + j];
+#pragma unroll
+        for (int dt = 0; dt < G::ND; ++dt) {
+            c.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb.v, c.o[dt], 0, 0, 0);
+            asm volatile("" : "+v"(c.o[dt]));
+            if (NEXT) {
+                const int e0 = (ks * G::ND + dt) * EPM;
+#pragma unroll
+                for (int e = 0; e < EPM; e += 2) mx = fmaxf(mx, fmaxf(s_next[e0 + e], s_next[e0 + e + 1]));
+                asm volatile("" : "+v"(mx));
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        step_compute<D, QT>(c, kf, vf, cur.j0, cur.need_mask, hh, sl2);
-        cur = nxt;
+    }
+    return mx;
+}
+
+// Non-pipelined step (pair phase): fragments, scores, softmax and PV of one tile in sequence.
+template <int D, int NP>
+__device__ __forceinline__ void step_compute(WaveCtx<D, NP> &c, const char *slot, int lane, float sl2) {
+    using G = Geo<D, NP>;
+    bf16x8 kf[G::NS];
+    bf16x8 vf[G::ND][2];
+    read_k<D, NP>(c, slot, kf);
+    read_v<D, NP>(c, slot, vf);
+    f32x16 s = qk_scores<D, NP>(c, kf);
+    update_max<D, NP>(c, lane_max(s), sl2);
+    uint32_t pu[8];
+    f32x16 unused;
+    exp_block<D, NP, false>(c, s, kf, unused, pu, sl2);
+    pv_block<D, NP, false>(c, vf, pu, unused);
+}
+
+// Shared phase (compressed and window branches): every tile is used by all query blocks of
+// the workgroup.  Tiles go through the ring of NSLOT slots; a slot is refilled as soon as
+// every wavefront is done with it, so up to NSLOT - 1 tiles are in flight ahead of the one
+// being consumed.
+//   src(t)  -> TileSrc of tile t (uniform over the workgroup)
+//   msk(t)  -> (j0, need_mask) of tile t for this wavefront
+// Iteration t: exponentials of tile t interleaved with the QK^T MFMAs of tile t+1, then the
+// PV MFMAs of tile t; K fragments are fetched from LDS two tiles ahead and V fragments one
+// tile ahead.  Every wavefront runs every step: a tile outside a wavefront's own key range
+// is simply fully masked (the step body is kept unconditional on purpose -- a conditional
+// update of the accumulator tuples makes the compiler shuffle them through copies).
+template <int D, int NP, typename SrcFn, typename MaskFn>
+__device__ __forceinline__ void run_shared(WaveCtx<D, NP> &c, int n_steps, SrcFn src, MaskFn msk,
+                                           uint32_t row_stride_bytes, char *lds, int wave, int lane, float sl2) {
+    using G = Geo<D, NP>;
+    constexpr int R = G::NSLOT;
+    if (n_steps <= 0) return;
+    auto slot = [&](int t) { return lds + (t % R) * G::TILE; };
+    __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+    wg_barrier();  // every wavefront is done with the slots (previous phase)
+    for (int t = 0; t < R && t < n_steps; ++t) issue_shared<D, NP>(c, src(t), row_stride_bytes, slot(t), wave, lane);
+    // tiles 0 and 1 must have landed before they are read
+    if (n_steps >= R)
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 2) * G::SH_IPT));
+    else
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    wg_barrier();
+    bf16x8 kf[G::NS];
+    bf16x8 vf[G::ND][2];
+    uint32_t pu[8];
+    int j0;
+    bool need_mask;
+    read_k<D, NP>(c, slot(0), kf);
+    f32x16 s_cur = qk_scores<D, NP>(c, kf);
+    read_v<D, NP>(c, slot(0), vf);
+    read_k<D, NP>(c, slot(1), kf);  // (stale but finite data if there is no tile 1)
+    msk(0, &j0, &need_mask);
+    mfma_settle();  // once per phase: a branch follows the MFMAs that produced s_cur
+    if (need_mask) mask_scores<D, NP>(c, s_cur, j0, lane);
+    update_max<D, NP>(c, lane_max(s_cur), sl2);
+    for (int t = 0; t + 1 < n_steps; ++t) {
+        f32x16 s_next;
+        exp_block<D, NP, true>(c, s_cur, kf, s_next, pu, sl2);  // exp(tile t) || QK^T(tile t+1)
+        msk(t + 1, &j0, &need_mask);
+        if (__builtin_expect(need_mask, 0)) {
+            mfma_settle();
+            mask_scores<D, NP>(c, s_next, j0, lane);
+        }
+        // Before the barrier: this wavefront's LDS reads have returned (the slot of tile t is
+        // about to be refilled) and its share of tile t+2 has landed; tiles t+3 .. t+R-1 may
+        // stay in flight.  Near the end fewer are, so wait for all.
+        if (t + R <= n_steps)
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((R - 3) * G::SH_IPT));
+        else
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        wg_barrier();
+        if (t + R < n_steps) issue_shared<D, NP>(c, src(t + R), row_stride_bytes, slot(t), wave, lane);
+        read_k<D, NP>(c, slot(t + 2), kf);  // (unused stale data on the last iteration)
+        const float mx = pv_block<D, NP, true>(c, vf, pu, s_next);  // PV(tile t) || max(tile t+1)
+        read_v<D, NP>(c, slot(t + 1), vf);
+        update_max<D, NP>(c, mx, sl2);
+        s_cur = s_next;
+    }
+    f32x16 unused;
+    exp_block<D, NP, false>(c, s_cur, kf, unused, pu, sl2);
+    pv_block<D, NP, false>(c, vf, pu, unused);
+}
+
+// Pair phase (selected branch): each query block streams its own routed blocks in 32-key
+// steps; its two wavefronts split the copies.  Two stages of NP slots, copied one step
+// ahead.  A pair whose list is shorter than the longest of the workgroup keeps meeting the
+// barriers (second loop) without computing.
+template <int D, int NP, typename SrcFn>
+__device__ __forceinline__ void run_pairs(WaveCtx<D, NP> &c, int n_steps, int my_steps, SrcFn src, char *lds, int pair,
+                                          int half, int lane, float sl2) {
+    using G = Geo<D, NP>;
+    if (n_steps <= 0) return;
+    __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+    wg_barrier();
+    if (my_steps > 0) issue_pair<D, NP>(c, src(0), lds + pair * G::TILE, half, lane);
+    for (int t = 0; t < my_steps; ++t) {
+        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        wg_barrier();
+        if (t + 1 < my_steps) issue_pair<D, NP>(c, src(t + 1), lds + (((t + 1) & 1) * NP + pair) * G::TILE, half, lane);
+        step_compute<D, NP>(c, lds + ((t & 1) * NP + pair) * G::TILE, lane, sl2);
+    }
+    for (int t = my_steps; t < n_steps; ++t) {
+        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        wg_barrier();
     }
 }
 
@@ -289,197 +488,248 @@ __device__ __forceinline__ void run_steps(WaveCtx<D, QT> &c, int n_steps, SrcFn 
 // gated sum kept in the fp32 scratch tile (written by branch 0, updated by branch 1,
 // consumed by branch 2, which converts to bf16 and stores the output rows through LDS).
 // Optionally stores the un-gated branch output and its log-sum-exp.
-template <int D, int QT>
-__device__ __forceinline__ void finish_branch(WaveCtx<D, QT> &c, const FwdArgs &a, int branch, int qb, int head,
+template <int D, int NP>
+__device__ __forceinline__ void finish_branch(WaveCtx<D, NP> &c, const FwdArgs &a, int branch, int64_t row0, int head,
                                               int wave, int lane, char *lds) {
-    using G = Geo<D, QT>;
+    using G = Geo<D, NP>;
     const int r = lane & 31, hh = lane >> 5;
-    if (branch == 2 && G::NW > 1) __syncthreads();  // the copy stages are about to be reused for the output
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int64_t row0 = (int64_t)qb * 64 + 32 * (wave * QT + qt);
-        const int64_t row = row0 + r;
-        const float l_tot = half_sum(c.l[qt]);
-        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-        const float w = a.gates[(row * a.h + head) * 3 + branch] * inv;
-        if (a.lse != nullptr && hh == 0) {
-            float v = l_tot > 0.f ? c.m[qt] * a.scale + __logf(l_tot) : -__builtin_inff();
-            a.lse[((int64_t)branch * a.n + row) * a.h + head] = v;
-        }
-        if (a.out_branch != nullptr) {
-#pragma unroll
-            for (int dt = 0; dt < G::ND; ++dt) {
-                uint16_t *dst = a.out_branch + (((int64_t)branch * a.n + row) * a.h + head) * D + 32 * dt + 4 * hh;
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    uint2 w2;
-                    w2.x = pack_bf16(c.o[qt][dt][4 * gq + 0] * inv, c.o[qt][dt][4 * gq + 1] * inv);
-                    w2.y = pack_bf16(c.o[qt][dt][4 * gq + 2] * inv, c.o[qt][dt][4 * gq + 3] * inv);
-                    *reinterpret_cast<uint2 *>(dst + 8 * gq) = w2;
-                }
-            }
-        }
-        // scratch tile of this (32-row tile, head): [ND][4][64 lanes] float4
-        f32x4 *gs = reinterpret_cast<f32x4 *>(a.gsum) + (((row0 >> 5) * a.h + head) * (G::ND * 4)) * 64 + lane;
-        char *tr = lds + wave * 32 * G::OUT_ROW;  // output transpose region of this wavefront
+    const int64_t row = row0 + r;
+    const float l_tot = half_sum(c.l);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    const float w = a.gates[(row * a.h + head) * 3 + branch] * inv;
+    if (a.lse != nullptr && hh == 0) {
+        float v = l_tot > 0.f ? c.m * a.scale + __logf(l_tot) : -__builtin_inff();
+        a.lse[((int64_t)branch * a.n + row) * a.h + head] = v;
+    }
+    if (a.out_branch != nullptr) {
 #pragma unroll
         for (int dt = 0; dt < G::ND; ++dt) {
+            uint16_t *dst = a.out_branch + (((int64_t)branch * a.n + row) * a.h + head) * D + 32 * dt + 4 * hh;
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
-                f32x4 v;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) v[j] = w * c.o[qt][dt][4 * gq + j];
-                if (branch > 0) {
-                    f32x4 prev = gs[(dt * 4 + gq) * 64];
-                    v += prev;
-                }
-                if (branch < 2) {
-                    gs[(dt * 4 + gq) * 64] = v;
-                } else {
-                    uint2 w2;
-                    w2.x = pack_bf16(v[0], v[1]);
-                    w2.y = pack_bf16(v[2], v[3]);
-                    *reinterpret_cast<uint2 *>(tr + r * G::OUT_ROW + (32 * dt + 8 * gq + 4 * hh) * 2) = w2;
-                }
+                uint2 w2;
+                w2.x = pack_bf16(c.o[dt][4 * gq + 0] * inv, c.o[dt][4 * gq + 1] * inv);
+                w2.y = pack_bf16(c.o[dt][4 * gq + 2] * inv, c.o[dt][4 * gq + 3] * inv);
+                *reinterpret_cast<uint2 *>(dst + 8 * gq) = w2;
             }
         }
-        if (branch == 2) {
-            // rows of this tile back from LDS as whole 16-byte chunks: 4 (d=128) or 8 (d=64) rows per pass
-            constexpr int CH = D / 8;
-            constexpr int ROWS = 64 / CH;
+    }
+    // scratch tile of this (32-row tile, head): [ND][4][64 lanes] float4
+    f32x4 *gs = reinterpret_cast<f32x4 *>(a.gsum) + (((row0 >> 5) * a.h + head) * (G::ND * 4)) * 64 + lane;
+    char *tr = lds + wave * 32 * G::OUT_ROW;  // output staging region of this wavefront
 #pragma unroll
-            for (int it = 0; it < 32 / ROWS; ++it) {
-                const int rr = it * ROWS + lane / CH, ch = lane % CH;
-                uint4 val = *reinterpret_cast<const uint4 *>(tr + rr * G::OUT_ROW + ch * 16);
-                *reinterpret_cast<uint4 *>(a.out + ((row0 + rr) * a.h + head) * D + ch * 8) = val;
+    for (int dt = 0; dt < G::ND; ++dt) {
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            f32x4 v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = w * c.o[dt][4 * gq + j];
+            if (branch > 0) {
+                f32x4 prev = gs[(dt * 4 + gq) * 64];
+                v += prev;
             }
+            if (branch < 2) {
+                gs[(dt * 4 + gq) * 64] = v;
+            } else {
+                uint2 w2;
+                w2.x = pack_bf16(v[0], v[1]);
+                w2.y = pack_bf16(v[2], v[3]);
+                *reinterpret_cast<uint2 *>(tr + r * G::OUT_ROW + (32 * dt + 8 * gq + 4 * hh) * 2) = w2;
+            }
+        }
+    }
+    if (branch == 2) {
+        // rows of this tile back from LDS as whole 16-byte chunks: 4 (d=128) or 8 (d=64) rows per pass
+        constexpr int CH = D / 8;
+        constexpr int ROWS = 64 / CH;
+#pragma unroll
+        for (int it = 0; it < 32 / ROWS; ++it) {
+            const int rr = it * ROWS + lane / CH, ch = lane % CH;
+            uint4 val = *reinterpret_cast<const uint4 *>(tr + rr * G::OUT_ROW + ch * 16);
+            *reinterpret_cast<uint4 *>(a.out + ((row0 + rr) * a.h + head) * D + ch * 8) = val;
         }
     }
 }
 
-template <int D, int QT>
-__global__ __launch_bounds__((Geo<D, QT>::THREADS), 2) void nsa_forward_kernel(FwdArgs a) {
-    using G = Geo<D, QT>;
+// Window geometry of one query block (all values uniform over its wavefronts).
+struct WinRange {
+    int seg_lo, seg_hi;    // segment of the block
+    int full_lo, full_hi;  // keys inside [full_lo, full_hi) are visible to all 64 queries of the block
+    int st0, st1;          // 32-key tiles [st0, st1) intersect the block's window
+};
+
+__device__ __forceinline__ WinRange window_range(const FwdArgs &a, int qb) {
+    WinRange w;
+    const int q0 = qb * 64;
+    w.seg_lo = 0;
+    w.seg_hi = 0;
+    for (int s = 0; s < a.n_seg; ++s) {
+        int lo = a.seg[s], hi = a.seg[s + 1];
+        if (q0 >= lo && q0 < hi) {
+            w.seg_lo = lo;
+            w.seg_hi = hi;
+        }
+    }
+    const int half = a.window / 2;
+    const int k_start = max(w.seg_lo, q0 - half);
+    const int k_end = min(w.seg_hi, q0 + 63 + half);  // exclusive
+    w.full_lo = max(w.seg_lo, q0 + 63 - half);
+    w.full_hi = min(w.seg_hi, q0 + half);
+    w.st0 = k_start / 32;
+    w.st1 = k_end > k_start ? (k_end - 1) / 32 + 1 : w.st0;
+    return w;
+}
+
+template <int D, int NP>
+__global__ __launch_bounds__((Geo<D, NP>::THREADS), 2) void nsa_forward_kernel(FwdArgs a) {
+    using G = Geo<D, NP>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // XCD-aware numbering: hardware deals consecutive workgroups round-robin to the 8 XCDs
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    if (slot >= a.units_per_xcd) return;
-    const int unit = xcd * a.units_per_xcd + slot;
+    const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
+    if (slot_id >= a.units_per_xcd) return;
+    const int unit = xcd * a.units_per_xcd + slot_id;
     if (unit >= a.units) return;
-    const int head = unit / a.nb;
-    const int qb = unit % a.nb;
+    const int head = unit / a.groups_per_head;
+    const int group = unit % a.groups_per_head;
     const int lane = threadIdx.x & 63;
-    const int wave = G::NW > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : 0;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int pair = wave >> 1, half = wave & 1;
     const int r = lane & 31, hh = lane >> 5;
+    const int qb = group * NP + pair;
+    const bool active = qb < a.nb;  // a trailing group may have fewer than NP query blocks
+    const int64_t row0 = (int64_t)(active ? qb : 0) * 64 + 32 * half;
     const uint32_t row_stride_bytes = (uint32_t)a.h * D * 2;
     const float sl2 = a.scale_log2e;
 
-    WaveCtx<D, QT> c;
-    {
-        constexpr int ROWS_PER_INST = 1024 / (D * 2);
-        constexpr int CHUNKS = D / 8;
+    WaveCtx<D, NP> c;
 #pragma unroll
-        for (int j = 0; j < G::K_INST; ++j) {
-            const int i = wave + G::NW * j;
-            const int row = i * ROWS_PER_INST + lane / CHUNKS;
-            const int chunk = (lane % CHUNKS) ^ k_swz<D>(row);
-            c.krow[j] = row;
-            c.kchunk[j] = chunk;
-            c.koff[j] = (uint32_t)row * row_stride_bytes + (uint32_t)chunk * 16u;
+    for (int j = 0; j < G::SH_K; ++j)
+        k_copy_geometry<D>((wave + G::WAVES * j) % G::K_INST, lane, row_stride_bytes, &c.sh_krow[j], &c.sh_kchunk[j],
+                           &c.sh_koff[j]);
+#pragma unroll
+    for (int j = 0; j < G::PR_K; ++j) {
+        int row, chunk;
+        k_copy_geometry<D>(half + 2 * j, lane, row_stride_bytes, &row, &chunk, &c.pr_koff[j]);
+    }
+    {
+        const int r_perm = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
+        const int ksw = k_swz<D>(r_perm);
+#pragma unroll
+        for (int ks = 0; ks < G::NS; ++ks) c.kf_off[ks] = r_perm * (2 * D) + (((2 * ks + hh) ^ ksw) * 16);
+#pragma unroll
+        for (int dt = 0; dt < G::ND; ++dt) {
+            const int row = 32 * dt + r;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                c.vf_off[dt][ks] = G::K_BYTES + row * 64 + (((2 * ks + hh) ^ ((row >> 2) & 3)) * 16);
         }
     }
+    // A fully masked step may read a slot that no copy has filled yet: make sure it holds
+    // finite values (0 * NaN would poison the accumulators).
+    for (int off = threadIdx.x * 16; off < G::LDS_BYTES; off += G::THREADS * 16)
+        *reinterpret_cast<uint4 *>(lds + off) = make_uint4(0, 0, 0, 0);
+    {
+        // (an inactive pair reads the rows of block 0: finite values, results discarded)
+        const uint16_t *qrow = a.q + ((row0 + r) * a.h + head) * D + 8 * hh;
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const uint16_t *qrow = a.q + (((int64_t)qb * 64 + 32 * (wave * QT + qt) + r) * a.h + head) * D + 8 * hh;
-#pragma unroll
-        for (int ks = 0; ks < G::NS; ++ks) c.qf[qt][ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
+        for (int ks = 0; ks < G::NS; ++ks) c.qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
     }
 
     // ---------------- compressed branch: all NB pooled pairs
     {
-        reset_branch<D, QT>(c);
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            c.lo[qt] = 0;
-            c.hi[qt] = a.nb;
-        }
+        reset_branch<D, NP>(c);
+        c.lo = 0;
+        c.hi = a.nb;
         const int n_steps = (a.nb + 31) / 32;
         auto src = [&](int t) {
             TileSrc s;
             s.k_rows = a.kc + ((int64_t)(32 * t) * a.h + head) * D;
             s.rows_valid = a.nb - 32 * t;
             s.v_t = a.vc_t + (((int64_t)(t >> 1) * a.h + head) * 2 + (t & 1)) * (D * 32);
-            s.j0 = 32 * t;
-            s.need_mask = 32 * t + 32 > a.nb;
             return s;
         };
-        run_steps<D, QT>(c, n_steps, src, row_stride_bytes, lds, wave, lane, sl2);
-        finish_branch<D, QT>(c, a, 0, qb, head, wave, lane, lds);
+        auto msk = [&](int t, int *j0, bool *need) {
+            *j0 = 32 * t;
+            *need = 32 * t + 32 > a.nb;
+        };
+        run_shared<D, NP>(c, n_steps, src, msk, row_stride_bytes, lds, wave, lane, sl2);
+        if (active) finish_branch<D, NP>(c, a, 0, row0, head, wave, lane, lds);
     }
 
     // ---------------- selected branch: every token of the routed blocks
     {
-        reset_branch<D, QT>(c);
-        int my = lane < a.topk ? a.idx[(int64_t)qb * a.topk + lane] : -1;
-        if (my >= a.nb) my = -1;
-        const unsigned long long valid = __ballot(my >= 0);
-        const int n_valid = __popcll(valid);
-        const int rank = __popcll(valid & ((1ull << lane) - 1ull));
-        // compact the valid entries to lanes 0..n_valid-1
-        int packed = __builtin_amdgcn_ds_permute((my >= 0 ? rank : 63) * 4, my);
-        if (n_valid == 64) packed = my;
+        reset_branch<D, NP>(c);
+        c.lo = 0;
+        c.hi = 0;  // (no masking in this branch)
+        int packed = -1, my_valid = 0, max_valid = 0;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int qbp = group * NP + p;
+            int v = (qbp < a.nb && lane < a.topk) ? a.idx[(int64_t)qbp * a.topk + lane] : -1;
+            if (v >= a.nb) v = -1;
+            const unsigned long long valid = __ballot(v >= 0);
+            const int n_valid = __popcll(valid);
+            max_valid = max(max_valid, n_valid);
+            if (p == pair) {
+                // compact the valid entries of this block's row to lanes 0..n_valid-1
+                const int rank = __popcll(valid & ((1ull << lane) - 1ull));
+                packed = __builtin_amdgcn_ds_permute((v >= 0 ? rank : 63) * 4, v);
+                if (n_valid == 64) packed = v;
+                my_valid = n_valid;
+            }
+        }
         auto src = [&](int t) {
             int kb = __builtin_amdgcn_readlane(packed, t >> 1);
             TileSrc s;
             s.k_rows = a.k + (((int64_t)kb * 64 + 32 * (t & 1)) * a.h + head) * D;
             s.rows_valid = 32;
             s.v_t = a.v_t + (((int64_t)kb * a.h + head) * 2 + (t & 1)) * (D * 32);
-            s.j0 = 0;
-            s.need_mask = false;
             return s;
         };
-        run_steps<D, QT>(c, 2 * n_valid, src, row_stride_bytes, lds, wave, lane, sl2);
-        finish_branch<D, QT>(c, a, 1, qb, head, wave, lane, lds);
+        run_pairs<D, NP>(c, 2 * max_valid, 2 * my_valid, src, lds, pair, half, lane, sl2);
+        if (active) finish_branch<D, NP>(c, a, 1, row0, head, wave, lane, lds);
     }
 
     // ---------------- window branch: keys j with -W/2 <= j - i < W/2 inside the segment
     {
-        reset_branch<D, QT>(c);
-        const int q0 = qb * 64;
-        int seg_lo = 0, seg_hi = 0;
-        for (int s = 0; s < a.n_seg; ++s) {
-            int lo = a.seg[s], hi = a.seg[s + 1];
-            if (q0 >= lo && q0 < hi) {
-                seg_lo = lo;
-                seg_hi = hi;
+        reset_branch<D, NP>(c);
+        WinRange mine = window_range(a, active ? qb : 0);
+        int st_min = 0x7fffffff, st_max = 0;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int qbp = group * NP + p;
+            if (qbp < a.nb) {
+                WinRange w = window_range(a, qbp);
+                if (w.st1 > w.st0) {
+                    st_min = min(st_min, w.st0);
+                    st_max = max(st_max, w.st1);
+                }
             }
         }
-        const int half = a.window / 2;
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            int i = q0 + 32 * (wave * QT + qt) + r;
-            c.lo[qt] = max(seg_lo, i - half);
-            c.hi[qt] = min(seg_hi, i + half);
+        {
+            const int half_w = a.window / 2;
+            const int i = (int)row0 + r;
+            c.lo = max(mine.seg_lo, i - half_w);
+            c.hi = min(mine.seg_hi, i + half_w);
         }
-        // tile range of the whole query block (uniform over the workgroup)
-        const int k_start = max(seg_lo, q0 - half);
-        const int k_end = min(seg_hi, q0 + 63 + half);  // exclusive
-        const int full_lo = max(seg_lo, q0 + 63 - half);
-        const int full_hi = min(seg_hi, q0 + half);
-        const int st0 = k_start / 32;
-        const int n_steps = k_end > k_start ? (k_end - 1) / 32 - st0 + 1 : 0;
+        const int n_steps = st_max > st_min ? st_max - st_min : 0;
         auto src = [&](int t) {
-            int st = st0 + t;
+            int st = st_min + t;
             TileSrc s;
             s.k_rows = a.k + ((int64_t)(32 * st) * a.h + head) * D;
             s.rows_valid = 32;
             s.v_t = a.v_t + (((int64_t)(st >> 1) * a.h + head) * 2 + (st & 1)) * (D * 32);
-            s.j0 = 32 * st;
-            s.need_mask = (32 * st < full_lo) || (32 * st + 32 > full_hi);
             return s;
         };
-        run_steps<D, QT>(c, n_steps, src, row_stride_bytes, lds, wave, lane, sl2);
-        finish_branch<D, QT>(c, a, 2, qb, head, wave, lane, lds);
+        auto msk = [&](int t, int *j0, bool *need) {
+            int st = st_min + t;
+            *j0 = 32 * st;
+            *need = (32 * st < mine.full_lo) || (32 * st + 32 > mine.full_hi);  // also true outside [st0, st1)
+        };
+        run_shared<D, NP>(c, n_steps, src, msk, row_stride_bytes, lds, wave, lane, sl2);
+        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        wg_barrier();  // the tile slots are about to be reused for the output rows
+        if (active) finish_branch<D, NP>(c, a, 2, row0, head, wave, lane, lds);
     }
 }
 
@@ -537,11 +787,11 @@ WsLayout ws_layout(const Shape &s) {
     return w;
 }
 
-template <int D, int QT>
+template <int D, int NP>
 lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg, FwdArgs a, const uint16_t *d_v,
                              const uint16_t *d_vc, char *ws, const WsLayout &w, hipStream_t st, hipEvent_t ev_start,
                              hipEvent_t ev_stop) {
-    using G = Geo<D, QT>;
+    using G = Geo<D, NP>;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     hipLaunchKernelGGL(pack_transposed<D>, dim3(s.nb, s.h), dim3(256), 0, st, d_v, (uint16_t *)(ws + w.v_t), s.n, s.h);
     LSRM_HIP_CHECK(hipGetLastError());
@@ -551,10 +801,17 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     a.v_t = (const uint16_t *)(ws + w.v_t);
     a.vc_t = (const uint16_t *)(ws + w.vc_t);
     a.gsum = (float *)(ws + w.gsum);
-    a.units = s.nb * s.h;
+    a.groups_per_head = (s.nb + NP - 1) / NP;
+    a.units = a.groups_per_head * s.h;
     a.units_per_xcd = (a.units + 7) / 8;
+    static bool attr_set = false;
+    if (!attr_set) {
+        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<D, NP>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
+        attr_set = true;
+    }
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
-    hipLaunchKernelGGL((nsa_forward_kernel<D, QT>), dim3(a.units_per_xcd * 8), dim3(G::THREADS), G::LDS_BYTES, st, a);
+    hipLaunchKernelGGL((nsa_forward_kernel<D, NP>), dim3(a.units_per_xcd * 8), dim3(G::THREADS), G::LDS_BYTES, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;
@@ -590,8 +847,8 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.scale_log2e = s.scale * 1.4426950408889634f;
     WsLayout w = ws_layout(s);
     char *ws = reinterpret_cast<char *>(d_ws);
-    if (s.d == 64) return launch_forward_d<64, 2>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
-    return launch_forward_d<128, 1>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
+    if (s.d == 64) return launch_forward_d<64, 4>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
+    return launch_forward_d<128, 4>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
 }
 
 }  // namespace lsrm
