@@ -24,9 +24,9 @@
 //   O^T += V^T P^T     A = 32 channels x 16 keys from a pre-transposed copy of V.
 //   A wavefront issues in order and the matrix pipe takes one MFMA at a time, so MFMA and
 //   VALU work only overlap if they alternate in program order.  The shared phases are
-//   therefore software pipelined by hand: the QK^T MFMAs of tile t+1 are interleaved, one
-//   by one, with the exponentials of tile t, and the PV MFMAs of tile t with the row max
-//   of tile t+1 (scheduling barriers keep the compiler from regrouping them).
+//   therefore software pipelined by hand over three tiles: the QK^T MFMAs of tile t+1 and
+//   the PV MFMAs of tile t-1 are issued alternately, each followed by its share of the
+//   exponentials of tile t (scheduling barriers keep the compiler from regrouping them).
 //
 // Data movement
 //   K rows come straight from the caller's [N, H, d] tensor, V from a packed transposed
@@ -133,8 +133,8 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 // after issue, and the hardware does not interlock that dependency: the compiler pads
 // with s_nop, but it has been seen to misplace the padding when a branch separates the
 // MFMA from its first VALU reader.  Every such (rare) path starts with this explicit
-// settle instead; 32 wait states cover the longest MFMA used here.
-__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+// settle instead; 24 wait states cover the 8-pass MFMA used here.
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
 
 struct TileSrc {
     const uint16_t *k_rows;  // row 0 of the 32-key tile, this head
@@ -284,8 +284,11 @@ __device__ __forceinline__ float lane_max(const f32x16 &s) {
 // appears; a fully masked tile (maximum -inf) never does.
 constexpr float kLag = 8.0f;
 
+// `pending` (nullable) are probabilities that were computed against the old maximum but not
+// yet accumulated into O (the software pipeline keeps one tile of them): they are rescaled
+// together with O and l.
 template <int D, int NP>
-__device__ __forceinline__ void update_max(WaveCtx<D, NP> &c, float mx_lane, float sl2) {
+__device__ __forceinline__ void update_max(WaveCtx<D, NP> &c, float mx_lane, float sl2, uint32_t *pending) {
     using G = Geo<D, NP>;
     const float mx = half_max(mx_lane);
     const bool raise = (mx - c.m) * sl2 > kLag;
@@ -299,81 +302,117 @@ __device__ __forceinline__ void update_max(WaveCtx<D, NP> &c, float mx_lane, flo
         for (int dt = 0; dt < G::ND; ++dt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) c.o[dt][i] *= alpha;
+        if (pending != nullptr) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                float lo = __uint_as_float(pending[k] << 16), hi = __uint_as_float(pending[k] & 0xffff0000u);
+                pending[k] = pack_bf16(lo * alpha, hi * alpha);
+            }
+        }
     }
 }
 
-// Exponentials of the current tile (scores s, already masked, maximum already folded into
-// c.m) -> bf16 probabilities pu[k] = (p[2k], p[2k+1]).  When NEXT is set, the QK^T MFMAs of
-// the next tile (fragments kf) are issued one by one between groups of these VALU
-// instructions, so both pipes stay busy from within one wavefront.
-template <int D, int NP, bool NEXT>
-__device__ __forceinline__ void exp_block(WaveCtx<D, NP> &c, const f32x16 &s, const bf16x8 (&kf)[Geo<D, NP>::NS],
-                                          f32x16 &s_next, uint32_t (&pu)[8], float sl2) {
+// The MFMA block of one step.  Up to three tiles are in flight in a wavefront:
+//   QK   the QK^T MFMAs of the tile whose scores are produced now        (-> s_next)
+//   exp  the exponentials of the tile whose scores `s` are complete, already masked and
+//        folded into the running maximum                                  (-> pu, c.l)
+//   PV   the V^T P^T MFMAs of the tile before that (probabilities pu_prev, fragments vf)
+// A wavefront issues in order and the matrix pipe runs one MFMA at a time, so MFMA and VALU
+// work only overlap when they alternate in program order: the QK and PV MFMAs are issued
+// alternately and every MFMA is followed by its share of the exponentials (one v_exp, its
+// fma and sum, half a bf16 pack at d = 128) -- about as many VALU cycles as the MFMA takes.
+// The empty asm statements pin each result to its place in the program (the compiler
+// otherwise sinks the arithmetic to its first use) and the scheduling barriers keep the
+// machine scheduler from regrouping; neither emits an instruction.
+// pu[k] = bf16 pair (p[2k], p[2k+1]): pu[0..3] / pu[4..7] are the B operands of the two
+// 16-key slabs of the PV contraction.
+// When k_refill / v_refill are given, every operand fragment is reloaded from that tile slot
+// right after the MFMA that consumed it (the K fragments of the tile after next, the V
+// fragments of the next PV tile): the LDS reads of the following step are spread under this
+// step's MFMAs instead of forming a burst of all wavefronts after the barrier.
+template <int D, int NP, bool QK, bool PV>
+__device__ __forceinline__ void mfma_block(WaveCtx<D, NP> &c, const f32x16 &s, bf16x8 (&kf)[Geo<D, NP>::NS],
+                                           f32x16 &s_next, bf16x8 (&vf)[Geo<D, NP>::ND][2],
+                                           const uint32_t (&pu_prev)[8], uint32_t (&pu)[8], float sl2,
+                                           const char *k_refill = nullptr, const char *v_refill = nullptr) {
     using G = Geo<D, NP>;
-    constexpr int EPG = 16 / G::NS;  // score elements handled per MFMA of the next tile
+    constexpr int NQ = QK ? G::NS : 0, NPV = PV ? 2 * G::ND : 0, NG = NQ + NPV;
     const float mc = c.m * sl2;
     float psum = 0.f;
-    if (NEXT) {
+    float p[16];
+    if constexpr (NG == 0) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s_next[i] = 0.f;
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int ks = 0; ks < G::NS; ++ks) {
-        // The empty asm statements pin each result to this point of the program: without
-        // them the compiler sinks the arithmetic to its first use and regroups the MFMAs.
-        if (NEXT) {
-            s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], c.qf[ks], s_next, 0, 0, 0);
-            asm volatile("" : "+v"(s_next));
-        }
-        float p[EPG];
-#pragma unroll
-        for (int e = 0; e < EPG; ++e) {
-            p[e] = __builtin_amdgcn_exp2f(s[ks * EPG + e] * sl2 - mc);
+        for (int e = 0; e < 16; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(s[e] * sl2 - mc);
             psum += p[e];
         }
 #pragma unroll
-        for (int e = 0; e < EPG; e += 2) {
-            pu[(ks * EPG + e) / 2] = pack_bf16(p[e], p[e + 1]);
-            asm volatile("" : "+v"(pu[(ks * EPG + e) / 2]));
+        for (int k = 0; k < 8; ++k) pu[k] = pack_bf16(p[2 * k], p[2 * k + 1]);
+    } else {
+        constexpr int E = 16 / NG;  // exponentials per MFMA
+        static_assert(E >= 1 && E * NG == 16, "");
+        union {
+            bf16x8 v;
+            uint32_t u[4];
+        } pb[2];
+        if (PV) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) pb[k / 4].u[k % 4] = pu_prev[k];
         }
-        asm volatile("" : "+v"(psum));
+        if (QK) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s_next[i] = 0.f;
+        }
         __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const bool do_qk = QK && (!PV || (g % 2) == 0);
+            if (do_qk) {
+                const int ks = PV ? g / 2 : g;
+                s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], c.qf[ks], s_next, 0, 0, 0);
+                asm volatile("" : "+v"(s_next));
+                if (k_refill != nullptr) kf[ks] = *reinterpret_cast<const bf16x8 *>(k_refill + c.kf_off[ks]);
+            } else {
+                const int i = QK ? g / 2 : g;
+                const int ks = i / G::ND, dt = i % G::ND;
+                c.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb[ks].v, c.o[dt], 0, 0, 0);
+                asm volatile("" : "+v"(c.o[dt]));
+                if (v_refill != nullptr) vf[dt][ks] = *reinterpret_cast<const bf16x8 *>(v_refill + c.vf_off[dt][ks]);
+            }
+#pragma unroll
+            for (int e = g * E; e < (g + 1) * E; ++e) {
+                p[e] = __builtin_amdgcn_exp2f(s[e] * sl2 - mc);
+                psum += p[e];
+                if (e & 1) {
+                    pu[e / 2] = pack_bf16(p[e - 1], p[e]);
+                    asm volatile("" : "+v"(pu[e / 2]));
+                } else {
+                    asm volatile("" : "+v"(p[e]));
+                }
+            }
+            asm volatile("" : "+v"(psum));
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     c.l += psum;
 }
 
-// O^T += V^T P^T for the current tile; when NEXT is set the in-lane maximum of the next
-// tile's scores is folded in between the MFMAs and returned.
-template <int D, int NP, bool NEXT>
-__device__ __forceinline__ float pv_block(WaveCtx<D, NP> &c, const bf16x8 (&vf)[Geo<D, NP>::ND][2],
-                                          const uint32_t (&pu)[8], const f32x16 &s_next) {
+// Plain O^T += V^T P^T of one tile (pipeline drain, pair phase).
+template <int D, int NP>
+__device__ __forceinline__ void pv_plain(WaveCtx<D, NP> &c, const bf16x8 (&vf)[Geo<D, NP>::ND][2],
+                                         const uint32_t (&pu)[8]) {
     using G = Geo<D, NP>;
-    constexpr int EPM = 16 / (2 * G::ND);  // score elements folded per PV MFMA
-    float mx = -__builtin_inff();
-    __builtin_amdgcn_sched_barrier(0);
+    union {
+        bf16x8 v;
+        uint32_t u[4];
+    } pb[2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        union {
-            bf16x8 v;
-            uint32_t u[4];
-        } pb;
+    for (int k = 0; k < 8; ++k) pb[k / 4].u[k % 4] = pu[k];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) pb.u[j] = pu[4 * ks + j];
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt) {
-            c.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb.v, c.o[dt], 0, 0, 0);
-            asm volatile("" : "+v"(c.o[dt]));
-            if (NEXT) {
-                const int e0 = (ks * G::ND + dt) * EPM;
-#pragma unroll
-                for (int e = 0; e < EPM; e += 2) mx = fmaxf(mx, fmaxf(s_next[e0 + e], s_next[e0 + e + 1]));
-                asm volatile("" : "+v"(mx));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    return mx;
+        for (int dt = 0; dt < G::ND; ++dt)
+            c.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb[ks].v, c.o[dt], 0, 0, 0);
 }
 
 // Non-pipelined step (pair phase): fragments, scores, softmax and PV of one tile in sequence.
@@ -385,79 +424,95 @@ __device__ __forceinline__ void step_compute(WaveCtx<D, NP> &c, const char *slot
     read_k<D, NP>(c, slot, kf);
     read_v<D, NP>(c, slot, vf);
     f32x16 s = qk_scores<D, NP>(c, kf);
-    update_max<D, NP>(c, lane_max(s), sl2);
+    update_max<D, NP>(c, lane_max(s), sl2, nullptr);
     uint32_t pu[8];
     f32x16 unused;
-    exp_block<D, NP, false>(c, s, kf, unused, pu, sl2);
-    pv_block<D, NP, false>(c, vf, pu, unused);
+    mfma_block<D, NP, false, false>(c, s, kf, unused, vf, pu, pu, sl2);
+    pv_plain<D, NP>(c, vf, pu);
 }
 
 // Shared phase (compressed and window branches): every tile is used by all query blocks of
 // the workgroup.  Tiles go through the ring of NSLOT slots; a slot is refilled as soon as
-// every wavefront is done with it, so up to NSLOT - 1 tiles are in flight ahead of the one
-// being consumed.
+// every wavefront is done with it.
 //   src(t)  -> TileSrc of tile t (uniform over the workgroup)
 //   msk(t)  -> (j0, need_mask) of tile t for this wavefront
-// Iteration t: exponentials of tile t interleaved with the QK^T MFMAs of tile t+1, then the
-// PV MFMAs of tile t; K fragments are fetched from LDS two tiles ahead and V fragments one
-// tile ahead.  Every wavefront runs every step: a tile outside a wavefront's own key range
-// is simply fully masked (the step body is kept unconditional on purpose -- a conditional
+// Step t runs mfma_block with QK of tile t+1, the exponentials of tile t and PV of tile t-1,
+// reloading its operand registers on the fly with the K fragments of tile t+2 and the V
+// fragments of tile t.  After the block (one barrier per step) the slot of tile t-1 is
+// refilled with tile t-1+NSLOT and the maximum of tile t+1 is folded into the running
+// maximum.  Every wavefront runs every step: a tile outside a wavefront's own key range is
+// simply fully masked (the step body is kept unconditional on purpose -- a conditional
 // update of the accumulator tuples makes the compiler shuffle them through copies).
 template <int D, int NP, typename SrcFn, typename MaskFn>
 __device__ __forceinline__ void run_shared(WaveCtx<D, NP> &c, int n_steps, SrcFn src, MaskFn msk,
                                            uint32_t row_stride_bytes, char *lds, int wave, int lane, float sl2) {
     using G = Geo<D, NP>;
     constexpr int R = G::NSLOT;
+    static_assert(R >= 6, "the ring must hold the three tiles being read plus tiles in flight");
     if (n_steps <= 0) return;
     auto slot = [&](int t) { return lds + (t % R) * G::TILE; };
     __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
     wg_barrier();  // every wavefront is done with the slots (previous phase)
     for (int t = 0; t < R && t < n_steps; ++t) issue_shared<D, NP>(c, src(t), row_stride_bytes, slot(t), wave, lane);
-    // tiles 0 and 1 must have landed before they are read
+    // tiles 0, 1 and 2 must have landed before the first block reads them
     if (n_steps >= R)
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 2) * G::SH_IPT));
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 3) * G::SH_IPT));
     else
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     wg_barrier();
     bf16x8 kf[G::NS];
     bf16x8 vf[G::ND][2];
-    uint32_t pu[8];
+    uint32_t pu[8], pu_prev[8];
+    f32x16 s_cur, s_next;
     int j0;
     bool need_mask;
     read_k<D, NP>(c, slot(0), kf);
-    f32x16 s_cur = qk_scores<D, NP>(c, kf);
-    read_v<D, NP>(c, slot(0), vf);
+    s_cur = qk_scores<D, NP>(c, kf);
     read_k<D, NP>(c, slot(1), kf);  // (stale but finite data if there is no tile 1)
+    read_v<D, NP>(c, slot(0), vf);
     msk(0, &j0, &need_mask);
-    mfma_settle();  // once per phase: a branch follows the MFMAs that produced s_cur
+    mfma_settle();  // a branch follows the MFMAs that produced s_cur
     if (need_mask) mask_scores<D, NP>(c, s_cur, j0, lane);
-    update_max<D, NP>(c, lane_max(s_cur), sl2);
-    for (int t = 0; t + 1 < n_steps; ++t) {
-        f32x16 s_next;
-        exp_block<D, NP, true>(c, s_cur, kf, s_next, pu, sl2);  // exp(tile t) || QK^T(tile t+1)
-        msk(t + 1, &j0, &need_mask);
-        if (__builtin_expect(need_mask, 0)) {
-            mfma_settle();
-            mask_scores<D, NP>(c, s_next, j0, lane);
-        }
-        // Before the barrier: this wavefront's LDS reads have returned (the slot of tile t is
-        // about to be refilled) and its share of tile t+2 has landed; tiles t+3 .. t+R-1 may
-        // stay in flight.  Near the end fewer are, so wait for all.
-        if (t + R <= n_steps)
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((R - 3) * G::SH_IPT));
+    update_max<D, NP>(c, lane_max(s_cur), sl2, nullptr);
+
+    // What follows every MFMA block but the last: sync, refill a slot, fold the maximum.
+    auto after_block = [&](int t) {
+        // Before the barrier this wavefront's LDS reads have returned and its share of tile
+        // t+3 (read during the next block) has landed; later tiles may stay in flight.
+        // Copies issued so far: tiles 0 .. t-2+R.  Near the end fewer are outstanding: wait for all.
+        if (t - 2 + R < n_steps && t >= 1)
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((R - 5) * G::SH_IPT));
+        else if (t == 0 && n_steps >= R)
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((R - 4) * G::SH_IPT));
         else
             __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
-        wg_barrier();
-        if (t + R < n_steps) issue_shared<D, NP>(c, src(t + R), row_stride_bytes, slot(t), wave, lane);
-        read_k<D, NP>(c, slot(t + 2), kf);  // (unused stale data on the last iteration)
-        const float mx = pv_block<D, NP, true>(c, vf, pu, s_next);  // PV(tile t) || max(tile t+1)
-        read_v<D, NP>(c, slot(t + 1), vf);
-        update_max<D, NP>(c, mx, sl2);
+        wg_barrier();  // tile t+3 has landed for everyone; everyone has fetched the fragments of tile t-1
+        if (t >= 1 && t - 1 + R < n_steps)
+            issue_shared<D, NP>(c, src(t - 1 + R), row_stride_bytes, slot(t - 1), wave, lane);
+        msk(t + 1, &j0, &need_mask);
+        mfma_settle();  // s_next and O come from the MFMAs just issued; branches follow
+        if (__builtin_expect(need_mask, 0)) mask_scores<D, NP>(c, s_next, j0, lane);
+        update_max<D, NP>(c, lane_max(s_next), sl2, pu);
         s_cur = s_next;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) pu_prev[k] = pu[k];
+    };
+
+    if (n_steps >= 2) {
+        // QK(1) || exp(0); K fragments of tile 2 fetched on the fly (V of tile 0 is already in vf)
+        mfma_block<D, NP, true, false>(c, s_cur, kf, s_next, vf, pu_prev, pu, sl2, slot(2), nullptr);
+        after_block(0);
+        for (int t = 1; t + 1 < n_steps; ++t) {
+            // QK(t+1) || exp(t) || PV(t-1); fetches K(t+2) and V(t)  (stale slots past the end: unused)
+            mfma_block<D, NP, true, true>(c, s_cur, kf, s_next, vf, pu_prev, pu, sl2, slot(t + 2), slot(t));
+            after_block(t);
+        }
+        // exp(n-1) || PV(n-2); fetches V(n-1) for the drain
+        mfma_block<D, NP, false, true>(c, s_cur, kf, s_next, vf, pu_prev, pu, sl2, nullptr, slot(n_steps - 1));
+    } else {
+        mfma_block<D, NP, false, false>(c, s_cur, kf, s_next, vf, pu_prev, pu, sl2);
     }
-    f32x16 unused;
-    exp_block<D, NP, false>(c, s_cur, kf, unused, pu, sl2);
-    pv_block<D, NP, false>(c, vf, pu, unused);
+    pv_plain<D, NP>(c, vf, pu);  // drain: PV of the last tile
 }
 
 // Pair phase (selected branch): each query block streams its own routed blocks in 32-key
