@@ -43,10 +43,13 @@
 #include <type_traits>
 
 #ifndef LSRM_QT64
-#define LSRM_QT64 1
+#define LSRM_QT64 1  // (two row tiles per wavefront were measured slower at d = 64 and do not fit the registers at d = 128)
 #endif
 #ifndef LSRM_QT128
 #define LSRM_QT128 1
+#endif
+#ifndef LSRM_PINGPONG
+#define LSRM_PINGPONG 1
 #endif
 #ifndef LSRM_PAR64
 #define LSRM_PAR64 1
@@ -71,7 +74,8 @@ constexpr float kMinusHuge = -1.0e30f;  // initial running maximum: finite, so n
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
 struct FwdArgs {
-    const uint16_t *q, *k, *v_t, *kc, *vc_t;  // v_t / vc_t: packed transposed copies
+    const uint16_t *q;
+    const char *kv, *kvc;  // packed tile images of (k, v) and of the pooled (kc, vc)
     const int32_t *idx;
     const float *gates;
     int32_t seg[kMaxSeg + 1];  // window segment offsets (tokens)
@@ -81,7 +85,7 @@ struct FwdArgs {
     float *gsum;  // scratch: running gated sum, fragment order
     int64_t n;
     int nb, h, topk, window, n_seg;
-    int units, units_per_xcd, groups_per_head;
+    int groups_per_head, groups_per_xcd;  // query-block groups of one head, and the share of one XCD
     float scale_log2e, scale;
 };
 
@@ -103,26 +107,17 @@ struct Geo {
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int WAVES_PER_SIMD = WAVES / 4;
     static constexpr int NSLOT = 2 * NP;        // tile slots in LDS
-    static constexpr int K_INST = K_BYTES / 1024;  // 1 KB copy instructions per tile
-    static constexpr int V_INST = V_BYTES / 1024;
-    static constexpr int SH_IPT = (K_INST + V_INST) / WAVES;  // shared phases: copy instructions per wavefront and tile
-    static constexpr int SH_K = K_INST % WAVES == 0 ? K_INST / WAVES : 1;  // of which key instructions (at most)
-    static constexpr int PR_K = K_INST / NW;    // selected phase: a wavefront copies its share of its block's tile
-    static constexpr int PR_V = V_INST / NW;
+    static constexpr int T_INST = TILE / 1024;  // 1 KB copy instructions per tile
+    static constexpr int SH_IPT = T_INST / WAVES;  // shared phases: copy instructions per wavefront and tile
+    static constexpr int OWN_IPT = T_INST / NW;    // selected phase: a wavefront copies its share of its block's tile
     static constexpr int KQ = NS < 4 ? NS : 4;  // operand fragments kept in registers (rolling queues)
     static constexpr int VQ = 2 * ND < 4 ? 2 * ND : 4;
     static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output staging (bytes)
     static constexpr int LDS_BYTES = NSLOT * TILE;
     static_assert(QT == 1 || QT == 2, "");
     static_assert(WAVES % 4 == 0 && WAVES * ROWS * OUT_ROW <= LDS_BYTES, "output staging must fit in the tile slots");
-    static_assert(SH_IPT >= 1 && (K_INST + V_INST) % WAVES == 0 && NSLOT >= 6, "");
+    static_assert(SH_IPT >= 1 && T_INST % WAVES == 0 && NSLOT >= 7, "");
 };
-
-// swizzle of the 16-byte chunk index inside a K row held in LDS
-template <int D>
-__device__ __forceinline__ int k_swz(int row) {
-    return D == 128 ? (row & 15) : ((row >> 1) & 7);
-}
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     bf16x2 p;
@@ -159,96 +154,44 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 // settle instead; 24 wait states cover the 8-pass MFMA used here.
 __device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
 
-struct TileSrc {
-    const uint16_t *k_rows;  // row 0 of the 32-key tile, this head
-    int rows_valid;          // rows >= rows_valid are clamped (their scores get masked)
-    const uint16_t *v_t;     // packed transposed V tile, contiguous V_BYTES
-};
-
 template <class G>
 struct WaveCtx {
     bf16x8 qf[G::QT][G::NS];
     f32x16 o[G::QT][G::ND];
     float m[G::QT], l[G::QT];
     int lo[G::QT], hi[G::QT];   // valid key range of this lane's queries in mask coordinates
-    uint32_t kf_off[G::NS];     // per-lane LDS byte offsets (inside a tile slot) of the K and V^T fragments
-    uint32_t vf_off[G::ND][2];
+    uint32_t lane16;            // lane * 16: byte offset of this lane inside any 1 KB fragment or copy instruction
 };
 
-template <int D>
-__device__ __forceinline__ void k_copy_geometry(int inst, int lane, uint32_t row_stride_bytes, int *row, int *chunk,
-                                                uint32_t *off) {
-    constexpr int ROWS_PER_INST = 1024 / (D * 2);
-    constexpr int CHUNKS = D / 8;
-    *row = inst * ROWS_PER_INST + lane / CHUNKS;
-    *chunk = (lane % CHUNKS) ^ k_swz<D>(*row);
-    *off = (uint32_t)(*row) * row_stride_bytes + (uint32_t)(*chunk) * 16u;
-}
+// A tile (32 keys of one head) is stored in global memory as the exact image of its LDS slot:
+// K_BYTES of K fragments, then V_BYTES of V^T fragments, each fragment 64 lanes x 16 bytes in
+// the order the MFMA A operand wants them.  A copy instruction therefore moves 1 KB that is
+// contiguous on both sides, and a fragment read is one ds_read_b128 at (slot + lane * 16) plus
+// an immediate offset: conflict free, no per-fragment address registers or arithmetic.
+//   K fragment ks (hh = lane bit 5, r = lane & 31): key perm(r), channels 16 ks + 8 hh + 0..7,
+//     perm = bits 2 and 3 of r swapped (makes the S^T accumulator the B operand of the PV MFMA);
+//   V^T fragment f = ks2 * ND + dt: channel 32 dt + r, keys 16 ks2 + 8 hh + 0..7.
+// (Gathering the K fragments straight from the caller's [N, H, d] tensor instead -- every copy
+// instruction touching 32 rows -- was measured: the attention kernel lost more than the packing
+// pass costs.)
 
-// Shared phases: the wavefronts of the workgroup split the K_INST + V_INST copy instructions
-// of one tile evenly (SH_IPT each).
-// Per-lane source geometry of a wavefront's K copy instructions in the shared phases.
+// Shared phases: the wavefronts of the workgroup split the T_INST copy instructions of a tile.
 template <class G>
-struct SharedCopy {
-    uint32_t koff[G::SH_K];
-    int krow[G::SH_K], kchunk[G::SH_K];
-    __device__ __forceinline__ void init(int wave, int lane, uint32_t row_stride_bytes) {
+__device__ __forceinline__ void issue_shared(const WaveCtx<G> &c, const char *tile, char *slot, int wave) {
 #pragma unroll
-        for (int j = 0; j < G::SH_K; ++j)
-            k_copy_geometry<G::D>((wave + G::WAVES * j) % G::K_INST, lane, row_stride_bytes, &krow[j], &kchunk[j],
-                                  &koff[j]);
-    }
-};
-
-template <class G>
-__device__ __forceinline__ void issue_shared(const SharedCopy<G> &c, const TileSrc &t, uint32_t row_stride_bytes,
-                                             char *slot, int wave, int lane) {
-    const char *kbase = reinterpret_cast<const char *>(t.k_rows);
-    const char *vbase = reinterpret_cast<const char *>(t.v_t);
-    auto copy_k = [&](int j, int inst) {
-        uint32_t off = c.koff[j];
-        if (__builtin_expect(t.rows_valid < 32, 0)) {
-            const int srow = c.krow[j] < t.rows_valid ? c.krow[j] : t.rows_valid - 1;
-            off = (uint32_t)srow * row_stride_bytes + (uint32_t)c.kchunk[j] * 16u;
-        }
-        __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + off), LDS_PTR(slot + inst * 1024), 16, 0, 0);
-    };
-    auto copy_v = [&](int inst) {
-        __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + inst * 1024 + (uint32_t)lane * 16u),
-                                         LDS_PTR(slot + G::K_BYTES + inst * 1024), 16, 0, 0);
-    };
-    if constexpr (G::K_INST % G::WAVES == 0) {
-        // every wavefront copies K_INST / WAVES key instructions and as many value instructions
-#pragma unroll
-        for (int j = 0; j < G::SH_K; ++j) copy_k(j, wave + G::WAVES * j);
-#pragma unroll
-        for (int j = 0; j < G::V_INST / G::WAVES; ++j) copy_v(wave + G::WAVES * j);
-    } else {
-        // fewer key instructions than wavefronts: the first K_INST wavefronts copy keys, the rest values
-        static_assert(G::K_INST % G::WAVES == 0 || (G::SH_IPT == 1 && G::K_INST + G::V_INST == G::WAVES), "");
-        if (wave < G::K_INST)
-            copy_k(0, wave);
-        else
-            copy_v(wave - G::K_INST);
+    for (int j = 0; j < G::SH_IPT; ++j) {
+        const int i = wave + G::WAVES * j;
+        __builtin_amdgcn_global_load_lds(GLB_PTR(tile + i * 1024 + c.lane16), LDS_PTR(slot + i * 1024), 16, 0, 0);
     }
 }
 
 // Selected phase: the NW wavefronts of a query block split the copies of their own tile.
 template <class G>
-__device__ __forceinline__ void issue_own(const uint32_t (&koff)[G::PR_K], const TileSrc &t, char *slot, int sub,
-                                          int lane) {
-    const char *kbase = reinterpret_cast<const char *>(t.k_rows);
-    const char *vbase = reinterpret_cast<const char *>(t.v_t);
+__device__ __forceinline__ void issue_own(const WaveCtx<G> &c, const char *tile, char *slot, int sub) {
 #pragma unroll
-    for (int j = 0; j < G::PR_K; ++j) {
+    for (int j = 0; j < G::OWN_IPT; ++j) {
         const int i = sub + G::NW * j;
-        __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + koff[j]), LDS_PTR(slot + i * 1024), 16, 0, 0);
-    }
-#pragma unroll
-    for (int j = 0; j < G::PR_V; ++j) {
-        const int i = sub + G::NW * j;
-        __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + i * 1024 + (uint32_t)lane * 16u),
-                                         LDS_PTR(slot + G::K_BYTES + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLB_PTR(tile + i * 1024 + c.lane16), LDS_PTR(slot + i * 1024), 16, 0, 0);
     }
 }
 
@@ -269,14 +212,15 @@ __device__ __forceinline__ void reset_branch(WaveCtx<G> &c) {
 template <class G>
 __device__ __forceinline__ void read_k(const WaveCtx<G> &c, const char *slot, bf16x8 (&kf)[G::NS]) {
 #pragma unroll
-    for (int ks = 0; ks < G::NS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(slot + c.kf_off[ks]);
+    for (int ks = 0; ks < G::NS; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(slot + c.lane16 + ks * 1024);
 }
 template <class G>
 __device__ __forceinline__ void read_v(const WaveCtx<G> &c, const char *slot, bf16x8 (&vf)[G::ND][2]) {
 #pragma unroll
     for (int dt = 0; dt < G::ND; ++dt)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = *reinterpret_cast<const bf16x8 *>(slot + c.vf_off[dt][ks]);
+        for (int ks = 0; ks < 2; ++ks)
+            vf[dt][ks] = *reinterpret_cast<const bf16x8 *>(slot + c.lane16 + G::K_BYTES + (ks * G::ND + dt) * 1024);
 }
 
 // S^T = K Q^T for 32 keys x the 32 queries of row tile qt
@@ -369,7 +313,7 @@ union BFrag {
 // The A operands come from two rolling queues of LDS fragments (kq: K rows, vq: V^T rows):
 // the MFMA that consumes fragment i is followed by the ds_read of fragment i + queue depth
 // of the same stream, which continues into the next tile (k_nxt / v_nxt), so the queues
-// enter the next block already primed.  LDS reads are thereby spread under the MFMAs, and
+// enter the next block already primed.  k_cur .. v_nxt are per-lane addresses: slot + lane * 16.  LDS reads are thereby spread under the MFMAs, and
 // only a few fragments are live at a time.
 template <class G, bool QK, bool PV>
 __device__ __forceinline__ void mfma_block(WaveCtx<G> &c, const f32x16 (&s)[G::QT], bf16x8 (&kq)[G::KQ],
@@ -422,7 +366,7 @@ __device__ __forceinline__ void mfma_block(WaveCtx<G> &c, const f32x16 (&s)[G::Q
                 if (qt == QT - 1) {
                     const int nf = ks + G::KQ;
                     kq[ks % G::KQ] =
-                        *reinterpret_cast<const bf16x8 *>((nf < G::NS ? k_cur : k_nxt) + c.kf_off[nf % G::NS]);
+                        *reinterpret_cast<const bf16x8 *>((nf < G::NS ? k_cur : k_nxt) + (nf % G::NS) * 1024);
                 }
             } else {
                 const int i = QK ? g / 2 : g;
@@ -433,7 +377,7 @@ __device__ __forceinline__ void mfma_block(WaveCtx<G> &c, const f32x16 (&s)[G::Q
                 if (qt == QT - 1) {
                     const int nf = (f + G::VQ) % (2 * G::ND);
                     vq[f % G::VQ] = *reinterpret_cast<const bf16x8 *>((f + G::VQ < 2 * G::ND ? v_cur : v_nxt) +
-                                                                      c.vf_off[nf % G::ND][nf / G::ND]);
+                                                                      G::K_BYTES + nf * 1024);
                 }
             }
 #pragma unroll
@@ -473,68 +417,80 @@ __device__ __forceinline__ void pv_drain(WaveCtx<G> &c, bf16x8 (&vq)[G::VQ], con
             c.o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[f % G::VQ], pb[qt][ks].v, c.o[qt][dt], 0, 0, 0);
         if (f + G::VQ < 2 * G::ND) {
             const int nf = f + G::VQ;
-            vq[f % G::VQ] = *reinterpret_cast<const bf16x8 *>(v_cur + c.vf_off[nf % G::ND][nf / G::ND]);
+            vq[f % G::VQ] = *reinterpret_cast<const bf16x8 *>(v_cur + G::K_BYTES + nf * 1024);
         }
     }
 }
 
-// Exponentials of the scores of one row tile against its running maximum -> bf16 pairs.
-template <class G>
-__device__ __forceinline__ void exp_tile(WaveCtx<G> &c, int qt, const f32x16 &s, uint32_t (&pu)[8], float sl2) {
-    const float mc = c.m[qt] * sl2;
+// Selected phase, two wavefronts per query block: the two halves of a pipelined step.
+// First half: the QK^T MFMAs of the next tile (fragments kf) with the exponentials of the
+// current tile (scores s, already folded into the running maximum) in their shadow.
+template <class G, bool QK>
+__device__ __forceinline__ void own_qk_exp(WaveCtx<G> &c, const f32x16 &s, const bf16x8 (&kf)[G::NS], f32x16 &s_next,
+                                           uint32_t (&pu)[8], float sl2) {
+    static_assert(G::QT == 1, "");
+    const float mc = c.m[0] * sl2;
     float psum = 0.f, p[16];
+    if constexpr (!QK) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(s[e] * sl2 - mc);
-        psum += p[e];
+        for (int e = 0; e < 16; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(s[e] * sl2 - mc);
+            psum += p[e];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) pu[k] = pack_bf16(p[2 * k], p[2 * k + 1]);
+    } else {
+        constexpr int E = 16 / G::NS;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_next[i] = 0.f;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < G::NS; ++g) {
+            s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[g], c.qf[0][g], s_next, 0, 0, 0);
+            asm volatile("" : "+v"(s_next));
+#pragma unroll
+            for (int e = g * E; e < (g + 1) * E; ++e) {
+                p[e] = __builtin_amdgcn_exp2f(s[e] * sl2 - mc);
+                psum += p[e];
+                if (e & 1) {
+                    pu[e / 2] = pack_bf16(p[e - 1], p[e]);
+                    asm volatile("" : "+v"(pu[e / 2]));
+                } else {
+                    asm volatile("" : "+v"(p[e]));
+                }
+            }
+            asm volatile("" : "+v"(psum));
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) pu[k] = pack_bf16(p[2 * k], p[2 * k + 1]);
-    c.l[qt] += psum;
+    c.l[0] += psum;
 }
 
-// PV of row tile 0 (probabilities pu0) with the exponentials of row tile 1 in its shadow.
-template <class G>
-__device__ __forceinline__ void pv0_exp1(WaveCtx<G> &c, const bf16x8 (&vf)[G::ND][2], const uint32_t (&pu0)[8],
-                                         const f32x16 &s1, uint32_t (&pu1)[8], float sl2) {
+// Second half: the PV MFMAs of the current tile with the in-lane maximum of the next tile's
+// scores in their shadow (returned; folding it into the running maximum branches, so it
+// follows the MFMAs).
+template <class G, bool MAX>
+__device__ __forceinline__ float own_pv_max(WaveCtx<G> &c, const bf16x8 (&vf)[G::ND][2], const uint32_t (&pu)[8],
+                                            const f32x16 &s_next) {
     constexpr int NG = 2 * G::ND, E = 16 / NG;
     BFrag pb[2];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) pb[k / 4].u[k % 4] = pu0[k];
-    const float mc = c.m[1] * sl2;
-    float psum = 0.f, p[16];
+    for (int k = 0; k < 8; ++k) pb[k / 4].u[k % 4] = pu[k];
+    float mx = -__builtin_inff();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         const int ks = g / G::ND, dt = g % G::ND;
         c.o[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb[ks].v, c.o[0][dt], 0, 0, 0);
+        asm volatile("" : "+v"(c.o[0][dt]));
+        if constexpr (MAX) {
 #pragma unroll
-        for (int e = g * E; e < (g + 1) * E; ++e) {
-            p[e] = __builtin_amdgcn_exp2f(s1[e] * sl2 - mc);
-            psum += p[e];
-            if (e & 1) {
-                pu1[e / 2] = pack_bf16(p[e - 1], p[e]);
-                asm volatile("" : "+v"(pu1[e / 2]));
-            } else {
-                asm volatile("" : "+v"(p[e]));
-            }
+            for (int e = g * E; e < (g + 1) * E; e += 2) mx = fmaxf(mx, fmaxf(s_next[e], s_next[e + 1]));
+            asm volatile("" : "+v"(mx));
         }
-        asm volatile("" : "+v"(psum));
         __builtin_amdgcn_sched_barrier(0);
     }
-    c.l[1] += psum;
-}
-
-template <class G>
-__device__ __forceinline__ void pv_tile(WaveCtx<G> &c, int qt, const bf16x8 (&vf)[G::ND][2], const uint32_t (&pu)[8]) {
-    BFrag pb[2];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) pb[k / 4].u[k % 4] = pu[k];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt)
-            c.o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb[ks].v, c.o[qt][dt], 0, 0, 0);
+    return mx;
 }
 
 // Non-pipelined step (selected phase): fragments, scores, softmax and PV of one tile in
@@ -562,29 +518,32 @@ __device__ __forceinline__ void step_compute(WaveCtx<G> &c, const char *slot, in
 // Shared phase (compressed and window branches): every tile is used by all query blocks of
 // the workgroup.  Tiles go through the ring of NSLOT slots; a slot is refilled as soon as
 // every wavefront is done with it.
-//   src(t)  -> TileSrc of tile t (uniform over the workgroup)
-//   msk(t)  -> (j0, need_mask) of tile t for this wavefront
+//   src(t)  -> global address of the image of tile t (uniform over the workgroup)
+//   msk(t)  -> (j0, need_mask) of tile t for this wavefront; tiles in [mf_lo, mf_hi) need none
 // Step t runs mfma_block with QK of tile t+1, the exponentials of tile t and PV of tile t-1,
 // reloading its operand registers on the fly with the K fragments of tile t+2 and the V
-// fragments of tile t.  After the block (one barrier per step) the slot of tile t-1 is
-// refilled with tile t-1+NSLOT and the maximum of tile t+1 is folded into the running
+// fragments of tile t.  Once per step (one barrier) the slot of tile t-2 is refilled with
+// tile t-2+NSLOT, and after the block the maximum of tile t+1 is folded into the running
 // maximum.  Every wavefront runs every step: a tile outside a wavefront's own key range is
 // simply fully masked (the step body is kept unconditional on purpose -- a conditional
 // update of the accumulator tuples makes the compiler shuffle them through copies).
 // Scores and probabilities alternate between two register sets (index = tile parity), so
 // nothing is copied from step to step.
 template <class G, typename SrcFn, typename MaskFn>
-__device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src, MaskFn msk,
-                                           uint32_t row_stride_bytes, char *lds, int wave, int lane, float sl2) {
+__device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src, MaskFn msk, int mf_lo, int mf_hi,
+                                           char *lds, int wave, int lane, float sl2) {
     constexpr int R = G::NSLOT, QT = G::QT;
     constexpr bool PAR = G::D == 64 ? LSRM_PAR64 : LSRM_PAR128;
     if (n_steps <= 0) return;
     auto slot = [&](int t) { return lds + (t % R) * G::TILE; };
-    SharedCopy<G> cp;
-    cp.init(wave, lane, row_stride_bytes);
+    auto lslot = [&](int t) { return lds + (t % R) * G::TILE + c.lane16; };  // this lane's fragment base
+    // The two wavefronts that share a SIMD (w and w + 4 of an 8-wavefront workgroup) run half a
+    // step apart: one meets the step's barrier before its MFMA block, the other after it, so
+    // one's latency-bound work between blocks coincides with the other's MFMA block.
+    const bool lag = LSRM_PINGPONG && G::WAVES == 8 && wave >= 4;
     __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
     wg_barrier();  // every wavefront is done with the slots (previous phase)
-    for (int t = 0; t < R && t < n_steps; ++t) issue_shared<G>(cp, src(t), row_stride_bytes, slot(t), wave, lane);
+    for (int t = 0; t < R && t < n_steps; ++t) issue_shared<G>(c, src(t), slot(t), wave);
     // tiles 0, 1 and 2 must have landed before the first block reads them
     if (n_steps >= R)
         __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 3) * G::SH_IPT));
@@ -603,9 +562,9 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
     }
     // prime the queues: first K fragments of tile 1 (stale but finite data if there is none), first V fragments of tile 0
 #pragma unroll
-    for (int i = 0; i < G::KQ; ++i) kq[i] = *reinterpret_cast<const bf16x8 *>(slot(1) + c.kf_off[i]);
+    for (int i = 0; i < G::KQ; ++i) kq[i] = *reinterpret_cast<const bf16x8 *>(lslot(1) + i * 1024);
 #pragma unroll
-    for (int f = 0; f < G::VQ; ++f) vq[f] = *reinterpret_cast<const bf16x8 *>(slot(0) + c.vf_off[f % G::ND][f / G::ND]);
+    for (int f = 0; f < G::VQ; ++f) vq[f] = *reinterpret_cast<const bf16x8 *>(lslot(0) + G::K_BYTES + f * 1024);
     msk(0, &j0, &need_mask);
     mfma_settle();  // a branch follows the MFMAs that produced the scores
 #pragma unroll
@@ -614,21 +573,26 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
         update_max<G>(c, qt, lane_max(S[0][qt]), sl2, nullptr);
     }
 
-    // What follows every MFMA block but the last: sync, refill a slot, fold the maximum of
-    // the scores just produced (s_next); pu are the probabilities still to be accumulated.
-    auto after_block = [&](int t, f32x16 (&s_next)[QT], uint32_t (&pu)[QT][8]) {
-        // Before the barrier this wavefront's LDS reads have returned and its share of tile
-        // t+3 (read during the next block) has landed; later tiles may stay in flight.
-        // Copies issued so far: tiles 0 .. t-2+R.  Near the end fewer are outstanding: wait for all.
-        if (t - 2 + R < n_steps && t >= 1)
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((R - 5) * G::SH_IPT));
+    // One workgroup barrier per step keeps the ring consistent.  Before barrier t a wavefront has
+    // finished (at least) MFMA block t-1 and waited for its own copies of tiles <= t+3; after it,
+    // tile t+3 is complete for everyone and nobody reads tile t-2 any more, whose slot is refilled.
+    // Copies issued before the wait: tiles 0 .. t-3+R; tiles t+4 and later may stay in flight
+    // (near the end of the phase fewer are outstanding: wait for all).
+    auto sync = [&](int t) {
+        if (t >= 2 && t - 3 + R < n_steps)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 6) * G::SH_IPT));
+        else if (t == 1 && n_steps >= R)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 5) * G::SH_IPT));
         else if (t == 0 && n_steps >= R)
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((R - 4) * G::SH_IPT));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 4) * G::SH_IPT));
         else
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
-        wg_barrier();  // tile t+3 has landed for everyone; everyone has fetched the fragments of tile t-1
-        if (t >= 1 && t - 1 + R < n_steps)
-            issue_shared<G>(cp, src(t - 1 + R), row_stride_bytes, slot(t - 1), wave, lane);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        wg_barrier();
+        if (t >= 2 && t - 2 + R < n_steps) issue_shared<G>(c, src(t - 2 + R), slot(t - 2), wave);
+    };
+    // After an MFMA block: fold the maximum of the scores just produced (s_next) into the running
+    // maximum; pu are the probabilities still to be accumulated.
+    auto post = [&](int t, f32x16 (&s_next)[QT], uint32_t (&pu)[QT][8]) {
         msk(t + 1, &j0, &need_mask);
         mfma_settle();  // s_next and O come from the MFMAs just issued; branches follow
 #pragma unroll
@@ -649,113 +613,162 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
             }
         }
     };
+    // The same two pieces for the steps in the middle of a phase, where nothing is conditional:
+    // every copy exists and the tile needs no mask.
+    auto sync_fast = [&](int t) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((R - 6) * G::SH_IPT));
+        wg_barrier();
+        issue_shared<G>(c, src(t - 2 + R), slot(t - 2), wave);
+    };
+    auto post_fast = [&](f32x16 (&s_next)[QT], uint32_t (&pu)[QT][8]) {
+        mfma_settle();
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) update_max<G>(c, qt, lane_max(s_next[qt]), sl2, pu[qt]);
+    };
     // QK(t+1) || exp(t) || PV(t-1); the queues move on to K(t+2) and V(t)  (stale slots past the end: unused)
-    auto full_step = [&](auto par, int t) {
+    auto full_step = [&](auto par, auto fast, int t) {
         constexpr int A = PAR ? decltype(par)::value : 0;
-        mfma_block<G, true, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], sl2, slot(t + 1), slot(t + 2),
-                                  slot(t - 1), slot(t));
-        after_block(t, S[A ^ 1], P[A]);
+        constexpr bool FAST = decltype(fast)::value;
+        if (lag) {
+            if constexpr (FAST) sync_fast(t); else sync(t);
+        }
+        mfma_block<G, true, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], sl2, lslot(t + 1), lslot(t + 2),
+                                  lslot(t - 1), lslot(t));
+        if (!lag) {
+            if constexpr (FAST) sync_fast(t); else sync(t);
+        }
+        if constexpr (FAST) post_fast(S[A ^ 1], P[A]); else post(t, S[A ^ 1], P[A]);
         rotate();
     };
     // exp(n-1) || PV(n-2); then the drain: PV of the last tile
     auto last_step = [&](auto par, int t) {
         constexpr int A = PAR ? decltype(par)::value : 0;
-        mfma_block<G, false, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], sl2, nullptr, nullptr, slot(t - 1),
-                                   slot(t));
-        pv_drain<G>(c, vq, P[A], slot(t));
+        mfma_block<G, false, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], sl2, nullptr, nullptr, lslot(t - 1),
+                                   lslot(t));
+        pv_drain<G>(c, vq, P[A], lslot(t));
     };
     using Even = std::integral_constant<int, 0>;
     using Odd = std::integral_constant<int, 1>;
+    // full steps t0 .. t1-1
+    auto run_range = [&](int t0, int t1, auto fast) {
+        int t = t0;
+        if constexpr (PAR) {
+            if (t < t1 && (t & 1) == 0) {
+                full_step(Even{}, fast, t);
+                ++t;
+            }
+            for (; t + 1 < t1; t += 2) {
+                full_step(Odd{}, fast, t);
+                full_step(Even{}, fast, t + 1);
+            }
+            if (t < t1) full_step(Odd{}, fast, t);
+        } else {
+            for (; t < t1; ++t) full_step(Even{}, fast, t);
+        }
+    };
 
     if (n_steps >= 2) {
         // QK(1) || exp(0)
-        mfma_block<G, true, false>(c, S[0], kq, S[1], vq, P[1], P[0], sl2, slot(1), slot(2), nullptr, nullptr);
-        after_block(0, S[1], P[0]);
+        if (lag) sync(0);
+        mfma_block<G, true, false>(c, S[0], kq, S[1], vq, P[1], P[0], sl2, lslot(1), lslot(2), nullptr, nullptr);
+        if (!lag) sync(0);
+        post(0, S[1], P[0]);
         rotate();
-        if constexpr (PAR) {
-            int t = 1;
-            for (; t + 2 < n_steps; t += 2) {
-                full_step(Odd{}, t);
-                full_step(Even{}, t + 1);
-            }
-            if (t + 1 < n_steps) {
-                full_step(Odd{}, t);
-                last_step(Even{}, t + 1);
-            } else {
-                last_step(Odd{}, t);
-            }
-        } else {
-            for (int t = 1; t + 1 < n_steps; ++t) full_step(Even{}, t);
-            last_step(Even{}, n_steps - 1);
-        }
+        // full steps 1 .. n-2; those in [t_lo, t_hi) take the unconditional path
+        const int t_end = n_steps - 1;
+        int t_lo = max(2, mf_lo - 1), t_hi = min(n_steps - R + 2, mf_hi - 1);
+        t_lo = min(t_lo, t_end);
+        t_hi = max(min(t_hi, t_end), t_lo);
+        run_range(1, t_lo, std::false_type{});
+        run_range(t_lo, t_hi, std::true_type{});
+        run_range(t_hi, t_end, std::false_type{});
+        if (PAR && (t_end & 1))
+            last_step(Odd{}, t_end);
+        else
+            last_step(Even{}, t_end);
     } else {
         mfma_block<G, false, false>(c, S[0], kq, S[1], vq, P[1], P[0], sl2, nullptr, nullptr, nullptr, nullptr);
-        pv_drain<G>(c, vq, P[0], slot(0));
+        pv_drain<G>(c, vq, P[0], lslot(0));
     }
 }
 
-// Selected phase: each query block streams its own routed blocks in 32-key steps through
-// two stages of NP slots, copied ahead.
-//   One wavefront per query block: nothing is shared, so the wavefronts run free of each
-//   other between the barrier that opens the phase and the one that opens the next.
-//   Two wavefronts per query block: they split the copies and meet at a workgroup barrier
-//   every step; a block whose list is shorter than the longest of the workgroup keeps
-//   meeting the barriers (second loop) without computing.
+// Selected phase: each query block streams its own routed blocks in 32-key steps through its
+// two tile slots; its two wavefronts split the copies and meet at a workgroup barrier every step.
 template <class G, typename SrcFn>
-__device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src,
-                                        uint32_t row_stride_bytes, char *lds, int qbi, int sub, int lane, float sl2) {
+__device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src, char *lds, int qbi,
+                                        int sub, int lane, float sl2) {
     constexpr int NP = G::NP;
     if (n_steps <= 0) return;
-    uint32_t koff[G::PR_K];  // per-lane source offsets of this wavefront's K copy instructions
-#pragma unroll
-    for (int j = 0; j < G::PR_K; ++j) {
-        int row, chunk;
-        k_copy_geometry<G::D>(sub + G::NW * j, lane, row_stride_bytes, &row, &chunk, &koff[j]);
-    }
+    static_assert(G::NW == 2, "two wavefronts per query block");
     __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
     wg_barrier();
-    if constexpr (G::NW == 1) {
-        constexpr int IPT = G::PR_K + G::PR_V;
-        char *stage[2] = {lds + qbi * G::TILE, lds + (NP + qbi) * G::TILE};
-        if (my_steps > 0) issue_own<G>(koff, src(0), stage[0], 0, lane);
-        if (my_steps > 1) issue_own<G>(koff, src(1), stage[1], 0, lane);
-        for (int t = 0; t < my_steps; ++t) {
-            // tile t has landed (the copies of tile t+1 may stay in flight)
-            if (t + 1 < my_steps)
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(IPT));
-            else
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            bf16x8 kf[G::NS];
-            bf16x8 vf[G::ND][2];
-            read_k<G>(c, stage[t & 1], kf);
-            read_v<G>(c, stage[t & 1], vf);
-            f32x16 s[G::QT];
-            qk_scores<G>(c, kf, s);
-            // the fragments are in registers: the slot can take the tile after next
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(63));
-            if (t + 2 < my_steps) issue_own<G>(koff, src(t + 2), stage[t & 1], 0, lane);
-            mfma_settle();
-#pragma unroll
-            for (int qt = 0; qt < G::QT; ++qt) update_max<G>(c, qt, lane_max(s[qt]), sl2, nullptr);
-            uint32_t pu[G::QT][8];
-            exp_tile<G>(c, 0, s[0], pu[0], sl2);
-            if constexpr (G::QT == 2) {
-                pv0_exp1<G>(c, vf, pu[0], s[1], pu[1], sl2);
-                pv_tile<G>(c, 1, vf, pu[1]);
-            } else {
-                pv_tile<G>(c, 0, vf, pu[0]);
+    {
+        // Pipelined over two tiles: block t = [QK(t+1) || exp(t)] [PV(t) || max(t+1)], fragments of
+        // K(t+1) and V(t) in registers.  Tile tau lives in stage tau & 1 of the query block's two
+        // slots, its K and V parts copied separately: once block t is done (barrier t) nobody needs
+        // K(t+1) and V(t) any more, so K(t+3) and V(t+2) are copied over them -- a full block
+        // ahead of their use.  Every wavefront meets the same barriers; a query block with a
+        // shorter list than the longest of the workgroup idles through the rest (second loop).
+        constexpr int KI = G::K_BYTES / 1024 / G::NW, VI = G::V_BYTES / 1024 / G::NW;
+        const int n = my_steps;
+        auto stage = [&](int tau) { return lds + ((tau & 1) * NP + qbi) * G::TILE; };
+        auto issue_part = [&](const char *tile, char *slot, int n_inst) {
+#pragma unroll 8
+            for (int j = 0; j < n_inst; ++j) {
+                const int i = sub + G::NW * j;
+                __builtin_amdgcn_global_load_lds(GLB_PTR(tile + i * 1024 + c.lane16), LDS_PTR(slot + i * 1024), 16, 0, 0);
             }
+        };
+        auto issue_k = [&](int tau) { issue_part(src(tau), stage(tau), KI); };
+        auto issue_v = [&](int tau) { issue_part(src(tau) + G::K_BYTES, stage(tau) + G::K_BYTES, VI); };
+        bf16x8 kf[G::NS];
+        bf16x8 vf[G::ND][2];
+        f32x16 s_cur, s_next;
+        uint32_t pu[8];
+        if (n > 0) {
+            issue_k(0);
+            issue_v(0);
         }
-    } else {
-        if (my_steps > 0) issue_own<G>(koff, src(0), lds + qbi * G::TILE, sub, lane);
-        for (int t = 0; t < my_steps; ++t) {
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        if (n > 1) {
+            issue_k(1);
+            issue_v(1);
+        }
+        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        wg_barrier();
+        if (n > 0) {
+            read_k<G>(c, stage(0), kf);
+            f32x16 s0[1];
+            qk_scores<G>(c, kf, s0);
+            s_cur = s0[0];
+        }
+        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        wg_barrier();  // K(0) has been fetched by both wavefronts of the query block
+        if (n > 2) issue_k(2);
+        if (n > 0) {
+            mfma_settle();
+            update_max<G>(c, 0, lane_max(s_cur), sl2, nullptr);
+            read_v<G>(c, stage(0), vf);
+        }
+        if (n > 1) read_k<G>(c, stage(1), kf);
+        for (int t = 0; t + 1 < n; ++t) {
+            own_qk_exp<G, true>(c, s_cur, kf, s_next, pu, sl2);
+            const float mx = own_pv_max<G, true>(c, vf, pu, s_next);
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));  // K(t+2) and V(t+1) have landed
             wg_barrier();
-            if (t + 1 < my_steps)
-                issue_own<G>(koff, src(t + 1), lds + (((t + 1) & 1) * NP + qbi) * G::TILE, sub, lane);
-            step_compute<G>(c, lds + ((t & 1) * NP + qbi) * G::TILE, lane, sl2);
+            if (t + 3 < n) issue_k(t + 3);
+            if (t + 2 < n) issue_v(t + 2);
+            if (t + 2 < n) read_k<G>(c, stage(t + 2), kf);
+            read_v<G>(c, stage(t + 1), vf);
+            mfma_settle();
+            update_max<G>(c, 0, mx, sl2, nullptr);
+            s_cur = s_next;
         }
-        for (int t = my_steps; t < n_steps; ++t) {
+        if (n > 0) {
+            own_qk_exp<G, false>(c, s_cur, kf, s_next, pu, sl2);
+            own_pv_max<G, false>(c, vf, pu, s_next);
+        }
+        // barriers 0 .. n_steps - 2 in total; n - 1 of them are behind us
+        for (int t = (n > 0 ? n - 1 : 0); t + 1 < n_steps; ++t) {
             __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
             wg_barrier();
         }
@@ -866,12 +879,14 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
     constexpr int D = G::D, NP = G::NP;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // XCD-aware numbering: hardware deals consecutive workgroups round-robin to the 8 XCDs
+    // and runs them roughly in launch order.  All XCDs work on the same head at the same time (so the
+    // K/V working set of the moment is one head: it fits the last-level cache and the pooled
+    // keys/values fit every L2), each XCD on its own contiguous eighth of the head's query blocks
+    // (so neighbouring windows and routed blocks meet in its L2).
     const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
-    if (slot_id >= a.units_per_xcd) return;
-    const int unit = xcd * a.units_per_xcd + slot_id;
-    if (unit >= a.units) return;
-    const int head = unit / a.groups_per_head;
-    const int group = unit % a.groups_per_head;
+    const int head = slot_id / a.groups_per_xcd;
+    const int group = xcd * a.groups_per_xcd + slot_id % a.groups_per_xcd;
+    if (group >= a.groups_per_head) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int qbi = wave / G::NW, sub = wave % G::NW;  // query block inside the group, wavefront inside the block
@@ -879,23 +894,11 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
     const int qb = group * NP + qbi;
     const bool active = qb < a.nb;  // a trailing group may have fewer than NP query blocks
     const int64_t row0 = (int64_t)(active ? qb : 0) * 64 + G::ROWS * sub;
-    const uint32_t row_stride_bytes = (uint32_t)a.h * D * 2;
+    const int64_t tile_stride = (int64_t)a.h * G::TILE;  // bytes between consecutive tiles of one head
     const float sl2 = a.scale_log2e;
 
     WaveCtx<G> c;
-    {
-        const int r_perm = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
-        const int ksw = k_swz<D>(r_perm);
-#pragma unroll
-        for (int ks = 0; ks < G::NS; ++ks) c.kf_off[ks] = r_perm * (2 * D) + (((2 * ks + hh) ^ ksw) * 16);
-#pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt) {
-            const int row = 32 * dt + r;
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                c.vf_off[dt][ks] = G::K_BYTES + row * 64 + (((2 * ks + hh) ^ ((row >> 2) & 3)) * 16);
-        }
-    }
+    c.lane16 = (uint32_t)lane * 16u;
     // A fully masked step may read a slot that no copy has filled yet: make sure it holds
     // finite values (0 * NaN would poison the accumulators).
     for (int off = threadIdx.x * 16; off < G::LDS_BYTES; off += G::THREADS * 16)
@@ -919,18 +922,13 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
             c.hi[qt] = a.nb;
         }
         const int n_steps = (a.nb + 31) / 32;
-        auto src = [&](int t) {
-            TileSrc s;
-            s.k_rows = a.kc + ((int64_t)(32 * t) * a.h + head) * D;
-            s.rows_valid = a.nb - 32 * t;
-            s.v_t = a.vc_t + (((int64_t)(t >> 1) * a.h + head) * 2 + (t & 1)) * (D * 32);
-            return s;
-        };
+        const char *base = a.kvc + (int64_t)head * G::TILE;
+        auto src = [&](int t) { return base + t * tile_stride; };
         auto msk = [&](int t, int *j0, bool *need) {
             *j0 = 32 * t;
             *need = 32 * t + 32 > a.nb;
         };
-        run_shared<G>(c, n_steps, src, msk, row_stride_bytes, lds, wave, lane, sl2);
+        run_shared<G>(c, n_steps, src, msk, 0, a.nb / 32, lds, wave, lane, sl2);
         if (active) finish_branch<G>(c, a, 0, row0, head, wave, lane, lds);
     }
 
@@ -954,15 +952,12 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
                 my_valid = n_valid;
             }
         }
+        const char *base = a.kv + (int64_t)head * G::TILE;
         auto src = [&](int t) {
             int kb = __builtin_amdgcn_readlane(packed, t >> 1);
-            TileSrc s;
-            s.k_rows = a.k + (((int64_t)kb * 64 + 32 * (t & 1)) * a.h + head) * D;
-            s.rows_valid = 32;
-            s.v_t = a.v_t + (((int64_t)kb * a.h + head) * 2 + (t & 1)) * (D * 32);
-            return s;
+            return base + (2 * kb + (t & 1)) * tile_stride;
         };
-        run_own<G>(c, 2 * max_valid, 2 * my_valid, src, row_stride_bytes, lds, qbi, sub, lane, sl2);
+        run_own<G>(c, 2 * max_valid, 2 * my_valid, src, lds, qbi, sub, lane, sl2);
         if (active) finish_branch<G>(c, a, 1, row0, head, wave, lane, lds);
     }
 
@@ -992,74 +987,89 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
             }
         }
         const int n_steps = st_max > st_min ? st_max - st_min : 0;
-        auto src = [&](int t) {
-            int st = st_min + t;
-            TileSrc s;
-            s.k_rows = a.k + ((int64_t)(32 * st) * a.h + head) * D;
-            s.rows_valid = 32;
-            s.v_t = a.v_t + (((int64_t)(st >> 1) * a.h + head) * 2 + (st & 1)) * (D * 32);
-            return s;
-        };
+        const char *base = a.kv + (int64_t)head * G::TILE;
+        auto src = [&](int t) { return base + (st_min + t) * tile_stride; };
         auto msk = [&](int t, int *j0, bool *need) {
             int st = st_min + t;
             *j0 = 32 * st;
             *need = (32 * st < mine.full_lo) || (32 * st + 32 > mine.full_hi);  // also true outside [st0, st1)
         };
-        run_shared<G>(c, n_steps, src, msk, row_stride_bytes, lds, wave, lane, sl2);
+        // tiles wholly inside the range that every query of the block sees
+        const int mf_lo = max(0, (mine.full_lo - 32 * st_min + 31) >> 5);
+        const int mf_hi = (mine.full_hi - 32 * st_min) >> 5;
+        run_shared<G>(c, n_steps, src, msk, mf_lo, mf_hi, lds, wave, lane, sl2);
         __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         wg_barrier();  // the tile slots are about to be reused for the output rows
         if (active) finish_branch<G>(c, a, 2, row0, head, wave, lane, lds);
     }
 }
 
-// Packs a [n_rows, H, D] bf16 tensor into per-block transposed sub-tiles:
-//   dst[block][head][half][channel][slot][8]  with key t = 32 half + 8 (slot ^ ((channel >> 2) & 3)) + j
-// Rows at or beyond n_rows read as zero.  One workgroup per (block, head).
+// Builds the tile images (see issue_shared) of a K and a V tensor, both [n_rows, H, D] bf16:
+// img[tile][head] = K fragments (K_BYTES) then V^T fragments (V_BYTES).
+// Rows at or beyond n_rows read as zero (their scores are masked in the attention kernel).
+// One workgroup per (64-row block, head) = two tiles.
 template <int D>
-__global__ __launch_bounds__(256) void pack_transposed(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                       int64_t n_rows, int h) {
-    __shared__ uint16_t tile[64][D + 2];
+__global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
+                                                  char *__restrict__ img, int64_t n_rows, int h, int n_tiles) {
+    constexpr int K_BYTES = 32 * D * 2, TILE = K_BYTES + D * 64;
+    constexpr int CH = D / 8;  // 16-byte chunks per row
+    __shared__ uint16_t vt[64][D + 2];
     const int64_t blk = blockIdx.x;
     const int head = blockIdx.y;
-    constexpr int CH = D / 8;
+    // K: a permutation of 16-byte chunks.  Source chunk (row t, chunk cc) goes to fragment
+    // ks = cc / 2, lane (hh = cc % 2, r = perm(t % 32)) of tile t / 32.
     for (int e = threadIdx.x; e < 64 * CH; e += 256) {
-        int t = e / CH, cc = e % CH;
-        int64_t row = blk * 64 + t;
-        uint4 val = make_uint4(0, 0, 0, 0);
-        if (row < n_rows) val = *reinterpret_cast<const uint4 *>(src + (row * h + head) * D + cc * 8);
-        uint32_t w[4] = {val.x, val.y, val.z, val.w};
+        const int t = e / CH, cc = e % CH;
+        const int64_t row = blk * 64 + t;
+        uint4 kval = make_uint4(0, 0, 0, 0), vval = make_uint4(0, 0, 0, 0);
+        if (row < n_rows) {
+            kval = *reinterpret_cast<const uint4 *>(k + (row * h + head) * D + cc * 8);
+            vval = *reinterpret_cast<const uint4 *>(v + (row * h + head) * D + cc * 8);
+        }
+        const int64_t tile = blk * 2 + t / 32;
+        if (tile < n_tiles) {
+            const int tt = t % 32;
+            const int r = (tt & ~12) | ((tt & 4) << 1) | ((tt & 8) >> 1);
+            *reinterpret_cast<uint4 *>(img + (tile * h + head) * TILE + (cc * 32 + r) * 16) = kval;
+        }
+        uint32_t w[4] = {vval.x, vval.y, vval.z, vval.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            tile[t][cc * 8 + 2 * j] = (uint16_t)(w[j] & 0xffffu);
-            tile[t][cc * 8 + 2 * j + 1] = (uint16_t)(w[j] >> 16);
+            vt[t][cc * 8 + 2 * j] = (uint16_t)(w[j] & 0xffffu);
+            vt[t][cc * 8 + 2 * j + 1] = (uint16_t)(w[j] >> 16);
         }
     }
     __syncthreads();
-    uint16_t *out = dst + ((blk * h + head) * 2) * (int64_t)(D * 32);
-    for (int e = threadIdx.x; e < 2 * D * 4; e += 256) {
-        int half = e / (D * 4);
-        int ch = (e / 4) % D;
-        int slot = e % 4;
-        int cidx = slot ^ ((ch >> 2) & 3);
-        int t0 = 32 * half + 8 * cidx;
+    // V^T: chunk e of a tile = fragment f = e / 64 (ks2 = f / ND, dt = f % ND), lane = e % 64
+    // (hh = lane / 32, r = lane % 32): channel 32 dt + r, keys 16 ks2 + 8 hh + 0..7.
+    constexpr int ND = D / 32;
+    for (int e = threadIdx.x; e < 2 * 2 * ND * 64; e += 256) {
+        const int half = e / (2 * ND * 64);
+        const int f = (e / 64) % (2 * ND), ln = e % 64;
+        const int ks2 = f / ND, dt = f % ND, hh = ln / 32, r = ln % 32;
+        const int ch = 32 * dt + r, t0 = 32 * half + 16 * ks2 + 8 * hh;
+        const int64_t tile = blk * 2 + half;
+        if (tile >= n_tiles) continue;
         uint32_t w[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = (uint32_t)tile[t0 + 2 * j][ch] | ((uint32_t)tile[t0 + 2 * j + 1][ch] << 16);
-        *reinterpret_cast<uint4 *>(out + (int64_t)e * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+        for (int j = 0; j < 4; ++j) w[j] = (uint32_t)vt[t0 + 2 * j][ch] | ((uint32_t)vt[t0 + 2 * j + 1][ch] << 16);
+        *reinterpret_cast<uint4 *>(img + (tile * h + head) * TILE + K_BYTES + (f * 64 + ln) * 16) =
+            make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
 struct WsLayout {
-    size_t v_t, vc_t, gsum, total;
+    size_t kv, kvc, gsum, total;
 };
 
 WsLayout ws_layout(const Shape &s) {
     WsLayout w;
+    const size_t tile = (size_t)32 * s.d * 2 * 2;  // K and V^T parts of one (tile, head)
     size_t off = 0;
-    w.v_t = off;
-    off += align_up((size_t)s.nb * 64 * s.h * s.d * 2, 256);
-    w.vc_t = off;
-    off += align_up((size_t)((s.nb + 63) / 64) * 64 * s.h * s.d * 2, 256);
+    w.kv = off;
+    off += align_up((size_t)s.nb * 2 * s.h * tile, 256);
+    w.kvc = off;
+    off += align_up((size_t)((s.nb + 31) / 32) * s.h * tile, 256);
     w.gsum = off;
     off += align_up((size_t)s.nb * 64 * s.h * s.d * 4, 256);
     w.total = off > 0 ? off : 256;
@@ -1067,22 +1077,22 @@ WsLayout ws_layout(const Shape &s) {
 }
 
 template <class G>
-lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg, FwdArgs a, const uint16_t *d_v,
-                             const uint16_t *d_vc, char *ws, const WsLayout &w, hipStream_t st, hipEvent_t ev_start,
-                             hipEvent_t ev_stop) {
+lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg, FwdArgs a, const uint16_t *d_k,
+                             const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc, char *ws,
+                             const WsLayout &w, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
     constexpr int D = G::D, NP = G::NP;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
-    hipLaunchKernelGGL(pack_transposed<D>, dim3(s.nb, s.h), dim3(256), 0, st, d_v, (uint16_t *)(ws + w.v_t), s.n, s.h);
+    const int tiles_c = (s.nb + 31) / 32;
+    hipLaunchKernelGGL(pack_tiles<D>, dim3(s.nb, s.h), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h, 2 * s.nb);
     LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(pack_transposed<D>, dim3((s.nb + 63) / 64, s.h), dim3(256), 0, st, d_vc,
-                       (uint16_t *)(ws + w.vc_t), (int64_t)s.nb, s.h);
+    hipLaunchKernelGGL(pack_tiles<D>, dim3((s.nb + 63) / 64, s.h), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
+                       (int64_t)s.nb, s.h, tiles_c);
     LSRM_HIP_CHECK(hipGetLastError());
-    a.v_t = (const uint16_t *)(ws + w.v_t);
-    a.vc_t = (const uint16_t *)(ws + w.vc_t);
+    a.kv = ws + w.kv;
+    a.kvc = ws + w.kvc;
     a.gsum = (float *)(ws + w.gsum);
     a.groups_per_head = (s.nb + NP - 1) / NP;
-    a.units = a.groups_per_head * s.h;
-    a.units_per_xcd = (a.units + 7) / 8;
+    a.groups_per_xcd = (a.groups_per_head + 7) / 8;
     static bool attr_set = false;
     if (!attr_set) {
         LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<G>),
@@ -1090,7 +1100,7 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
         attr_set = true;
     }
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
-    hipLaunchKernelGGL((nsa_forward_kernel<G>), dim3(a.units_per_xcd * 8), dim3(G::THREADS), G::LDS_BYTES, st, a);
+    hipLaunchKernelGGL((nsa_forward_kernel<G>), dim3(8 * a.groups_per_xcd * s.h), dim3(G::THREADS), G::LDS_BYTES, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;
@@ -1109,8 +1119,6 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     if (n_seg > kMaxSeg) return LSRM_ERR_UNSUPPORTED;
     FwdArgs a{};
     a.q = d_q;
-    a.k = d_k;
-    a.kc = d_kc;
     a.idx = d_idx;
     a.gates = d_gates;
     a.out = d_out;
@@ -1126,8 +1134,8 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.scale_log2e = s.scale * 1.4426950408889634f;
     WsLayout w = ws_layout(s);
     char *ws = reinterpret_cast<char *>(d_ws);
-    if (s.d == 64) return launch_forward_d<Geo<64, 4, LSRM_QT64>>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
-    return launch_forward_d<Geo<128, 4, LSRM_QT128>>(s, seg_host, n_seg, a, d_v, d_vc, ws, w, st, ev_start, ev_stop);
+    if (s.d == 64) return launch_forward_d<Geo<64, 4, LSRM_QT64>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
+    return launch_forward_d<Geo<128, 4, LSRM_QT128>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
 }
 
 }  // namespace lsrm
