@@ -23,6 +23,11 @@ sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
+# HBM bytes per launch of the attention kernel (fetched + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs of this script scaled by the same counters of a plain 1 GiB copy; the readings and the commands are
+# in profiles/nsa_forward_kernel_config4_hbm_traffic.txt.  Only the workloads that were profiled appear.
+MEASURED_HBM_BYTES = {4: 74.9e9 + 8.8e9}
+
 
 def cpu_baseline(cfg, arrays, idx, target_seconds=20.0):
     """Times the CPU oracle (as it stands) on a bounded sample of query blocks."""
@@ -182,7 +187,8 @@ def main():
             "peak": BF16_MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(attn_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_HBM_BYTES.get(args.config) if args.topk is None and args.window is None else None,
+            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
         },
     }
     if not args.no_cpu_baseline:
