@@ -352,3 +352,125 @@ void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, float sc
     free(gq); free(gk); free(gv); free(gkc); free(gvc);
     free(rc); free(rs); free(rw); free(p); free(o);
 }
+
+/*
+ * Gradients of the same layer for a sample of blocks and heads (full-size parity checks).
+ * The arithmetic per (query, head, branch) is that of oracle_nsa_backward; only what is
+ * accumulated differs:
+ *   dq  [n_qb*64, n_hs, d]  rows of the listed query blocks,
+ *   dk, dv [n_kb*64, n_hs, d]  rows of the listed key blocks -- every query of the sequence
+ *           that attends them contributes (pooled keys of the listed blocks included, spread
+ *           back over their 64 tokens as in the full function).
+ * A (query, branch) whose key set meets none of the listed key blocks is skipped unless its
+ * dq is wanted.  OpenMP over queries with per-thread accumulators, summed in thread order.
+ */
+void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, float scale, int n_seg,
+                                 const int32_t *seg, const float *q, const float *k, const float *v,
+                                 const float *kc, const float *vc, const int32_t *idx, const float *gates,
+                                 const float *dout, const int32_t *qblocks, int n_qb, const int32_t *kblocks,
+                                 int n_kb, const int32_t *heads, int n_hs, float *dq, float *dk, float *dv) {
+    int64_t nb = n / BLK;
+    size_t stride = (size_t)h * d;
+    double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
+    size_t maxkeys = (size_t)nb;
+    if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
+    if ((size_t)window + 1 > maxkeys) maxkeys = (size_t)window + 1;
+    /* position of a block in the sample lists, or -1 */
+    int32_t *qpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nb > 0 ? nb : 1));
+    int32_t *kpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nb > 0 ? nb : 1));
+    for (int64_t b = 0; b < nb; ++b) qpos[b] = kpos[b] = -1;
+    for (int a = 0; a < n_qb; ++a) qpos[qblocks[a]] = a;
+    for (int a = 0; a < n_kb; ++a) kpos[kblocks[a]] = a;
+    size_t ostride = (size_t)n_hs * d;
+    size_t tot_q = (size_t)n_qb * BLK * ostride, tot_k = (size_t)n_kb * BLK * ostride, tot_c = (size_t)n_kb * ostride;
+    double *gq = (double *)calloc(tot_q > 0 ? tot_q : 1, sizeof(double));
+    double *gk = (double *)calloc(tot_k > 0 ? tot_k : 1, sizeof(double));
+    double *gv = (double *)calloc(tot_k > 0 ? tot_k : 1, sizeof(double));
+    double *gkc = (double *)calloc(tot_c > 0 ? tot_c : 1, sizeof(double));
+    double *gvc = (double *)calloc(tot_c > 0 ? tot_c : 1, sizeof(double));
+#pragma omp parallel
+    {
+        double *tk = (double *)calloc(tot_k > 0 ? tot_k : 1, sizeof(double));
+        double *tv = (double *)calloc(tot_k > 0 ? tot_k : 1, sizeof(double));
+        double *tkc = (double *)calloc(tot_c > 0 ? tot_c : 1, sizeof(double));
+        double *tvc = (double *)calloc(tot_c > 0 ? tot_c : 1, sizeof(double));
+        int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
+        int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
+        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + 1));
+        double *p = (double *)malloc(sizeof(double) * maxkeys);
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t i = 0; i < n; ++i) {
+            int nc, ns, nw;
+            key_sets(i, nb, topk, window, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+            int qa = qpos[i / BLK];
+            for (int br = 0; br < 3; ++br) {
+                const int64_t *rows = br == 0 ? rc : (br == 1 ? rs : rw);
+                int cnt = br == 0 ? nc : (br == 1 ? ns : nw);
+                if (cnt == 0) continue;
+                int touches = 0; /* does the key set meet a listed key block? */
+                for (int j = 0; j < cnt && !touches; ++j) {
+                    int64_t blk = br == 0 ? rows[j] : rows[j] / BLK;
+                    if (kpos[blk] >= 0) touches = 1;
+                }
+                if (!touches && qa < 0) continue;
+                for (int a = 0; a < n_hs; ++a) {
+                    int hh = heads[a];
+                    const float *qv = q + (size_t)i * stride + (size_t)hh * d;
+                    const float *dor = dout + (size_t)i * stride + (size_t)hh * d;
+                    double g = (double)gates[((size_t)i * h + hh) * 3 + br];
+                    const float *kb = (br == 0 ? kc : k) + (size_t)hh * d;
+                    const float *vb = (br == 0 ? vc : v) + (size_t)hh * d;
+                    attend(qv, d, sc, kb, vb, stride, rows, cnt, p, o);
+                    double delta = 0.0;
+                    for (int c = 0; c < d; ++c) delta += g * (double)dor[c] * o[c];
+                    for (int j = 0; j < cnt; ++j) {
+                        int64_t blk = br == 0 ? rows[j] : rows[j] / BLK;
+                        int ka = kpos[blk];
+                        if (ka < 0 && qa < 0) continue;
+                        const float *kr = kb + (size_t)rows[j] * stride;
+                        const float *vr = vb + (size_t)rows[j] * stride;
+                        double dp = 0.0;
+                        for (int c = 0; c < d; ++c) dp += g * (double)dor[c] * (double)vr[c];
+                        double ds = p[j] * (dp - delta) * sc;
+                        if (qa >= 0) {
+                            double *gqr = gq + ((size_t)qa * BLK + (size_t)(i % BLK)) * ostride + (size_t)a * d;
+                            for (int c = 0; c < d; ++c) gqr[c] += ds * (double)kr[c];
+                        }
+                        if (ka >= 0) {
+                            double *gkr, *gvr;
+                            if (br == 0) {
+                                gkr = tkc + (size_t)ka * ostride + (size_t)a * d;
+                                gvr = tvc + (size_t)ka * ostride + (size_t)a * d;
+                            } else {
+                                size_t row = (size_t)ka * BLK + (size_t)(rows[j] % BLK);
+                                gkr = tk + row * ostride + (size_t)a * d;
+                                gvr = tv + row * ostride + (size_t)a * d;
+                            }
+                            for (int c = 0; c < d; ++c) {
+                                gkr[c] += ds * (double)qv[c];
+                                gvr[c] += p[j] * g * (double)dor[c];
+                            }
+                        }
+                    }
+                }
+            }
+        }
+#pragma omp critical
+        {
+            for (size_t e = 0; e < tot_k; ++e) { gk[e] += tk[e]; gv[e] += tv[e]; }
+            for (size_t e = 0; e < tot_c; ++e) { gkc[e] += tkc[e]; gvc[e] += tvc[e]; }
+        }
+        free(tk); free(tv); free(tkc); free(tvc);
+        free(rc); free(rs); free(rw); free(p); free(o);
+    }
+    for (size_t e = 0; e < tot_q; ++e) dq[e] = (float)gq[e];
+    for (int a = 0; a < n_kb; ++a)
+        for (int t = 0; t < BLK; ++t)
+            for (size_t c = 0; c < ostride; ++c) {
+                size_t e = ((size_t)a * BLK + (size_t)t) * ostride + c;
+                dk[e] = (float)(gk[e] + gkc[(size_t)a * ostride + c] / 64.0);
+                dv[e] = (float)(gv[e] + gvc[(size_t)a * ostride + c] / 64.0);
+            }
+    free(gq); free(gk); free(gv); free(gkc); free(gvc); free(qpos); free(kpos);
+}

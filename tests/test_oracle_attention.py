@@ -197,3 +197,24 @@ def test_backward_finite_difference_of_dense_formulation():
             args[which][pos] -= 2 * eps
             dn = loss(*args)
             assert abs((up - dn) / (2 * eps) - grad[pos]) < 1e-6
+
+
+def test_backward_sampled_matches_autograd_and_full(oracle_lib):
+    """The sampled-gradient function (used for full-size parity) against the library autograd of the
+    dense formulation and against the full function, on listed blocks and heads only."""
+    cfg, q, k, v, gates, idx = _case(12, n_obj=192, grid=8, n_views=2, heads=3, d=8, topk=2, window=80)
+    seg = cfg.seg_offsets()
+    dout = I.bf16_bits_to_f32(I.make_dout(cfg))
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout)
+    fq, fk, fv = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout)
+    qblocks, kblocks, heads = [4, 0], [1, 3, 2], [2, 0]
+    dq, dk, dv = oracle_lib.nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout, qblocks, kblocks,
+                                                 heads)
+    rows_q = np.concatenate([np.arange(64 * b, 64 * b + 64) for b in qblocks])
+    rows_k = np.concatenate([np.arange(64 * b, 64 * b + 64) for b in kblocks])
+    for got, ref, full, rows in ((dq, rq, fq, rows_q), (dk, rk, fk, rows_k), (dv, rv, fv, rows_k)):
+        want = ref[rows][:, heads]
+        assert got.shape == want.shape
+        assert np.abs(got - want).max() < 1e-5 * max(1.0, np.abs(want).max())
+        assert np.abs(got - full[rows][:, heads]).max() < 1e-6 * max(1.0, np.abs(want).max())
