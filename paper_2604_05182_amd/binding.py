@@ -52,6 +52,8 @@ _lib.lsrm_nsa_compress.restype = ctypes.c_int32
 _lib.lsrm_nsa_compress.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
 _lib.lsrm_nsa_forward.restype = ctypes.c_int32
 _lib.lsrm_nsa_forward.argtypes = [_pp] + [_vp] * 11 + [_sz, _vp, _vp, _vp]
+_lib.lsrm_nsa_backward.restype = ctypes.c_int32
+_lib.lsrm_nsa_backward.argtypes = [_pp] + [_vp] * 14 + [_sz, _vp, _vp, _vp]
 
 
 def strerror(status: int) -> str:
@@ -124,6 +126,15 @@ def lsrm_nsa_forward(p, q, k, v, kc, vc, idx, gates, out, lse=None, out_branch=N
     _check(_lib.lsrm_nsa_forward(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kc), _ptr(vc), _ptr(idx),
                                  _ptr(gates), _ptr(out), _ptr(lse), _ptr(out_branch), _ptr(ws), nbytes,
                                  _stream(stream), _event(ev_attn_start), _event(ev_attn_stop)), "lsrm_nsa_forward")
+
+
+def lsrm_nsa_backward(p, q, k, v, kc, vc, idx, gates, lse, out_branch, dout, dq, dk, dv, ws=None, stream=None,
+                      ev_start=None, ev_stop=None):
+    nbytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(_lib.lsrm_nsa_backward(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(kc), _ptr(vc), _ptr(idx),
+                                  _ptr(gates), _ptr(lse), _ptr(out_branch), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv),
+                                  _ptr(ws), nbytes, _stream(stream), _event(ev_start), _event(ev_stop)),
+           "lsrm_nsa_backward")
 
 
 def alloc_workspace(p, which: int, device="cuda") -> torch.Tensor:

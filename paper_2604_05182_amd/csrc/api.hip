@@ -81,6 +81,7 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call) {
     switch (which_call) {
         case LSRM_WS_ROUTE: return route_ws_bytes(s);
         case LSRM_WS_FORWARD: return forward_ws_bytes(s);
+        case LSRM_WS_BACKWARD: return s.d == 64 ? backward_ws_bytes(s) : 0;
         default: return 0;
     }
 }
@@ -131,6 +132,30 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
     return launch_forward(s, seg.data(), (int)seg.size() - 1, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_lse,
                           d_out_branch, d_ws, static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(ev_attn_start),
                           static_cast<hipEvent_t>(ev_attn_stop));
+}
+
+lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k, const uint16_t *d_v,
+                              const uint16_t *d_kc, const uint16_t *d_vc, const int32_t *d_idx, const float *d_gates,
+                              const float *d_lse, const uint16_t *d_out_branch, const uint16_t *d_dout, uint16_t *d_dq,
+                              uint16_t *d_dk, uint16_t *d_dv, void *d_ws, size_t ws_bytes, void *stream, void *ev_start,
+                              void *ev_stop) {
+    Shape s;
+    lsrm_status rc = make_shape(p, &s);
+    if (rc != LSRM_OK) return rc;
+    if (s.d != 64) return LSRM_ERR_UNSUPPORTED;
+    std::vector<int32_t> seg;
+    rc = make_segments(p, s, &seg);
+    if (rc != LSRM_OK) return rc;
+    if (s.nb == 0) return LSRM_OK;
+    const void *in[] = {d_q, d_k, d_v, d_kc, d_vc, d_out_branch, d_dout, d_dq, d_dk, d_dv};
+    for (const void *ptr : in)
+        if (ptr == nullptr || !aligned(ptr, 16)) return LSRM_ERR_INVALID_ARG;
+    if (d_gates == nullptr || d_lse == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (s.topk > 0 && d_idx == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < backward_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
+    return launch_backward(s, seg.data(), (int)seg.size() - 1, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_lse,
+                           d_out_branch, d_dout, d_dq, d_dk, d_dv, d_ws, static_cast<hipStream_t>(stream),
+                           static_cast<hipEvent_t>(ev_start), static_cast<hipEvent_t>(ev_stop));
 }
 
 }  // extern "C"

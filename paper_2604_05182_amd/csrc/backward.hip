@@ -1,0 +1,684 @@
+// NSA backward on gfx950 (App. A, Eq. nsa_1 differentiated): gradients with respect to q, k, v
+// of the gated sum of the compressed, selected and window branches, routing table and gate
+// weights held constant, average pooling differentiated.
+//
+// Per branch, with P the softmax probabilities (recomputed from the saved log-sum-exp), g the
+// gate, D_i = dout_i . o_branch_i and dP = dout V^T:
+//     dV = (g P)^T dout        dS = (g P) o (dP - D)        dQ = scale dS K        dK = scale dS^T Q
+// The gate is folded into the exponent: g P = exp2(S scale log2e - (lse log2e - log2 g)).
+//
+// No floating-point atomics: the work is split into passes that each own their output rows.
+//   bwd_dq_kernel    one workgroup per (query block, head): walks the same key tiles as the forward
+//                    (pooled, routed, window) and accumulates dQ^T in registers.
+//   bwd_dkv_kernel   one workgroup per (key block, head): walks the query tiles that attend it --
+//                    MODE 1: pooled keys, every query tile of the sequence (split into ranges whose
+//                    partial sums are added in order by MODE 0); MODE 0: token keys, the query tiles
+//                    of the window and of the reverse routing list (query blocks in ascending order)
+//                    -- accumulates dK^T and dV^T in registers, adds the pooled gradients / 64.
+// Every operand tile is a "tile image" (see forward.hip): MFMA A-operand fragments in row order
+// (rows permuted so that an accumulator is directly the B operand of the next contraction)
+// followed by fragments of the transposed tile.  The transposed S^T = K Q^T form of the forward is
+// used in the dQ pass (one query per lane: lse and D are per-lane scalars); the dK/dV pass uses
+// S = Q K^T (one key per lane; lse and D of the 32 queries of the tile come from a small
+// per-tile table copied to LDS with the tile).
+// Steps are not software pipelined: copy of tile t+1 (LDS DMA) overlaps the arithmetic of tile t.
+#include "lsrm_internal.h"
+
+namespace lsrm {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxSeg = 63;
+constexpr float kLog2e = 1.4426950408889634f;
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+struct BwdArgs {
+    const uint16_t *q, *k, *v, *kc, *vc, *dout, *out_branch;
+    const int32_t *idx;
+    const float *gates, *lse;
+    const char *img_q, *img_do, *img_k, *img_v, *img_kc, *img_vc;  // tile images
+    float *aux;               // [3][N/32][H][64]: per query tile, 32 x (lse log2e - log2 g) then 32 x D, rows permuted
+    float *part_k, *part_v;   // [n_split][nbp][H][d] fp32 partial gradients of the pooled keys / values
+    int32_t *rev_cnt, *rev_ptr, *rev_cur, *rev_idx;  // reverse routing lists
+    uint16_t *dq, *dk, *dv;
+    int32_t seg[kMaxSeg + 1];
+    int64_t n;
+    int nb, h, topk, window, n_seg;
+    int nt;               // query / key tiles of 32 tokens
+    int n_split, nbp, tiles_per_split;
+    float scale, sl2;
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    bf16x2 p;
+    p[0] = (__bf16)a;
+    p[1] = (__bf16)b;
+    return *reinterpret_cast<uint32_t *>(&p);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// row permutation of the tile images: bits 2 and 3 swapped
+__device__ __forceinline__ int perm32(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+union BFrag {
+    bf16x8 v;
+    uint32_t u[4];
+};
+
+// accumulator tile -> the two B operands (16-row slabs) of the next contraction
+__device__ __forceinline__ void to_b_operand(const float (&x)[16], BFrag (&b)[2]) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) b[k / 4].u[k % 4] = pack_bf16(x[2 * k], x[2 * k + 1]);
+}
+
+// copies n_kb KB, contiguous on both sides, global -> LDS; the two wavefronts of the workgroup split it
+template <int N_KB>
+__device__ __forceinline__ void copy_kb(const char *src, char *dst, int wave, uint32_t lane16) {
+#pragma unroll
+    for (int i = 0; i < N_KB; i += 2)
+        if (i + wave < N_KB)
+            __builtin_amdgcn_global_load_lds(GLB_PTR(src + (i + wave) * 1024 + lane16), LDS_PTR(dst + (i + wave) * 1024),
+                                             16, 0, 0);
+}
+
+template <int D>
+struct BGeo {
+    static constexpr int NS = D / 16, ND = D / 32;
+    static constexpr int ROW = 32 * D * 2;  // row-order fragments of a tile
+    static constexpr int TB = D * 64;       // fragments of the transposed tile
+    static constexpr int IMG = ROW + TB;
+    static constexpr int OUT_ROW = 2 * D + 8;  // padded bf16 row of the output staging (bytes)
+};
+
+// rows of a [D x 32] accumulator pair set (transposed gradient tile) -> bf16 rows of `dst`
+// (32 rows of this wavefront, row stride h*D elements), staged through LDS so that rows are
+// written as whole 16-byte chunks.  x[dt][i]: channel 32 dt + (i/4)*8 + hh*4 + i%4, row lane%32.
+template <int D>
+__device__ __forceinline__ void store_rows_transposed(const float (&x)[D / 32][16], char *stage, uint16_t *dst,
+                                                      int64_t row_stride, int lane) {
+    using G = BGeo<D>;
+    const int r = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int dt = 0; dt < G::ND; ++dt)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            uint2 w2;
+            w2.x = pack_bf16(x[dt][4 * gq + 0], x[dt][4 * gq + 1]);
+            w2.y = pack_bf16(x[dt][4 * gq + 2], x[dt][4 * gq + 3]);
+            *reinterpret_cast<uint2 *>(stage + r * G::OUT_ROW + (32 * dt + 8 * gq + 4 * hh) * 2) = w2;
+        }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wavefront's own staging writes
+    constexpr int CH = D / 8, RPP = 64 / CH;
+#pragma unroll
+    for (int it = 0; it < 32 / RPP; ++it) {
+        const int rr = it * RPP + lane / CH, ch = lane % CH;
+        uint4 val = *reinterpret_cast<const uint4 *>(stage + rr * G::OUT_ROW + ch * 16);
+        *reinterpret_cast<uint4 *>(dst + rr * row_stride + ch * 8) = val;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// per (token, head): the per-branch exponent offset and D = dout . o_branch, in tile-image row order
+template <int D>
+__global__ __launch_bounds__(256) void bwd_prep(BwdArgs a) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= a.n * a.h) return;
+    const int64_t row = e / a.h;
+    const int head = (int)(e % a.h);
+    const uint4 *dor = reinterpret_cast<const uint4 *>(a.dout + (row * a.h + head) * D);
+    float dov[D];
+#pragma unroll
+    for (int c = 0; c < D / 8; ++c) {
+        uint4 w = dor[c];
+        uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            dov[8 * c + 2 * j] = bf16_lo(u[j]);
+            dov[8 * c + 2 * j + 1] = bf16_hi(u[j]);
+        }
+    }
+    const int64_t tile = row >> 5;
+    const int pr = perm32((int)(row & 31));
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        const uint4 *obr = reinterpret_cast<const uint4 *>(a.out_branch + (((int64_t)b * a.n + row) * a.h + head) * D);
+        float dl = 0.f;
+#pragma unroll
+        for (int c = 0; c < D / 8; ++c) {
+            uint4 w = obr[c];
+            uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dl += dov[8 * c + 2 * j] * bf16_lo(u[j]) + dov[8 * c + 2 * j + 1] * bf16_hi(u[j]);
+        }
+        const float lse = a.lse[((int64_t)b * a.n + row) * a.h + head];
+        const float g = a.gates[(row * a.h + head) * 3 + b];
+        // an empty key set (lse = -inf) or a zero gate gives zero probabilities: offset +inf
+        float l2 = __builtin_inff();
+        if (g > 0.f && lse > -__builtin_inff()) l2 = lse * kLog2e - __log2f(g);
+        float *ax = a.aux + (((int64_t)b * a.nt + tile) * a.h + head) * 64;
+        ax[pr] = l2;
+        ax[32 + pr] = dl;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// reverse routing lists: for every key block the query blocks that list it, ascending
+__global__ void fill_zero(int32_t *p, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+__global__ void rev_count(BwdArgs a) {
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= a.nb * a.topk) return;
+    int v = a.idx[e];
+    if (v >= 0 && v < a.nb) atomicAdd(&a.rev_cnt[v], 1);
+}
+__global__ __launch_bounds__(1024) void rev_scan(BwdArgs a) {
+    __shared__ int part[1024];
+    const int t = threadIdx.x;
+    const int chunk = (a.nb + 1023) / 1024;
+    const int lo = min(t * chunk, a.nb), hi = min(lo + chunk, a.nb);
+    int s = 0;
+    for (int i = lo; i < hi; ++i) s += a.rev_cnt[i];
+    part[t] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        int x = t >= off ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += x;
+        __syncthreads();
+    }
+    int run = part[t] - s;  // exclusive prefix of this chunk
+    for (int i = lo; i < hi; ++i) {
+        a.rev_ptr[i] = run;
+        a.rev_cur[i] = run;
+        run += a.rev_cnt[i];
+    }
+    if (t == 1023) a.rev_ptr[a.nb] = part[1023];
+}
+__global__ void rev_fill(BwdArgs a) {
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= a.nb * a.topk) return;
+    int v = a.idx[e];
+    if (v >= 0 && v < a.nb) a.rev_idx[atomicAdd(&a.rev_cur[v], 1)] = e / a.topk;
+}
+__global__ void rev_sort(BwdArgs a) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= a.nb) return;
+    int32_t *x = a.rev_idx + a.rev_ptr[b];
+    const int len = a.rev_ptr[b + 1] - a.rev_ptr[b];
+    for (int i = 1; i < len; ++i) {
+        int v = x[i], j = i - 1;
+        while (j >= 0 && x[j] > v) {
+            x[j + 1] = x[j];
+            --j;
+        }
+        x[j + 1] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dQ: one workgroup (2 wavefronts x 32 query rows) per (query block, head)
+template <int D>
+__global__ __launch_bounds__(128) void bwd_dq_kernel(BwdArgs a) {
+    using G = BGeo<D>;
+    constexpr int NS = G::NS, ND = G::ND;
+    constexpr int TILE = G::IMG + G::ROW;  // K rows | K^T | V rows
+    static_assert(2 * 32 * G::OUT_ROW <= 2 * TILE, "output staging fits in the tile buffers");
+    __shared__ __attribute__((aligned(1024))) char lds[2 * TILE];
+    const int qb = blockIdx.x, head = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, hh = lane >> 5;
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    const int64_t row0 = (int64_t)qb * 64 + 32 * wave;
+    const int half_w = a.window / 2;
+
+    bf16x8 qf[NS], dof[NS];
+    {
+        const uint16_t *qrow = a.q + ((row0 + r) * a.h + head) * D + 8 * hh;
+        const uint16_t *drow = a.dout + ((row0 + r) * a.h + head) * D + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks) {
+            qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
+            dof[ks] = *reinterpret_cast<const bf16x8 *>(drow + 16 * ks);
+        }
+    }
+    float l2[3], dl[3];
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        const float *ax = a.aux + (((int64_t)b * a.nt + (row0 >> 5)) * a.h + head) * 64;
+        l2[b] = ax[perm32(r)];
+        dl[b] = ax[32 + perm32(r)];
+    }
+    f32x16 acc[ND];
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
+
+    // ---- the tiles of this query block: pooled, routed, window
+    const int tc = (a.nb + 31) / 32;
+    int packed = -1, n_valid = 0;
+    {
+        int v = lane < a.topk ? a.idx[(int64_t)qb * a.topk + lane] : -1;
+        if (v >= a.nb) v = -1;
+        const unsigned long long valid = __ballot(v >= 0);
+        n_valid = __popcll(valid);
+        const int rank = __popcll(valid & ((1ull << lane) - 1ull));
+        packed = __builtin_amdgcn_ds_permute((v >= 0 ? rank : 63) * 4, v);
+        if (n_valid == 64) packed = v;
+    }
+    const int ts = 2 * n_valid;
+    int seg_lo = 0, seg_hi = 0;
+    for (int s = 0; s < a.n_seg; ++s)
+        if (qb * 64 >= a.seg[s] && qb * 64 < a.seg[s + 1]) {
+            seg_lo = a.seg[s];
+            seg_hi = a.seg[s + 1];
+        }
+    const int k_start = max(seg_lo, qb * 64 - half_w), k_end = min(seg_hi, qb * 64 + 63 + half_w);
+    const int st0 = k_start / 32;
+    const int tw = k_end > k_start ? (k_end - 1) / 32 + 1 - st0 : 0;
+    const int T = tc + ts + tw;
+    const int wlo = max(seg_lo, (int)row0 + r - half_w), whi = min(seg_hi, (int)row0 + r + half_w);
+
+    auto issue = [&](int t, char *buf) {
+        const char *kimg, *vimg;
+        int64_t tile;
+        if (t < tc) {
+            tile = t;
+            kimg = a.img_kc;
+            vimg = a.img_vc;
+        } else {
+            if (t < tc + ts) {
+                const int u = t - tc;
+                tile = 2 * (int64_t)__builtin_amdgcn_readlane(packed, u >> 1) + (u & 1);
+            } else {
+                tile = st0 + (t - tc - ts);
+            }
+            kimg = a.img_k;
+            vimg = a.img_v;
+        }
+        const int64_t off = (tile * a.h + head) * G::IMG;
+        copy_kb<G::IMG / 1024>(kimg + off, buf, wave, lane16);
+        copy_kb<G::ROW / 1024>(vimg + off, buf + G::IMG, wave, lane16);
+    };
+
+    if (T > 0) issue(0, lds);
+    for (int t = 0; t < T; ++t) {
+        __syncthreads();  // tile t has landed for both wavefronts; both are done with the other buffer
+        if (t + 1 < T) issue(t + 1, lds + ((t + 1) & 1) * TILE);
+        const int br = t < tc ? 0 : (t < tc + ts ? 1 : 2);
+        const int j0 = br == 0 ? 32 * t : (br == 1 ? 0 : 32 * (st0 + t - tc - ts));
+        const int lo = br == 0 ? 0 : (br == 1 ? -0x40000000 : wlo);
+        const int hi = br == 0 ? a.nb : (br == 1 ? 0x7fffffff : whi);
+        const float lb = br == 0 ? l2[0] : (br == 1 ? l2[1] : l2[2]);
+        const float db = br == 0 ? dl[0] : (br == 1 ? dl[1] : dl[2]);
+        const char *base = lds + (t & 1) * TILE + lane16;
+
+        f32x16 s, dp;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), qf[ks], s, 0,
+                                                        0, 0);
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks)
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::IMG + ks * 1024),
+                                                         dof[ks], dp, 0, 0, 0);
+        float ds[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
+            float p = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb);
+            p = (j >= lo && j < hi) ? p : 0.f;
+            ds[i] = p * (dp[i] - db);
+        }
+        BFrag dsb[2];
+        to_b_operand(ds, dsb);
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+            for (int dt = 0; dt < ND; ++dt)
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + (ks2 * ND + dt) * 1024), dsb[ks2].v, acc[dt], 0, 0, 0);
+    }
+    __syncthreads();  // the tile buffers become the output staging
+    float x[ND][16];
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[dt][i] = acc[dt][i] * a.scale;
+    store_rows_transposed<D>(x, lds + wave * 32 * G::OUT_ROW, a.dq + (row0 * a.h + head) * D, (int64_t)a.h * D, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dK, dV: one workgroup (2 wavefronts x 32 keys) per (key block, head[, query range])
+template <int D, int MODE>
+__global__ __launch_bounds__(128) void bwd_dkv_kernel(BwdArgs a) {
+    using G = BGeo<D>;
+    constexpr int NS = G::NS, ND = G::ND;
+    constexpr int AUX = 2 * G::IMG;         // Q rows | Q^T | dO rows | dO^T | table (64 floats)
+    constexpr int TILE = 2 * G::IMG + 1024;  // (table padded to keep the next buffer aligned)
+    static_assert(2 * 32 * G::OUT_ROW <= 2 * TILE, "output staging fits in the tile buffers");
+    __shared__ __attribute__((aligned(1024))) char lds[2 * TILE];
+    const int kb = blockIdx.x, head = blockIdx.y;
+    const int split = MODE == 1 ? blockIdx.z : 0;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, hh = lane >> 5;
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    const int64_t key0 = (int64_t)kb * 64 + 32 * wave;  // token index (MODE 0) or pooled-key index (MODE 1)
+    const int64_t key = key0 + r;
+    const int64_t limit = MODE == 0 ? a.n : (int64_t)a.nb;
+    const int half_w = a.window / 2;
+
+    bf16x8 kB[NS], vB[NS];
+    {
+        const int64_t krow_i = key < limit ? key : limit - 1;  // (rows past the end are masked below)
+        const uint16_t *krow = (MODE == 0 ? a.k : a.kc) + (krow_i * a.h + head) * D + 8 * hh;
+        const uint16_t *vrow = (MODE == 0 ? a.v : a.vc) + (krow_i * a.h + head) * D + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks) {
+            kB[ks] = *reinterpret_cast<const bf16x8 *>(krow + 16 * ks);
+            vB[ks] = *reinterpret_cast<const bf16x8 *>(vrow + 16 * ks);
+        }
+    }
+    f32x16 acck[ND], accv[ND];
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acck[dt][i] = accv[dt][i] = 0.f;
+
+    // ---- the query tiles that attend these keys
+    int tw = 0, wt0 = 0, ts = 0, e0 = 0, T;
+    if (MODE == 1) {
+        wt0 = split * a.tiles_per_split;
+        T = max(0, min(a.nt, wt0 + a.tiles_per_split) - wt0);
+    } else {
+        const int k0 = kb * 64;
+        int seg_lo = 0, seg_hi = 0;
+        for (int s = 0; s < a.n_seg; ++s)
+            if (k0 >= a.seg[s] && k0 < a.seg[s + 1]) {
+                seg_lo = a.seg[s];
+                seg_hi = a.seg[s + 1];
+            }
+        // query i sees key j iff -W/2 <= j - i < W/2, i.e. j - W/2 < i <= j + W/2
+        const int i_lo = max(seg_lo, k0 - half_w + 1), i_hi = min(seg_hi, k0 + 63 + half_w + 1);
+        wt0 = i_lo / 32;
+        tw = (half_w > 0 && i_hi > i_lo) ? (i_hi - 1) / 32 + 1 - wt0 : 0;
+        e0 = a.rev_ptr[kb];
+        ts = 2 * (a.rev_ptr[kb + 1] - e0);
+        T = tw + ts;
+    }
+    auto tile_of = [&](int t) -> int64_t {
+        if (MODE == 1 || t < tw) return wt0 + t;
+        const int u = t - tw;
+        return 2 * (int64_t)a.rev_idx[e0 + (u >> 1)] + (u & 1);
+    };
+    auto branch_of = [&](int t) { return MODE == 1 ? 0 : (t < tw ? 2 : 1); };
+    auto issue = [&](int t, char *buf) {
+        const int64_t tile = tile_of(t);
+        const int64_t off = (tile * a.h + head) * G::IMG;
+        copy_kb<G::IMG / 1024>(a.img_q + off, buf, wave, lane16);
+        copy_kb<G::IMG / 1024>(a.img_do + off, buf + G::IMG, wave, lane16);
+        if (wave == 0) {
+            const float *ax = a.aux + (((int64_t)branch_of(t) * a.nt + tile) * a.h + head) * 64;
+            __builtin_amdgcn_global_load_lds(GLB_PTR(ax + lane), LDS_PTR(buf + AUX), 4, 0, 0);
+        }
+    };
+
+    if (T > 0) issue(0, lds);
+    for (int t = 0; t < T; ++t) {
+        __syncthreads();
+        if (t + 1 < T) issue(t + 1, lds + ((t + 1) & 1) * TILE);
+        const char *buf = lds + (t & 1) * TILE;
+        const char *base = buf + lane16;
+        const int q0 = 32 * (int)tile_of(t);
+        const bool win = MODE == 0 && t < tw;
+
+        f32x16 s;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), kB[ks], s, 0,
+                                                        0, 0);
+        // table entries of the 16 query rows this lane holds: rows (i/4)*8 + hh*4 + i%4
+        float lv[16], dv_[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(buf + AUX + (8 * g + 4 * hh) * 4);
+            const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                lv[4 * g + j] = x[j];
+                dv_[4 * g + j] = y[j];
+            }
+        }
+        float p[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float pi = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lv[i]);
+            if (MODE == 1) {
+                pi = key < limit ? pi : 0.f;
+            } else if (win) {
+                const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);  // the query behind accumulator row i
+                const int dj = (int)key - qi;
+                pi = (dj >= -half_w && dj < half_w) ? pi : 0.f;
+            }
+            p[i] = pi;
+        }
+        BFrag pb[2];
+        to_b_operand(p, pb);
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+            for (int dt = 0; dt < ND; ++dt)
+                accv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    *reinterpret_cast<const bf16x8 *>(base + G::IMG + G::ROW + (ks2 * ND + dt) * 1024), pb[ks2].v, accv[dt], 0,
+                    0, 0);
+        f32x16 dp;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dp[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks)
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::IMG + ks * 1024),
+                                                         vB[ks], dp, 0, 0, 0);
+        float ds[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ds[i] = p[i] * (dp[i] - dv_[i]);
+        BFrag dsb[2];
+        to_b_operand(ds, dsb);
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+            for (int dt = 0; dt < ND; ++dt)
+                acck[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + (ks2 * ND + dt) * 1024), dsb[ks2].v, acck[dt], 0, 0, 0);
+    }
+
+    if (MODE == 1) {
+        // partial sums of this query range: [split][pooled key][head][channel] fp32
+        const int64_t o = (((int64_t)split * a.nbp + key) * a.h + head) * D;
+#pragma unroll
+        for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 xk, xv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    xk[j] = acck[dt][4 * g + j];
+                    xv[j] = accv[dt][4 * g + j];
+                }
+                *reinterpret_cast<f32x4 *>(a.part_k + o + 32 * dt + 8 * g + 4 * hh) = xk;
+                *reinterpret_cast<f32x4 *>(a.part_v + o + 32 * dt + 8 * g + 4 * hh) = xv;
+            }
+    } else {
+        // add the gradient of the pooled key / value of this block (its query ranges in order), / 64
+        float xk[ND][16], xv[ND][16];
+#pragma unroll
+        for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 pk = {0.f, 0.f, 0.f, 0.f}, pv = {0.f, 0.f, 0.f, 0.f};
+                for (int sp = 0; sp < a.n_split; ++sp) {
+                    const int64_t o = (((int64_t)sp * a.nbp + kb) * a.h + head) * D + 32 * dt + 8 * g + 4 * hh;
+                    pk += *reinterpret_cast<const f32x4 *>(a.part_k + o);
+                    pv += *reinterpret_cast<const f32x4 *>(a.part_v + o);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    xk[dt][4 * g + j] = (acck[dt][4 * g + j] + pk[j] * (1.0f / 64.0f)) * a.scale;
+                    xv[dt][4 * g + j] = accv[dt][4 * g + j] + pv[j] * (1.0f / 64.0f);
+                }
+            }
+        __syncthreads();  // the tile buffers become the output staging
+        char *stage = lds + wave * 32 * G::OUT_ROW;
+        store_rows_transposed<D>(xk, stage, a.dk + (key0 * a.h + head) * D, (int64_t)a.h * D, lane);
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // staging reads of dK done before it is overwritten
+        store_rows_transposed<D>(xv, stage, a.dv + (key0 * a.h + head) * D, (int64_t)a.h * D, lane);
+    }
+}
+
+struct WsLayout {
+    size_t img_q, img_do, img_k, img_v, img_kc, img_vc, aux, part_k, part_v, rev_cnt, rev_ptr, rev_cur, rev_idx, total;
+    int n_split, nbp, tiles_per_split;
+};
+
+WsLayout ws_layout(const Shape &s) {
+    WsLayout w;
+    const size_t img = (size_t)s.d * 128;  // bytes of one (tile, head) image
+    const size_t nt = (size_t)s.nb * 2, ntc = (size_t)(s.nb + 31) / 32;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off += align_up(bytes > 0 ? bytes : 1, 256);
+        return at;
+    };
+    w.img_q = take(nt * s.h * img);
+    w.img_do = take(nt * s.h * img);
+    w.img_k = take(nt * s.h * img);
+    w.img_v = take(nt * s.h * img);
+    w.img_kc = take(ntc * s.h * img);
+    w.img_vc = take(ntc * s.h * img);
+    w.aux = take((size_t)3 * nt * s.h * 64 * 4);
+    // pooled keys: enough query ranges to fill the chip
+    w.nbp = (s.nb + 63) / 64 * 64;
+    const int wgs = (w.nbp / 64) * s.h;
+    int n_split = (2048 + wgs - 1) / wgs;
+    n_split = n_split < 1 ? 1 : (n_split > 16 ? 16 : n_split);
+    w.tiles_per_split = (int)((nt + n_split - 1) / n_split);
+    w.n_split = (int)((nt + w.tiles_per_split - 1) / (w.tiles_per_split > 0 ? w.tiles_per_split : 1));
+    if (w.n_split < 1) w.n_split = 1;
+    w.part_k = take((size_t)w.n_split * w.nbp * s.h * s.d * 4);
+    w.part_v = take((size_t)w.n_split * w.nbp * s.h * s.d * 4);
+    w.rev_cnt = take((size_t)s.nb * 4);
+    w.rev_ptr = take((size_t)(s.nb + 1) * 4);
+    w.rev_cur = take((size_t)s.nb * 4);
+    w.rev_idx = take((size_t)s.nb * (s.topk > 0 ? s.topk : 1) * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t backward_ws_bytes(const Shape &s) { return ws_layout(s).total; }
+
+lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
+                            const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,
+                            const int32_t *d_idx, const float *d_gates, const float *d_lse,
+                            const uint16_t *d_out_branch, const uint16_t *d_dout, uint16_t *d_dq, uint16_t *d_dk,
+                            uint16_t *d_dv, void *d_ws, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    if (s.nb == 0) return LSRM_OK;
+    if (n_seg > kMaxSeg || s.d != 64) return LSRM_ERR_UNSUPPORTED;
+    constexpr int D = 64;
+    const WsLayout w = ws_layout(s);
+    char *ws = reinterpret_cast<char *>(d_ws);
+    BwdArgs a{};
+    a.q = d_q;
+    a.k = d_k;
+    a.v = d_v;
+    a.kc = d_kc;
+    a.vc = d_vc;
+    a.dout = d_dout;
+    a.out_branch = d_out_branch;
+    a.idx = d_idx;
+    a.gates = d_gates;
+    a.lse = d_lse;
+    a.img_q = ws + w.img_q;
+    a.img_do = ws + w.img_do;
+    a.img_k = ws + w.img_k;
+    a.img_v = ws + w.img_v;
+    a.img_kc = ws + w.img_kc;
+    a.img_vc = ws + w.img_vc;
+    a.aux = reinterpret_cast<float *>(ws + w.aux);
+    a.part_k = reinterpret_cast<float *>(ws + w.part_k);
+    a.part_v = reinterpret_cast<float *>(ws + w.part_v);
+    a.rev_cnt = reinterpret_cast<int32_t *>(ws + w.rev_cnt);
+    a.rev_ptr = reinterpret_cast<int32_t *>(ws + w.rev_ptr);
+    a.rev_cur = reinterpret_cast<int32_t *>(ws + w.rev_cur);
+    a.rev_idx = reinterpret_cast<int32_t *>(ws + w.rev_idx);
+    a.dq = d_dq;
+    a.dk = d_dk;
+    a.dv = d_dv;
+    for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
+    a.n = s.n;
+    a.nb = s.nb;
+    a.h = s.h;
+    a.topk = s.topk;
+    a.window = s.window;
+    a.n_seg = n_seg;
+    a.nt = s.nb * 2;
+    a.n_split = w.n_split;
+    a.nbp = w.nbp;
+    a.tiles_per_split = w.tiles_per_split;
+    a.scale = s.scale;
+    a.sl2 = s.scale * kLog2e;
+
+    if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
+    const int ntc = (s.nb + 31) / 32;
+    lsrm_status rc;
+    if ((rc = launch_pack_tiles(D, d_q, d_q, ws + w.img_q, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, d_dout, d_dout, ws + w.img_do, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, d_k, d_k, ws + w.img_k, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, d_v, d_v, ws + w.img_v, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, d_kc, d_kc, ws + w.img_kc, (int64_t)s.nb, s.h, ntc, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, d_vc, d_vc, ws + w.img_vc, (int64_t)s.nb, s.h, ntc, st)) != LSRM_OK) return rc;
+    hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)((s.n * s.h + 255) / 256)), dim3(256), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    // reverse routing lists
+    hipLaunchKernelGGL(fill_zero, dim3((s.nb + 255) / 256), dim3(256), 0, st, a.rev_cnt, s.nb);
+    LSRM_HIP_CHECK(hipGetLastError());
+    if (s.topk > 0) {
+        hipLaunchKernelGGL(rev_count, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
+        LSRM_HIP_CHECK(hipGetLastError());
+    }
+    hipLaunchKernelGGL(rev_scan, dim3(1), dim3(1024), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    if (s.topk > 0) {
+        hipLaunchKernelGGL(rev_fill, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
+        LSRM_HIP_CHECK(hipGetLastError());
+        hipLaunchKernelGGL(rev_sort, dim3((s.nb + 63) / 64), dim3(64), 0, st, a);
+        LSRM_HIP_CHECK(hipGetLastError());
+    }
+    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3(s.nb, s.h), dim3(128), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3(w.nbp / 64, s.h, w.n_split), dim3(128), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3(s.nb, s.h), dim3(128), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
+    return LSRM_OK;
+}
+
+}  // namespace lsrm

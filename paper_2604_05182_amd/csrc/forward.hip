@@ -493,28 +493,6 @@ __device__ __forceinline__ float own_pv_max(WaveCtx<G> &c, const bf16x8 (&vf)[G:
     return mx;
 }
 
-// Non-pipelined step (selected phase): fragments, scores, softmax and PV of one tile in
-// sequence; with two row tiles the exponentials of the second run under the PV of the first.
-template <class G>
-__device__ __forceinline__ void step_compute(WaveCtx<G> &c, const char *slot, int lane, float sl2) {
-    bf16x8 kf[G::NS];
-    bf16x8 vf[G::ND][2];
-    read_k<G>(c, slot, kf);
-    read_v<G>(c, slot, vf);
-    f32x16 s[G::QT];
-    qk_scores<G>(c, kf, s);
-#pragma unroll
-    for (int qt = 0; qt < G::QT; ++qt) update_max<G>(c, qt, lane_max(s[qt]), sl2, nullptr);
-    uint32_t pu[G::QT][8];
-    exp_tile<G>(c, 0, s[0], pu[0], sl2);
-    if constexpr (G::QT == 2) {
-        pv0_exp1<G>(c, vf, pu[0], s[1], pu[1], sl2);
-        pv_tile<G>(c, 1, vf, pu[1]);
-    } else {
-        pv_tile<G>(c, 0, vf, pu[0]);
-    }
-}
-
 // Shared phase (compressed and window branches): every tile is used by all query blocks of
 // the workgroup.  Tiles go through the ring of NSLOT slots; a slot is refilled as soon as
 // every wavefront is done with it.
@@ -1109,6 +1087,18 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
 }  // namespace
 
 size_t forward_ws_bytes(const Shape &s) { return ws_layout(s).total; }
+
+lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t_src, char *img, int64_t n_rows, int h,
+                              int n_tiles, hipStream_t st) {
+    if (n_tiles <= 0) return LSRM_OK;
+    const dim3 grid((n_tiles + 1) / 2, h);
+    if (d == 64)
+        hipLaunchKernelGGL(pack_tiles<64>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
+    else
+        hipLaunchKernelGGL(pack_tiles<128>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
+    LSRM_HIP_CHECK(hipGetLastError());
+    return LSRM_OK;
+}
 
 lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
                            const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,

@@ -41,5 +41,16 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
                            float *d_lse, uint16_t *d_out_branch, void *d_ws, hipStream_t st, hipEvent_t ev_start,
                            hipEvent_t ev_stop);
 size_t forward_ws_bytes(const Shape &s);
+// Tile images (see forward.hip): img[tile][head] = row-order fragments of `rows_src`, then transposed
+// fragments of `t_src`, both [n_rows, H, d] bf16; n_tiles tiles of 32 rows.
+lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t_src, char *img, int64_t n_rows, int h,
+                              int n_tiles, hipStream_t st);
+
+lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
+                            const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,
+                            const int32_t *d_idx, const float *d_gates, const float *d_lse,
+                            const uint16_t *d_out_branch, const uint16_t *d_dout, uint16_t *d_dq, uint16_t *d_dk,
+                            uint16_t *d_dv, void *d_ws, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+size_t backward_ws_bytes(const Shape &s);
 
 }  // namespace lsrm

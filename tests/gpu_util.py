@@ -66,6 +66,27 @@ def run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets="default
     return res
 
 
+def run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offsets="default", scale=0.0, window=None):
+    """compress + forward (saving lse and branch outputs) + backward on the device -> dq, dk, dv as float32 numpy."""
+    topk = idx.shape[1]
+    p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window)
+    dq_in, ddo = bf16_dev(q_bits), bf16_dev(dout_bits)
+    dk_in, dv_in, kc, vc = run_compress(B, cfg, k_bits, v_bits)
+    d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
+    d_g = torch.from_numpy(gates).cuda()
+    out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((3, cfg.n, cfg.heads), dtype=torch.float32, device="cuda")
+    ob = torch.empty((3, cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
+    ws = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
+    B.lsrm_nsa_forward(p, dq_in, dk_in, dv_in, kc, vc, d_idx, d_g, out, lse, ob, ws)
+    gq = torch.full_like(out, float("nan"))
+    gk, gv = torch.full_like(out, float("nan")), torch.full_like(out, float("nan"))
+    wsb = B.alloc_workspace(p, B.LSRM_WS_BACKWARD)
+    B.lsrm_nsa_backward(p, dq_in, dk_in, dv_in, kc, vc, d_idx, d_g, lse, ob, ddo, gq, gk, gv, wsb)
+    torch.cuda.synchronize()
+    return bf16_host(gq), bf16_host(gk), bf16_host(gv)
+
+
 def attention_errors(got: np.ndarray, ref: np.ndarray):
     """(max-abs error, relative L2 error) in float64."""
     g, r = got.astype(np.float64), ref.astype(np.float64)

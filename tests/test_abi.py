@@ -15,8 +15,8 @@ def _declared():
 
 def test_header_declares_the_entry_points():
     names = _declared()
-    for must in ("lsrm_route_blocks", "lsrm_nsa_compress", "lsrm_nsa_forward", "lsrm_workspace_bytes",
-                 "lsrm_strerror"):
+    for must in ("lsrm_route_blocks", "lsrm_nsa_compress", "lsrm_nsa_forward", "lsrm_nsa_backward",
+                 "lsrm_workspace_bytes", "lsrm_strerror"):
         assert must in names
 
 
@@ -41,4 +41,12 @@ def test_host_side_argument_checks():
     assert B.strerror(B.LSRM_ERR_WORKSPACE).startswith("workspace")
     # null pointers are rejected before anything is launched
     rc = B._lib.lsrm_nsa_compress(__import__("ctypes").byref(ok), None, None, None, None, None)
+    assert rc == B.LSRM_ERR_INVALID_ARG
+    # the backward supports d = 64 only and says so before anything is launched
+    assert B.lsrm_workspace_bytes(ok, B.LSRM_WS_BACKWARD) > 0
+    wide = B.make_params(512, 2, 16, 2, 128, 3, 128)
+    assert B.lsrm_workspace_bytes(wide, B.LSRM_WS_BACKWARD) == 0
+    rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(wide), *([None] * 14), 0, None, None, None)
+    assert rc == B.LSRM_ERR_UNSUPPORTED
+    rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(ok), *([None] * 14), 0, None, None, None)
     assert rc == B.LSRM_ERR_INVALID_ARG

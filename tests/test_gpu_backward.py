@@ -1,0 +1,109 @@
+"""GPU parity of lsrm_nsa_backward (d = 64) against the CPU oracle's analytic gradients, element by
+element on small cases and on a sample of blocks and heads at the full size of config 5.
+Tolerance as for the forward: max-abs <= 2e-2 and relative L2 <= 5e-3 per gradient tensor."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2604_05182_amd import inputs as I
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2604_05182_amd import binding
+    return binding
+
+
+def _log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def _case(B, oracle_lib, cfg, idx=None, seg="default", scale=0.0, window=None):
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates, dout_bits = I.make_gates(cfg), I.make_dout(cfg)
+    if idx is None:
+        idx, _ = oracle_lib.route(I.make_points(cfg), I.make_cameras(cfg), cfg.grid, cfg.topk)
+    seg_arr = cfg.seg_offsets() if isinstance(seg, str) else np.asarray(seg, dtype=np.int32)
+    window = cfg.window if window is None else window
+    got = G.run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offsets=seg, scale=scale,
+                         window=window)
+    q, k, v, dout = (I.bf16_bits_to_f32(a) for a in (q_bits, k_bits, v_bits, dout_bits))
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    return got, (q, k, v, kc, vc, idx, gates, seg_arr, window, dout)
+
+
+def _assert_grads(got, ref, tag):
+    for name, g, r in zip(("dq", "dk", "dv"), got, ref):
+        assert np.isfinite(g).all(), f"{tag} {name}: non-finite values"
+        ma, rl = G.attention_errors(g, r)
+        _log(f"[backward] {tag} {name}: max-abs {ma:.3e} rel-L2 {rl:.3e}  (|ref| max {np.abs(r).max():.3e})")
+        assert ma <= G.MAX_ABS_TOL and rl <= G.REL_L2_TOL, (tag, name, ma, rl)
+
+
+def test_backward_small(B, oracle_lib):
+    cfg = I.small_config(name="b-small", n_obj=512, n_views=2, grid=16, heads=2, d=64, topk=3, window=128)
+    _log(f"[backward] {cfg.name}")
+    got, args = _case(B, oracle_lib, cfg)
+    _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
+
+
+def test_backward_ragged_and_holes(B, oracle_lib):
+    """NB not a multiple of 32, odd head count, -1 holes, an empty routed row, key blocks nobody routes
+    to, a window that is not a multiple of the block, explicit scale."""
+    cfg = I.small_config(name="b-ragged", n_obj=1088, n_views=3, grid=24, heads=3, d=64, topk=5, window=200, seed=21)
+    _log(f"[backward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(5)
+    idx = np.stack([rng.choice(cfg.nb // 2, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.2] = -1
+    idx[2] = -1
+    got, args = _case(B, oracle_lib, cfg, idx=idx, scale=0.2)
+    _assert_grads(got, oracle_lib.nsa_backward(*args, scale=0.2), cfg.name)
+
+
+def test_backward_zero_window_and_topk_one(B, oracle_lib):
+    cfg = I.small_config(name="b-w0", n_obj=256, n_views=1, grid=16, heads=1, d=64, topk=1, window=0)
+    got, args = _case(B, oracle_lib, cfg)
+    _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
+
+
+def test_backward_single_segment_wide_window(B, oracle_lib):
+    """One segment, window wider than the sequence, every block routed by every block."""
+    cfg = I.small_config(name="b-dense", n_obj=512, n_views=0, grid=0, heads=2, d=64, topk=8, window=1024)
+    idx = np.tile(np.arange(8, dtype=np.int32), (8, 1))
+    got, args = _case(B, oracle_lib, cfg, idx=idx, seg=[0, 512])
+    _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
+
+
+def test_backward_config5_full_size_sampled(B, oracle_lib):
+    """Full-size launch of config 5; the oracle evaluates dq on sampled query blocks and dk, dv on
+    sampled key blocks (contributions of every query of the sequence), three heads."""
+    cfg = I.CONFIGS[5]
+    qblocks = I.sample_query_blocks(cfg, 3)
+    kblocks = I.sample_query_blocks(cfg, 2, seed=5)[::2]
+    heads = [0, 7, cfg.heads - 1]
+    _log(f"[backward] config 5 full-size launch; oracle on {len(qblocks)} query blocks, {len(kblocks)} key blocks, "
+         f"heads {heads}")
+    got, args = _case(B, oracle_lib, cfg)
+    (q, k, v, kc, vc, idx, gates, seg_arr, window, dout) = args
+    ref = oracle_lib.nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg_arr, window, dout, qblocks, kblocks, heads)
+    rows_q = (np.asarray(qblocks)[:, None] * 64 + np.arange(64)[None]).reshape(-1)
+    rows_k = (np.asarray(kblocks)[:, None] * 64 + np.arange(64)[None]).reshape(-1)
+    sub = (got[0][rows_q][:, heads], got[1][rows_k][:, heads], got[2][rows_k][:, heads])
+    _assert_grads(sub, ref, "config5-sampled")
+    assert all(np.isfinite(g).all() for g in got)
+
+
+def test_backward_is_deterministic(B, oracle_lib):
+    cfg = I.small_config(name="b-det", n_obj=1024, n_views=2, grid=16, heads=2, d=64, topk=4, window=256)
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates, dout_bits = I.make_gates(cfg), I.make_dout(cfg)
+    idx, _ = oracle_lib.route(I.make_points(cfg), I.make_cameras(cfg), cfg.grid, cfg.topk)
+    a = G.run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits)
+    b = G.run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
