@@ -6,7 +6,10 @@ lsrm_nsa_compress -> lsrm_nsa_forward, inputs already resident in HBM.  The metr
 effective attention TFLOP/s (4 d h x attended (query, key) pairs; masked or padded work
 does not count) and ms per layer.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..4] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+
+--config 5 times the backward instead (config 2 shapes): a step is one lsrm_nsa_backward call on
+resident inputs and saved forward results; effective FLOPs = 2.5 x the forward's (5 contractions).
 """
 from __future__ import annotations
 
@@ -61,12 +64,111 @@ def cpu_baseline(cfg, arrays, idx, target_seconds=20.0):
     }
 
 
+def cpu_baseline_backward(cfg, arrays, idx, dout_bits, target_seconds=20.0):
+    """Times the CPU oracle's sampled gradient function on a bounded sample (query blocks only: dq)."""
+    import oracle
+    from paper_2604_05182_amd import inputs as I
+    q, k, v = (I.bf16_bits_to_f32(a) for a in arrays["qkv_bits"])
+    dout = I.bf16_bits_to_f32(dout_bits)
+    kc, vc = oracle.pool(k), oracle.pool(v)
+    seg = cfg.seg_offsets()
+    threads = oracle.num_threads()
+    heads = list(range(cfg.heads))
+    none = np.zeros((0,), dtype=np.int32)
+    probe = I.sample_query_blocks(cfg, 0)[:2]
+    t0 = time.perf_counter()
+    oracle.nsa_backward_sampled(q, k, v, kc, vc, idx, arrays["gates"], seg, cfg.window, dout, probe, none, heads)
+    per_block = (time.perf_counter() - t0) / len(probe)
+    n_blocks = int(min(cfg.nb, max(threads, target_seconds / max(per_block, 1e-6))))
+    blocks = I.sample_query_blocks(cfg, n_blocks, seed=1)[:n_blocks]
+    t0 = time.perf_counter()
+    oracle.nsa_backward_sampled(q, k, v, kc, vc, idx, arrays["gates"], seg, cfg.window, dout, blocks, none, heads)
+    dt = time.perf_counter() - t0
+    flops_per_block = 2.5 * cfg.forward_flops(int((idx >= 0).sum())) / cfg.nb
+    return {
+        "value": round(flops_per_block * len(blocks) / dt / 1e12, 6),
+        "unit": "TFLOP/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"gradient oracle (one pass computing dq; dk and dv accumulate in the same pass) on the rows of "
+                  f"{len(blocks)} of {cfg.nb} query blocks, all heads, {dt:.1f} s; extrapolated ms/layer "
+                  f"{dt / len(blocks) * cfg.nb * 1e3:.0f}",
+    }
+
+
+def run_backward_bench(args, cfg, B, I, p, dev, tensors, workspaces, host):
+    import torch
+    d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_pos, d_cams = tensors
+    ws_route, ws_fwd = workspaces
+    q_bits, k_bits, v_bits, gates = host
+    dout_bits = I.make_dout(cfg)
+    d_dout = torch.from_numpy(dout_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    d_lse = torch.empty((3, cfg.n, cfg.heads), dtype=torch.float32, device=dev)
+    d_ob = torch.empty((3, cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
+    d_dq, d_dk, d_dv = (torch.empty_like(d_q) for _ in range(3))
+    ws_bwd = B.alloc_workspace(p, B.LSRM_WS_BACKWARD)
+    # forward results the backward consumes (not timed)
+    B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route)
+    B.lsrm_nsa_compress(p, d_k, d_v, d_kc, d_vc)
+    B.lsrm_nsa_forward(p, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_lse, d_ob, ws_fwd)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    for row in ev:
+        for e in row:
+            e.record()
+
+    def step(i=None):
+        e = ev[i] if i is not None else [None, None]
+        B.lsrm_nsa_backward(p, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_lse, d_ob, d_dout, d_dq, d_dk, d_dv, ws_bwd,
+                            ev_start=e[0], ev_stop=e[1])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    ms_call = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    idx = d_idx.cpu().numpy()
+    flops = 2.5 * cfg.forward_flops(int((idx >= 0).sum()))
+    value = flops / (ms_step * 1e-3) / 1e12
+    call_tflops = flops / (ms_call * 1e-3) / 1e12
+    result = {
+        "metric": "NSA layer backward effective TFLOP/s (lsrm_nsa_backward), 1 MI355X",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": f"config 5 ({cfg.name}): {cfg.n_obj} object + {cfg.n_views}x{cfg.grid}x{cfg.grid} image tokens = "
+                        f"{cfg.n}, {cfg.heads} heads, d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}; "
+                        f"gradients of q, k, v",
+            "effective_flops": flops,
+            "pct_of_bf16_mfma_peak": round(100.0 * value / BF16_MFMA_PEAK_TFLOPS, 2),
+        },
+        "breakdown_ms": {"backward_call": round(ms_call, 4)},
+        "roofline": {
+            "kernel": "all kernels of lsrm_nsa_backward (HIP events around the call's launches; per-kernel split in "
+                      "profiles/)",
+            "bound": "mfma", "achieved": round(call_tflops, 3), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(call_tflops / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline_backward(cfg, {"qkv_bits": (q_bits, k_bits, v_bits), "gates": gates}, idx,
+                                                       dout_bits)
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, help="workload id 1..4 (default 4: the largest single-GPU config)")
+    ap.add_argument("--config", type=int, default=4,
+                    help="workload id 1..4 forward (default 4: the largest single-GPU config), 5 backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--topk", type=int, default=None, help="override the config's routed top-k (experiments)")
     ap.add_argument("--window", type=int, default=None, help="override the config's window (experiments)")
@@ -109,6 +211,11 @@ def main():
     d_out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
     ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE)
     ws_fwd = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
+
+    if args.config == 5:
+        run_backward_bench(args, cfg, B, I, p, dev, (d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_pos, d_cams),
+                           (ws_route, ws_fwd), (q_bits, k_bits, v_bits, gates))
+        return
 
     n_ev = args.steps
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_ev)]
