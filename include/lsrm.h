@@ -151,7 +151,7 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
  * implementation details); the paper gives no backward algorithm.  Reading: analytic gradients
  * of the three softmax branches with the routing table and the gate weights held constant, and
  * the average pooling differentiated: dk[t] += dk_cmp[t / 64] / 64, likewise dv.]
- *   d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates   as passed to lsrm_nsa_forward
+ *   d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates   as passed to lsrm_nsa_forward (gates must be >= 0)
  *   d_lse        [3, N, h_q] fp32          as written by lsrm_nsa_forward (required)
  *   d_out_branch [3, N, h_q, d] bf16       as written by lsrm_nsa_forward (required)
  *   d_dout       [N, h_q, d] bf16          gradient of the loss with respect to d_out
