@@ -48,6 +48,9 @@
 #ifndef LSRM_QT128
 #define LSRM_QT128 1
 #endif
+#ifndef LSRM_QDEPTH
+#define LSRM_QDEPTH 2
+#endif
 #ifndef LSRM_PINGPONG
 #define LSRM_PINGPONG 1
 #endif
@@ -55,7 +58,7 @@
 #define LSRM_PAR64 1
 #endif
 #ifndef LSRM_PAR128
-#define LSRM_PAR128 0
+#define LSRM_PAR128 1
 #endif
 
 namespace lsrm {
@@ -110,8 +113,8 @@ struct Geo {
     static constexpr int T_INST = TILE / 1024;  // 1 KB copy instructions per tile
     static constexpr int SH_IPT = T_INST / WAVES;  // shared phases: copy instructions per wavefront and tile
     static constexpr int OWN_IPT = T_INST / NW;    // selected phase: a wavefront copies its share of its block's tile
-    static constexpr int KQ = NS < 4 ? NS : 4;  // operand fragments kept in registers (rolling queues)
-    static constexpr int VQ = 2 * ND < 4 ? 2 * ND : 4;
+    static constexpr int KQ = NS < LSRM_QDEPTH ? NS : LSRM_QDEPTH;  // operand fragments kept in registers (rolling queues)
+    static constexpr int VQ = 2 * ND < LSRM_QDEPTH ? 2 * ND : LSRM_QDEPTH;
     static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output staging (bytes)
     static constexpr int LDS_BYTES = NSLOT * TILE;
     static_assert(QT == 1 || QT == 2, "");
