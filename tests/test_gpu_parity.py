@@ -155,6 +155,18 @@ def test_forward_zero_window_and_topk_one(B, oracle_lib):
     _assert_forward(*_forward_case(B, oracle_lib, cfg), cfg.name)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_forward_large_scale_moves_the_running_max(B, oracle_lib, d):
+    """Scores many units apart (score standard deviation about 5 nats): the running maximum is raised
+    several times per row, including while probabilities of the previous tile are still waiting to be
+    accumulated.  (Not larger: with a near one-hot softmax the outputs are single V rows of magnitude 4,
+    whose bf16 rounding alone reaches the absolute tolerance.)"""
+    cfg = I.small_config(name=f"f-bigscale-d{d}", n_obj=2048, n_views=2, grid=16, heads=2, d=d, topk=6, window=384,
+                         seed=33)
+    _log(f"[forward] {cfg.name}")
+    _assert_forward(*_forward_case(B, oracle_lib, cfg, scale=0.6 if d == 64 else 0.45), cfg.name)
+
+
 def test_forward_config1_full(B, oracle_lib):
     cfg = I.CONFIGS[1]
     _log(f"[forward] config 1 full ({cfg.n} tokens)")
