@@ -24,6 +24,10 @@
 // Steps are not software pipelined: copy of tile t+1 (LDS DMA) overlaps the arithmetic of tile t.
 #include "lsrm_internal.h"
 
+#ifndef LSRM_BWD_NBUF
+#define LSRM_BWD_NBUF 2
+#endif
+
 namespace lsrm {
 
 namespace {
@@ -88,6 +92,10 @@ __device__ __forceinline__ void copy_kb(const char *src, char *dst, int wave, ui
             __builtin_amdgcn_global_load_lds(GLB_PTR(src + (i + wave) * 1024 + lane16), LDS_PTR(dst + (i + wave) * 1024),
                                              16, 0, 0);
 }
+
+// s_waitcnt vmcnt <= n (and lgkmcnt == 0); a raw barrier: __syncthreads() would wait for every copy in flight
+constexpr int vm_lgkm_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 template <int D>
 struct BGeo {
@@ -228,13 +236,20 @@ __global__ void rev_sort(BwdArgs a) {
 // ---------------------------------------------------------------------------------------------
 // dQ: one workgroup (2 wavefronts x 32 query rows) per (query block, head)
 template <int D>
-__global__ __launch_bounds__(128) void bwd_dq_kernel(BwdArgs a) {
+__global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int TILE = G::IMG + G::ROW;  // K rows | K^T | V rows
-    static_assert(2 * 32 * G::OUT_ROW <= 2 * TILE, "output staging fits in the tile buffers");
-    __shared__ __attribute__((aligned(1024))) char lds[2 * TILE];
-    const int qb = blockIdx.x, head = blockIdx.y;
+    constexpr int NBUF = LSRM_BWD_NBUF;    // tile buffers: copies run NBUF - 1 tiles ahead
+    constexpr int IPW = (G::IMG / 1024 + G::ROW / 1024) / 2;  // copy instructions per wavefront and tile
+    static_assert((G::IMG / 1024) % 2 == 0 && (G::ROW / 1024) % 2 == 0, "");
+    static_assert(2 * 32 * G::OUT_ROW <= NBUF * TILE, "output staging fits in the tile buffers");
+    __shared__ __attribute__((aligned(1024))) char lds[NBUF * TILE];
+    // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous range of
+    // blocks so that neighbouring blocks (overlapping windows, similar routed sets) share its L2
+    const int per_xcd = (a.nb + 7) / 8;
+    const int qb = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), head = blockIdx.y;
+    if (qb >= a.nb) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, hh = lane >> 5;
@@ -312,17 +327,30 @@ __global__ __launch_bounds__(128) void bwd_dq_kernel(BwdArgs a) {
         copy_kb<G::ROW / 1024>(vimg + off, buf + G::IMG, wave, lane16);
     };
 
-    if (T > 0) issue(0, lds);
+    for (int t = 0; t < NBUF - 1 && t < T; ++t) issue(t, lds + t * TILE);
     for (int t = 0; t < T; ++t) {
-        __syncthreads();  // tile t has landed for both wavefronts; both are done with the other buffer
-        if (t + 1 < T) issue(t + 1, lds + ((t + 1) & 1) * TILE);
+        // tile t has landed (this wavefront's share; the barrier covers the other's) while the
+        // copies of the tiles after it stay in flight; both wavefronts are done with tile t-1
+        const int ahead = min(T - 1, t + NBUF - 2) - t;  // tiles issued beyond t
+        if (ahead >= 2)
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(2 * IPW));
+        else if (ahead == 1)
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW));
+        else
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        wg_barrier();
+        if (t + NBUF - 1 < T) issue(t + NBUF - 1, lds + ((t + NBUF - 1) % NBUF) * TILE);
         const int br = t < tc ? 0 : (t < tc + ts ? 1 : 2);
         const int j0 = br == 0 ? 32 * t : (br == 1 ? 0 : 32 * (st0 + t - tc - ts));
         const int lo = br == 0 ? 0 : (br == 1 ? -0x40000000 : wlo);
         const int hi = br == 0 ? a.nb : (br == 1 ? 0x7fffffff : whi);
+        // does any lane of this wavefront need the mask on this tile?  (pooled tail; window edges)
+        const bool need_mask =
+            br == 0 ? (j0 + 32 > a.nb)
+                    : (br == 2 && (j0 < max(seg_lo, (int)row0 + 31 - half_w) || j0 + 32 > min(seg_hi, (int)row0 + half_w)));
         const float lb = br == 0 ? l2[0] : (br == 1 ? l2[1] : l2[2]);
         const float db = br == 0 ? dl[0] : (br == 1 ? dl[1] : dl[2]);
-        const char *base = lds + (t & 1) * TILE + lane16;
+        const char *base = lds + (t % NBUF) * TILE + lane16;
 
         f32x16 s, dp;
 #pragma unroll
@@ -336,12 +364,17 @@ __global__ __launch_bounds__(128) void bwd_dq_kernel(BwdArgs a) {
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::IMG + ks * 1024),
                                                          dof[ks], dp, 0, 0, 0);
         float ds[16];
+        if (__builtin_expect(need_mask, 0)) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
-            float p = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb);
-            p = (j >= lo && j < hi) ? p : 0.f;
-            ds[i] = p * (dp[i] - db);
+            for (int i = 0; i < 16; ++i) {
+                const int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
+                float p = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb);
+                p = (j >= lo && j < hi) ? p : 0.f;
+                ds[i] = p * (dp[i] - db);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb) * (dp[i] - db);
         }
         BFrag dsb[2];
         to_b_operand(ds, dsb);
@@ -353,6 +386,7 @@ __global__ __launch_bounds__(128) void bwd_dq_kernel(BwdArgs a) {
                     *reinterpret_cast<const bf16x8 *>(base + G::ROW + (ks2 * ND + dt) * 1024), dsb[ks2].v, acc[dt], 0, 0, 0);
     }
     __syncthreads();  // the tile buffers become the output staging
+    static_assert(NBUF >= 2 && NBUF <= 4, "");
     float x[ND][16];
 #pragma unroll
     for (int dt = 0; dt < ND; ++dt)
@@ -364,14 +398,17 @@ __global__ __launch_bounds__(128) void bwd_dq_kernel(BwdArgs a) {
 // ---------------------------------------------------------------------------------------------
 // dK, dV: one workgroup (2 wavefronts x 32 keys) per (key block, head[, query range])
 template <int D, int MODE>
-__global__ __launch_bounds__(128) void bwd_dkv_kernel(BwdArgs a) {
+__global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int AUX = 2 * G::IMG;         // Q rows | Q^T | dO rows | dO^T | table (64 floats)
     constexpr int TILE = 2 * G::IMG + 1024;  // (table padded to keep the next buffer aligned)
     static_assert(2 * 32 * G::OUT_ROW <= 2 * TILE, "output staging fits in the tile buffers");
     __shared__ __attribute__((aligned(1024))) char lds[2 * TILE];
-    const int kb = blockIdx.x, head = blockIdx.y;
+    const int n_kb = MODE == 0 ? a.nb : a.nbp / 64;
+    const int per_xcd = (n_kb + 7) / 8;
+    const int kb = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), head = blockIdx.y;  // (see bwd_dq_kernel)
+    if (kb >= n_kb) return;
     const int split = MODE == 1 ? blockIdx.z : 0;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -420,10 +457,17 @@ __global__ __launch_bounds__(128) void bwd_dkv_kernel(BwdArgs a) {
         ts = 2 * (a.rev_ptr[kb + 1] - e0);
         T = tw + ts;
     }
+    // the reverse list is held 64 entries at a time, one per lane (reloaded by whoever crosses a chunk)
+    int rev_chunk = -1, rev_held = 0;
     auto tile_of = [&](int t) -> int64_t {
         if (MODE == 1 || t < tw) return wt0 + t;
-        const int u = t - tw;
-        return 2 * (int64_t)a.rev_idx[e0 + (u >> 1)] + (u & 1);
+        const int u = t - tw, e = u >> 1;
+        if ((e >> 6) != rev_chunk) {
+            rev_chunk = e >> 6;
+            const int at = e0 + rev_chunk * 64 + lane;
+            rev_held = at < e0 + (ts >> 1) ? a.rev_idx[at] : 0;
+        }
+        return 2 * (int64_t)__builtin_amdgcn_readlane(rev_held, e & 63) + (u & 1);
     };
     auto branch_of = [&](int t) { return MODE == 1 ? 0 : (t < tw ? 2 : 1); };
     auto issue = [&](int t, char *buf) {
@@ -444,7 +488,9 @@ __global__ __launch_bounds__(128) void bwd_dkv_kernel(BwdArgs a) {
         const char *buf = lds + (t & 1) * TILE;
         const char *base = buf + lane16;
         const int q0 = 32 * (int)tile_of(t);
-        const bool win = MODE == 0 && t < tw;
+        // window tiles away from the band's edges (and all routed tiles) need no mask
+        const bool win = MODE == 0 && t < tw &&
+                         ((int)key0 - (q0 + 31) < -half_w || (int)key0 + 31 - q0 >= half_w);
 
         f32x16 s;
 #pragma unroll
@@ -671,11 +717,11 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
         hipLaunchKernelGGL(rev_sort, dim3((s.nb + 63) / 64), dim3(64), 0, st, a);
         LSRM_HIP_CHECK(hipGetLastError());
     }
-    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3(s.nb, s.h), dim3(128), 0, st, a);
+    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3(w.nbp / 64, s.h, w.n_split), dim3(128), 0, st, a);
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3((w.nbp / 64 + 7) / 8 * 8, s.h, w.n_split), dim3(128), 0, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3(s.nb, s.h), dim3(128), 0, st, a);
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;
