@@ -74,6 +74,23 @@ def route(pos: np.ndarray, cams: np.ndarray, grid: int, topk: int):
     return idx, d2
 
 
+def route_3d(pos, pos_img, cams, grid: int, width: int, prefilter: int, k_v2v: int, k_v2i: int, k_i2v: int,
+             k_i2i: int):
+    """The four selection rules at block level -> (idx int32 [NB, width], dist2 float32 [NB, width]);
+    rows hold the selected volume blocks, then the selected image blocks, then -1."""
+    pos, pos_img, cams = _f32(pos), _f32(pos_img), _f32(cams)
+    n_obj, m = pos.shape[0], cams.shape[0]
+    assert pos_img.shape[0] == m * grid * grid
+    nb = n_obj // 64 + m * (grid // 8) ** 2
+    idx = np.empty((nb, width), dtype=np.int32)
+    d2 = np.empty((nb, width), dtype=np.float32)
+    _load().oracle_route_3d(ctypes.c_int(n_obj), ctypes.c_int(m), ctypes.c_int(grid), ctypes.c_int(width),
+                            ctypes.c_int(prefilter), ctypes.c_int(k_v2v), ctypes.c_int(k_v2i), ctypes.c_int(k_i2v),
+                            ctypes.c_int(k_i2i), _p(pos, ctypes.c_float), _p(pos_img, ctypes.c_float),
+                            _p(cams, ctypes.c_float), _p(idx, ctypes.c_int32), _p(d2, ctypes.c_float))
+    return idx, d2
+
+
 def pool(x: np.ndarray) -> np.ndarray:
     """x fp32 [N, H, d] -> block means fp32 [N/64, H, d]."""
     x = _f32(x)

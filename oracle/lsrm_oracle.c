@@ -141,6 +141,90 @@ void oracle_route(int n_obj, int n_views, int grid, int topk, const float *pos, 
     free(cand); free(dm); free(cent);
 }
 
+/*
+ * The four geometric selection rules of Sec. 3.3 ("Image/Volume to Image Blocks",
+ * "Image/Volume to Volume Blocks") at block granularity: the query is a block, represented by
+ * the centroid p of the 3-D coordinates of its 64 tokens (object tokens: voxel centres; image
+ * tokens: the surface point assigned to each patch, an input here).
+ *   to volume blocks : squared 3-D distance from p to the centre (centroid) of every object
+ *                      block; the k_v2v (object query) or k_i2v (image query) smallest.
+ *   to image blocks  : p is projected into every view; per view the `prefilter` tiles whose 2-D
+ *                      centres are nearest to the projection are candidates (a view that has p
+ *                      behind its image plane contributes none); a candidate's distance is the
+ *                      smallest squared 3-D distance from p to the 64 points of the tile; the
+ *                      k_v2i (object query) or k_i2i (image query) smallest over all views.
+ * Row layout: [volume ids ascending by (d2, id)] [image ids (nb_obj + tile) ascending by (d2, id)]
+ * then -1 / +inf up to `width`.  All arithmetic fp32 in the order written, no fused multiply-add.
+ *   pos [n_obj, 3], pos_img [n_views * grid^2, 3] (sequence order: 64 consecutive tokens = one
+ *   tile), cams [n_views, 16];  idx, dist2 [NB, width].
+ */
+static float sqdist3(const float *a, const float *b) {
+    float dx = a[0] - b[0], dy = a[1] - b[1], dz = a[2] - b[2];
+    return (dx * dx + dy * dy) + dz * dz;
+}
+
+void oracle_route_3d(int n_obj, int n_views, int grid, int width, int prefilter, int k_v2v, int k_v2i, int k_i2v,
+                     int k_i2i, const float *pos, const float *pos_img, const float *cams, int32_t *idx,
+                     float *dist2) {
+    int nbo = n_obj / BLK;
+    int tg = grid / 8;
+    int tpv = tg * tg;
+    int nt = n_views * tpv;
+    int nb = nbo + nt;
+    float *cent = (float *)malloc(sizeof(float) * 3 * (size_t)(nb > 0 ? nb : 1));
+    oracle_centroids(n_obj, pos, cent);
+    oracle_centroids(nt * BLK, pos_img, cent + 3 * (size_t)nbo);
+    int maxc = nbo > n_views * prefilter ? nbo : n_views * prefilter;
+    if (tpv > maxc) maxc = tpv;
+    cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(maxc > 0 ? maxc : 1));
+    cand_t *view = (cand_t *)malloc(sizeof(cand_t) * (size_t)(tpv > 0 ? tpv : 1));
+    for (int b = 0; b < nb; ++b) {
+        const float *p = cent + 3 * (size_t)b;
+        int kv = b < nbo ? k_v2v : k_i2v, ki = b < nbo ? k_v2i : k_i2i;
+        int at = 0;
+        /* volume blocks */
+        for (int j = 0; j < nbo; ++j) { cand[j].d2 = sqdist3(p, cent + 3 * (size_t)j); cand[j].id = j; }
+        qsort(cand, nbo, sizeof(cand_t), cand_cmp);
+        for (int k = 0; k < kv && k < nbo && at < width; ++k, ++at) {
+            idx[(size_t)b * width + at] = cand[k].id;
+            if (dist2) dist2[(size_t)b * width + at] = cand[k].d2;
+        }
+        /* image blocks */
+        int nc = 0;
+        for (int m = 0; m < n_views; ++m) {
+            if (tile_dist2(p, cams + 16 * m, 0, 0) == INFINITY) continue; /* behind the image plane */
+            for (int ti = 0; ti < tg; ++ti)
+                for (int tj = 0; tj < tg; ++tj) {
+                    view[ti * tg + tj].d2 = tile_dist2(p, cams + 16 * m, ti, tj);
+                    view[ti * tg + tj].id = m * tpv + ti * tg + tj;
+                }
+            qsort(view, tpv, sizeof(cand_t), cand_cmp);
+            for (int c = 0; c < prefilter && c < tpv; ++c) {
+                int tile = view[c].id;
+                const float *pts = pos_img + 3 * (size_t)tile * BLK;
+                float best = sqdist3(p, pts);
+                for (int t = 1; t < BLK; ++t) {
+                    float d = sqdist3(p, pts + 3 * t);
+                    if (d < best) best = d;
+                }
+                cand[nc].d2 = best;
+                cand[nc].id = nbo + tile;
+                ++nc;
+            }
+        }
+        qsort(cand, nc, sizeof(cand_t), cand_cmp);
+        for (int k = 0; k < ki && k < nc && at < width; ++k, ++at) {
+            idx[(size_t)b * width + at] = cand[k].id;
+            if (dist2) dist2[(size_t)b * width + at] = cand[k].d2;
+        }
+        for (; at < width; ++at) {
+            idx[(size_t)b * width + at] = -1;
+            if (dist2) dist2[(size_t)b * width + at] = INFINITY;
+        }
+    }
+    free(view); free(cand); free(cent);
+}
+
 /* ------------------------------------------------------------------ pooling */
 
 /* out[b, h, :] = (1/64) sum_t x[64 b + t, h, :];  x is [N, H, d], out is [N/64, H, d]. */

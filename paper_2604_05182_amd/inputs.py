@@ -254,6 +254,40 @@ def make_cameras(cfg: NSAConfig, radius: float = 2.5, fov_deg: float = 40.0) -> 
     return cams.astype(np.float32)
 
 
+def image_token_patch(cfg: NSAConfig):
+    """(view, row, col) int arrays [n_img] of every image token, in sequence (tile-major) order."""
+    s, tg = cfg.grid, cfg.grid // 8
+    i = np.arange(cfg.n_img, dtype=np.int64)
+    view, r = i // (s * s), i % (s * s)
+    tile, inner = r // BLOCK, r % BLOCK
+    row = (tile // tg) * 8 + inner // 8
+    col = (tile % tg) * 8 + inner % 8
+    return view, row, col
+
+
+def make_points_img(cfg: NSAConfig, cams: np.ndarray) -> np.ndarray:
+    """A 3-D point for every image token, float32 [n_img, 3] in sequence order: where the ray
+    through the patch centre first meets a rough sphere around the origin (radius drawn per
+    token from U(0.6, 0.8)); a ray that misses takes its point nearest to the origin.  Stands
+    in for the rendered surface point of a patch (synthetic: no renderer, no trained volume)."""
+    rng = _rng(cfg.seed, 3)
+    view, row, col = image_token_patch(cfg)
+    c = cams.astype(np.float64)
+    rot = c[:, :9].reshape(-1, 3, 3)
+    centre = -np.einsum("mji,mj->mi", rot, c[:, 9:12])             # -R^T t
+    fx, fy, cx, cy = (c[view, 12 + j] for j in range(4))
+    d_cam = np.stack([(col + 0.5 - cx) / fx, (row + 0.5 - cy) / fy, np.ones(cfg.n_img)], axis=1)
+    d = np.einsum("nji,nj->ni", rot[view], d_cam)                   # R^T d_cam
+    d /= np.linalg.norm(d, axis=1, keepdims=True)
+    o = centre[view]
+    radius = rng.uniform(0.6, 0.8, size=cfg.n_img)
+    b = (o * d).sum(1)
+    disc = b * b - ((o * o).sum(1) - radius * radius)
+    s_hit = -b - np.sqrt(np.maximum(disc, 0.0))
+    s_par = np.where(disc >= 0.0, s_hit, -b)
+    return np.ascontiguousarray((o + s_par[:, None] * d).astype(np.float32))
+
+
 # ----------------------------------------------------------------------------- tensors
 def _normal_bf16(shape, seed: int, stream: int, chunk_rows: int = 1 << 12) -> np.ndarray:
     """N(0,1) rounded to bf16.  Chunk c of 4096 rows draws from its own counter-based Philox
