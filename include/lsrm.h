@@ -77,7 +77,7 @@ typedef struct lsrm_nsa_params {
     float scale;      /* softmax scale; 0 selects 1/sqrt(d)                                */
 } lsrm_nsa_params;
 
-enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2 };
+enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2, LSRM_WS_ROUTE_3D = 3 };
 
 /* Bytes of scratch the given call needs for these params (0 on invalid params). */
 size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call);
@@ -107,6 +107,50 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call);
  */
 lsrm_status lsrm_route_blocks(const lsrm_nsa_params *p, const float *d_pos, const lsrm_camera *d_cams,
                               int32_t *d_idx, float *d_dist2, void *d_ws, size_t ws_bytes, void *stream);
+
+/*
+ * Budgets of the four geometric selection rules.  [Sec. 3.3, paragraphs "Image/Volume to Image
+ * Blocks" and "Image/Volume to Volume Blocks"; App. hyper-parameter table: volume budgets
+ * B^i2v = B^v2v in {8, 16}, image budgets B^v2i = B^i2i in {2M, 4M}.  The paper gives no value
+ * for the per-view candidate count B^i.]
+ */
+typedef struct lsrm_route3d_params {
+    int32_t prefilter; /* B^i >= 1: tiles kept per view by 2-D centre distance (clipped to the
+                          number of tiles of a view)                                          */
+    int32_t k_v2v;     /* volume blocks selected by a volume (object) query block, >= 0       */
+    int32_t k_v2i;     /* image blocks selected by a volume query block                       */
+    int32_t k_i2v;     /* volume blocks selected by an image query block                      */
+    int32_t k_i2i;     /* image blocks selected by an image query block                       */
+} lsrm_route3d_params;
+
+/*
+ * Routing by the four geometric selection rules, per query block.  [Sec. 3.3: a query with 3-D
+ * point p selects (a) the volume blocks whose spatial centres are nearest to p and (b) image
+ * blocks in two steps: per view, the B^i blocks whose 2-D centres lie nearest to the projection
+ * of p are candidates; candidates are ranked by the smallest 3-D distance between p and the
+ * points of the block.  Block-level reading: p is the centroid of the query block's 64 token
+ * points; a volume block's centre is the centroid of its 64 positions.]
+ *
+ *   r          HOST budgets; max(k_v2v + k_v2i, k_i2v + k_i2i) must not exceed p->topk
+ *   d_pos      [n_obj, 3] fp32            object token positions (voxel centres), sequence order
+ *   d_pos_img  [n_views * grid^2, 3] fp32 the 3-D point of every image token (the surface point
+ *              seen by its patch), sequence order: 64 consecutive points = one tile
+ *   d_cams     [n_views] lsrm_camera
+ *   d_idx      [NB, topk] int32  OUT.  Row of query block b: first the selected volume blocks
+ *              (ids in [0, n_obj/64)), ascending by (squared centre distance, id) and including b
+ *              itself when b is a volume block; then the selected image blocks (ids n_obj/64 +
+ *              tile), ascending by (squared minimum point distance, id); then -1.  Fewer entries
+ *              than the budget appear when there are fewer candidates (a view that has p at or
+ *              behind its image plane, z <= 1e-6, contributes none).
+ *   d_dist2    [NB, topk] fp32  OUT, nullable: the squared 3-D distances (+inf for -1).
+ * The table is a valid d_idx for lsrm_nsa_forward / lsrm_nsa_backward.  Arithmetic is fp32 in a
+ * fixed order without fused multiply-add (bit-reproducible): centroids and projection as in
+ * lsrm_route_blocks; d2 = ((dx dx + dy dy) + dz dz).  Positions must be finite.
+ * LSRM_ERR_UNSUPPORTED if n_views * min(prefilter, tiles per view) exceeds 4096.
+ */
+lsrm_status lsrm_route_blocks_3d(const lsrm_nsa_params *p, const lsrm_route3d_params *r, const float *d_pos,
+                                 const float *d_pos_img, const lsrm_camera *d_cams, int32_t *d_idx,
+                                 float *d_dist2, void *d_ws, size_t ws_bytes, void *stream);
 
 /*
  * Block compression.  [Sec. 3.2, k_cmp = AvgPool(.), v_cmp = AvgPool(.); App. A

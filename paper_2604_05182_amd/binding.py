@@ -19,7 +19,7 @@ LSRM_ERR_INVALID_ARG = -1
 LSRM_ERR_UNSUPPORTED = -2
 LSRM_ERR_WORKSPACE = -3
 LSRM_ERR_HIP = -4
-LSRM_WS_ROUTE, LSRM_WS_FORWARD, LSRM_WS_BACKWARD = 0, 1, 2
+LSRM_WS_ROUTE, LSRM_WS_FORWARD, LSRM_WS_BACKWARD, LSRM_WS_ROUTE_3D = 0, 1, 2, 3
 
 
 class LsrmError(RuntimeError):
@@ -36,6 +36,11 @@ class lsrm_nsa_params(ctypes.Structure):
                 ("scale", ctypes.c_float)]
 
 
+class lsrm_route3d_params(ctypes.Structure):
+    _fields_ = [("prefilter", ctypes.c_int32), ("k_v2v", ctypes.c_int32), ("k_v2i", ctypes.c_int32),
+                ("k_i2v", ctypes.c_int32), ("k_i2i", ctypes.c_int32)]
+
+
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_05182_amd.build` "
                       "(there is no CPU fallback)")
@@ -48,6 +53,8 @@ _lib.lsrm_workspace_bytes.restype = _sz
 _lib.lsrm_workspace_bytes.argtypes = [_pp, ctypes.c_int]
 _lib.lsrm_route_blocks.restype = ctypes.c_int32
 _lib.lsrm_route_blocks.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.lsrm_route_blocks_3d.restype = ctypes.c_int32
+_lib.lsrm_route_blocks_3d.argtypes = [_pp, ctypes.POINTER(lsrm_route3d_params), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.lsrm_nsa_compress.restype = ctypes.c_int32
 _lib.lsrm_nsa_compress.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
 _lib.lsrm_nsa_forward.restype = ctypes.c_int32
@@ -103,6 +110,14 @@ def lsrm_route_blocks(p, pos, cams, idx, dist2=None, ws=None, stream=None):
     nbytes = ws.numel() * ws.element_size() if ws is not None else 0
     _check(_lib.lsrm_route_blocks(ctypes.byref(p), _ptr(pos), _ptr(cams), _ptr(idx), _ptr(dist2), _ptr(ws),
                                   nbytes, _stream(stream)), "lsrm_route_blocks")
+
+
+def lsrm_route_blocks_3d(p, r, pos, pos_img, cams, idx, dist2=None, ws=None, stream=None):
+    """pos fp32 [n_obj,3], pos_img fp32 [n_img,3], cams fp32 [M,16] -> idx int32 [NB,topk] (and dist2)."""
+    nbytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(_lib.lsrm_route_blocks_3d(ctypes.byref(p), ctypes.byref(r) if r is not None else None, _ptr(pos),
+                                     _ptr(pos_img), _ptr(cams), _ptr(idx), _ptr(dist2), _ptr(ws), nbytes,
+                                     _stream(stream)), "lsrm_route_blocks_3d")
 
 
 def lsrm_nsa_compress(p, k, v, kc, vc, stream=None):

@@ -82,6 +82,7 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call) {
         case LSRM_WS_ROUTE: return route_ws_bytes(s);
         case LSRM_WS_FORWARD: return forward_ws_bytes(s);
         case LSRM_WS_BACKWARD: return s.d == 64 ? backward_ws_bytes(s) : 0;
+        case LSRM_WS_ROUTE_3D: return route3d_ws_bytes(s);
         default: return 0;
     }
 }
@@ -97,6 +98,25 @@ lsrm_status lsrm_route_blocks(const lsrm_nsa_params *p, const float *d_pos, cons
     if (s.n_views > 0 && d_cams == nullptr) return LSRM_ERR_INVALID_ARG;
     if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < route_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
     return launch_route(s, d_pos, d_cams, d_idx, d_dist2, d_ws, static_cast<hipStream_t>(stream));
+}
+
+lsrm_status lsrm_route_blocks_3d(const lsrm_nsa_params *p, const lsrm_route3d_params *r, const float *d_pos,
+                                 const float *d_pos_img, const lsrm_camera *d_cams, int32_t *d_idx, float *d_dist2,
+                                 void *d_ws, size_t ws_bytes, void *stream) {
+    Shape s;
+    lsrm_status rc = make_shape(p, &s);
+    if (rc != LSRM_OK) return rc;
+    if (r == nullptr || r->prefilter < 1 || r->k_v2v < 0 || r->k_v2i < 0 || r->k_i2v < 0 || r->k_i2i < 0)
+        return LSRM_ERR_INVALID_ARG;
+    if ((int64_t)r->k_v2v + r->k_v2i > s.topk || (int64_t)r->k_i2v + r->k_i2i > s.topk) return LSRM_ERR_INVALID_ARG;
+    if (s.nb == 0 || s.topk == 0) return LSRM_OK;
+    if (d_idx == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (s.n_obj > 0 && d_pos == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (s.n_tiles > 0 && (d_cams == nullptr || d_pos_img == nullptr)) return LSRM_ERR_INVALID_ARG;
+    const int pre = r->prefilter < s.tiles_per_view ? r->prefilter : s.tiles_per_view;
+    if ((int64_t)s.n_views * pre > 4096) return LSRM_ERR_UNSUPPORTED;
+    if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < route3d_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
+    return launch_route_3d(s, *r, d_pos, d_pos_img, d_cams, d_idx, d_dist2, d_ws, static_cast<hipStream_t>(stream));
 }
 
 lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,

@@ -32,6 +32,10 @@ lsrm_status launch_route(const Shape &s, const float *d_pos, const lsrm_camera *
                          float *d_dist2, void *d_ws, hipStream_t st);
 size_t route_ws_bytes(const Shape &s);
 
+lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const float *d_pos, const float *d_pos_img,
+                            const lsrm_camera *d_cams, int32_t *d_idx, float *d_dist2, void *d_ws, hipStream_t st);
+size_t route3d_ws_bytes(const Shape &s);
+
 lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
                             uint16_t *d_vc, hipStream_t st);
 

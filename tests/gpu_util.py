@@ -34,6 +34,18 @@ def run_route(B, cfg, pos, cams, want_dist=True):
     return idx.cpu().numpy(), (d2.cpu().numpy() if want_dist else None)
 
 
+def run_route_3d(B, cfg, pos, pos_img, cams, width, prefilter, k_v2v, k_v2i, k_i2v, k_i2i, want_dist=True):
+    p = params_for(B, cfg, topk=width)
+    r = B.lsrm_route3d_params(prefilter, k_v2v, k_v2i, k_i2v, k_i2i)
+    d_pos, d_img, d_cams = (torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in (pos, pos_img, cams))
+    idx = torch.full((cfg.nb, width), -7, dtype=torch.int32, device="cuda")
+    d2 = torch.full((cfg.nb, width), -1.0, dtype=torch.float32, device="cuda") if want_dist else None
+    ws = B.alloc_workspace(p, B.LSRM_WS_ROUTE_3D)
+    B.lsrm_route_blocks_3d(p, r, d_pos, d_img, d_cams, idx, d2, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), (d2.cpu().numpy() if want_dist else None)
+
+
 def run_compress(B, cfg, k_bits, v_bits):
     p = params_for(B, cfg)
     dk, dv = bf16_dev(k_bits), bf16_dev(v_bits)

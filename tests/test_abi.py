@@ -10,13 +10,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "lsrm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lsrm_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(lsrm_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_entry_points():
     names = _declared()
-    for must in ("lsrm_route_blocks", "lsrm_nsa_compress", "lsrm_nsa_forward", "lsrm_nsa_backward",
-                 "lsrm_workspace_bytes", "lsrm_strerror"):
+    for must in ("lsrm_route_blocks", "lsrm_route_blocks_3d", "lsrm_nsa_compress", "lsrm_nsa_forward",
+                 "lsrm_nsa_backward", "lsrm_workspace_bytes", "lsrm_strerror"):
         assert must in names
 
 
@@ -50,3 +50,12 @@ def test_host_side_argument_checks():
     assert rc == B.LSRM_ERR_UNSUPPORTED
     rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(ok), *([None] * 14), 0, None, None, None)
     assert rc == B.LSRM_ERR_INVALID_ARG
+    # four-rule routing: budgets must fit the row width; the budget struct is required
+    r_bad, r_ok = B.lsrm_route3d_params(2, 3, 1, 1, 1), B.lsrm_route3d_params(2, 2, 1, 1, 1)
+    assert B.lsrm_workspace_bytes(ok, B.LSRM_WS_ROUTE_3D) >= 16 * 16
+    call = B._lib.lsrm_route_blocks_3d
+    assert call(__import__("ctypes").byref(ok), __import__("ctypes").byref(r_bad), *([None] * 6), 0, None) \
+        == B.LSRM_ERR_INVALID_ARG
+    assert call(__import__("ctypes").byref(ok), None, *([None] * 6), 0, None) == B.LSRM_ERR_INVALID_ARG
+    assert call(__import__("ctypes").byref(ok), __import__("ctypes").byref(r_ok), *([None] * 6), 0, None) \
+        == B.LSRM_ERR_INVALID_ARG          # null output table
