@@ -172,6 +172,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--topk", type=int, default=None, help="override the config's routed top-k (experiments)")
     ap.add_argument("--window", type=int, default=None, help="override the config's window (experiments)")
+    ap.add_argument("--routing", choices=("projected", "four-rule"), default="projected",
+                    help="routing table: the configs' projected-centroid rule (default) or the four geometric "
+                         "selection rules (lsrm_route_blocks_3d: B^i = 4, a quarter of top-k volume blocks, the "
+                         "rest image blocks)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings against)")
@@ -211,8 +215,23 @@ def main():
     d_out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
     ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE)
     ws_fwd = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
+    four_rule = args.routing == "four-rule"
+    if four_rule:
+        k_vol = cfg.topk // 4
+        r3d = B.lsrm_route3d_params(4, k_vol, cfg.topk - k_vol, k_vol, cfg.topk - k_vol)
+        d_pos_img = torch.from_numpy(I.make_points_img(cfg, cams)).to(dev)
+        ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE_3D)
+
+    def route():
+        if four_rule:
+            B.lsrm_route_blocks_3d(p, r3d, d_pos, d_pos_img, d_cams, d_idx, None, ws_route)
+        else:
+            B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route)
 
     if args.config == 5:
+        if four_rule:
+            print("bench.py: --routing four-rule is wired for the forward configs only", file=sys.stderr)
+            sys.exit(2)
         run_backward_bench(args, cfg, B, I, p, dev, (d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_pos, d_cams),
                            (ws_route, ws_fwd), (q_bits, k_bits, v_bits, gates))
         return
@@ -227,7 +246,7 @@ def main():
         e = ev[i] if i is not None else [None] * 6
         if i is not None:
             e[0].record()
-        B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route)
+        route()
         if i is not None:
             e[1].record()
         B.lsrm_nsa_compress(p, d_k, d_v, d_kc, d_vc)
@@ -281,7 +300,9 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"config {args.config} ({cfg.name}): {cfg.n_obj} object + {cfg.n_views}x{cfg.grid}x{cfg.grid} image "
-                        f"tokens = {cfg.n}, {cfg.heads} heads, d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}",
+                        f"tokens = {cfg.n}, {cfg.heads} heads, d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}"
+                        + (f", four-rule routing (B^i 4, {k_vol} volume + {cfg.topk - k_vol} image blocks)"
+                           if four_rule else ""),
             "effective_flops": flops,
             "pct_of_bf16_mfma_peak": round(100.0 * value / BF16_MFMA_PEAK_TFLOPS, 2),
         },
@@ -294,7 +315,8 @@ def main():
             "peak": BF16_MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(attn_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
-            "traffic": MEASURED_HBM_BYTES.get(args.config) if args.topk is None and args.window is None else None,
+            "traffic": (MEASURED_HBM_BYTES.get(args.config)
+                        if args.topk is None and args.window is None and not four_rule else None),
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
         },
     }

@@ -74,29 +74,97 @@ __device__ __forceinline__ unsigned long long make_key(float d2, unsigned id) {
     return ((unsigned long long)__float_as_uint(d2) << 32) | id;
 }
 
-__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
-    for (int off = 32; off >= 1; off >>= 1) {
-        unsigned long long o = __shfl_xor(v, off, 64);
-        v = o < v ? o : v;
-    }
+// Wave-wide minima without the LDS crossbar: four data-parallel-primitive steps fold each row of
+// 16 lanes (lane xor 1, xor 2, mirror within 8, mirror within 16), then the four row results are
+// read as scalars.  All 64 lanes must be active.  The result is wave-uniform.
+template <class Op>
+__device__ __forceinline__ unsigned row_fold(unsigned v, Op op) {
+    v = op(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+    v = op(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    v = op(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+    v = op(v, (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
     return v;
 }
 
-// Keys of all candidates of one query block are computed once into LDS; every thread
-// remembers the smallest key of its own strided slice that is still unselected, a round
-// is one workgroup-wide minimum over those, and only the winning thread rescans its slice.
-// `cache_keys` is false when the candidate keys do not fit in LDS: keys are then
-// recomputed on every scan (same results, slower).
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v) {
+    v = row_fold(v, [](unsigned a, unsigned b) { return a < b ? a : b; });
+    unsigned r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+    unsigned r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+    unsigned a = r0 < r1 ? r0 : r1, b = r2 < r3 ? r2 : r3;
+    return a < b ? a : b;
+}
+
+// Non-negative floats order like their bit patterns.
+__device__ __forceinline__ float wave_min_nonneg_f32(float v) { return __uint_as_float(wave_min_u32(__float_as_uint(v))); }
+
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
+    const unsigned hi = (unsigned)(v >> 32), lo = (unsigned)v;
+    const unsigned hi_min = wave_min_u32(hi);
+    const unsigned lo_min = wave_min_u32(hi == hi_min ? lo : 0xffffffffu);
+    return ((unsigned long long)hi_min << 32) | lo_min;
+}
+
+constexpr unsigned long long kNoKey = ~0ull;
+
+// The k smallest of a set of distinct keys (none equal to all-ones), in ascending order, found by
+// one wave: lane l looks at candidates first + l', first + l' + step, ... below n_cand, where l' is
+// `me` (the lane id for a wave working alone, the thread id when the four waves of a workgroup
+// each take a quarter).  A round is one wave-wide minimum; only the lane that owned the winner
+// rescans its candidates.  emit(r, key) is called by every lane for r = 0 .. count-1; returns count.
+template <class KeyAt, class Emit>
+__device__ __forceinline__ int wave_extract(int me, int step, int n_cand, KeyAt key_at, int k, Emit emit) {
+    auto scan = [&](bool have_floor, unsigned long long floor_key) {
+        unsigned long long best = kNoKey;
+        for (int c = me; c < n_cand; c += step) {
+            unsigned long long key = key_at(c);
+            if ((!have_floor || key > floor_key) && key < best) best = key;
+        }
+        return best;
+    };
+    unsigned long long mine = scan(false, 0);
+    int n = 0;
+    for (; n < k; ++n) {
+        const unsigned long long best = wave_min_u64(mine);
+        if (best == kNoKey) break;
+        emit(n, best);
+        if (mine == best) mine = scan(true, best);
+    }
+    return n;
+}
+
+// Top-k over the whole workgroup (256 threads): every wave extracts the k smallest keys of its
+// quarter into `stage` (LDS, 4 * k entries), then wave 0 merges them.  Returns, in wave 0 only,
+// the number of keys emitted; the other waves get -1 and have nothing left to do for this list.
+template <class KeyAt, class Emit>
+__device__ __forceinline__ int wg_topk(int n_cand, KeyAt key_at, int k, unsigned long long *stage, Emit emit) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long *mine = stage + (size_t)wave * k;
+    int n = wave_extract(threadIdx.x, 256, n_cand, key_at, k, [&](int r, unsigned long long key) {
+        if (lane == 0) mine[r] = key;
+    });
+    for (int r = n + lane; r < k; r += 64) mine[r] = kNoKey;
+    __syncthreads();
+    if (wave != 0) return -1;
+    return wave_extract(lane, 64, 4 * k, [&](int c) { return stage[c]; }, k, emit);
+}
+
+// One workgroup per query block.  The squared distances of all candidates are computed once into
+// LDS (the candidate id is the array index), then extracted with wg_topk.  `cache_keys` is false
+// when they do not fit: distances are then recomputed on every scan (same results, slower).
+// Dynamic LDS: [n_cand floats if cache_keys, padded to 8 bytes][4 * topk keys].
 __global__ __launch_bounds__(256) void select_topk(int nb_obj, int n_views, int tg, int topk, int cache_keys,
                                                    const float2 *__restrict__ uv, int32_t *__restrict__ idx,
                                                    float *__restrict__ dist2_out) {
-    extern __shared__ unsigned long long key_cache[];
+    extern __shared__ unsigned long long lds_base[];
     const int row = blockIdx.x;  // query block
     const int tpv = tg * tg;
     const int n_tiles = n_views * tpv;
     const bool obj_row = row < nb_obj;
     const int n_cand = obj_row ? n_tiles : nb_obj;
     const int id_base = obj_row ? nb_obj : 0;
+    const int max_cand = nb_obj > n_tiles ? nb_obj : n_tiles;
+    float *d2_cache = reinterpret_cast<float *>(lds_base);
+    unsigned long long *stage = lds_base + (cache_keys ? (max_cand + 1) / 2 : 0);
     int qm = 0, qi = 0, qj = 0;
     if (!obj_row) {
         int t = row - nb_obj;
@@ -105,58 +173,33 @@ __global__ __launch_bounds__(256) void select_topk(int nb_obj, int n_views, int 
         qi = r / tg;
         qj = r % tg;
     }
-    auto key_of = [&](int c) {
-        float d2;
+    auto d2_of = [&](int c) {
         if (obj_row) {
             int m = c / tpv, r = c % tpv;
-            d2 = dist2(uv[(size_t)row * n_views + m], r / tg, r % tg);
-        } else {
-            d2 = dist2(uv[(size_t)c * n_views + qm], qi, qj);
+            return dist2(uv[(size_t)row * n_views + m], r / tg, r % tg);
         }
-        return make_key(d2, (unsigned)c);
+        return dist2(uv[(size_t)c * n_views + qm], qi, qj);
     };
-    __shared__ unsigned long long wmin[4];
-    const unsigned long long kNone = ~0ull;
-    // smallest key of this thread's slice strictly above `floor_key` (any key if !have_floor)
-    auto scan = [&](bool have_floor, unsigned long long floor_key) {
-        unsigned long long best = kNone;
-        for (int c = threadIdx.x; c < n_cand; c += blockDim.x) {
-            unsigned long long key = cache_keys ? key_cache[c] : key_of(c);
-            if ((!have_floor || key > floor_key) && key < best) best = key;
+    int32_t *idx_row = idx + (size_t)row * topk;
+    float *d2_row = dist2_out ? dist2_out + (size_t)row * topk : nullptr;
+    auto emit = [&](int r, unsigned long long key) {
+        if ((threadIdx.x & 63) == 0) {
+            idx_row[r] = id_base + (int)(unsigned)(key & 0xffffffffu);
+            if (d2_row) d2_row[r] = __uint_as_float((unsigned)(key >> 32));
         }
-        return best;
     };
+    int n;
     if (cache_keys) {
-        for (int c = threadIdx.x; c < n_cand; c += blockDim.x) key_cache[c] = key_of(c);
-        // each thread only ever reads back the entries it wrote itself: no barrier needed
+        // every thread reads back only the entries it wrote itself: no barrier needed
+        for (int c = threadIdx.x; c < n_cand; c += blockDim.x) d2_cache[c] = d2_of(c);
+        n = wg_topk(n_cand, [&](int c) { return make_key(d2_cache[c], (unsigned)c); }, topk, stage, emit);
+    } else {
+        n = wg_topk(n_cand, [&](int c) { return make_key(d2_of(c), (unsigned)c); }, topk, stage, emit);
     }
-    unsigned long long mine = scan(false, 0);
-    for (int k = 0; k < topk; ++k) {
-        unsigned long long best = wave_min_u64(mine);
-        if ((threadIdx.x & 63) == 0) wmin[threadIdx.x >> 6] = best;
-        __syncthreads();
-        unsigned long long b0 = wmin[0], b1 = wmin[1], b2 = wmin[2], b3 = wmin[3];
-        __syncthreads();
-        unsigned long long m01 = b0 < b1 ? b0 : b1, m23 = b2 < b3 ? b2 : b3;
-        best = m01 < m23 ? m01 : m23;
-        if (threadIdx.x == 0) {
-            if (best == kNone) {
-                idx[(size_t)row * topk + k] = -1;
-                if (dist2_out) dist2_out[(size_t)row * topk + k] = __builtin_inff();
-            } else {
-                idx[(size_t)row * topk + k] = id_base + (int)(unsigned)(best & 0xffffffffu);
-                if (dist2_out) dist2_out[(size_t)row * topk + k] = __uint_as_float((unsigned)(best >> 32));
-            }
-        }
-        if (best == kNone) {
-            // no candidates left: the remaining entries are all empty
-            for (int kk = k + 1 + threadIdx.x; kk < topk; kk += blockDim.x) {
-                idx[(size_t)row * topk + kk] = -1;
-                if (dist2_out) dist2_out[(size_t)row * topk + kk] = __builtin_inff();
-            }
-            return;
-        }
-        if (mine == best) mine = scan(true, best);  // keys are distinct: exactly one thread owns the winner
+    if (n < 0) return;
+    for (int k = n + (threadIdx.x & 63); k < topk; k += 64) {  // fewer candidates than topk
+        idx_row[k] = -1;
+        if (d2_row) d2_row[k] = __builtin_inff();
     }
 }
 
@@ -184,61 +227,20 @@ __device__ __forceinline__ float sqdist3(float ax, float ay, float az, float bx,
     return (dx * dx + dy * dy) + dz * dz;
 }
 
-__device__ __forceinline__ float wave_min_f32(float v) {
-    for (int off = 32; off >= 1; off >>= 1) v = fminf(v, __shfl_xor(v, off, 64));
-    return v;
-}
-
-// Emits the k smallest of n_cand distinct keys (key_at(c), c < n_cand) in ascending order, as
-// (id = low word, distance = high word), by rounds of a workgroup-wide minimum; keys equal to
-// all-ones do not exist.  Every thread of the 256-thread workgroup must call it; returns the
-// number emitted (the same in every thread).
-template <class KeyAt>
-__device__ __forceinline__ int wg_extract(int n_cand, KeyAt key_at, int k, int32_t *idx_out, float *d2_out,
-                                          unsigned long long *wmin /* LDS, 4 entries */) {
-    const unsigned long long kNone = ~0ull;
-    auto scan = [&](bool have_floor, unsigned long long floor_key) {
-        unsigned long long best = kNone;
-        for (int c = threadIdx.x; c < n_cand; c += blockDim.x) {
-            unsigned long long key = key_at(c);
-            if ((!have_floor || key > floor_key) && key < best) best = key;
-        }
-        return best;
-    };
-    unsigned long long mine = scan(false, 0);
-    int n = 0;
-    for (; n < k; ++n) {
-        unsigned long long best = wave_min_u64(mine);
-        if ((threadIdx.x & 63) == 0) wmin[threadIdx.x >> 6] = best;
-        __syncthreads();
-        unsigned long long b0 = wmin[0], b1 = wmin[1], b2 = wmin[2], b3 = wmin[3];
-        __syncthreads();
-        unsigned long long m01 = b0 < b1 ? b0 : b1, m23 = b2 < b3 ? b2 : b3;
-        best = m01 < m23 ? m01 : m23;
-        if (best == kNone) break;
-        if (threadIdx.x == 0) {
-            idx_out[n] = (int)(unsigned)(best & 0xffffffffu);
-            if (d2_out) d2_out[n] = __uint_as_float((unsigned)(best >> 32));
-        }
-        if (mine == best) mine = scan(true, best);
-    }
-    return n;
-}
-
 struct Route3d {
     int nb_obj, n_views, tg, width, prefilter, k_v2v, k_v2i, k_i2v, k_i2i, cache_keys;
 };
 
-// Dynamic LDS: [nb_obj keys if cache_keys][n_views * prefilter candidate keys].
+// Dynamic LDS: [n_views * prefilter candidate keys][4 * max(k_v2v, k_i2v) staged keys]
+// [nb_obj floats if cache_keys].
 __global__ __launch_bounds__(256) void select_3d(Route3d a, const float4 *__restrict__ cent,
                                                  const float *__restrict__ pos_img,
                                                  const lsrm_camera *__restrict__ cams, int32_t *__restrict__ idx,
                                                  float *__restrict__ dist2_out) {
-    extern __shared__ unsigned long long key_cache[];
-    __shared__ unsigned long long wmin[4];
-    const unsigned long long kNone = ~0ull;
-    unsigned long long *vol_keys = key_cache;
-    unsigned long long *img_keys = key_cache + (a.cache_keys ? a.nb_obj : 0);
+    extern __shared__ unsigned long long lds_base[];
+    unsigned long long *img_keys = lds_base;
+    unsigned long long *stage = img_keys + (size_t)a.n_views * a.prefilter;
+    float *vol_d2 = reinterpret_cast<float *>(stage + 4 * (size_t)(a.k_v2v > a.k_i2v ? a.k_v2v : a.k_i2v));
     const int row = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tpv = a.tg * a.tg;
@@ -253,48 +255,81 @@ __global__ __launch_bounds__(256) void select_3d(Route3d a, const float4 *__rest
             const float2 uv = project(cams[m], p.x, p.y, p.z);
             unsigned long long *out = img_keys + (size_t)m * a.prefilter;
             if (dist2(uv, 0, 0) == __builtin_inff()) {  // no tile of this view is a candidate
-                for (int c = lane; c < a.prefilter; c += 64) out[c] = kNone;
+                for (int c = lane; c < a.prefilter; c += 64) out[c] = kNoKey;
                 continue;
             }
+            // candidates in groups of four: pick four tiles, then fetch and measure their point sets
+            // together so that the memory latency is paid once per group
             unsigned long long floor_key = 0;
-            for (int c = 0; c < a.prefilter; ++c) {
-                unsigned long long best = kNone;
-                for (int t = lane; t < tpv; t += 64) {
-                    unsigned long long key = make_key(dist2(uv, t / a.tg, t % a.tg), (unsigned)t);
-                    if ((c == 0 || key > floor_key) && key < best) best = key;
+            for (int c0 = 0; c0 < a.prefilter; c0 += 4) {
+                int tile[4];
+                float d[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    tile[u] = -1;
+                    if (c0 + u < a.prefilter) {
+                        unsigned long long best = kNoKey;
+                        for (int t = lane; t < tpv; t += 64) {
+                            unsigned long long key = make_key(dist2(uv, t / a.tg, t % a.tg), (unsigned)t);
+                            if ((c0 + u == 0 || key > floor_key) && key < best) best = key;
+                        }
+                        best = wave_min_u64(best);
+                        floor_key = best;
+                        tile[u] = m * tpv + (int)(unsigned)(best & 0xffffffffu);
+                    }
                 }
-                best = wave_min_u64(best);
-                floor_key = best;
-                const int tile = m * tpv + (int)(unsigned)(best & 0xffffffffu);
-                const float *q = pos_img + ((size_t)tile * kBlock + lane) * 3;
-                float d = wave_min_f32(sqdist3(p.x, p.y, p.z, q[0], q[1], q[2]));
-                if (lane == 0) out[c] = make_key(d, (unsigned)(a.nb_obj + tile));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    d[u] = 0.0f;
+                    if (tile[u] >= 0) {
+                        const float *q = pos_img + ((size_t)tile[u] * kBlock + lane) * 3;
+                        d[u] = sqdist3(p.x, p.y, p.z, q[0], q[1], q[2]);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (tile[u] >= 0) {
+                        float dmin = wave_min_nonneg_f32(d[u]);
+                        if (lane == 0) out[c0 + u] = make_key(dmin, (unsigned)(a.nb_obj + tile[u]));
+                    }
+                }
             }
         }
     }
 
-    // volume rule
+    // volume rule: per-wave extraction, merged by wave 0 (the barrier inside also publishes img_keys)
     int32_t *idx_row = idx + (size_t)row * a.width;
     float *d2_row = dist2_out ? dist2_out + (size_t)row * a.width : nullptr;
-    auto vol_key = [&](int j) {
+    auto vol_d2_of = [&](int j) {
         float4 c = cent[j];
-        return make_key(sqdist3(p.x, p.y, p.z, c.x, c.y, c.z), (unsigned)j);
+        return sqdist3(p.x, p.y, p.z, c.x, c.y, c.z);
     };
     int at = 0;
+    auto emit = [&](int r, unsigned long long key) {
+        if (lane == 0) {
+            idx_row[at + r] = (int)(unsigned)(key & 0xffffffffu);
+            if (d2_row) d2_row[at + r] = __uint_as_float((unsigned)(key >> 32));
+        }
+    };
     if (kv > 0) {
+        int n;
         if (a.cache_keys) {
             // every thread reads back only the entries it wrote itself
-            for (int j = threadIdx.x; j < a.nb_obj; j += blockDim.x) vol_keys[j] = vol_key(j);
-            at = wg_extract(a.nb_obj, [&](int j) { return vol_keys[j]; }, kv, idx_row, d2_row, wmin);
+            for (int j = threadIdx.x; j < a.nb_obj; j += blockDim.x) vol_d2[j] = vol_d2_of(j);
+            n = wg_topk(a.nb_obj, [&](int j) { return make_key(vol_d2[j], (unsigned)j); }, kv, stage, emit);
         } else {
-            at = wg_extract(a.nb_obj, vol_key, kv, idx_row, d2_row, wmin);
+            n = wg_topk(a.nb_obj, [&](int j) { return make_key(vol_d2_of(j), (unsigned)j); }, kv, stage, emit);
         }
+        if (n < 0) return;
+        at = n;
+    } else {
+        __syncthreads();
+        if (wave != 0) return;
     }
-    __syncthreads();  // candidate keys of all views are in LDS
+    // wave 0 alone: the image budget out of the surviving candidates, then the padding
     if (ki > 0)
-        at += wg_extract(a.n_views * a.prefilter, [&](int c) { return img_keys[c]; }, ki, idx_row + at,
-                         d2_row ? d2_row + at : nullptr, wmin);
-    for (int k = at + threadIdx.x; k < a.width; k += blockDim.x) {
+        at += wave_extract(lane, 64, a.n_views * a.prefilter, [&](int c) { return img_keys[c]; }, ki, emit);
+    for (int k = at + lane; k < a.width; k += 64) {
         idx_row[k] = -1;
         if (d2_row) d2_row[k] = __builtin_inff();
     }
@@ -325,9 +360,11 @@ lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const 
     a.k_i2v = r.k_i2v;
     a.k_i2i = r.k_i2i;
     if (a.prefilter < 1) a.k_v2i = a.k_i2i = 0;  // no tiles at all
-    const size_t cand_bytes = (size_t)s.n_views * (a.prefilter > 0 ? a.prefilter : 0) * sizeof(unsigned long long);
-    const size_t vol_bytes = (size_t)s.nb_obj * sizeof(unsigned long long);
-    if (cand_bytes > 32 * 1024) return LSRM_ERR_UNSUPPORTED;
+    const int k_vol = a.k_v2v > a.k_i2v ? a.k_v2v : a.k_i2v;
+    const size_t cand_bytes = ((size_t)s.n_views * (a.prefilter > 0 ? a.prefilter : 0) + 4 * (size_t)k_vol) *
+                              sizeof(unsigned long long);
+    const size_t vol_bytes = (size_t)s.nb_obj * sizeof(float);
+    if (cand_bytes > 36 * 1024) return LSRM_ERR_UNSUPPORTED;  // api.hip has bounded both terms below this
     a.cache_keys = vol_bytes + cand_bytes <= 60 * 1024 ? 1 : 0;
     const size_t lds = cand_bytes + (a.cache_keys ? vol_bytes : 0);
     hipLaunchKernelGGL(select_3d, dim3(s.nb), dim3(256), lds, st, a, cent, d_pos_img, d_cams, d_idx, d_dist2);
@@ -350,9 +387,12 @@ lsrm_status launch_route(const Shape &s, const float *d_pos, const lsrm_camera *
     }
     if (s.nb > 0 && s.topk > 0) {
         const int max_cand = s.nb_obj > s.n_tiles ? s.nb_obj : s.n_tiles;
-        const size_t lds = (size_t)max_cand * sizeof(unsigned long long);
-        const int cache_keys = lds <= 60 * 1024 ? 1 : 0;  // default dynamic-LDS limit; beyond it keys are recomputed
-        hipLaunchKernelGGL(select_topk, dim3(s.nb), dim3(256), cache_keys ? lds : 0, st, s.nb_obj, s.n_views,
+        const size_t stage_bytes = 4 * (size_t)s.topk * sizeof(unsigned long long);
+        const size_t cache_bytes = (size_t)((max_cand + 1) / 2) * sizeof(unsigned long long);
+        // default dynamic-LDS limit; beyond it distances are recomputed
+        const int cache_keys = cache_bytes + stage_bytes <= 60 * 1024 ? 1 : 0;
+        const size_t lds = stage_bytes + (cache_keys ? cache_bytes : 0);
+        hipLaunchKernelGGL(select_topk, dim3(s.nb), dim3(256), lds, st, s.nb_obj, s.n_views,
                            s.grid / 8, s.topk, cache_keys, uv, d_idx, d_dist2);
         LSRM_HIP_CHECK(hipGetLastError());
     }
