@@ -105,12 +105,18 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
                 want_lse=False, want_branches=False):
     """NSA forward for the query blocks in `qblocks` (all blocks if None).
 
+    q [N, H, d]; k, v [N, h_kv, d] and kc, vc [NB, h_kv, d] with h_kv dividing H (grouped-query
+    heads); gates [N, H, 3] (per head) or [N, 3, H, d] (per channel).
     Returns out fp32 [nq*64, H, d] (compact over the listed blocks) and, on request,
     lse fp32 [3, nq*64, H] and the three branch outputs fp32 [3, nq*64, H, d].
     """
     q, k, v, kc, vc, gates = map(_f32, (q, k, v, kc, vc, gates))
     idx, seg = _i32(idx), _i32(seg_offsets)
     n, h, d = q.shape
+    h_kv = k.shape[1]
+    assert h % h_kv == 0 and v.shape == k.shape and kc.shape[1] == h_kv and vc.shape == kc.shape
+    assert gates.shape in ((n, h, 3), (n, 3, h, d))
+    gate_channels = 1 if gates.ndim == 4 else 0
     topk = idx.shape[1] if idx.ndim == 2 else 0
     if qblocks is None:
         qblocks = np.arange(n // 64, dtype=np.int32)
@@ -120,10 +126,10 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
     lse = np.empty((3, nq * 64, h), dtype=np.float32) if want_lse else None
     ob = np.empty((3, nq * 64, h, d), dtype=np.float32) if want_branches else None
     _load().oracle_nsa_forward(
-        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), ctypes.c_int(topk), ctypes.c_int(window),
-        ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
+        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(h_kv), ctypes.c_int(d), ctypes.c_int(topk),
+        ctypes.c_int(window), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
         _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
-        _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
+        _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float), ctypes.c_int(gate_channels),
         _p(qblocks, ctypes.c_int32), ctypes.c_int(nq), _p(out, ctypes.c_float),
         _p(lse, ctypes.c_float), _p(ob, ctypes.c_float))
     res = [out]

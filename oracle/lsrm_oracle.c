@@ -301,18 +301,25 @@ static void key_sets(int64_t i, int64_t nb, int topk, int window, int n_seg, con
 }
 
 /*
- * NSA forward for the listed query blocks.
- *   q, k, v  [N, H, d] fp32;  kc, vc [NB, H, d] fp32 (pooled);  idx [NB, K];
- *   gates [N, H, 3];  seg [n_seg + 1] token offsets;  qblocks [nq] block ids.
+ * NSA forward for the listed query blocks (App. A, Eq. nsa_1 and nsa_2), with grouped-query
+ * heads: h query heads, h_kv key/value heads, query head hh reads key/value head hh / (h / h_kv)
+ * (App. A: q in R^{N x h_q x d_h}, k, v in R^{N x h_kv x d_h}; LSRM uses h_q = 32, h_kv = 2).
+ *   q [N, H, d];  k, v [N, h_kv, d];  kc, vc [NB, h_kv, d] (pooled), all fp32;  idx [NB, K];
+ *   gates: gate_channels == 0: [N, H, 3], one weight per head and branch;
+ *          gate_channels == 1: [N, 3, H, d], one weight per output channel and branch (App. A:
+ *          the gating weights have the dimension of the token, h_q * d_h);
+ *   seg [n_seg + 1] token offsets;  qblocks [nq] block ids.
  * Outputs are compact over the listed blocks (row r = 64 * position-in-list + t):
  *   out [nq*64, H, d];  lse [3, nq*64, H] (nullable);  ob [3, nq*64, H, d] (nullable).
  */
-void oracle_nsa_forward(int64_t n, int h, int d, int topk, int window, float scale, int n_seg,
+void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window, float scale, int n_seg,
                         const int32_t *seg, const float *q, const float *k, const float *v,
                         const float *kc, const float *vc, const int32_t *idx, const float *gates,
-                        const int32_t *qblocks, int nq, float *out, float *lse, float *ob) {
+                        int gate_channels, const int32_t *qblocks, int nq, float *out, float *lse, float *ob) {
     int64_t nb = n / BLK;
-    size_t stride = (size_t)h * d;
+    size_t stride = (size_t)h * d;        /* row stride of q and the outputs */
+    size_t stride_kv = (size_t)h_kv * d;  /* row stride of k, v, kc, vc */
+    int group = h / h_kv;
     double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
     size_t maxkeys = (size_t)nb;
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
@@ -328,19 +335,25 @@ void oracle_nsa_forward(int64_t n, int h, int d, int topk, int window, float sca
 #pragma omp for schedule(dynamic, 1) collapse(2)
         for (int iq = 0; iq < nq; ++iq) {
             for (int hh = 0; hh < h; ++hh) {
+                size_t kvo = (size_t)(hh / group) * d; /* offset of this query head's key/value head */
                 for (int t = 0; t < BLK; ++t) {
                     int64_t i = (int64_t)qblocks[iq] * BLK + t;
                     int64_t r = (int64_t)iq * BLK + t;
                     int nc, ns, nw;
                     key_sets(i, nb, topk, window, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
                     const float *qv = q + (size_t)i * stride + (size_t)hh * d;
-                    double l0 = attend(qv, d, sc, kc + (size_t)hh * d, vc + (size_t)hh * d, stride, rc, nc, s, o);
-                    double l1 = attend(qv, d, sc, k + (size_t)hh * d, v + (size_t)hh * d, stride, rs, ns, s, o + d);
-                    double l2 = attend(qv, d, sc, k + (size_t)hh * d, v + (size_t)hh * d, stride, rw, nw, s, o + 2 * d);
-                    const float *g = gates + ((size_t)i * h + hh) * 3;
-                    for (int c = 0; c < d; ++c)
-                        out[((size_t)r * h + hh) * d + c] =
-                            (float)((double)g[0] * o[c] + (double)g[1] * o[d + c] + (double)g[2] * o[2 * d + c]);
+                    double l0 = attend(qv, d, sc, kc + kvo, vc + kvo, stride_kv, rc, nc, s, o);
+                    double l1 = attend(qv, d, sc, k + kvo, v + kvo, stride_kv, rs, ns, s, o + d);
+                    double l2 = attend(qv, d, sc, k + kvo, v + kvo, stride_kv, rw, nw, s, o + 2 * d);
+                    for (int c = 0; c < d; ++c) {
+                        double acc = 0.0;
+                        for (int br = 0; br < 3; ++br) {
+                            double g = gate_channels ? (double)gates[(((size_t)i * 3 + br) * h + hh) * d + c]
+                                                     : (double)gates[((size_t)i * h + hh) * 3 + br];
+                            acc += g * o[br * d + c];
+                        }
+                        out[((size_t)r * h + hh) * d + c] = (float)acc;
+                    }
                     if (lse) {
                         lse[((size_t)0 * rows_out + r) * h + hh] = (float)l0;
                         lse[((size_t)1 * rows_out + r) * h + hh] = (float)l1;

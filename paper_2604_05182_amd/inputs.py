@@ -37,6 +37,12 @@ class NSAConfig:
     points: str        # "uniform" | "ellipsoids"
     near_views: int = 0  # views placed at half distance
     seed: int = 0
+    h_kv: int = 0        # key/value heads (0 = same as `heads`); query head i reads head i // (heads / h_kv)
+    gate_channels: bool = False  # gates per output channel [N, 3, H, d] instead of per head [N, H, 3]
+
+    @property
+    def kv_heads(self) -> int:
+        return self.h_kv if self.h_kv > 0 else self.heads
 
     @property
     def n_img(self) -> int:
@@ -100,9 +106,10 @@ CONFIGS = {
 
 
 def small_config(name="unit", n_obj=512, n_views=2, grid=16, heads=2, d=64, topk=3, window=128,
-                 points="uniform", seed=7, near_views=0) -> NSAConfig:
+                 points="uniform", seed=7, near_views=0, h_kv=0, gate_channels=False) -> NSAConfig:
     """A config small enough for pure-Python / dense-matrix checks."""
-    return NSAConfig(name, n_obj, n_views, grid, heads, d, topk, window, points, near_views, seed)
+    return NSAConfig(name, n_obj, n_views, grid, heads, d, topk, window, points, near_views, seed, h_kv,
+                     gate_channels)
 
 
 # ----------------------------------------------------------------------------- bf16 helpers
@@ -307,15 +314,18 @@ def _normal_bf16(shape, seed: int, stream: int, chunk_rows: int = 1 << 12) -> np
 
 
 def make_qkv(cfg: NSAConfig):
-    """(q, k, v) bf16 bit patterns, each uint16 [N, H, d], values ~ N(0, 1) rounded to bf16."""
-    shape = (cfg.n, cfg.heads, cfg.d)
-    return tuple(_normal_bf16(shape, cfg.seed, 10 + i) for i in range(3))
+    """(q, k, v) bf16 bit patterns, uint16: q [N, H, d], k and v [N, h_kv, d]; values ~ N(0, 1)
+    rounded to bf16."""
+    return tuple(_normal_bf16((cfg.n, cfg.heads if i == 0 else cfg.kv_heads, cfg.d), cfg.seed, 10 + i)
+                 for i in range(3))
 
 
 def make_gates(cfg: NSAConfig) -> np.ndarray:
-    """Gate weights sigmoid(N(0,1)), float32 [N, H, 3] in branch order (cmp, sel, win)."""
+    """Gate weights sigmoid(N(0,1)), float32, branch order (cmp, sel, win): [N, H, 3], or
+    [N, 3, H, d] when the config asks for one gate per output channel."""
     rng = _rng(cfg.seed, 20)
-    g = rng.standard_normal((cfg.n, cfg.heads, 3), dtype=np.float32)
+    shape = (cfg.n, 3, cfg.heads, cfg.d) if cfg.gate_channels else (cfg.n, cfg.heads, 3)
+    g = rng.standard_normal(shape, dtype=np.float32)
     return (1.0 / (1.0 + np.exp(-g.astype(np.float64)))).astype(np.float32)
 
 

@@ -44,9 +44,13 @@ def masked_attention(q, k, v, mask, scale):
 
 
 def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None):
-    """All float64.  Returns out [N,H,d], branches [3,N,H,d], lse [3,N,H]."""
+    """All float64.  Returns out [N,H,d], branches [3,N,H,d], lse [3,N,H].
+    Grouped-query heads (k, v with fewer heads than q) are expanded to one key/value head per
+    query head first; gates are [N,H,3] or, per channel, [N,3,H,d]."""
     q, k, v, gates = (np.asarray(a, dtype=np.float64) for a in (q, k, v, gates))
     n, h, d = q.shape
+    if k.shape[1] != h:
+        k, v = (np.repeat(a, h // a.shape[1], axis=1) for a in (k, v))
     scale = 1.0 / np.sqrt(d) if not scale else scale
     kc, vc = pooled(k), pooled(v)
     sel, win = masks(n, idx, seg_offsets, window)
@@ -57,7 +61,10 @@ def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None):
         ob[0, :, hh], lse[0, :, hh], _ = masked_attention(q[:, hh], kc[:, hh], vc[:, hh], allc, scale)
         ob[1, :, hh], lse[1, :, hh], _ = masked_attention(q[:, hh], k[:, hh], v[:, hh], sel, scale)
         ob[2, :, hh], lse[2, :, hh], _ = masked_attention(q[:, hh], k[:, hh], v[:, hh], win, scale)
-    out = sum(gates[:, :, b, None] * ob[b] for b in range(3))
+    if gates.ndim == 4:
+        out = np.einsum("nbhc,bnhc->nhc", gates, ob)
+    else:
+        out = sum(gates[:, :, b, None] * ob[b] for b in range(3))
     return out, ob, lse
 
 

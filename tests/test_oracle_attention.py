@@ -77,6 +77,73 @@ def test_branches_match_torch_sdpa(oracle_lib):
     assert np.abs(ob[2] - o_win).max() < 2e-6
 
 
+def _gqa_case(seed, heads=8, h_kv=2, d=16, gate_channels=True):
+    cfg = I.small_config(n_obj=256, n_views=2, grid=16, heads=heads, d=d, topk=2, window=96, seed=seed, h_kv=h_kv,
+                         gate_channels=gate_channels)
+    q, k, v = (I.bf16_bits_to_f32(a) for a in I.make_qkv(cfg))
+    rng = np.random.default_rng(seed)
+    idx = np.stack([rng.choice(cfg.nb, size=2, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    return cfg, q, k, v, I.make_gates(cfg), idx
+
+
+@pytest.mark.parametrize("gate_channels", [False, True])
+def test_grouped_heads_and_channel_gates_match_dense_formulation(oracle_lib, gate_channels):
+    cfg, q, k, v, gates, idx = _gqa_case(11, gate_channels=gate_channels)
+    assert k.shape == (cfg.n, 2, 16) and gates.shape == ((cfg.n, 3, 8, 16) if gate_channels else (cfg.n, 8, 3))
+    idx[3, 0] = -1
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    out, lse, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, want_lse=True,
+                                          want_branches=True)
+    rout, rob, rlse = D.dense_nsa(q, k, v, idx, gates, seg, cfg.window)
+    assert np.abs(out - rout).max() < 2e-6 and np.abs(ob - rob).max() < 2e-6 and np.abs(lse - rlse).max() < 2e-6
+
+
+def test_grouped_heads_match_library_gqa(oracle_lib):
+    """torch's scaled_dot_product_attention with enable_gqa groups consecutive query heads on
+    one key/value head, the grouping of App. A (h_q = 32 query heads on h_kv = 2)."""
+    import torch
+    cfg, q, k, v, gates, idx = _gqa_case(12, heads=8, h_kv=2)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    _, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, want_branches=True)
+    sel, win = D.masks(cfg.n, idx, seg, cfg.window)
+    F = torch.nn.functional.scaled_dot_product_attention
+    tq, tk, tv, tkc, tvc = (torch.tensor(a, dtype=torch.float64).permute(1, 0, 2)[None] for a in (q, k, v, kc, vc))
+    o_cmp = F(tq, tkc, tvc, enable_gqa=True)[0].permute(1, 0, 2).numpy()
+    o_sel = F(tq, tk, tv, attn_mask=torch.tensor(sel), enable_gqa=True)[0].permute(1, 0, 2).numpy()
+    o_win = F(tq, tk, tv, attn_mask=torch.tensor(win), enable_gqa=True)[0].permute(1, 0, 2).numpy()
+    assert np.abs(ob[0] - o_cmp).max() < 2e-6
+    assert np.abs(ob[1] - o_sel).max() < 2e-6
+    assert np.abs(ob[2] - o_win).max() < 2e-6
+    # the heads of one group see the same keys: with equal queries they give equal outputs,
+    # and heads of different groups do not
+    q2 = q.copy()
+    q2[:, 1:4] = q2[:, 0:1]
+    q2[:, 4] = q2[:, 0]
+    _, ob2 = oracle_lib.nsa_forward(q2, k, v, kc, vc, idx, gates, seg, cfg.window, want_branches=True)
+    assert np.array_equal(ob2[:, :, 1], ob2[:, :, 0]) and np.array_equal(ob2[:, :, 3], ob2[:, :, 0])
+    assert np.abs(ob2[:, :, 4] - ob2[:, :, 0]).max() > 1e-2
+
+
+def test_channel_gates_reduce_to_head_gates_and_weigh_channels(oracle_lib):
+    cfg, q, k, v, gates, idx = _gqa_case(13, gate_channels=False)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    out, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, want_branches=True)
+    # the same weight on every channel of a head is the per-head gate
+    wide = np.ascontiguousarray(np.broadcast_to(gates.transpose(0, 2, 1)[:, :, :, None], (cfg.n, 3, 8, 16)))
+    out_w = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, wide, seg, cfg.window)
+    assert np.array_equal(out_w, out)
+    # a gate that opens one channel of one branch lets exactly that channel through
+    one = np.zeros((cfg.n, 3, 8, 16), dtype=np.float32)
+    one[:, 2, 5, 7] = 1.0
+    out_1 = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, one, seg, cfg.window)
+    expect = np.zeros_like(out_1)
+    expect[:, 5, 7] = ob[2, :, 5, 7]
+    assert np.array_equal(out_1, expect)
+
+
 def test_dense_equivalence(oracle_lib):
     """One segment, window covering everything and all blocks routed: the selected and
     window branches are plain full attention; with K, V constant inside each block the
