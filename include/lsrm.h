@@ -36,7 +36,7 @@ typedef int32_t lsrm_status;
 enum {
     LSRM_OK = 0,
     LSRM_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, misaligned segment, ... */
-    LSRM_ERR_UNSUPPORTED = -2, /* block != 64, d not in {64,128}, h_kv != h_q, topk > 64    */
+    LSRM_ERR_UNSUPPORTED = -2, /* block != 64, d not in {64,128}, topk > 64, ...            */
     LSRM_ERR_WORKSPACE = -3,   /* d_ws null / too small / misaligned                        */
     LSRM_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed                */
 };
@@ -66,7 +66,8 @@ typedef struct lsrm_nsa_params {
     int32_t grid;     /* S, patches per image side, multiple of 8                          */
     int32_t block;    /* tokens per block; must be 64                                      */
     int32_t h_q;      /* query heads                                                       */
-    int32_t h_kv;     /* key/value heads; must equal h_q                                   */
+    int32_t h_kv;     /* key/value heads, a divisor of h_q: query head i reads key/value
+                         head i / (h_q / h_kv) (grouped-query heads, App. A)               */
     int32_t d;        /* head dimension, 64 or 128                                         */
     int32_t topk;     /* K routed key blocks per query block (<= 64)                       */
     int32_t window;   /* W, even: query i sees keys j with -W/2 <= j - i < W/2             */
@@ -75,6 +76,9 @@ typedef struct lsrm_nsa_params {
                                    first 0, last N; the window never crosses a boundary.
                                    NULL means the default: [objects], [view 0], [view 1]... */
     float scale;      /* softmax scale; 0 selects 1/sqrt(d)                                */
+    int32_t gate_channels; /* 0: d_gates is [N, h_q, 3], one weight per head and branch;
+                              1: d_gates is [N, 3, h_q, d], one weight per output channel
+                              and branch (App. A: gating weights of the token's dimension) */
 } lsrm_nsa_params;
 
 enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2, LSRM_WS_ROUTE_3D = 3 };
@@ -172,7 +176,8 @@ lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, con
  *           all queries of block b attend every token of the listed blocks.  A row
  *           of -1 gives a zero selected branch.
  *   d_gates [N, h_q, 3] fp32  gate weights (cmp, sel, win), already passed through
- *           the sigmoid of Eq. (nsa_2)
+ *           the sigmoid of Eq. (nsa_2); [N, 3, h_q, d] fp32, 16-byte aligned, when
+ *           params.gate_channels is 1 (the sum of Eq. (nsa_1) is then taken per channel)
  *   d_out   [N, h_q, d] bf16  OUT
  *   d_lse   [3, N, h_q] fp32  OUT, nullable: natural-log sum-exp of the scaled scores
  *           of each branch (-inf for an empty key set)
@@ -208,7 +213,7 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
  * rounded to bf16 as MFMA operands.  No atomics on floating-point data: every gradient element
  * is summed in a fixed order (dK/dV go through reverse lists of the routing table, sorted by
  * query block), so results are reproducible bit for bit.
- * Only d = 64 is supported (LSRM_ERR_UNSUPPORTED otherwise).
+ * Only d = 64 with h_kv = h_q and per-head gates is supported (LSRM_ERR_UNSUPPORTED otherwise).
  */
 lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k,
                               const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,

@@ -33,7 +33,7 @@ class lsrm_nsa_params(ctypes.Structure):
                 ("block", ctypes.c_int32), ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("topk", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("n_seg", ctypes.c_int32), ("seg_offsets", ctypes.POINTER(ctypes.c_int32)),
-                ("scale", ctypes.c_float)]
+                ("scale", ctypes.c_float), ("gate_channels", ctypes.c_int32)]
 
 
 class lsrm_route3d_params(ctypes.Structure):
@@ -68,10 +68,11 @@ def strerror(status: int) -> str:
 
 
 def make_params(n_obj, n_views, grid, heads, d, topk, window, seg_offsets=None, scale=0.0, h_kv=None,
-                block=64) -> lsrm_nsa_params:
+                block=64, gate_channels=False) -> lsrm_nsa_params:
     p = lsrm_nsa_params()
+    p.gate_channels = 1 if gate_channels else 0
     p.n_obj, p.n_views, p.grid, p.block = n_obj, n_views, grid, block
-    p.h_q, p.h_kv, p.d, p.topk, p.window = heads, heads if h_kv is None else h_kv, d, topk, window
+    p.h_q, p.h_kv, p.d, p.topk, p.window = heads, heads if not h_kv else h_kv, d, topk, window
     p.scale = scale
     if seg_offsets is None:
         p.n_seg, p.seg_offsets = 0, None

@@ -13,8 +13,8 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
         return LSRM_ERR_INVALID_ARG;
     if (p->n_obj % kBlock != 0 || p->grid % 8 != 0 || (p->window & 1) != 0) return LSRM_ERR_INVALID_ARG;
     if (!(p->scale >= 0.0f) || __builtin_isinf(p->scale)) return LSRM_ERR_INVALID_ARG;
-    if (p->block != kBlock || (p->d != 64 && p->d != 128) || p->h_kv != p->h_q || p->topk > 64)
-        return LSRM_ERR_UNSUPPORTED;
+    if (p->h_q % p->h_kv != 0 || (p->gate_channels != 0 && p->gate_channels != 1)) return LSRM_ERR_INVALID_ARG;
+    if (p->block != kBlock || (p->d != 64 && p->d != 128) || p->topk > 64) return LSRM_ERR_UNSUPPORTED;
     int64_t n_img = (int64_t)p->n_views * p->grid * p->grid;
     int64_t n = (int64_t)p->n_obj + n_img;
     if (n > (int64_t)1 << 30) return LSRM_ERR_UNSUPPORTED;
@@ -22,6 +22,8 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     s->n_views = p->n_views;
     s->grid = p->grid;
     s->h = p->h_q;
+    s->h_kv = p->h_kv;
+    s->gate_channels = p->gate_channels;
     s->d = p->d;
     s->topk = p->topk;
     s->window = p->window;
@@ -81,7 +83,7 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call) {
     switch (which_call) {
         case LSRM_WS_ROUTE: return route_ws_bytes(s);
         case LSRM_WS_FORWARD: return forward_ws_bytes(s);
-        case LSRM_WS_BACKWARD: return s.d == 64 ? backward_ws_bytes(s) : 0;
+        case LSRM_WS_BACKWARD: return s.d == 64 && s.h_kv == s.h && !s.gate_channels ? backward_ws_bytes(s) : 0;
         case LSRM_WS_ROUTE_3D: return route3d_ws_bytes(s);
         default: return 0;
     }
@@ -148,6 +150,7 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
     if (!aligned(d_q, 16) || !aligned(d_k, 16) || !aligned(d_v, 16) || !aligned(d_kc, 16) || !aligned(d_vc, 16) ||
         !aligned(d_out, 16) || (d_out_branch != nullptr && !aligned(d_out_branch, 16)))
         return LSRM_ERR_INVALID_ARG;
+    if (s.gate_channels && !aligned(d_gates, 16)) return LSRM_ERR_INVALID_ARG;
     if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < forward_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
     return launch_forward(s, seg.data(), (int)seg.size() - 1, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_lse,
                           d_out_branch, d_ws, static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(ev_attn_start),
@@ -162,7 +165,7 @@ lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, con
     Shape s;
     lsrm_status rc = make_shape(p, &s);
     if (rc != LSRM_OK) return rc;
-    if (s.d != 64) return LSRM_ERR_UNSUPPORTED;
+    if (s.d != 64 || s.h_kv != s.h || s.gate_channels) return LSRM_ERR_UNSUPPORTED;
     std::vector<int32_t> seg;
     rc = make_segments(p, s, &seg);
     if (rc != LSRM_OK) return rc;

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void pool_blocks(int nb, int row_chunks /* h*d
 lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
                             uint16_t *d_vc, hipStream_t st) {
     if (s.nb == 0) return LSRM_OK;
-    int row_chunks = s.h * s.d / 8;
+    int row_chunks = s.h_kv * s.d / 8;
     dim3 grid((unsigned)(((size_t)s.nb * row_chunks + 255) / 256), 2);
     hipLaunchKernelGGL(pool_blocks, grid, dim3(256), 0, st, s.nb, row_chunks, reinterpret_cast<const uint4 *>(d_k),
                        reinterpret_cast<const uint4 *>(d_v), reinterpret_cast<uint4 *>(d_kc),

@@ -10,7 +10,9 @@
 //   the selected branch each query block streams its own routed blocks (two stages of NP
 //   slots).  Workgroups are numbered so that each of the 8 XCDs walks a contiguous range
 //   of (head, query block) units: the L2 of an XCD then holds one head's pooled
-//   keys/values and the neighbouring windows / routed blocks.
+//   keys/values and the neighbouring windows / routed blocks.  With grouped-query heads the
+//   query heads that share a key/value head are consecutive, hence run back to back on the
+//   same tile images.
 //
 // Per 32-key step, per wavefront
 //   S^T = K Q^T        v_mfma_f32_32x32x16_bf16, A = 32 keys x 16 channels, B = Q^T.
@@ -88,6 +90,8 @@ struct FwdArgs {
     float *gsum;  // scratch: running gated sum, fragment order
     int64_t n;
     int nb, h, topk, window, n_seg;
+    int h_kv, group;    // key/value heads; query heads per key/value head (query head i reads head i / group)
+    int gate_channels;  // gates are [N, 3, H, d] (one per output channel) instead of [N, H, 3]
     int groups_per_head, groups_per_xcd;  // query-block groups of one head, and the share of one XCD
     float scale_log2e, scale;
 };
@@ -771,7 +775,9 @@ __device__ __forceinline__ void finish_branch(WaveCtx<G> &c, const FwdArgs &a, i
         const int64_t row = row0 + 32 * qt + r;
         const float l_tot = half_sum(c.l[qt]);
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-        const float w = a.gates[(row * a.h + head) * 3 + branch] * inv;
+        const float w = a.gate_channels ? inv : a.gates[(row * a.h + head) * 3 + branch] * inv;
+        // per-channel gates of this row, branch and head: D floats
+        const f32x4 *gch = reinterpret_cast<const f32x4 *>(a.gates + ((row * 3 + branch) * a.h + head) * D) + hh;
         if (a.lse != nullptr && hh == 0) {
             float v = l_tot > 0.f ? c.m[qt] * a.scale + __logf(l_tot) : -__builtin_inff();
             a.lse[((int64_t)branch * a.n + row) * a.h + head] = v;
@@ -798,6 +804,7 @@ __device__ __forceinline__ void finish_branch(WaveCtx<G> &c, const FwdArgs &a, i
                 f32x4 v;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) v[j] = w * c.o[qt][dt][4 * gq + j];
+                if (a.gate_channels) v *= gch[8 * dt + 2 * gq];  // channels 32 dt + 8 gq + 4 hh + 0..3
                 if (branch > 0) {
                     f32x4 prev = gs[(dt * 4 + gq) * 64];
                     v += prev;
@@ -875,7 +882,8 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
     const int qb = group * NP + qbi;
     const bool active = qb < a.nb;  // a trailing group may have fewer than NP query blocks
     const int64_t row0 = (int64_t)(active ? qb : 0) * 64 + G::ROWS * sub;
-    const int64_t tile_stride = (int64_t)a.h * G::TILE;  // bytes between consecutive tiles of one head
+    const int kvh = head / a.group;                         // key/value head of this query head
+    const int64_t tile_stride = (int64_t)a.h_kv * G::TILE;  // bytes between consecutive tiles of one head
     const float sl2 = a.scale_log2e;
 
     WaveCtx<G> c;
@@ -903,7 +911,7 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
             c.hi[qt] = a.nb;
         }
         const int n_steps = (a.nb + 31) / 32;
-        const char *base = a.kvc + (int64_t)head * G::TILE;
+        const char *base = a.kvc + (int64_t)kvh * G::TILE;
         auto src = [&](int t) { return base + t * tile_stride; };
         auto msk = [&](int t, int *j0, bool *need) {
             *j0 = 32 * t;
@@ -933,7 +941,7 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
                 my_valid = n_valid;
             }
         }
-        const char *base = a.kv + (int64_t)head * G::TILE;
+        const char *base = a.kv + (int64_t)kvh * G::TILE;
         auto src = [&](int t) {
             int kb = __builtin_amdgcn_readlane(packed, t >> 1);
             return base + (2 * kb + (t & 1)) * tile_stride;
@@ -968,7 +976,7 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
             }
         }
         const int n_steps = st_max > st_min ? st_max - st_min : 0;
-        const char *base = a.kv + (int64_t)head * G::TILE;
+        const char *base = a.kv + (int64_t)kvh * G::TILE;
         auto src = [&](int t) { return base + (st_min + t) * tile_stride; };
         auto msk = [&](int t, int *j0, bool *need) {
             int st = st_min + t;
@@ -1048,9 +1056,9 @@ WsLayout ws_layout(const Shape &s) {
     const size_t tile = (size_t)32 * s.d * 2 * 2;  // K and V^T parts of one (tile, head)
     size_t off = 0;
     w.kv = off;
-    off += align_up((size_t)s.nb * 2 * s.h * tile, 256);
+    off += align_up((size_t)s.nb * 2 * s.h_kv * tile, 256);
     w.kvc = off;
-    off += align_up((size_t)((s.nb + 31) / 32) * s.h * tile, 256);
+    off += align_up((size_t)((s.nb + 31) / 32) * s.h_kv * tile, 256);
     w.gsum = off;
     off += align_up((size_t)s.nb * 64 * s.h * s.d * 4, 256);
     w.total = off > 0 ? off : 256;
@@ -1064,10 +1072,11 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     constexpr int D = G::D, NP = G::NP;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     const int tiles_c = (s.nb + 31) / 32;
-    hipLaunchKernelGGL(pack_tiles<D>, dim3(s.nb, s.h), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h, 2 * s.nb);
+    hipLaunchKernelGGL(pack_tiles<D>, dim3(s.nb, s.h_kv), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h_kv,
+                       2 * s.nb);
     LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(pack_tiles<D>, dim3((s.nb + 63) / 64, s.h), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
-                       (int64_t)s.nb, s.h, tiles_c);
+    hipLaunchKernelGGL(pack_tiles<D>, dim3((s.nb + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
+                       (int64_t)s.nb, s.h_kv, tiles_c);
     LSRM_HIP_CHECK(hipGetLastError());
     a.kv = ws + w.kv;
     a.kvc = ws + w.kvc;
@@ -1120,6 +1129,9 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.n = s.n;
     a.nb = s.nb;
     a.h = s.h;
+    a.h_kv = s.h_kv;
+    a.group = s.h / s.h_kv;
+    a.gate_channels = s.gate_channels;
     a.topk = s.topk;
     a.window = s.window;
     a.n_seg = n_seg;

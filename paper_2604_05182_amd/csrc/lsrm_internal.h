@@ -11,6 +11,8 @@ constexpr int kBlock = 64;
 
 struct Shape {
     int n_obj, n_views, grid, h, d, topk, window;
+    int h_kv;           // key/value heads, divides h
+    int gate_channels;  // 0: gates [N, H, 3]; 1: gates [N, 3, H, d]
     int nb_obj, tiles_per_view, n_tiles, nb;
     int64_t n;
     float scale;

@@ -19,7 +19,7 @@ def params_for(B, cfg, seg_offsets="default", scale=0.0, topk=None, window=None)
     seg = None if isinstance(seg_offsets, str) else seg_offsets
     return B.make_params(cfg.n_obj, cfg.n_views, cfg.grid, cfg.heads, cfg.d,
                          cfg.topk if topk is None else topk, cfg.window if window is None else window,
-                         seg_offsets=seg, scale=scale)
+                         seg_offsets=seg, scale=scale, h_kv=cfg.kv_heads, gate_channels=cfg.gate_channels)
 
 
 def run_route(B, cfg, pos, cams, want_dist=True):
@@ -49,7 +49,7 @@ def run_route_3d(B, cfg, pos, pos_img, cams, width, prefilter, k_v2v, k_v2i, k_i
 def run_compress(B, cfg, k_bits, v_bits):
     p = params_for(B, cfg)
     dk, dv = bf16_dev(k_bits), bf16_dev(v_bits)
-    kc = torch.empty((cfg.nb, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
+    kc = torch.empty((cfg.nb, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device="cuda")
     vc = torch.empty_like(kc)
     B.lsrm_nsa_compress(p, dk, dv, kc, vc)
     torch.cuda.synchronize()

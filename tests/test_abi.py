@@ -36,7 +36,7 @@ def test_host_side_argument_checks():
     assert B.lsrm_workspace_bytes(ok, B.LSRM_WS_FORWARD) >= 1024 * 2 * 64 * 2
     for bad in (B.make_params(500, 2, 16, 2, 64, 3, 128), B.make_params(512, 2, 12, 2, 64, 3, 128),
                 B.make_params(512, 2, 16, 2, 64, 3, 127), B.make_params(512, 2, 16, 2, 96, 3, 128),
-                B.make_params(512, 2, 16, 2, 64, 65, 128), B.make_params(512, 2, 16, 2, 64, 3, 128, h_kv=1)):
+                B.make_params(512, 2, 16, 2, 64, 65, 128), B.make_params(512, 2, 16, 3, 64, 3, 128, h_kv=2)):
         assert B.lsrm_workspace_bytes(bad, B.LSRM_WS_FORWARD) == 0
     assert B.strerror(B.LSRM_ERR_WORKSPACE).startswith("workspace")
     # null pointers are rejected before anything is launched
@@ -59,3 +59,14 @@ def test_host_side_argument_checks():
     assert call(__import__("ctypes").byref(ok), None, *([None] * 6), 0, None) == B.LSRM_ERR_INVALID_ARG
     assert call(__import__("ctypes").byref(ok), __import__("ctypes").byref(r_ok), *([None] * 6), 0, None) \
         == B.LSRM_ERR_INVALID_ARG          # null output table
+    # grouped-query heads and per-channel gates: forward only
+    gqa = B.make_params(512, 2, 16, 4, 64, 3, 128, h_kv=2)
+    chan = B.make_params(512, 2, 16, 2, 64, 3, 128, gate_channels=True)
+    for p in (gqa, chan):
+        assert B.lsrm_workspace_bytes(p, B.LSRM_WS_FORWARD) > 0
+        assert B.lsrm_workspace_bytes(p, B.LSRM_WS_BACKWARD) == 0
+        rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(p), *([None] * 14), 0, None, None, None)
+        assert rc == B.LSRM_ERR_UNSUPPORTED
+    # fewer key/value heads need less room for the packed tiles
+    assert B.lsrm_workspace_bytes(gqa, B.LSRM_WS_FORWARD) < B.lsrm_workspace_bytes(
+        B.make_params(512, 2, 16, 4, 64, 3, 128), B.LSRM_WS_FORWARD)

@@ -139,6 +139,17 @@ def test_forward_ragged_and_holes(B, oracle_lib, d):
     _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx, scale=0.2), cfg.name)
 
 
+@pytest.mark.parametrize("d,heads,h_kv,gate_channels", [(64, 8, 2, False), (64, 3, 1, True), (128, 4, 2, True),
+                                                        (128, 2, 2, True)])
+def test_forward_grouped_heads_and_channel_gates(B, oracle_lib, d, heads, h_kv, gate_channels):
+    """Query heads sharing key/value heads (App. A) and one gate per output channel."""
+    cfg = I.small_config(name=f"gqa-d{d}-h{heads}-kv{h_kv}-ch{int(gate_channels)}", n_obj=640, n_views=2, grid=16,
+                         heads=heads, d=d, topk=3, window=160, seed=31, h_kv=h_kv, gate_channels=gate_channels)
+    _log(f"[forward] {cfg.name}")
+    res, ref_out, ref_lse, ref_ob = _forward_case(B, oracle_lib, cfg)
+    _assert_forward(res, ref_out, ref_lse, ref_ob, cfg.name)
+
+
 def test_forward_dense_equivalence(B, oracle_lib):
     """Single segment, window covering the sequence, every block routed: the selected and
     window branches both equal plain full attention (compared with the oracle's)."""
