@@ -14,7 +14,7 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     if (p->n_obj % kBlock != 0 || p->grid % 8 != 0 || (p->window & 1) != 0) return LSRM_ERR_INVALID_ARG;
     if (!(p->scale >= 0.0f) || __builtin_isinf(p->scale)) return LSRM_ERR_INVALID_ARG;
     if (p->h_q % p->h_kv != 0 || (p->gate_channels != 0 && p->gate_channels != 1)) return LSRM_ERR_INVALID_ARG;
-    if (p->block != kBlock || (p->d != 64 && p->d != 128) || p->topk > 64) return LSRM_ERR_UNSUPPORTED;
+    if (p->block != kBlock || (p->d != 32 && p->d != 64 && p->d != 128) || p->topk > 64) return LSRM_ERR_UNSUPPORTED;
     int64_t n_img = (int64_t)p->n_views * p->grid * p->grid;
     int64_t n = (int64_t)p->n_obj + n_img;
     if (n > (int64_t)1 << 30) return LSRM_ERR_UNSUPPORTED;

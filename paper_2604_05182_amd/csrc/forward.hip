@@ -115,7 +115,10 @@ struct Geo {
     static constexpr int WAVES_PER_SIMD = WAVES / 4;
     static constexpr int NSLOT = 2 * NP;        // tile slots in LDS
     static constexpr int T_INST = TILE / 1024;  // 1 KB copy instructions per tile
-    static constexpr int SH_IPT = T_INST / WAVES;  // shared phases: copy instructions per wavefront and tile
+    // shared phases: copy instructions per wavefront and tile (a small tile, d = 32, has fewer
+    // instructions than the workgroup has wavefronts: the first T_INST wavefronts issue one each
+    // and the others none, whose waits for SH_IPT copies per tile are then trivially met)
+    static constexpr int SH_IPT = T_INST >= WAVES ? T_INST / WAVES : 1;
     static constexpr int OWN_IPT = T_INST / NW;    // selected phase: a wavefront copies its share of its block's tile
     static constexpr int KQ = NS < LSRM_QDEPTH ? NS : LSRM_QDEPTH;  // operand fragments kept in registers (rolling queues)
     static constexpr int VQ = 2 * ND < LSRM_QDEPTH ? 2 * ND : LSRM_QDEPTH;
@@ -123,7 +126,7 @@ struct Geo {
     static constexpr int LDS_BYTES = NSLOT * TILE;
     static_assert(QT == 1 || QT == 2, "");
     static_assert(WAVES % 4 == 0 && WAVES * ROWS * OUT_ROW <= LDS_BYTES, "output staging must fit in the tile slots");
-    static_assert(SH_IPT >= 1 && T_INST % WAVES == 0 && NSLOT >= 7, "");
+    static_assert((T_INST % WAVES == 0 || WAVES % T_INST == 0) && T_INST % NW == 0 && NSLOT >= 7, "");
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -185,6 +188,7 @@ struct WaveCtx {
 // Shared phases: the wavefronts of the workgroup split the T_INST copy instructions of a tile.
 template <class G>
 __device__ __forceinline__ void issue_shared(const WaveCtx<G> &c, const char *tile, char *slot, int wave) {
+    if (G::T_INST < G::WAVES && wave >= G::T_INST) return;
 #pragma unroll
     for (int j = 0; j < G::SH_IPT; ++j) {
         const int i = wave + G::WAVES * j;
@@ -518,7 +522,7 @@ template <class G, typename SrcFn, typename MaskFn>
 __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src, MaskFn msk, int mf_lo, int mf_hi,
                                            char *lds, int wave, int lane, float sl2) {
     constexpr int R = G::NSLOT, QT = G::QT;
-    constexpr bool PAR = G::D == 64 ? LSRM_PAR64 : LSRM_PAR128;
+    constexpr bool PAR = G::D == 128 ? LSRM_PAR128 : LSRM_PAR64;
     if (n_steps <= 0) return;
     auto slot = [&](int t) { return lds + (t % R) * G::TILE; };
     auto lslot = [&](int t) { return lds + (t % R) * G::TILE + c.lane16; };  // this lane's fragment base
@@ -1104,7 +1108,9 @@ lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t
                               int n_tiles, hipStream_t st) {
     if (n_tiles <= 0) return LSRM_OK;
     const dim3 grid((n_tiles + 1) / 2, h);
-    if (d == 64)
+    if (d == 32)
+        hipLaunchKernelGGL(pack_tiles<32>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
+    else if (d == 64)
         hipLaunchKernelGGL(pack_tiles<64>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
     else
         hipLaunchKernelGGL(pack_tiles<128>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
@@ -1139,6 +1145,7 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.scale_log2e = s.scale * 1.4426950408889634f;
     WsLayout w = ws_layout(s);
     char *ws = reinterpret_cast<char *>(d_ws);
+    if (s.d == 32) return launch_forward_d<Geo<32, 4, 1>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
     if (s.d == 64) return launch_forward_d<Geo<64, 4, LSRM_QT64>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
     return launch_forward_d<Geo<128, 4, LSRM_QT128>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
 }
