@@ -6,7 +6,7 @@ lsrm_nsa_compress -> lsrm_nsa_forward, inputs already resident in HBM.  The metr
 effective attention TFLOP/s (4 d h x attended (query, key) pairs; masked or padded work
 does not count) and ms per layer.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..6] [--no-cpu-baseline]
 
 --config 5 times the backward instead (config 2 shapes): a step is one lsrm_nsa_backward call on
 resident inputs and saved forward results; effective FLOPs = 2.5 x the forward's (5 contractions).
@@ -168,7 +168,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4,
-                    help="workload id 1..4 forward (default 4: the largest single-GPU config), 5 backward")
+                    help="workload id 1..4 forward (default 4: the largest single-GPU config), 5 backward, "
+                         "6 forward with the paper's head shape (32 x 32 on 2 key/value heads, channel gates, "
+                         "four-rule routing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--topk", type=int, default=None, help="override the config's routed top-k (experiments)")
     ap.add_argument("--window", type=int, default=None, help="override the config's window (experiments)")
@@ -208,16 +210,17 @@ def main():
     d_pos, d_cams = torch.from_numpy(pos).to(dev), torch.from_numpy(cams).to(dev)
     d_q, d_k, d_v = bf16_dev(q_bits), bf16_dev(k_bits), bf16_dev(v_bits)
     d_gates = torch.from_numpy(gates).to(dev)
-    p = B.make_params(cfg.n_obj, cfg.n_views, cfg.grid, cfg.heads, cfg.d, cfg.topk, cfg.window)
+    p = B.make_params(cfg.n_obj, cfg.n_views, cfg.grid, cfg.heads, cfg.d, cfg.topk, cfg.window, h_kv=cfg.kv_heads,
+                      gate_channels=cfg.gate_channels)
     d_idx = torch.empty((cfg.nb, cfg.topk), dtype=torch.int32, device=dev)
-    d_kc = torch.empty((cfg.nb, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
+    d_kc = torch.empty((cfg.nb, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device=dev)
     d_vc = torch.empty_like(d_kc)
     d_out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
     ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE)
     ws_fwd = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
-    four_rule = args.routing == "four-rule"
+    four_rule = args.routing == "four-rule" or args.config in I.ROUTE3D
     if four_rule:
-        k_vol = cfg.topk // 4
+        k_vol = I.ROUTE3D[args.config]["k_v2v"] if args.config in I.ROUTE3D else cfg.topk // 4
         r3d = B.lsrm_route3d_params(4, k_vol, cfg.topk - k_vol, k_vol, cfg.topk - k_vol)
         d_pos_img = torch.from_numpy(I.make_points_img(cfg, cams)).to(dev)
         ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE_3D)
@@ -300,7 +303,10 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"config {args.config} ({cfg.name}): {cfg.n_obj} object + {cfg.n_views}x{cfg.grid}x{cfg.grid} image "
-                        f"tokens = {cfg.n}, {cfg.heads} heads, d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}"
+                        f"tokens = {cfg.n}, {cfg.heads} heads"
+                        + (f" on {cfg.kv_heads} key/value heads" if cfg.kv_heads != cfg.heads else "")
+                        + f", d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}"
+                        + (", per-channel gates" if cfg.gate_channels else "")
                         + (f", four-rule routing (B^i 4, {k_vol} volume + {cfg.topk - k_vol} image blocks)"
                            if four_rule else ""),
             "effective_flops": flops,
@@ -320,6 +326,19 @@ def main():
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
         },
     }
+    if cfg.d == 32:
+        # At d = 32 a 32 x 32 score tile costs 4 MFMAs but still 1024 exponentials: the softmax arithmetic,
+        # not the matrix pipe, bounds the kernel.  Per score element and head: scale-and-subtract, running
+        # sum, running maximum and the bf16 conversion (4 plain issue slots) plus one exponential (a
+        # quarter-rate instruction: 4 slots).  Peak issue rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+        p_all = cfg.forward_pairs(n_valid)
+        slots = 8.0 * cfg.heads * (p_all["cmp"] + p_all["sel"] + p_all["win"])
+        peak = 256 * 4 * 16 * 2.4e9 / 1e12
+        ach = slots / (ms_attn * 1e-3) / 1e12
+        result["roofline"] = {"kernel": "nsa_forward_kernel", "bound": "alu", "achieved": round(ach, 3),
+                              "peak": round(peak, 2), "unit": "T fp32 lane-op slots/s", "frac": round(ach / peak, 4),
+                              "traffic": None,
+                              "mfma_tflops": round(attn_tflops, 3)}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, {"qkv_bits": (q_bits, k_bits, v_bits), "gates": gates}, idx)
     print(json.dumps(result), flush=True)

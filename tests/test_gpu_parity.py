@@ -186,14 +186,19 @@ def test_forward_config1_full(B, oracle_lib):
     _assert_forward(*_forward_case(B, oracle_lib, cfg), "config1")
 
 
-@pytest.mark.parametrize("cid,n_random", [(2, 24), (3, 12), (4, 4)])
+@pytest.mark.parametrize("cid,n_random", [(2, 24), (3, 12), (4, 4), (6, 8)])
 def test_forward_full_size_sampled(B, oracle_lib, cid, n_random):
     """Full-size launch (the configuration the benchmark times), oracle on a stratified sample of
     query blocks: first and last block of every segment plus random ones, all heads."""
     cfg = I.CONFIGS[cid]
     qblocks = I.sample_query_blocks(cfg, n_random)
     _log(f"[forward] config {cid} full-size launch, oracle on {len(qblocks)} query blocks")
-    _assert_forward(*_forward_case(B, oracle_lib, cfg, qblocks=qblocks), f"config{cid}-sampled")
+    idx = None
+    if cid in I.ROUTE3D:   # routed by the four geometric rules (table from the oracle; the GPU routing has its own tests)
+        cams = I.make_cameras(cfg)
+        idx, _ = oracle_lib.route_3d(I.make_points(cfg), I.make_points_img(cfg, cams), cams, cfg.grid, cfg.topk,
+                                     **I.ROUTE3D[cid])
+    _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx, qblocks=qblocks), f"config{cid}-sampled")
 
 
 def test_forward_is_deterministic(B, oracle_lib):
