@@ -91,22 +91,34 @@ def route_3d(pos, pos_img, cams, grid: int, width: int, prefilter: int, k_v2v: i
     return idx, d2
 
 
-def pool(x: np.ndarray) -> np.ndarray:
-    """x fp32 [N, H, d] -> block means fp32 [N/64, H, d]."""
+def _counts(block_count, nb):
+    if block_count is None:
+        return None
+    cnt = _i32(block_count)
+    assert cnt.shape == (nb,) and cnt.min() >= 1 and cnt.max() <= 64, "active tokens per block: 1..64"
+    return cnt
+
+
+def pool(x: np.ndarray, block_count=None) -> np.ndarray:
+    """x fp32 [N, H, d] -> block means fp32 [N/64, H, d] (over the first block_count[b] tokens of
+    block b when block_count is given, 1..64 each)."""
     x = _f32(x)
     n, h, d = x.shape
     out = np.empty((n // 64, h, d), dtype=np.float32)
+    cnt = _counts(block_count, n // 64)
     _load().oracle_pool(ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), _p(x, ctypes.c_float),
-                        _p(out, ctypes.c_float))
+                        _p(cnt, ctypes.c_int32), _p(out, ctypes.c_float))
     return out
 
 
 def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qblocks=None,
-                want_lse=False, want_branches=False):
+                want_lse=False, want_branches=False, window_mode=0, block_count=None):
     """NSA forward for the query blocks in `qblocks` (all blocks if None).
 
     q [N, H, d]; k, v [N, h_kv, d] and kc, vc [NB, h_kv, d] with h_kv dividing H (grouped-query
     heads); gates [N, H, 3] (per head) or [N, 3, H, d] (per channel).
+    window_mode 0: sliding window of `window` tokens inside the segment; 1: the query's own block.
+    block_count [NB] (optional): active tokens per block (kc, vc pooled with the same counts).
     Returns out fp32 [nq*64, H, d] (compact over the listed blocks) and, on request,
     lse fp32 [3, nq*64, H] and the three branch outputs fp32 [3, nq*64, H, d].
     """
@@ -127,7 +139,8 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
     ob = np.empty((3, nq * 64, h, d), dtype=np.float32) if want_branches else None
     _load().oracle_nsa_forward(
         ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(h_kv), ctypes.c_int(d), ctypes.c_int(topk),
-        ctypes.c_int(window), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
+        ctypes.c_int(window), ctypes.c_int(window_mode), _p(_counts(block_count, n // 64), ctypes.c_int32),
+        ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
         _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
         _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float), ctypes.c_int(gate_channels),
         _p(qblocks, ctypes.c_int32), ctypes.c_int(nq), _p(out, ctypes.c_float),
@@ -140,7 +153,7 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
     return res[0] if len(res) == 1 else tuple(res)
 
 
-def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0):
+def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0, window_mode=0):
     """-> (dq, dk, dv) fp32 [N, H, d]; single-threaded definition, small inputs only."""
     q, k, v, kc, vc, gates, dout = map(_f32, (q, k, v, kc, vc, gates, dout))
     idx, seg = _i32(idx), _i32(seg_offsets)
@@ -149,14 +162,15 @@ def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0
     dq, dk, dv = (np.empty_like(q) for _ in range(3))
     _load().oracle_nsa_backward(
         ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), ctypes.c_int(topk), ctypes.c_int(window),
-        ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
+        ctypes.c_int(window_mode), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
         _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
         _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
         _p(dout, ctypes.c_float), _p(dq, ctypes.c_float), _p(dk, ctypes.c_float), _p(dv, ctypes.c_float))
     return dq, dk, dv
 
 
-def nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, qblocks, kblocks, heads, scale=0.0):
+def nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, qblocks, kblocks, heads, scale=0.0,
+                         window_mode=0):
     """Gradients for a sample: dq [len(qblocks)*64, len(heads), d] of the listed query blocks and
     dk, dv [len(kblocks)*64, len(heads), d] of the listed key blocks (all queries contribute)."""
     q, k, v, kc, vc, gates, dout = map(_f32, (q, k, v, kc, vc, gates, dout))
@@ -169,7 +183,7 @@ def nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout,
     dv = np.empty_like(dk)
     _load().oracle_nsa_backward_sampled(
         ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), ctypes.c_int(topk), ctypes.c_int(window),
-        ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
+        ctypes.c_int(window_mode), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
         _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
         _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float), _p(dout, ctypes.c_float),
         _p(qb, ctypes.c_int32), ctypes.c_int(qb.shape[0]), _p(kb, ctypes.c_int32), ctypes.c_int(kb.shape[0]),

@@ -23,9 +23,10 @@
  *   - three branches [App. A, Eq. (nsa_1)]: CmpAttn over all compressed pairs,
  *                    SelAttn over every token of the routed blocks, WinAttn over a
  *                    local window, each its own softmax, combined by a gated sum.
- *                    The window here is token level: keys j with
- *                    -W/2 <= j - i < W/2, clipped to the query's segment
- *                    (object tokens / each view).  No causal mask anywhere.
+ *                    The window is either token level (keys j with
+ *                    -W/2 <= j - i < W/2, clipped to the query's segment: object
+ *                    tokens / each view) or the query's own block (App. A).  Blocks
+ *                    may hold fewer than 64 active tokens.  No causal mask anywhere.
  *   - backward       analytic gradients of the above with routing and gates fixed.
  *
  * Precision: inputs are fp32 (bf16 values widened).  Routing distances are
@@ -227,16 +228,21 @@ void oracle_route_3d(int n_obj, int n_views, int grid, int width, int prefilter,
 
 /* ------------------------------------------------------------------ pooling */
 
-/* out[b, h, :] = (1/64) sum_t x[64 b + t, h, :];  x is [N, H, d], out is [N/64, H, d]. */
-void oracle_pool(int64_t n, int h, int d, const float *x, float *out) {
+/*
+ * out[b, h, :] = mean over the active tokens t of block b of x[64 b + t, h, :];  x is [N, H, d],
+ * out is [N/64, H, d].  count (nullable) [N/64]: block b has count[b] active tokens (1..64), held in
+ * its first slots (Sec. 3.2: blocks hold a variable number of active tokens); NULL = all 64.
+ */
+void oracle_pool(int64_t n, int h, int d, const float *x, const int32_t *count, float *out) {
     int64_t nb = n / BLK;
     size_t row = (size_t)h * d;
 #pragma omp parallel for schedule(static)
     for (int64_t b = 0; b < nb; ++b) {
+        int cnt = count ? count[b] : BLK;
         for (size_t c = 0; c < row; ++c) {
             double s = 0.0;
-            for (int t = 0; t < BLK; ++t) s += (double)x[((size_t)(BLK * b + t)) * row + c];
-            out[(size_t)b * row + c] = (float)(s / 64.0);
+            for (int t = 0; t < cnt; ++t) s += (double)x[((size_t)(BLK * b + t)) * row + c];
+            out[(size_t)b * row + c] = (float)(s / (double)cnt);
         }
     }
 }
@@ -278,9 +284,15 @@ static int segment_of(const int32_t *seg, int n_seg, int64_t i) {
     return -1;
 }
 
-/* Key rows of the three branches for query token i (block qb = i / 64). Returns counts. */
-static void key_sets(int64_t i, int64_t nb, int topk, int window, int n_seg, const int32_t *seg,
-                     const int32_t *idx, int64_t *rc, int *nc, int64_t *rs, int *ns, int64_t *rw, int *nw) {
+/*
+ * Key rows of the three branches for query token i (block qb = i / 64). Returns counts.
+ *   window_mode 0: keys j with -W/2 <= j - i < W/2 inside the query's segment (the configs' sliding window);
+ *   window_mode 1: the tokens of the query's own block (App. A, "Window").
+ *   count (nullable): active tokens per block (its first count[b] slots); inactive slots are nobody's key.
+ */
+static void key_sets(int64_t i, int64_t nb, int topk, int window, int window_mode, const int32_t *count, int n_seg,
+                     const int32_t *seg, const int32_t *idx, int64_t *rc, int *nc, int64_t *rs, int *ns,
+                     int64_t *rw, int *nw) {
     int64_t qb = i / BLK;
     *nc = 0;
     for (int64_t b = 0; b < nb; ++b) rc[(*nc)++] = b;
@@ -288,15 +300,22 @@ static void key_sets(int64_t i, int64_t nb, int topk, int window, int n_seg, con
     for (int k = 0; k < topk; ++k) {
         int32_t kb = idx[qb * topk + k];
         if (kb < 0) continue;
-        for (int t = 0; t < BLK; ++t) rs[(*ns)++] = (int64_t)kb * BLK + t;
+        int cnt = count ? count[kb] : BLK;
+        for (int t = 0; t < cnt; ++t) rs[(*ns)++] = (int64_t)kb * BLK + t;
     }
     *nw = 0;
+    if (window_mode == 1) {
+        int cnt = count ? count[qb] : BLK;
+        for (int t = 0; t < cnt; ++t) rw[(*nw)++] = qb * BLK + t;
+        return;
+    }
     int sg = segment_of(seg, n_seg, i);
     if (sg >= 0) {
         int64_t lo = i - window / 2, hi = i + window / 2;
         if (lo < seg[sg]) lo = seg[sg];
         if (hi > seg[sg + 1]) hi = seg[sg + 1];
-        for (int64_t j = lo; j < hi; ++j) rw[(*nw)++] = j;
+        for (int64_t j = lo; j < hi; ++j)
+            if (!count || (j % BLK) < count[j / BLK]) rw[(*nw)++] = j;
     }
 }
 
@@ -308,12 +327,14 @@ static void key_sets(int64_t i, int64_t nb, int topk, int window, int n_seg, con
  *   gates: gate_channels == 0: [N, H, 3], one weight per head and branch;
  *          gate_channels == 1: [N, 3, H, d], one weight per output channel and branch (App. A:
  *          the gating weights have the dimension of the token, h_q * d_h);
- *   seg [n_seg + 1] token offsets;  qblocks [nq] block ids.
+ *   seg [n_seg + 1] token offsets;  qblocks [nq] block ids;
+ *   window_mode, count: see key_sets (kc, vc must have been pooled with the same count); rows of
+ *   inactive slots are computed like any other query row (their outputs mean nothing).
  * Outputs are compact over the listed blocks (row r = 64 * position-in-list + t):
  *   out [nq*64, H, d];  lse [3, nq*64, H] (nullable);  ob [3, nq*64, H, d] (nullable).
  */
-void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window, float scale, int n_seg,
-                        const int32_t *seg, const float *q, const float *k, const float *v,
+void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window, int window_mode,
+                        const int32_t *count, float scale, int n_seg, const int32_t *seg, const float *q, const float *k, const float *v,
                         const float *kc, const float *vc, const int32_t *idx, const float *gates,
                         int gate_channels, const int32_t *qblocks, int nq, float *out, float *lse, float *ob) {
     int64_t nb = n / BLK;
@@ -323,13 +344,13 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
     double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
     size_t maxkeys = (size_t)nb;
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
-    if ((size_t)window + 1 > maxkeys) maxkeys = (size_t)window + 1;
+    if ((size_t)window + BLK > maxkeys) maxkeys = (size_t)window + BLK;
     int64_t rows_out = (int64_t)nq * BLK;
 #pragma omp parallel
     {
         int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
         int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
-        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + 1));
+        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + BLK));
         double *s = (double *)malloc(sizeof(double) * maxkeys);
         double *o = (double *)malloc(sizeof(double) * (size_t)d * 3);
 #pragma omp for schedule(dynamic, 1) collapse(2)
@@ -340,7 +361,7 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
                     int64_t i = (int64_t)qblocks[iq] * BLK + t;
                     int64_t r = (int64_t)iq * BLK + t;
                     int nc, ns, nw;
-                    key_sets(i, nb, topk, window, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+                    key_sets(i, nb, topk, window, window_mode, count, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
                     const float *qv = q + (size_t)i * stride + (size_t)hh * d;
                     double l0 = attend(qv, d, sc, kc + kvo, vc + kvo, stride_kv, rc, nc, s, o);
                     double l1 = attend(qv, d, sc, k + kvo, v + kvo, stride_kv, rs, ns, s, o + d);
@@ -383,7 +404,7 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
  * double, single-threaded over queries (this is a definition, not a fast path).
  * dq, dk, dv are fp32 outputs [N, H, d].
  */
-void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, float scale, int n_seg,
+void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, int window_mode, float scale, int n_seg,
                          const int32_t *seg, const float *q, const float *k, const float *v,
                          const float *kc, const float *vc, const int32_t *idx, const float *gates,
                          const float *dout, float *dq, float *dk, float *dv) {
@@ -393,7 +414,7 @@ void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, float sc
     double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
     size_t maxkeys = (size_t)nb;
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
-    if ((size_t)window + 1 > maxkeys) maxkeys = (size_t)window + 1;
+    if ((size_t)window + BLK > maxkeys) maxkeys = (size_t)window + BLK;
     double *gq = (double *)calloc(total, sizeof(double));
     double *gk = (double *)calloc(total, sizeof(double));
     double *gv = (double *)calloc(total, sizeof(double));
@@ -401,12 +422,12 @@ void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, float sc
     double *gvc = (double *)calloc(totalc > 0 ? totalc : 1, sizeof(double));
     int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
     int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
-    int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + 1));
+    int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + BLK));
     double *p = (double *)malloc(sizeof(double) * maxkeys);
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
     for (int64_t i = 0; i < n; ++i) {
         int nc, ns, nw;
-        key_sets(i, nb, topk, window, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+        key_sets(i, nb, topk, window, window_mode, NULL, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
         for (int hh = 0; hh < h; ++hh) {
             const float *qv = q + (size_t)i * stride + (size_t)hh * d;
             const float *dor = dout + (size_t)i * stride + (size_t)hh * d;
@@ -461,7 +482,8 @@ void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, float sc
  * A (query, branch) whose key set meets none of the listed key blocks is skipped unless its
  * dq is wanted.  OpenMP over queries with per-thread accumulators, summed in thread order.
  */
-void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, float scale, int n_seg,
+void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, int window_mode, float scale,
+                                 int n_seg,
                                  const int32_t *seg, const float *q, const float *k, const float *v,
                                  const float *kc, const float *vc, const int32_t *idx, const float *gates,
                                  const float *dout, const int32_t *qblocks, int n_qb, const int32_t *kblocks,
@@ -471,7 +493,7 @@ void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, 
     double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
     size_t maxkeys = (size_t)nb;
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
-    if ((size_t)window + 1 > maxkeys) maxkeys = (size_t)window + 1;
+    if ((size_t)window + BLK > maxkeys) maxkeys = (size_t)window + BLK;
     /* position of a block in the sample lists, or -1 */
     int32_t *qpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nb > 0 ? nb : 1));
     int32_t *kpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nb > 0 ? nb : 1));
@@ -493,13 +515,13 @@ void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, 
         double *tvc = (double *)calloc(tot_c > 0 ? tot_c : 1, sizeof(double));
         int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
         int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
-        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + 1));
+        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + BLK));
         double *p = (double *)malloc(sizeof(double) * maxkeys);
         double *o = (double *)malloc(sizeof(double) * (size_t)d);
 #pragma omp for schedule(dynamic, 16)
         for (int64_t i = 0; i < n; ++i) {
             int nc, ns, nw;
-            key_sets(i, nb, topk, window, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+            key_sets(i, nb, topk, window, window_mode, NULL, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
             int qa = qpos[i / BLK];
             for (int br = 0; br < 3; ++br) {
                 const int64_t *rows = br == 0 ? rc : (br == 1 ? rs : rw);

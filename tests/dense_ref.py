@@ -8,12 +8,18 @@ usable for small N.
 import numpy as np
 
 
-def pooled(x):
+def pooled(x, block_count=None):
     n, h, d = x.shape
-    return x.reshape(n // 64, 64, h, d).mean(axis=1)
+    xb = x.reshape(n // 64, 64, h, d)
+    if block_count is None:
+        return xb.mean(axis=1)
+    act = (np.arange(64)[None, :] < np.asarray(block_count)[:, None]).astype(x.dtype)
+    return (xb * act[:, :, None, None]).sum(axis=1) / np.asarray(block_count, dtype=x.dtype)[:, None, None]
 
 
-def masks(n, idx, seg_offsets, window):
+def masks(n, idx, seg_offsets, window, window_mode=0, block_count=None):
+    """Boolean [n, n] masks of the selected and window branches.  window_mode 1: the window is the
+    query's own block.  block_count: slots at or beyond a block's count are nobody's key."""
     nb = n // 64
     sel = np.zeros((n, n), dtype=bool)
     for qb in range(nb):
@@ -26,6 +32,12 @@ def masks(n, idx, seg_offsets, window):
     i = np.arange(n)[:, None]
     j = np.arange(n)[None, :]
     win = (seg_id[:, None] == seg_id[None, :]) & (seg_id[:, None] >= 0) & (j - i >= -(window // 2)) & (j - i < window // 2)
+    if window_mode == 1:
+        win = (i // 64) == (j // 64)
+    if block_count is not None:
+        active = (np.arange(n) % 64) < np.repeat(np.asarray(block_count), 64)
+        sel = sel & active[None, :]
+        win = win & active[None, :]
     return sel, win
 
 
@@ -43,7 +55,7 @@ def masked_attention(q, k, v, mask, scale):
     return p @ v, lse, p
 
 
-def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None):
+def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None, window_mode=0, block_count=None):
     """All float64.  Returns out [N,H,d], branches [3,N,H,d], lse [3,N,H].
     Grouped-query heads (k, v with fewer heads than q) are expanded to one key/value head per
     query head first; gates are [N,H,3] or, per channel, [N,3,H,d]."""
@@ -52,8 +64,8 @@ def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None):
     if k.shape[1] != h:
         k, v = (np.repeat(a, h // a.shape[1], axis=1) for a in (k, v))
     scale = 1.0 / np.sqrt(d) if not scale else scale
-    kc, vc = pooled(k), pooled(v)
-    sel, win = masks(n, idx, seg_offsets, window)
+    kc, vc = pooled(k, block_count), pooled(v, block_count)
+    sel, win = masks(n, idx, seg_offsets, window, window_mode, block_count)
     allc = np.ones((n, n // 64), dtype=bool)
     ob = np.zeros((3, n, h, d))
     lse = np.zeros((3, n, h))
@@ -68,14 +80,14 @@ def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None):
     return out, ob, lse
 
 
-def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None):
+def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None, window_mode=0):
     """Library autograd (float64) through the dense-mask formulation -> dq, dk, dv."""
     import torch
     tq, tk, tv = (torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True) for a in (q, k, v))
     g = torch.tensor(np.asarray(gates, dtype=np.float64))
     n, h, d = tq.shape
     scale = 1.0 / np.sqrt(d) if not scale else scale
-    sel, win = masks(n, idx, seg_offsets, window)
+    sel, win = masks(n, idx, seg_offsets, window, window_mode)
     sel, win = torch.tensor(sel), torch.tensor(win)
     kc = tk.reshape(n // 64, 64, h, d).mean(1)
     vc = tv.reshape(n // 64, 64, h, d).mean(1)

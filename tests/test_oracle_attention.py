@@ -144,6 +144,73 @@ def test_channel_gates_reduce_to_head_gates_and_weigh_channels(oracle_lib):
     assert np.array_equal(out_1, expect)
 
 
+def _counts(cfg, seed):
+    rng = np.random.default_rng(seed)
+    cnt = rng.integers(1, 65, size=cfg.nb).astype(np.int32)
+    cnt[0], cnt[1], cnt[2] = 64, 1, 33
+    return cnt
+
+
+@pytest.mark.parametrize("window_mode,with_counts", [(1, False), (0, True), (1, True)])
+def test_own_block_window_and_active_counts_match_dense_formulation(oracle_lib, window_mode, with_counts):
+    """App. A: the window branch sees the query's own block; Sec. 3.2: a block holds a variable
+    number of active tokens (here its first count[b] slots)."""
+    cfg, q, k, v, gates, idx = _case(21, heads=3)
+    cnt = _counts(cfg, 5) if with_counts else None
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k, cnt), oracle_lib.pool(v, cnt)
+    out, lse, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, want_lse=True,
+                                          want_branches=True, window_mode=window_mode, block_count=cnt)
+    rout, rob, rlse = D.dense_nsa(q, k, v, idx, gates, seg, cfg.window, window_mode=window_mode, block_count=cnt)
+    fin = np.isfinite(rlse)
+    assert np.array_equal(np.isfinite(lse), fin)
+    assert np.abs(out - rout).max() < 2e-6 and np.abs(ob - rob).max() < 2e-6
+    assert np.abs(lse[fin] - rlse[fin]).max() < 2e-6
+    if window_mode == 1 and not with_counts:
+        # library routine: block-diagonal boolean mask
+        import torch
+        tq, tk, tv = (torch.tensor(a, dtype=torch.float64).permute(1, 0, 2) for a in (q, k, v))
+        blk = torch.arange(cfg.n) // 64
+        o_win = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=blk[:, None] == blk[None, :])
+        assert np.abs(ob[2] - o_win.permute(1, 0, 2).numpy()).max() < 2e-6
+        # with one key the softmax is trivial: the window output of a lone active token is its own value
+    if with_counts:
+        # what sits in inactive slots never matters: scramble them and compare the active rows
+        act = (np.arange(cfg.n) % 64) < np.repeat(cnt, 64)
+        k2, v2 = k.copy(), v.copy()
+        k2[~act] = 37.0
+        v2[~act] = -1e3
+        kc2, vc2 = oracle_lib.pool(k2, cnt), oracle_lib.pool(v2, cnt)
+        assert np.array_equal(kc2, kc) and np.array_equal(vc2, vc)
+        out2 = oracle_lib.nsa_forward(q, k2, v2, kc2, vc2, idx, gates, seg, cfg.window, window_mode=window_mode,
+                                      block_count=cnt)
+        assert np.array_equal(out2, out)
+        if window_mode == 1:
+            # block 1 has a single active token: its window branch returns that token's value
+            assert np.abs(ob[2, 64] - v[64]).max() < 1e-6
+
+
+def test_pool_with_counts_is_the_mean_of_the_active_tokens(oracle_lib):
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((256, 2, 8)).astype(np.float32)
+    cnt = np.array([64, 1, 17, 40], dtype=np.int32)
+    got = oracle_lib.pool(x, cnt)
+    for b, c in enumerate(cnt):
+        assert np.allclose(got[b], x[64 * b:64 * b + c].astype(np.float64).mean(0), rtol=0, atol=1e-7)
+
+
+def test_backward_with_own_block_window_matches_library_autograd(oracle_lib):
+    cfg, q, k, v, gates, idx = _case(22, n_obj=128, n_views=1, grid=16, d=8)
+    seg = cfg.seg_offsets()
+    rng = np.random.default_rng(3)
+    dout = rng.standard_normal(q.shape).astype(np.float32)
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    dq, dk, dv = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout, window_mode=1)
+    rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout, window_mode=1)
+    for a, b in ((dq, rq), (dk, rk), (dv, rv)):
+        assert np.abs(a - b).max() < 1e-5 * max(1.0, np.abs(b).max())
+
+
 def test_dense_equivalence(oracle_lib):
     """One segment, window covering everything and all blocks routed: the selected and
     window branches are plain full attention; with K, V constant inside each block the
