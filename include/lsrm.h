@@ -79,6 +79,16 @@ typedef struct lsrm_nsa_params {
     int32_t gate_channels; /* 0: d_gates is [N, h_q, 3], one weight per head and branch;
                               1: d_gates is [N, 3, h_q, d], one weight per output channel
                               and branch (App. A: gating weights of the token's dimension) */
+    int32_t window_mode;   /* 0: sliding window (`window`, `seg_offsets`); 1: the window branch of a
+                              query sees the tokens of its own block (App. A, "Window"); `window`
+                              and the segments are then unused                                  */
+    const int32_t *d_block_count; /* DEVICE, nullable, [N/64]: block b holds d_block_count[b] active
+                              tokens (1..64) in its first slots (Sec. 3.2: blocks hold a variable
+                              number of active tokens); the other slots are padding: never a key
+                              in any branch, excluded from the block average, and their own
+                              output rows are unspecified.  NULL: every block is full.
+                              Read by lsrm_nsa_compress and lsrm_nsa_forward (pass the same
+                              counts to both); lsrm_nsa_backward does not support it yet.      */
 } lsrm_nsa_params;
 
 enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2, LSRM_WS_ROUTE_3D = 3 };
@@ -161,8 +171,9 @@ lsrm_status lsrm_route_blocks_3d(const lsrm_nsa_params *p, const lsrm_route3d_pa
  * "Compressed".  The learned residual module applied before the average in the paper
  * is upstream of this call.]
  *   d_k, d_v   [N, h_kv, d] bf16
- *   d_kc, d_vc [N/64, h_kv, d] bf16  OUT: mean over the 64 tokens of each block,
- *              accumulated in fp32, rounded to nearest-even bf16.
+ *   d_kc, d_vc [N/64, h_kv, d] bf16  OUT: mean over the 64 tokens of each block (over its
+ *              d_block_count[b] active tokens when counts are given), accumulated in fp32 in
+ *              token order, rounded to nearest-even bf16.
  */
 lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, const uint16_t *d_v,
                               uint16_t *d_kc, uint16_t *d_vc, void *stream);
@@ -213,7 +224,8 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
  * rounded to bf16 as MFMA operands.  No atomics on floating-point data: every gradient element
  * is summed in a fixed order (dK/dV go through reverse lists of the routing table, sorted by
  * query block), so results are reproducible bit for bit.
- * Only d = 64 with h_kv = h_q and per-head gates is supported (LSRM_ERR_UNSUPPORTED otherwise).
+ * Only d = 64 with h_kv = h_q, per-head gates and full blocks (d_block_count NULL) is supported
+ * (LSRM_ERR_UNSUPPORTED otherwise); both window modes are.
  */
 lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k,
                               const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,

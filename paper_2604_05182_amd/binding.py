@@ -33,7 +33,8 @@ class lsrm_nsa_params(ctypes.Structure):
                 ("block", ctypes.c_int32), ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("topk", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("n_seg", ctypes.c_int32), ("seg_offsets", ctypes.POINTER(ctypes.c_int32)),
-                ("scale", ctypes.c_float), ("gate_channels", ctypes.c_int32)]
+                ("scale", ctypes.c_float), ("gate_channels", ctypes.c_int32), ("window_mode", ctypes.c_int32),
+                ("d_block_count", ctypes.c_void_p)]
 
 
 class lsrm_route3d_params(ctypes.Structure):
@@ -68,9 +69,15 @@ def strerror(status: int) -> str:
 
 
 def make_params(n_obj, n_views, grid, heads, d, topk, window, seg_offsets=None, scale=0.0, h_kv=None,
-                block=64, gate_channels=False) -> lsrm_nsa_params:
+                block=64, gate_channels=False, window_mode=0, block_count=None) -> lsrm_nsa_params:
+    """block_count: int32 device tensor [N/64] of active tokens per block, or None (kept alive by the struct)."""
     p = lsrm_nsa_params()
     p.gate_channels = 1 if gate_channels else 0
+    p.window_mode = window_mode
+    if block_count is not None:
+        assert block_count.is_cuda and block_count.dtype == torch.int32 and block_count.is_contiguous()
+        p._count_keepalive = block_count
+        p.d_block_count = block_count.data_ptr()
     p.n_obj, p.n_views, p.grid, p.block = n_obj, n_views, grid, block
     p.h_q, p.h_kv, p.d, p.topk, p.window = heads, heads if not h_kv else h_kv, d, topk, window
     p.scale = scale

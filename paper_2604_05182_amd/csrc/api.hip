@@ -14,6 +14,7 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     if (p->n_obj % kBlock != 0 || p->grid % 8 != 0 || (p->window & 1) != 0) return LSRM_ERR_INVALID_ARG;
     if (!(p->scale >= 0.0f) || __builtin_isinf(p->scale)) return LSRM_ERR_INVALID_ARG;
     if (p->h_q % p->h_kv != 0 || (p->gate_channels != 0 && p->gate_channels != 1)) return LSRM_ERR_INVALID_ARG;
+    if (p->window_mode != 0 && p->window_mode != 1) return LSRM_ERR_INVALID_ARG;
     if (p->block != kBlock || (p->d != 32 && p->d != 64 && p->d != 128) || p->topk > 64) return LSRM_ERR_UNSUPPORTED;
     int64_t n_img = (int64_t)p->n_views * p->grid * p->grid;
     int64_t n = (int64_t)p->n_obj + n_img;
@@ -26,7 +27,9 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     s->gate_channels = p->gate_channels;
     s->d = p->d;
     s->topk = p->topk;
-    s->window = p->window;
+    s->own_block = p->window_mode == 1;
+    s->window = s->own_block ? 128 : p->window;
+    s->count = p->d_block_count;
     s->nb_obj = p->n_obj / kBlock;
     s->tiles_per_view = (p->grid / 8) * (p->grid / 8);
     s->n_tiles = p->n_views * s->tiles_per_view;
@@ -83,7 +86,7 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call) {
     switch (which_call) {
         case LSRM_WS_ROUTE: return route_ws_bytes(s);
         case LSRM_WS_FORWARD: return forward_ws_bytes(s);
-        case LSRM_WS_BACKWARD: return s.d == 64 && s.h_kv == s.h && !s.gate_channels ? backward_ws_bytes(s) : 0;
+        case LSRM_WS_BACKWARD: return s.d == 64 && s.h_kv == s.h && !s.gate_channels && s.count == nullptr ? backward_ws_bytes(s) : 0;
         case LSRM_WS_ROUTE_3D: return route3d_ws_bytes(s);
         default: return 0;
     }
@@ -165,7 +168,7 @@ lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, con
     Shape s;
     lsrm_status rc = make_shape(p, &s);
     if (rc != LSRM_OK) return rc;
-    if (s.d != 64 || s.h_kv != s.h || s.gate_channels) return LSRM_ERR_UNSUPPORTED;
+    if (s.d != 64 || s.h_kv != s.h || s.gate_channels || s.count != nullptr) return LSRM_ERR_UNSUPPORTED;
     std::vector<int32_t> seg;
     rc = make_segments(p, s, &seg);
     if (rc != LSRM_OK) return rc;

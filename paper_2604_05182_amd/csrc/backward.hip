@@ -55,6 +55,7 @@ struct BwdArgs {
     int32_t seg[kMaxSeg + 1];
     int64_t n;
     int nb, h, topk, window, n_seg;
+    int own_block;  // window branch = the query's own block
     int nt;               // query / key tiles of 32 tokens
     int n_split, nbp, tiles_per_split;
     float scale, sl2;
@@ -93,7 +94,8 @@ __device__ __forceinline__ void copy_kb(const char *src, char *dst, int wave, ui
                                              16, 0, 0);
 }
 
-// s_waitcnt vmcnt <= n (and lgkmcnt == 0); a raw barrier: __syncthreads() would wait for every copy in flight
+// s_waitcnt vmcnt <= n (and lgkmcnt == 0), and a raw barrier.  Neither this barrier nor __syncthreads() waits
+// for global -> LDS copies in flight: whoever issued them waits on vmcnt before the barrier that publishes them.
 constexpr int vm_lgkm_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
@@ -299,6 +301,10 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
             seg_lo = a.seg[s];
             seg_hi = a.seg[s + 1];
         }
+    if (a.own_block) {  // window = the query's own block: the block is its own segment (a.window is 128)
+        seg_lo = qb * 64;
+        seg_hi = qb * 64 + 64;
+    }
     const int k_start = max(seg_lo, qb * 64 - half_w), k_end = min(seg_hi, qb * 64 + 63 + half_w);
     const int st0 = k_start / 32;
     const int tw = k_end > k_start ? (k_end - 1) / 32 + 1 - st0 : 0;
@@ -449,6 +455,10 @@ __global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
                 seg_lo = a.seg[s];
                 seg_hi = a.seg[s + 1];
             }
+        if (a.own_block) {
+            seg_lo = k0;
+            seg_hi = k0 + 64;
+        }
         // query i sees key j iff -W/2 <= j - i < W/2, i.e. j - W/2 < i <= j + W/2
         const int i_lo = max(seg_lo, k0 - half_w + 1), i_hi = min(seg_hi, k0 + 63 + half_w + 1);
         wt0 = i_lo / 32;
@@ -483,6 +493,10 @@ __global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
 
     if (T > 0) issue(0, lds);
     for (int t = 0; t < T; ++t) {
+        // The barrier alone does not wait for copies in flight (they are counted by vmcnt, which a
+        // workgroup-scope fence leaves alone): every wavefront first waits for its own share of tile t,
+        // issued one iteration ago, then the barrier publishes all shares.
+        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         __syncthreads();
         if (t + 1 < T) issue(t + 1, lds + ((t + 1) & 1) * TILE);
         const char *buf = lds + (t & 1) * TILE;
@@ -683,6 +697,7 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     a.h = s.h;
     a.topk = s.topk;
     a.window = s.window;
+    a.own_block = s.own_block;
     a.n_seg = n_seg;
     a.nt = s.nb * 2;
     a.n_split = w.n_split;

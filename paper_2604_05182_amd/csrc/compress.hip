@@ -23,21 +23,24 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 }
 
 // grid: (ceil(NB * row_chunks / 256), 2)   y = 0 -> K, y = 1 -> V
+// count (nullable): block b averages its first count[b] rows only (1..64).
 __global__ __launch_bounds__(256) void pool_blocks(int nb, int row_chunks /* h*d/8 */, const uint4 *__restrict__ k,
                                                    const uint4 *__restrict__ v, uint4 *__restrict__ kc,
-                                                   uint4 *__restrict__ vc) {
+                                                   uint4 *__restrict__ vc, const int32_t *__restrict__ count) {
     const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t b = g / row_chunks;
     const int c = (int)(g % row_chunks);
     if (b >= (size_t)nb) return;
     const uint4 *src = (blockIdx.y == 0 ? k : v) + b * kBlock * (size_t)row_chunks + c;
     uint4 *dst = (blockIdx.y == 0 ? kc : vc) + b * (size_t)row_chunks + c;
+    const int n_act = count != nullptr ? count[b] : kBlock;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
     for (int t0 = 0; t0 < kBlock; t0 += 16) {
         uint4 r[16];
 #pragma unroll
-        for (int t = 0; t < 16; ++t) r[t] = src[(size_t)(t0 + t) * row_chunks];
+        for (int t = 0; t < 16; ++t)
+            r[t] = t0 + t < n_act ? src[(size_t)(t0 + t) * row_chunks] : make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             acc[0] += bf16_lo(r[t].x); acc[1] += bf16_hi(r[t].x);
@@ -46,12 +49,12 @@ __global__ __launch_bounds__(256) void pool_blocks(int nb, int row_chunks /* h*d
             acc[6] += bf16_lo(r[t].w); acc[7] += bf16_hi(r[t].w);
         }
     }
-    const float inv = 1.0f / 64.0f;
+    const float den = (float)n_act;  // 64: the division is exact, as a multiplication by 1/64 would be
     uint4 o;
-    o.x = f32_to_bf16_rne(acc[0] * inv) | (f32_to_bf16_rne(acc[1] * inv) << 16);
-    o.y = f32_to_bf16_rne(acc[2] * inv) | (f32_to_bf16_rne(acc[3] * inv) << 16);
-    o.z = f32_to_bf16_rne(acc[4] * inv) | (f32_to_bf16_rne(acc[5] * inv) << 16);
-    o.w = f32_to_bf16_rne(acc[6] * inv) | (f32_to_bf16_rne(acc[7] * inv) << 16);
+    o.x = f32_to_bf16_rne(acc[0] / den) | (f32_to_bf16_rne(acc[1] / den) << 16);
+    o.y = f32_to_bf16_rne(acc[2] / den) | (f32_to_bf16_rne(acc[3] / den) << 16);
+    o.z = f32_to_bf16_rne(acc[4] / den) | (f32_to_bf16_rne(acc[5] / den) << 16);
+    o.w = f32_to_bf16_rne(acc[6] / den) | (f32_to_bf16_rne(acc[7] / den) << 16);
     *dst = o;
 }
 
@@ -64,7 +67,7 @@ lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t 
     dim3 grid((unsigned)(((size_t)s.nb * row_chunks + 255) / 256), 2);
     hipLaunchKernelGGL(pool_blocks, grid, dim3(256), 0, st, s.nb, row_chunks, reinterpret_cast<const uint4 *>(d_k),
                        reinterpret_cast<const uint4 *>(d_v), reinterpret_cast<uint4 *>(d_kc),
-                       reinterpret_cast<uint4 *>(d_vc));
+                       reinterpret_cast<uint4 *>(d_vc), s.count);
     LSRM_HIP_CHECK(hipGetLastError());
     return LSRM_OK;
 }

@@ -92,6 +92,8 @@ struct FwdArgs {
     int nb, h, topk, window, n_seg;
     int h_kv, group;    // key/value heads; query heads per key/value head (query head i reads head i / group)
     int gate_channels;  // gates are [N, 3, H, d] (one per output channel) instead of [N, H, 3]
+    int own_block;      // the window branch sees the query's own block (App. A) instead of a sliding window
+    const int32_t *count;  // nullable [NB]: active tokens per block (its first count[b] slots)
     int groups_per_head, groups_per_xcd;  // query-block groups of one head, and the share of one XCD
     float scale_log2e, scale;
 };
@@ -508,7 +510,8 @@ __device__ __forceinline__ float own_pv_max(WaveCtx<G> &c, const bf16x8 (&vf)[G:
 // the workgroup.  Tiles go through the ring of NSLOT slots; a slot is refilled as soon as
 // every wavefront is done with it.
 //   src(t)  -> global address of the image of tile t (uniform over the workgroup)
-//   msk(t)  -> (j0, need_mask) of tile t for this wavefront; tiles in [mf_lo, mf_hi) need none
+//   msk(t)  -> (j0, need_mask, cap) of tile t for this wavefront: keys outside the lane's [lo, hi) or at and
+//              beyond cap are masked; tiles in [mf_lo, mf_hi) need none
 // Step t runs mfma_block with QK of tile t+1, the exponentials of tile t and PV of tile t-1,
 // reloading its operand registers on the fly with the K fragments of tile t+2 and the V
 // fragments of tile t.  Once per step (one barrier) the slot of tile t-2 is refilled with
@@ -542,7 +545,7 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
     bf16x8 kq[G::KQ], vq[G::VQ];
     f32x16 S[2][QT];         // scores
     uint32_t P[2][QT][8];    // probabilities
-    int j0;
+    int j0, cap;  // first key of the tile; keys at or beyond `cap` are inactive slots
     bool need_mask;
     {
         bf16x8 kf[G::NS];
@@ -554,11 +557,11 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
     for (int i = 0; i < G::KQ; ++i) kq[i] = *reinterpret_cast<const bf16x8 *>(lslot(1) + i * 1024);
 #pragma unroll
     for (int f = 0; f < G::VQ; ++f) vq[f] = *reinterpret_cast<const bf16x8 *>(lslot(0) + G::K_BYTES + f * 1024);
-    msk(0, &j0, &need_mask);
+    msk(0, &j0, &need_mask, &cap);
     mfma_settle();  // a branch follows the MFMAs that produced the scores
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        if (need_mask) mask_scores(c.lo[qt], c.hi[qt], S[0][qt], j0, lane);
+        if (need_mask) mask_scores(c.lo[qt], min(c.hi[qt], cap), S[0][qt], j0, lane);
         update_max<G>(c, qt, lane_max(S[0][qt]), sl2, nullptr);
     }
 
@@ -582,11 +585,11 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
     // After an MFMA block: fold the maximum of the scores just produced (s_next) into the running
     // maximum; pu are the probabilities still to be accumulated.
     auto post = [&](int t, f32x16 (&s_next)[QT], uint32_t (&pu)[QT][8]) {
-        msk(t + 1, &j0, &need_mask);
+        msk(t + 1, &j0, &need_mask, &cap);
         mfma_settle();  // s_next and O come from the MFMAs just issued; branches follow
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
-            if (__builtin_expect(need_mask, 0)) mask_scores(c.lo[qt], c.hi[qt], s_next[qt], j0, lane);
+            if (__builtin_expect(need_mask, 0)) mask_scores(c.lo[qt], min(c.hi[qt], cap), s_next[qt], j0, lane);
             update_max<G>(c, qt, lane_max(s_next[qt]), sl2, pu[qt]);
         }
     };
@@ -683,9 +686,11 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
 
 // Selected phase: each query block streams its own routed blocks in 32-key steps through its
 // two tile slots; its two wavefronts split the copies and meet at a workgroup barrier every step.
-template <class G, typename SrcFn>
-__device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src, char *lds, int qbi,
-                                        int sub, int lane, float sl2) {
+// CNT: blocks may hold fewer than 64 active tokens; valid(t) is the number of active keys of tile t
+// (0..32) and the scores of the others are masked (the in-shadow maximum is then taken afterwards).
+template <class G, bool CNT, typename SrcFn, typename ValidFn>
+__device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src, ValidFn valid, char *lds,
+                                        int qbi, int sub, int lane, float sl2) {
     constexpr int NP = G::NP;
     if (n_steps <= 0) return;
     static_assert(G::NW == 2, "two wavefronts per query block");
@@ -735,13 +740,17 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
         if (n > 2) issue_k(2);
         if (n > 0) {
             mfma_settle();
+            if constexpr (CNT) {
+                const int vld = valid(0);
+                if (vld < 32) mask_scores(0, vld, s_cur, 0, lane);
+            }
             update_max<G>(c, 0, lane_max(s_cur), sl2, nullptr);
             read_v<G>(c, stage(0), vf);
         }
         if (n > 1) read_k<G>(c, stage(1), kf);
         for (int t = 0; t + 1 < n; ++t) {
             own_qk_exp<G, true>(c, s_cur, kf, s_next, pu, sl2);
-            const float mx = own_pv_max<G, true>(c, vf, pu, s_next);
+            float mx = own_pv_max<G, !CNT>(c, vf, pu, s_next);
             __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));  // K(t+2) and V(t+1) have landed
             wg_barrier();
             if (t + 3 < n) issue_k(t + 3);
@@ -749,6 +758,11 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
             if (t + 2 < n) read_k<G>(c, stage(t + 2), kf);
             read_v<G>(c, stage(t + 1), vf);
             mfma_settle();
+            if constexpr (CNT) {
+                const int vld = valid(t + 1);
+                if (vld < 32) mask_scores(0, vld, s_next, 0, lane);
+                mx = lane_max(s_next);
+            }
             update_max<G>(c, 0, mx, sl2, nullptr);
             s_cur = s_next;
         }
@@ -856,6 +870,12 @@ __device__ __forceinline__ WinRange window_range(const FwdArgs &a, int qb) {
             w.seg_hi = hi;
         }
     }
+    if (a.own_block) {
+        // the block is its own segment (a.window is 128 in this mode: every query reaches every slot);
+        // with counts, the segment ends at the last active token
+        w.seg_lo = q0;
+        w.seg_hi = q0 + (a.count != nullptr ? a.count[qb] : 64);
+    }
     const int half = a.window / 2;
     const int k_start = max(w.seg_lo, q0 - half);
     const int k_end = min(w.seg_hi, q0 + 63 + half);  // exclusive
@@ -866,7 +886,8 @@ __device__ __forceinline__ WinRange window_range(const FwdArgs &a, int qb) {
     return w;
 }
 
-template <class G>
+// CNT: a.count is given (variable number of active tokens per block).
+template <class G, bool CNT>
 __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward_kernel(FwdArgs a) {
     constexpr int D = G::D, NP = G::NP;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -917,9 +938,10 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
         const int n_steps = (a.nb + 31) / 32;
         const char *base = a.kvc + (int64_t)kvh * G::TILE;
         auto src = [&](int t) { return base + t * tile_stride; };
-        auto msk = [&](int t, int *j0, bool *need) {
+        auto msk = [&](int t, int *j0, bool *need, int *cap) {
             *j0 = 32 * t;
             *need = 32 * t + 32 > a.nb;
+            *cap = 0x7fffffff;
         };
         run_shared<G>(c, n_steps, src, msk, 0, a.nb / 32, lds, wave, lane, sl2);
         if (active) finish_branch<G>(c, a, 0, row0, head, wave, lane, lds);
@@ -928,7 +950,7 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
     // ---------------- selected branch: every token of the routed blocks
     {
         reset_branch<G>(c);
-        int packed = -1, my_valid = 0, max_valid = 0;
+        int packed = -1, pcount = 0, my_valid = 0, max_valid = 0;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             const int qbp = group * NP + p;
@@ -945,12 +967,17 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
                 my_valid = n_valid;
             }
         }
+        if constexpr (CNT) pcount = lane < my_valid ? a.count[packed] : 0;
         const char *base = a.kv + (int64_t)kvh * G::TILE;
         auto src = [&](int t) {
             int kb = __builtin_amdgcn_readlane(packed, t >> 1);
             return base + (2 * kb + (t & 1)) * tile_stride;
         };
-        run_own<G>(c, 2 * max_valid, 2 * my_valid, src, lds, qbi, sub, lane, sl2);
+        auto valid = [&](int t) {  // active keys of tile t of this query block's list
+            int cnt = __builtin_amdgcn_readlane(pcount, t >> 1);
+            return min(32, max(0, cnt - 32 * (t & 1)));
+        };
+        run_own<G, CNT>(c, 2 * max_valid, 2 * my_valid, src, valid, lds, qbi, sub, lane, sl2);
         if (active) finish_branch<G>(c, a, 1, row0, head, wave, lane, lds);
     }
 
@@ -982,14 +1009,25 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
         const int n_steps = st_max > st_min ? st_max - st_min : 0;
         const char *base = a.kv + (int64_t)kvh * G::TILE;
         auto src = [&](int t) { return base + (st_min + t) * tile_stride; };
-        auto msk = [&](int t, int *j0, bool *need) {
+        auto msk = [&](int t, int *j0, bool *need, int *cap) {
             int st = st_min + t;
             *j0 = 32 * st;
             *need = (32 * st < mine.full_lo) || (32 * st + 32 > mine.full_hi);  // also true outside [st0, st1)
+            *cap = 0x7fffffff;
+            if constexpr (CNT) {
+                // slots of the tile's block beyond its active tokens (in own-block mode the segment already ends there)
+                if (!a.own_block && st < 2 * a.nb) {
+                    const int vld = min(32, max(0, a.count[st >> 1] - 32 * (st & 1)));
+                    if (vld < 32) {
+                        *need = true;
+                        *cap = 32 * st + vld;
+                    }
+                }
+            }
         };
-        // tiles wholly inside the range that every query of the block sees
-        const int mf_lo = max(0, (mine.full_lo - 32 * st_min + 31) >> 5);
-        const int mf_hi = (mine.full_hi - 32 * st_min) >> 5;
+        // tiles wholly inside the range that every query of the block sees (none is known to be, with counts)
+        const int mf_lo = CNT ? 0 : max(0, (mine.full_lo - 32 * st_min + 31) >> 5);
+        const int mf_hi = CNT ? 0 : (mine.full_hi - 32 * st_min) >> 5;
         run_shared<G>(c, n_steps, src, msk, mf_lo, mf_hi, lds, wave, lane, sl2);
         __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         wg_barrier();  // the tile slots are about to be reused for the output rows
@@ -1001,21 +1039,24 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
 // img[tile][head] = K fragments (K_BYTES) then V^T fragments (V_BYTES).
 // Rows at or beyond n_rows read as zero (their scores are masked in the attention kernel).
 // One workgroup per (64-row block, head) = two tiles.
+// count (nullable, one entry per 64-row block): rows of a block at or beyond its count read as zero too.
 template <int D>
 __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
-                                                  char *__restrict__ img, int64_t n_rows, int h, int n_tiles) {
+                                                  char *__restrict__ img, int64_t n_rows, int h, int n_tiles,
+                                                  const int32_t *__restrict__ count) {
     constexpr int K_BYTES = 32 * D * 2, TILE = K_BYTES + D * 64;
     constexpr int CH = D / 8;  // 16-byte chunks per row
     __shared__ uint16_t vt[64][D + 2];
     const int64_t blk = blockIdx.x;
     const int head = blockIdx.y;
+    const int n_act = count != nullptr ? count[blk] : 64;
     // K: a permutation of 16-byte chunks.  Source chunk (row t, chunk cc) goes to fragment
     // ks = cc / 2, lane (hh = cc % 2, r = perm(t % 32)) of tile t / 32.
     for (int e = threadIdx.x; e < 64 * CH; e += 256) {
         const int t = e / CH, cc = e % CH;
         const int64_t row = blk * 64 + t;
         uint4 kval = make_uint4(0, 0, 0, 0), vval = make_uint4(0, 0, 0, 0);
-        if (row < n_rows) {
+        if (row < n_rows && t < n_act) {
             kval = *reinterpret_cast<const uint4 *>(k + (row * h + head) * D + cc * 8);
             vval = *reinterpret_cast<const uint4 *>(v + (row * h + head) * D + cc * 8);
         }
@@ -1077,10 +1118,10 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     const int tiles_c = (s.nb + 31) / 32;
     hipLaunchKernelGGL(pack_tiles<D>, dim3(s.nb, s.h_kv), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h_kv,
-                       2 * s.nb);
+                       2 * s.nb, a.count);
     LSRM_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL(pack_tiles<D>, dim3((s.nb + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
-                       (int64_t)s.nb, s.h_kv, tiles_c);
+                       (int64_t)s.nb, s.h_kv, tiles_c, (const int32_t *)nullptr);
     LSRM_HIP_CHECK(hipGetLastError());
     a.kv = ws + w.kv;
     a.kvc = ws + w.kvc;
@@ -1089,12 +1130,18 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     a.groups_per_xcd = (a.groups_per_head + 7) / 8;
     static bool attr_set = false;
     if (!attr_set) {
-        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<G>),
+        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<G, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
+        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<G, true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
         attr_set = true;
     }
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
-    hipLaunchKernelGGL((nsa_forward_kernel<G>), dim3(8 * a.groups_per_xcd * s.h), dim3(G::THREADS), G::LDS_BYTES, st, a);
+    const dim3 grid(8 * a.groups_per_xcd * s.h);
+    if (a.count != nullptr)
+        hipLaunchKernelGGL((nsa_forward_kernel<G, true>), grid, dim3(G::THREADS), G::LDS_BYTES, st, a);
+    else
+        hipLaunchKernelGGL((nsa_forward_kernel<G, false>), grid, dim3(G::THREADS), G::LDS_BYTES, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;
@@ -1109,11 +1156,14 @@ lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t
     if (n_tiles <= 0) return LSRM_OK;
     const dim3 grid((n_tiles + 1) / 2, h);
     if (d == 32)
-        hipLaunchKernelGGL(pack_tiles<32>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
+        hipLaunchKernelGGL(pack_tiles<32>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles,
+                           (const int32_t *)nullptr);
     else if (d == 64)
-        hipLaunchKernelGGL(pack_tiles<64>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
+        hipLaunchKernelGGL(pack_tiles<64>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles,
+                           (const int32_t *)nullptr);
     else
-        hipLaunchKernelGGL(pack_tiles<128>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles);
+        hipLaunchKernelGGL(pack_tiles<128>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles,
+                           (const int32_t *)nullptr);
     LSRM_HIP_CHECK(hipGetLastError());
     return LSRM_OK;
 }
@@ -1138,6 +1188,8 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.h_kv = s.h_kv;
     a.group = s.h / s.h_kv;
     a.gate_channels = s.gate_channels;
+    a.own_block = s.own_block;
+    a.count = s.count;
     a.topk = s.topk;
     a.window = s.window;
     a.n_seg = n_seg;

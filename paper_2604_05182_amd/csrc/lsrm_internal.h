@@ -13,6 +13,9 @@ struct Shape {
     int n_obj, n_views, grid, h, d, topk, window;
     int h_kv;           // key/value heads, divides h
     int gate_channels;  // 0: gates [N, H, 3]; 1: gates [N, 3, H, d]
+    int own_block;      // window branch = the query's own block; `window` is then 128 (every slot of the block
+                        // within reach) and the kernels treat the block as its own segment
+    const int32_t *count;  // device, nullable [nb]: active tokens per block
     int nb_obj, tiles_per_view, n_tiles, nb;
     int64_t n;
     float scale;
@@ -39,7 +42,7 @@ lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const 
 size_t route3d_ws_bytes(const Shape &s);
 
 lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
-                            uint16_t *d_vc, hipStream_t st);
+                            uint16_t *d_vc, hipStream_t st);  // honours s.count
 
 lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
                            const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc,

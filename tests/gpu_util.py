@@ -15,11 +15,13 @@ def bf16_host(t: torch.Tensor) -> np.ndarray:
     return t.float().cpu().numpy()
 
 
-def params_for(B, cfg, seg_offsets="default", scale=0.0, topk=None, window=None):
+def params_for(B, cfg, seg_offsets="default", scale=0.0, topk=None, window=None, window_mode=0, block_count=None):
     seg = None if isinstance(seg_offsets, str) else seg_offsets
+    cnt = None if block_count is None else torch.from_numpy(np.ascontiguousarray(block_count, dtype=np.int32)).cuda()
     return B.make_params(cfg.n_obj, cfg.n_views, cfg.grid, cfg.heads, cfg.d,
                          cfg.topk if topk is None else topk, cfg.window if window is None else window,
-                         seg_offsets=seg, scale=scale, h_kv=cfg.kv_heads, gate_channels=cfg.gate_channels)
+                         seg_offsets=seg, scale=scale, h_kv=cfg.kv_heads, gate_channels=cfg.gate_channels,
+                         window_mode=window_mode, block_count=cnt)
 
 
 def run_route(B, cfg, pos, cams, want_dist=True):
@@ -46,8 +48,8 @@ def run_route_3d(B, cfg, pos, pos_img, cams, width, prefilter, k_v2v, k_v2i, k_i
     return idx.cpu().numpy(), (d2.cpu().numpy() if want_dist else None)
 
 
-def run_compress(B, cfg, k_bits, v_bits):
-    p = params_for(B, cfg)
+def run_compress(B, cfg, k_bits, v_bits, block_count=None):
+    p = params_for(B, cfg, block_count=block_count)
     dk, dv = bf16_dev(k_bits), bf16_dev(v_bits)
     kc = torch.empty((cfg.nb, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device="cuda")
     vc = torch.empty_like(kc)
@@ -57,12 +59,13 @@ def run_compress(B, cfg, k_bits, v_bits):
 
 
 def run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets="default", scale=0.0,
-                want_aux=False, window=None):
+                want_aux=False, window=None, window_mode=0, block_count=None):
     """compress + forward on the device.  Returns dict of numpy results (+ device kc, vc)."""
     topk = idx.shape[1]
-    p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window)
+    p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window, window_mode=window_mode,
+                   block_count=block_count)
     dq = bf16_dev(q_bits)
-    dk, dv, kc, vc = run_compress(B, cfg, k_bits, v_bits)
+    dk, dv, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count)
     d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
     d_g = torch.from_numpy(gates).cuda()
     out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
@@ -78,10 +81,11 @@ def run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets="default
     return res
 
 
-def run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offsets="default", scale=0.0, window=None):
+def run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offsets="default", scale=0.0, window=None,
+                 window_mode=0):
     """compress + forward (saving lse and branch outputs) + backward on the device -> dq, dk, dv as float32 numpy."""
     topk = idx.shape[1]
-    p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window)
+    p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window, window_mode=window_mode)
     dq_in, ddo = bf16_dev(q_bits), bf16_dev(dout_bits)
     dk_in, dv_in, kc, vc = run_compress(B, cfg, k_bits, v_bits)
     d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()

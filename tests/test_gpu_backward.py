@@ -23,7 +23,7 @@ def _log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
-def _case(B, oracle_lib, cfg, idx=None, seg="default", scale=0.0, window=None):
+def _case(B, oracle_lib, cfg, idx=None, seg="default", scale=0.0, window=None, window_mode=0):
     q_bits, k_bits, v_bits = I.make_qkv(cfg)
     gates, dout_bits = I.make_gates(cfg), I.make_dout(cfg)
     if idx is None:
@@ -31,7 +31,7 @@ def _case(B, oracle_lib, cfg, idx=None, seg="default", scale=0.0, window=None):
     seg_arr = cfg.seg_offsets() if isinstance(seg, str) else np.asarray(seg, dtype=np.int32)
     window = cfg.window if window is None else window
     got = G.run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offsets=seg, scale=scale,
-                         window=window)
+                         window=window, window_mode=window_mode)
     q, k, v, dout = (I.bf16_bits_to_f32(a) for a in (q_bits, k_bits, v_bits, dout_bits))
     kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
     return got, (q, k, v, kc, vc, idx, gates, seg_arr, window, dout)
@@ -63,6 +63,17 @@ def test_backward_ragged_and_holes(B, oracle_lib):
     idx[2] = -1
     got, args = _case(B, oracle_lib, cfg, idx=idx, scale=0.2)
     _assert_grads(got, oracle_lib.nsa_backward(*args, scale=0.2), cfg.name)
+
+
+def test_backward_own_block_window(B, oracle_lib):
+    """The window branch over the query's own block (App. A) instead of the sliding window."""
+    cfg = I.small_config(name="b-ownblock", n_obj=1088, n_views=3, grid=24, heads=3, d=64, topk=5, window=200, seed=23)
+    _log(f"[backward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(9)
+    idx = np.stack([rng.choice(cfg.nb, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.2] = -1
+    got, args = _case(B, oracle_lib, cfg, idx=idx, window_mode=1)
+    _assert_grads(got, oracle_lib.nsa_backward(*args, window_mode=1), cfg.name)
 
 
 def test_backward_zero_window_and_topk_one(B, oracle_lib):
@@ -107,3 +118,17 @@ def test_backward_is_deterministic(B, oracle_lib):
     b = G.run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits)
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+def test_backward_full_size_is_deterministic(B, oracle_lib):
+    """Config 5 at full size, three calls in a row (workspaces reused with whatever the call before left
+    in them, the chip fully loaded): a tile read before its copy has landed shows up as a difference."""
+    cfg = I.CONFIGS[5]
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates, dout_bits = I.make_gates(cfg), I.make_dout(cfg)
+    idx, _ = oracle_lib.route(I.make_points(cfg), I.make_cameras(cfg), cfg.grid, cfg.topk)
+    _log("[backward] config 5, three runs")
+    runs = [G.run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits) for _ in range(3)]
+    for other in runs[1:]:
+        for x, y in zip(runs[0], other):
+            assert np.array_equal(x, y)

@@ -85,22 +85,36 @@ def test_compress(B, oracle_lib, cfg):
 
 
 # ----------------------------------------------------------------------------- forward
-def _forward_case(B, oracle_lib, cfg, idx=None, seg="default", scale=0.0, qblocks=None, window=None):
+def _forward_case(B, oracle_lib, cfg, idx=None, seg="default", scale=0.0, qblocks=None, window=None, window_mode=0,
+                  block_count=None):
     q_bits, k_bits, v_bits = I.make_qkv(cfg)
     gates = I.make_gates(cfg)
     if idx is None:
         idx, _ = oracle_lib.route(I.make_points(cfg), I.make_cameras(cfg), cfg.grid, cfg.topk)
     seg_arr = cfg.seg_offsets() if isinstance(seg, str) else np.asarray(seg, dtype=np.int32)
     window = cfg.window if window is None else window
+    if block_count is not None:
+        # whatever sits in the inactive slots of K and V must never be looked at: make it NaN
+        inactive = (np.arange(cfg.n) % 64) >= np.repeat(np.asarray(block_count), 64)
+        k_bits, v_bits = k_bits.copy(), v_bits.copy()
+        k_bits[inactive] = 0x7FC0
+        v_bits[inactive] = 0x7FC0
     res = G.run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets=seg, scale=scale,
-                        want_aux=True, window=window)
+                        want_aux=True, window=window, window_mode=window_mode, block_count=block_count)
     q, k, v = (I.bf16_bits_to_f32(a) for a in (q_bits, k_bits, v_bits))
-    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    kc, vc = oracle_lib.pool(k, block_count), oracle_lib.pool(v, block_count)
     ref_out, ref_lse, ref_ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg_arr, window, scale=scale,
-                                                      qblocks=qblocks, want_lse=True, want_branches=True)
+                                                      qblocks=qblocks, want_lse=True, want_branches=True,
+                                                      window_mode=window_mode, block_count=block_count)
     if qblocks is not None:
         rows = (np.asarray(qblocks)[:, None] * 64 + np.arange(64)[None]).reshape(-1)
         res = {"out": res["out"][rows], "lse": res["lse"][:, rows], "ob": res["ob"][:, rows]}
+    if block_count is not None:
+        # rows of inactive slots are unspecified: compare the active ones
+        blocks = np.arange(cfg.nb) if qblocks is None else np.asarray(qblocks)
+        act = (np.arange(64)[None, :] < np.asarray(block_count)[blocks][:, None]).reshape(-1)
+        res = {"out": res["out"][act], "lse": res["lse"][:, act], "ob": res["ob"][:, act]}
+        ref_out, ref_lse, ref_ob = ref_out[act], ref_lse[:, act], ref_ob[:, act]
     return res, ref_out, ref_lse, ref_ob
 
 
@@ -150,6 +164,45 @@ def test_forward_grouped_heads_and_channel_gates(B, oracle_lib, d, heads, h_kv, 
     _log(f"[forward] {cfg.name}")
     res, ref_out, ref_lse, ref_ob = _forward_case(B, oracle_lib, cfg)
     _assert_forward(res, ref_out, ref_lse, ref_ob, cfg.name)
+
+
+def _block_counts(cfg, seed):
+    rng = np.random.default_rng(seed)
+    cnt = rng.integers(1, 65, size=cfg.nb).astype(np.int32)
+    cnt[:6] = (64, 1, 33, 32, 31, 64)
+    return cnt
+
+
+@pytest.mark.parametrize("d,window_mode,with_counts", [(64, 1, False), (128, 1, False), (64, 0, True), (128, 0, True),
+                                                       (64, 1, True), (128, 1, True), (32, 1, True)])
+def test_forward_own_block_window_and_active_counts(B, oracle_lib, d, window_mode, with_counts):
+    """Window branch over the query's own block (App. A) and blocks with fewer than 64 active
+    tokens (Sec. 3.2), alone and together; ragged block count, holes in the routing table."""
+    cfg = I.small_config(name=f"f-own{window_mode}-cnt{int(with_counts)}-d{d}", n_obj=1088, n_views=3, grid=24, heads=3,
+                         d=d, topk=5, window=200, seed=41)
+    _log(f"[forward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(6)
+    idx = np.stack([rng.choice(cfg.nb, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.2] = -1
+    idx[:, 0] = np.minimum(np.arange(cfg.nb), 5)      # the special counts (1, 31, 32, 33) are routed to
+    cnt = _block_counts(cfg, 7) if with_counts else None
+    res, ref_out, ref_lse, ref_ob = _forward_case(B, oracle_lib, cfg, idx=idx, window_mode=window_mode, block_count=cnt)
+    _assert_forward(res, ref_out, ref_lse, ref_ob, cfg.name)
+
+
+def test_compress_with_active_counts(B, oracle_lib):
+    cfg = I.small_config(name="p-counts", n_obj=1088, n_views=3, grid=24, heads=3, d=64, seed=42)
+    cnt = _block_counts(cfg, 8)
+    _, k_bits, v_bits = I.make_qkv(cfg)
+    # poison the inactive slots: they must not reach the averages
+    act = (np.arange(cfg.n) % 64) < np.repeat(cnt, 64)
+    k_bits = k_bits.copy()
+    k_bits[~act] = 0x7FC0          # bf16 NaN
+    _, _, kc, vc = G.run_compress(B, cfg, k_bits, v_bits, cnt)
+    for got, bits in ((kc, k_bits), (vc, v_bits)):
+        ref = oracle_lib.pool(I.bf16_bits_to_f32(bits), cnt)
+        got = G.bf16_host(got)
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-6)
 
 
 def test_forward_dense_equivalence(B, oracle_lib):
