@@ -153,10 +153,11 @@ __device__ __forceinline__ float half_sum(float x) {
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }            // vmcnt <= n
 constexpr int vm_lgkm_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }          // vmcnt <= n, lgkmcnt == 0
 
-// Workgroup barrier without the memory fence that __syncthreads() implies: the fence
-// would wait for every outstanding copy (vmcnt(0)) and defeat the prefetch ring.  What
-// must be visible is ordered by hand: a wavefront waits for its own copies (s_waitcnt
-// vmcnt) and its own LDS reads (lgkmcnt) before the barrier and reads LDS only after it.
+// Bare workgroup barrier.  No barrier, fenced or not, waits for global -> LDS copies in flight
+// (they are counted by vmcnt, which a workgroup-scope fence leaves alone), so what must be
+// visible is ordered by hand: a wavefront waits for its own copies (s_waitcnt vmcnt, counted so
+// that later tiles stay in flight) and its own LDS reads (lgkmcnt) before the barrier, and reads
+// what others copied only after it.
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // Results of an MFMA become readable by VALU instructions only a fixed number of cycles
