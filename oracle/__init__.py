@@ -75,18 +75,23 @@ def route(pos: np.ndarray, cams: np.ndarray, grid: int, topk: int):
 
 
 def route_3d(pos, pos_img, cams, grid: int, width: int, prefilter: int, k_v2v: int, k_v2i: int, k_i2v: int,
-             k_i2i: int):
-    """The four selection rules at block level -> (idx int32 [NB, width], dist2 float32 [NB, width]);
-    rows hold the selected volume blocks, then the selected image blocks, then -1."""
+             k_i2i: int, per_token: bool = False, queries=None):
+    """The four selection rules -> (idx int32 [rows, width], dist2 float32 [rows, width]); a row holds the
+    selected volume blocks, then the selected image blocks, then -1.  Queries are blocks (point = block
+    centroid) or, with per_token, tokens (point = the token's own coordinate); `queries` lists the query
+    ids to evaluate (default: all, in order)."""
     pos, pos_img, cams = _f32(pos), _f32(pos_img), _f32(cams)
     n_obj, m = pos.shape[0], cams.shape[0]
     assert pos_img.shape[0] == m * grid * grid
-    nb = n_obj // 64 + m * (grid // 8) ** 2
-    idx = np.empty((nb, width), dtype=np.int32)
-    d2 = np.empty((nb, width), dtype=np.float32)
+    n_all = n_obj + pos_img.shape[0] if per_token else n_obj // 64 + m * (grid // 8) ** 2
+    qs = None if queries is None else _i32(np.asarray(queries))
+    rows = n_all if qs is None else qs.shape[0]
+    idx = np.empty((rows, width), dtype=np.int32)
+    d2 = np.empty((rows, width), dtype=np.float32)
     _load().oracle_route_3d(ctypes.c_int(n_obj), ctypes.c_int(m), ctypes.c_int(grid), ctypes.c_int(width),
                             ctypes.c_int(prefilter), ctypes.c_int(k_v2v), ctypes.c_int(k_v2i), ctypes.c_int(k_i2v),
-                            ctypes.c_int(k_i2i), _p(pos, ctypes.c_float), _p(pos_img, ctypes.c_float),
+                            ctypes.c_int(k_i2i), ctypes.c_int(1 if per_token else 0), _p(qs, ctypes.c_int32),
+                            ctypes.c_int(rows), _p(pos, ctypes.c_float), _p(pos_img, ctypes.c_float),
                             _p(cams, ctypes.c_float), _p(idx, ctypes.c_int32), _p(d2, ctypes.c_float))
     return idx, d2
 

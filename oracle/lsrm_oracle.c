@@ -164,9 +164,16 @@ static float sqdist3(const float *a, const float *b) {
     return (dx * dx + dy * dy) + dz * dz;
 }
 
+/*
+ * per_token == 0: the queries are blocks (query id = block id, point = centroid of the block), the
+ * reading used for the attention kernels.  per_token == 1: the queries are tokens, as the paper words
+ * the rules (query id = token index in sequence order, point = the token's own coordinate; a token
+ * below n_obj is a volume query).  queries (nullable) lists the nq query ids to evaluate, in output
+ * row order; NULL = all of them (nq ignored).  idx, dist2: [number of queries, width].
+ */
 void oracle_route_3d(int n_obj, int n_views, int grid, int width, int prefilter, int k_v2v, int k_v2i, int k_i2v,
-                     int k_i2i, const float *pos, const float *pos_img, const float *cams, int32_t *idx,
-                     float *dist2) {
+                     int k_i2i, int per_token, const int32_t *queries, int nq, const float *pos,
+                     const float *pos_img, const float *cams, int32_t *idx, float *dist2) {
     int nbo = n_obj / BLK;
     int tg = grid / 8;
     int tpv = tg * tg;
@@ -179,16 +186,27 @@ void oracle_route_3d(int n_obj, int n_views, int grid, int width, int prefilter,
     if (tpv > maxc) maxc = tpv;
     cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(maxc > 0 ? maxc : 1));
     cand_t *view = (cand_t *)malloc(sizeof(cand_t) * (size_t)(tpv > 0 ? tpv : 1));
-    for (int b = 0; b < nb; ++b) {
-        const float *p = cent + 3 * (size_t)b;
-        int kv = b < nbo ? k_v2v : k_i2v, ki = b < nbo ? k_v2i : k_i2i;
+    int n_all = per_token ? n_obj + nt * BLK : nb;
+    int n_rows = queries ? nq : n_all;
+    for (int row = 0; row < n_rows; ++row) {
+        int b = queries ? queries[row] : row;
+        const float *p;
+        int volume_query;
+        if (per_token) {
+            volume_query = b < n_obj;
+            p = volume_query ? pos + 3 * (size_t)b : pos_img + 3 * (size_t)(b - n_obj);
+        } else {
+            volume_query = b < nbo;
+            p = cent + 3 * (size_t)b;
+        }
+        int kv = volume_query ? k_v2v : k_i2v, ki = volume_query ? k_v2i : k_i2i;
         int at = 0;
         /* volume blocks */
         for (int j = 0; j < nbo; ++j) { cand[j].d2 = sqdist3(p, cent + 3 * (size_t)j); cand[j].id = j; }
         qsort(cand, nbo, sizeof(cand_t), cand_cmp);
         for (int k = 0; k < kv && k < nbo && at < width; ++k, ++at) {
-            idx[(size_t)b * width + at] = cand[k].id;
-            if (dist2) dist2[(size_t)b * width + at] = cand[k].d2;
+            idx[(size_t)row * width + at] = cand[k].id;
+            if (dist2) dist2[(size_t)row * width + at] = cand[k].d2;
         }
         /* image blocks */
         int nc = 0;
@@ -215,12 +233,12 @@ void oracle_route_3d(int n_obj, int n_views, int grid, int width, int prefilter,
         }
         qsort(cand, nc, sizeof(cand_t), cand_cmp);
         for (int k = 0; k < ki && k < nc && at < width; ++k, ++at) {
-            idx[(size_t)b * width + at] = cand[k].id;
-            if (dist2) dist2[(size_t)b * width + at] = cand[k].d2;
+            idx[(size_t)row * width + at] = cand[k].id;
+            if (dist2) dist2[(size_t)row * width + at] = cand[k].d2;
         }
         for (; at < width; ++at) {
-            idx[(size_t)b * width + at] = -1;
-            if (dist2) dist2[(size_t)b * width + at] = INFINITY;
+            idx[(size_t)row * width + at] = -1;
+            if (dist2) dist2[(size_t)row * width + at] = INFINITY;
         }
     }
     free(view); free(cand); free(cent);

@@ -185,3 +185,68 @@ def test_budgets_larger_than_the_candidate_lists_pad(oracle_lib):
         assert sorted(idx[b, :2].tolist()) == [0, 1]                 # only two volume blocks exist
         assert ((idx[b, 2:5] >= 2) & (idx[b, 2:5] < 6)).all()        # three candidates survive the prefilter
         assert (idx[b, 5:] == -1).all() and np.isinf(d2[b, 5:]).all()
+
+
+def test_per_token_queries(oracle_lib):
+    """The rules as the paper words them, one query per token (Sec. 3.3): the query point is the
+    token's own coordinate.  Pins: tokens of a block whose points coincide route like the block;
+    a subset of queries equals the rows of the full table; and the hand scene's odd point."""
+    pos, pimg, cams = _hand_scene()
+    args = dict(grid=16, width=4, prefilter=2, k_v2v=2, k_v2i=2, k_i2v=1, k_i2i=1)
+    blk_idx, blk_d2 = oracle_lib.route_3d(pos, pimg, cams, **args)
+    tok_idx, tok_d2 = oracle_lib.route_3d(pos, pimg, cams, per_token=True, **args)
+    assert tok_idx.shape == (128 + 256, 4)
+    # blocks of coincident points (object blocks 0, 1; tiles 1, 2, 3): every token routes like its block
+    for b in (0, 1, 3, 4, 5):
+        assert (tok_idx[64 * b:64 * b + 64] == blk_idx[b]).all() and (tok_d2[64 * b:64 * b + 64] == blk_d2[b]).all()
+    # tile 0: 63 tokens at (2,0,0), token 17 at (0,0,0.5)
+    #   p = (2,0,0): nearest centre b1 (1); projects to (16, 8): t1, t3 at 32 -> t1: 2.25+0.25 = 2.5, t3: 1+1 = 2 -> t3
+    #   p = (0,0,0.5): b0 0.25 < b1 1.25; projects to (8,8): tie -> t0, t1; t0 contains the token itself: 0
+    assert tok_idx[128].tolist() == [1, 5, -1, -1] and tok_d2[128].tolist()[:2] == [1.0, 2.0]
+    assert tok_idx[128 + 17].tolist() == [0, 2, -1, -1] and tok_d2[128 + 17].tolist()[:2] == [0.25, 0.0]
+    pick = np.array([300, 0, 145, 64], dtype=np.int32)
+    sub_idx, sub_d2 = oracle_lib.route_3d(pos, pimg, cams, per_token=True, queries=pick, **args)
+    assert np.array_equal(sub_idx, tok_idx[pick]) and np.array_equal(sub_d2, tok_d2[pick])
+
+
+def test_per_token_float64_brute_force(oracle_lib):
+    cfg = I.small_config(n_obj=512, n_views=2, grid=16, points="ellipsoids", seed=31)
+    pos, cams = I.make_points(cfg), I.make_cameras(cfg)
+    pimg = I.make_points_img(cfg, cams)
+    idx, d2 = oracle_lib.route_3d(pos, pimg, cams, cfg.grid, 6, 2, 2, 4, 2, 4, per_token=True)
+    pts = np.concatenate([pos, pimg]).astype(np.float64)
+    cent = pts.reshape(-1, 64, 3).mean(1)
+    nbo = cfg.nb_obj
+    tg = cfg.grid // 8
+    centres = np.array([[8 * tj + 4, 8 * ti + 4] for ti in range(tg) for tj in range(tg)], dtype=np.float64)
+    loose = exact = 0
+    for i in range(0, cfg.n, 7):
+        p = pts[i]
+        dv = ((cent[:nbo] - p) ** 2).sum(1)
+        order = np.argsort(dv, kind="stable")[:2]
+        assert np.array_equal(order, idx[i, :2]) or np.min(np.diff(np.sort(dv)[:3])) < 1e-5
+        cand, gaps = [], []
+        for m in range(cfg.n_views):
+            c = cams[m].astype(np.float64)
+            x = c[:9].reshape(3, 3) @ p + c[9:12]
+            if x[2] <= 1e-6:
+                continue
+            uv = np.array([c[12] * x[0] / x[2] + c[14], c[13] * x[1] / x[2] + c[15]])
+            d2d = ((centres - uv) ** 2).sum(1)
+            near = np.argsort(d2d, kind="stable")[:2]
+            srt = np.sort(d2d)
+            gaps.append(srt[2] - srt[1])     # how clear the prefilter's cut is in this view
+            for t in near:
+                tile = m * tg * tg + int(t)
+                rows = slice(cfg.n_obj + 64 * tile, cfg.n_obj + 64 * tile + 64)
+                cand.append((((pts[rows] - p) ** 2).sum(1).min(), nbo + tile))
+        cand.sort()
+        if [c[1] for c in cand[:4]] != idx[i, 2:6].tolist():
+            # only where fp32 rounding decides: a patch centre reprojects onto an axis of symmetry of
+            # the 2 x 2 tile grid, or two candidates are equally far
+            assert min(gaps) < 1e-3 or np.min(np.diff([c[0] for c in cand[:5]])) < 1e-5, i
+            loose += 1
+        else:
+            assert np.allclose(d2[i, 2:6], [c[0] for c in cand[:4]], rtol=1e-5, atol=1e-6)
+            exact += 1
+    assert exact >= 60
