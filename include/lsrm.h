@@ -135,6 +135,9 @@ typedef struct lsrm_route3d_params {
     int32_t k_v2i;     /* image blocks selected by a volume query block                       */
     int32_t k_i2v;     /* volume blocks selected by an image query block                      */
     int32_t k_i2i;     /* image blocks selected by an image query block                       */
+    int32_t per_token; /* 0: one query per block, its point the centroid of the block (the table the
+                          attention calls take); 1: one query per token, its point the token's own
+                          coordinate, as Sec. 3.3 words the rules: d_idx, d_dist2 are [N, topk]  */
 } lsrm_route3d_params;
 
 /*
@@ -157,7 +160,10 @@ typedef struct lsrm_route3d_params {
  *              than the budget appear when there are fewer candidates (a view that has p at or
  *              behind its image plane, z <= 1e-6, contributes none).
  *   d_dist2    [NB, topk] fp32  OUT, nullable: the squared 3-D distances (+inf for -1).
- * The table is a valid d_idx for lsrm_nsa_forward / lsrm_nsa_backward.  Arithmetic is fp32 in a
+ * With r->per_token the rows are query tokens in sequence order (token i < n_obj is a volume query with
+ * point d_pos[i], the others image queries with point d_pos_img[i - n_obj]) and the outputs have N rows;
+ * the attention calls, which share one list per query block, do not take that table.
+ * The per-block table is a valid d_idx for lsrm_nsa_forward / lsrm_nsa_backward.  Arithmetic is fp32 in a
  * fixed order without fused multiply-add (bit-reproducible): centroids and projection as in
  * lsrm_route_blocks; d2 = ((dx dx + dy dy) + dz dz).  Positions must be finite.
  * LSRM_ERR_UNSUPPORTED if n_views * min(prefilter, tiles per view) exceeds 4096.

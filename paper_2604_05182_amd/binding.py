@@ -39,7 +39,7 @@ class lsrm_nsa_params(ctypes.Structure):
 
 class lsrm_route3d_params(ctypes.Structure):
     _fields_ = [("prefilter", ctypes.c_int32), ("k_v2v", ctypes.c_int32), ("k_v2i", ctypes.c_int32),
-                ("k_i2v", ctypes.c_int32), ("k_i2i", ctypes.c_int32)]
+                ("k_i2v", ctypes.c_int32), ("k_i2i", ctypes.c_int32), ("per_token", ctypes.c_int32)]
 
 
 if not os.path.exists(LIB_PATH):

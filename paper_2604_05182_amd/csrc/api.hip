@@ -111,7 +111,8 @@ lsrm_status lsrm_route_blocks_3d(const lsrm_nsa_params *p, const lsrm_route3d_pa
     Shape s;
     lsrm_status rc = make_shape(p, &s);
     if (rc != LSRM_OK) return rc;
-    if (r == nullptr || r->prefilter < 1 || r->k_v2v < 0 || r->k_v2i < 0 || r->k_i2v < 0 || r->k_i2i < 0)
+    if (r == nullptr || r->prefilter < 1 || r->k_v2v < 0 || r->k_v2i < 0 || r->k_i2v < 0 || r->k_i2i < 0 ||
+        (r->per_token != 0 && r->per_token != 1))
         return LSRM_ERR_INVALID_ARG;
     if ((int64_t)r->k_v2v + r->k_v2i > s.topk || (int64_t)r->k_i2v + r->k_i2i > s.topk) return LSRM_ERR_INVALID_ARG;
     if (s.nb == 0 || s.topk == 0) return LSRM_OK;

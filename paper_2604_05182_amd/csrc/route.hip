@@ -229,12 +229,13 @@ __device__ __forceinline__ float sqdist3(float ax, float ay, float az, float bx,
 
 struct Route3d {
     int nb_obj, n_views, tg, width, prefilter, k_v2v, k_v2i, k_i2v, k_i2i, cache_keys;
+    int per_token, n_obj;  // queries are tokens (point = own coordinate) instead of blocks (point = centroid)
 };
 
 // Dynamic LDS: [n_views * prefilter candidate keys][4 * max(k_v2v, k_i2v) staged keys]
 // [nb_obj floats if cache_keys].
 __global__ __launch_bounds__(256) void select_3d(Route3d a, const float4 *__restrict__ cent,
-                                                 const float *__restrict__ pos_img,
+                                                 const float *__restrict__ pos, const float *__restrict__ pos_img,
                                                  const lsrm_camera *__restrict__ cams, int32_t *__restrict__ idx,
                                                  float *__restrict__ dist2_out) {
     extern __shared__ unsigned long long lds_base[];
@@ -244,10 +245,16 @@ __global__ __launch_bounds__(256) void select_3d(Route3d a, const float4 *__rest
     const int row = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tpv = a.tg * a.tg;
-    const bool obj_row = row < a.nb_obj;
+    const bool obj_row = row < (a.per_token ? a.n_obj : a.nb_obj);
     const int kv = obj_row ? a.k_v2v : a.k_i2v;
     const int ki = obj_row ? a.k_v2i : a.k_i2i;
-    const float4 p = cent[row];
+    float4 p;
+    if (a.per_token) {
+        const float *q = obj_row ? pos + (size_t)row * 3 : pos_img + (size_t)(row - a.n_obj) * 3;
+        p = make_float4(q[0], q[1], q[2], 0.0f);
+    } else {
+        p = cent[row];
+    }
 
     // image rule, first two steps: a wave per view
     if (ki > 0) {
@@ -359,6 +366,8 @@ lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const 
     a.k_v2i = r.k_v2i;
     a.k_i2v = r.k_i2v;
     a.k_i2i = r.k_i2i;
+    a.per_token = r.per_token;
+    a.n_obj = s.n_obj;
     if (a.prefilter < 1) a.k_v2i = a.k_i2i = 0;  // no tiles at all
     const int k_vol = a.k_v2v > a.k_i2v ? a.k_v2v : a.k_i2v;
     const size_t cand_bytes = ((size_t)s.n_views * (a.prefilter > 0 ? a.prefilter : 0) + 4 * (size_t)k_vol) *
@@ -367,7 +376,9 @@ lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const 
     if (cand_bytes > 36 * 1024) return LSRM_ERR_UNSUPPORTED;  // api.hip has bounded both terms below this
     a.cache_keys = vol_bytes + cand_bytes <= 60 * 1024 ? 1 : 0;
     const size_t lds = cand_bytes + (a.cache_keys ? vol_bytes : 0);
-    hipLaunchKernelGGL(select_3d, dim3(s.nb), dim3(256), lds, st, a, cent, d_pos_img, d_cams, d_idx, d_dist2);
+    const unsigned n_queries = r.per_token ? (unsigned)s.n : (unsigned)s.nb;
+    hipLaunchKernelGGL(select_3d, dim3(n_queries), dim3(256), lds, st, a, cent, d_pos, d_pos_img, d_cams, d_idx,
+                       d_dist2);
     LSRM_HIP_CHECK(hipGetLastError());
     return LSRM_OK;
 }

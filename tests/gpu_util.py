@@ -36,12 +36,14 @@ def run_route(B, cfg, pos, cams, want_dist=True):
     return idx.cpu().numpy(), (d2.cpu().numpy() if want_dist else None)
 
 
-def run_route_3d(B, cfg, pos, pos_img, cams, width, prefilter, k_v2v, k_v2i, k_i2v, k_i2i, want_dist=True):
+def run_route_3d(B, cfg, pos, pos_img, cams, width, prefilter, k_v2v, k_v2i, k_i2v, k_i2i, want_dist=True,
+                 per_token=False):
     p = params_for(B, cfg, topk=width)
-    r = B.lsrm_route3d_params(prefilter, k_v2v, k_v2i, k_i2v, k_i2i)
+    r = B.lsrm_route3d_params(prefilter, k_v2v, k_v2i, k_i2v, k_i2i, 1 if per_token else 0)
     d_pos, d_img, d_cams = (torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in (pos, pos_img, cams))
-    idx = torch.full((cfg.nb, width), -7, dtype=torch.int32, device="cuda")
-    d2 = torch.full((cfg.nb, width), -1.0, dtype=torch.float32, device="cuda") if want_dist else None
+    rows = cfg.n if per_token else cfg.nb
+    idx = torch.full((rows, width), -7, dtype=torch.int32, device="cuda")
+    d2 = torch.full((rows, width), -1.0, dtype=torch.float32, device="cuda") if want_dist else None
     ws = B.alloc_workspace(p, B.LSRM_WS_ROUTE_3D)
     B.lsrm_route_blocks_3d(p, r, d_pos, d_img, d_cams, idx, d2, ws)
     torch.cuda.synchronize()

@@ -121,3 +121,33 @@ def test_route_3d_error_codes(B):
     with pytest.raises(B.LsrmError) as e:        # no workspace
         B.lsrm_route_blocks_3d(p, B.lsrm_route3d_params(2, 2, 2, 1, 1), t, t, t, i, None, None)
     assert e.value.status == B.LSRM_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("cfg,budgets", [
+    (I.small_config(name="r3-tok-small", n_obj=512, n_views=2, grid=16, seed=3), (8, 2, 3, 4, 2, 3)),
+    (I.small_config(name="r3-tok-mid", n_obj=8192, n_views=4, grid=32, seed=9, points="ellipsoids", near_views=1),
+     (24, 4, 8, 16, 8, 16)),
+], ids=lambda c: c.name if hasattr(c, "name") else "")
+def test_route_3d_per_token_bit_exact(B, oracle_lib, cfg, budgets):
+    """One query per token (its own coordinate as the query point), every row against the oracle."""
+    width, pre, kvv, kvi, kiv, kii = budgets
+    _log(f"[route3d] per token {cfg.name} n={cfg.n}")
+    pos, cams = I.make_points(cfg), I.make_cameras(cfg)
+    pimg = I.make_points_img(cfg, cams)
+    ref = oracle_lib.route_3d(pos, pimg, cams, cfg.grid, width, pre, kvv, kvi, kiv, kii, per_token=True)
+    got = G.run_route_3d(B, cfg, pos, pimg, cams, width, pre, kvv, kvi, kiv, kii, per_token=True)
+    assert got[0].shape == (cfg.n, width)
+    _same(got, ref)
+
+
+def test_route_3d_per_token_full_size_sampled(B, oracle_lib):
+    """Config 4 at full size (428032 query tokens); the oracle evaluates a sample of them."""
+    cfg = I.CONFIGS[4]
+    pos, cams = I.make_points(cfg), I.make_cameras(cfg)
+    pimg = I.make_points_img(cfg, cams)
+    rng = np.random.default_rng(17)
+    pick = np.unique(np.concatenate([[0, cfg.n_obj - 1, cfg.n_obj, cfg.n - 1], rng.integers(0, cfg.n, size=1500)]))
+    _log(f"[route3d] per token config 4, oracle on {len(pick)} of {cfg.n} tokens")
+    ref = oracle_lib.route_3d(pos, pimg, cams, cfg.grid, 44, 4, 8, 36, 8, 36, per_token=True, queries=pick)
+    idx, d2 = G.run_route_3d(B, cfg, pos, pimg, cams, 44, 4, 8, 36, 8, 36, per_token=True)
+    _same((idx[pick], d2[pick]), ref)
