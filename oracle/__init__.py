@@ -159,18 +159,23 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
 
 
 def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0, window_mode=0):
-    """-> (dq, dk, dv) fp32 [N, H, d]; single-threaded definition, small inputs only."""
+    """-> (dq fp32 [N, H, d], dk, dv fp32 [N, h_kv, d]); single-threaded definition, small inputs only.
+    Shapes and gate layouts as in nsa_forward."""
     q, k, v, kc, vc, gates, dout = map(_f32, (q, k, v, kc, vc, gates, dout))
     idx, seg = _i32(idx), _i32(seg_offsets)
     n, h, d = q.shape
+    h_kv = k.shape[1]
+    assert h % h_kv == 0 and gates.shape in ((n, h, 3), (n, 3, h, d))
     topk = idx.shape[1] if idx.ndim == 2 else 0
-    dq, dk, dv = (np.empty_like(q) for _ in range(3))
+    dq = np.empty_like(q)
+    dk, dv = np.empty_like(k), np.empty_like(k)
     _load().oracle_nsa_backward(
-        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), ctypes.c_int(topk), ctypes.c_int(window),
-        ctypes.c_int(window_mode), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
-        _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
-        _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
-        _p(dout, ctypes.c_float), _p(dq, ctypes.c_float), _p(dk, ctypes.c_float), _p(dv, ctypes.c_float))
+        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(h_kv), ctypes.c_int(d), ctypes.c_int(topk),
+        ctypes.c_int(window), ctypes.c_int(window_mode), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1),
+        _p(seg, ctypes.c_int32), _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float),
+        _p(kc, ctypes.c_float), _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
+        ctypes.c_int(1 if gates.ndim == 4 else 0), _p(dout, ctypes.c_float), _p(dq, ctypes.c_float),
+        _p(dk, ctypes.c_float), _p(dv, ctypes.c_float))
     return dq, dk, dv
 
 

@@ -420,22 +420,26 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
  * where do = gate * dout for that branch.  Pooled keys/values pass their gradient
  * to the 64 tokens of their block, divided by 64.  Gradients are accumulated in
  * double, single-threaded over queries (this is a definition, not a fast path).
- * dq, dk, dv are fp32 outputs [N, H, d].
+ * With grouped-query heads (h_kv < h) a key/value head collects the gradients of all the
+ * query heads that read it; with per-channel gates `gate * dout` is a product per channel.
+ * dq is fp32 [N, H, d]; dk, dv are fp32 [N, h_kv, d].
  */
-void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, int window_mode, float scale, int n_seg,
-                         const int32_t *seg, const float *q, const float *k, const float *v,
+void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window, int window_mode, float scale,
+                         int n_seg, const int32_t *seg, const float *q, const float *k, const float *v,
                          const float *kc, const float *vc, const int32_t *idx, const float *gates,
-                         const float *dout, float *dq, float *dk, float *dv) {
+                         int gate_channels, const float *dout, float *dq, float *dk, float *dv) {
     int64_t nb = n / BLK;
-    size_t stride = (size_t)h * d;
-    size_t total = (size_t)n * stride, totalc = (size_t)nb * stride;
+    size_t stride = (size_t)h * d;        /* rows of q, dout, dq */
+    size_t stride_kv = (size_t)h_kv * d;  /* rows of k, v, kc, vc, dk, dv */
+    int group = h / h_kv;
+    size_t total = (size_t)n * stride, total_kv = (size_t)n * stride_kv, totalc = (size_t)nb * stride_kv;
     double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
     size_t maxkeys = (size_t)nb;
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
     if ((size_t)window + BLK > maxkeys) maxkeys = (size_t)window + BLK;
     double *gq = (double *)calloc(total, sizeof(double));
-    double *gk = (double *)calloc(total, sizeof(double));
-    double *gv = (double *)calloc(total, sizeof(double));
+    double *gk = (double *)calloc(total_kv, sizeof(double));
+    double *gv = (double *)calloc(total_kv, sizeof(double));
     double *gkc = (double *)calloc(totalc > 0 ? totalc : 1, sizeof(double));
     double *gvc = (double *)calloc(totalc > 0 ? totalc : 1, sizeof(double));
     int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
@@ -443,50 +447,57 @@ void oracle_nsa_backward(int64_t n, int h, int d, int topk, int window, int wind
     int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + BLK));
     double *p = (double *)malloc(sizeof(double) * maxkeys);
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    double *gd = (double *)malloc(sizeof(double) * (size_t)d); /* gate times dout: the gradient reaching one branch */
     for (int64_t i = 0; i < n; ++i) {
         int nc, ns, nw;
         key_sets(i, nb, topk, window, window_mode, NULL, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
         for (int hh = 0; hh < h; ++hh) {
+            size_t kvo = (size_t)(hh / group) * d; /* this query head's key/value head */
             const float *qv = q + (size_t)i * stride + (size_t)hh * d;
             const float *dor = dout + (size_t)i * stride + (size_t)hh * d;
-            const float *g = gates + ((size_t)i * h + hh) * 3;
             double *gqr = gq + (size_t)i * stride + (size_t)hh * d;
             for (int br = 0; br < 3; ++br) {
-                const float *kb = (br == 0 ? kc : k) + (size_t)hh * d;
-                const float *vb = (br == 0 ? vc : v) + (size_t)hh * d;
-                double *gkb = (br == 0 ? gkc : gk) + (size_t)hh * d;
-                double *gvb = (br == 0 ? gvc : gv) + (size_t)hh * d;
+                const float *kb = (br == 0 ? kc : k) + kvo;
+                const float *vb = (br == 0 ? vc : v) + kvo;
+                double *gkb = (br == 0 ? gkc : gk) + kvo;
+                double *gvb = (br == 0 ? gvc : gv) + kvo;
                 const int64_t *rows = br == 0 ? rc : (br == 1 ? rs : rw);
                 int cnt = br == 0 ? nc : (br == 1 ? ns : nw);
                 if (cnt == 0) continue;
-                attend(qv, d, sc, kb, vb, stride, rows, cnt, p, o);
+                for (int c = 0; c < d; ++c) {
+                    double g = gate_channels ? (double)gates[(((size_t)i * 3 + br) * h + hh) * d + c]
+                                             : (double)gates[((size_t)i * h + hh) * 3 + br];
+                    gd[c] = g * (double)dor[c];
+                }
+                attend(qv, d, sc, kb, vb, stride_kv, rows, cnt, p, o);
                 double delta = 0.0;
-                for (int c = 0; c < d; ++c) delta += (double)g[br] * (double)dor[c] * o[c];
+                for (int c = 0; c < d; ++c) delta += gd[c] * o[c];
                 for (int j = 0; j < cnt; ++j) {
-                    const float *kr = kb + (size_t)rows[j] * stride;
-                    const float *vr = vb + (size_t)rows[j] * stride;
-                    double *gkr = gkb + (size_t)rows[j] * stride;
-                    double *gvr = gvb + (size_t)rows[j] * stride;
+                    const float *kr = kb + (size_t)rows[j] * stride_kv;
+                    const float *vr = vb + (size_t)rows[j] * stride_kv;
+                    double *gkr = gkb + (size_t)rows[j] * stride_kv;
+                    double *gvr = gvb + (size_t)rows[j] * stride_kv;
                     double dp = 0.0;
-                    for (int c = 0; c < d; ++c) dp += (double)g[br] * (double)dor[c] * (double)vr[c];
+                    for (int c = 0; c < d; ++c) dp += gd[c] * (double)vr[c];
                     double ds = p[j] * (dp - delta) * sc;
                     for (int c = 0; c < d; ++c) {
                         gqr[c] += ds * (double)kr[c];
                         gkr[c] += ds * (double)qv[c];
-                        gvr[c] += p[j] * (double)g[br] * (double)dor[c];
+                        gvr[c] += p[j] * gd[c];
                     }
                 }
             }
         }
     }
     for (int64_t j = 0; j < n; ++j)
-        for (size_t c = 0; c < stride; ++c) {
-            gk[(size_t)j * stride + c] += gkc[(size_t)(j / BLK) * stride + c] / 64.0;
-            gv[(size_t)j * stride + c] += gvc[(size_t)(j / BLK) * stride + c] / 64.0;
+        for (size_t c = 0; c < stride_kv; ++c) {
+            gk[(size_t)j * stride_kv + c] += gkc[(size_t)(j / BLK) * stride_kv + c] / 64.0;
+            gv[(size_t)j * stride_kv + c] += gvc[(size_t)(j / BLK) * stride_kv + c] / 64.0;
         }
-    for (size_t e = 0; e < total; ++e) { dq[e] = (float)gq[e]; dk[e] = (float)gk[e]; dv[e] = (float)gv[e]; }
+    for (size_t e = 0; e < total; ++e) dq[e] = (float)gq[e];
+    for (size_t e = 0; e < total_kv; ++e) { dk[e] = (float)gk[e]; dv[e] = (float)gv[e]; }
     free(gq); free(gk); free(gv); free(gkc); free(gvc);
-    free(rc); free(rs); free(rw); free(p); free(o);
+    free(rc); free(rs); free(rw); free(p); free(o); free(gd);
 }
 
 /*

@@ -83,9 +83,15 @@ def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None, window_mode=
 def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None, window_mode=0):
     """Library autograd (float64) through the dense-mask formulation -> dq, dk, dv."""
     import torch
-    tq, tk, tv = (torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True) for a in (q, k, v))
+    tq, tk0, tv0 = (torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True) for a in (q, k, v))
     g = torch.tensor(np.asarray(gates, dtype=np.float64))
     n, h, d = tq.shape
+    # grouped-query heads: every query head gets a view of its key/value head (autograd sums the group)
+    tk, tv = (t.repeat_interleave(h // t.shape[1], dim=1) for t in (tk0, tv0))
+    if g.ndim == 4:   # per-channel gates [N, 3, H, d] -> [N, H, 3, d]
+        g = g.permute(0, 2, 1, 3)
+    else:
+        g = g[..., None]
     scale = 1.0 / np.sqrt(d) if not scale else scale
     sel, win = masks(n, idx, seg_offsets, window, window_mode)
     sel, win = torch.tensor(sel), torch.tensor(win)
@@ -107,10 +113,10 @@ def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=
     out = torch.zeros_like(tq)
     outs = []
     for hh in range(h):
-        o = (g[:, hh, 0:1] * att(tq[:, hh], kc[:, hh], vc[:, hh], None)
-             + g[:, hh, 1:2] * att(tq[:, hh], tk[:, hh], tv[:, hh], sel)
-             + g[:, hh, 2:3] * att(tq[:, hh], tk[:, hh], tv[:, hh], win))
+        o = (g[:, hh, 0] * att(tq[:, hh], kc[:, hh], vc[:, hh], None)
+             + g[:, hh, 1] * att(tq[:, hh], tk[:, hh], tv[:, hh], sel)
+             + g[:, hh, 2] * att(tq[:, hh], tk[:, hh], tv[:, hh], win))
         outs.append(o)
     out = torch.stack(outs, dim=1)
     (out * torch.tensor(np.asarray(dout, dtype=np.float64))).sum().backward()
-    return tq.grad.numpy(), tk.grad.numpy(), tv.grad.numpy()
+    return tq.grad.numpy(), tk0.grad.numpy(), tv0.grad.numpy()

@@ -310,6 +310,26 @@ def test_backward_matches_library_autograd(oracle_lib):
         assert np.abs(a - b).max() < 1e-5 * max(1.0, np.abs(b).max())
 
 
+@pytest.mark.parametrize("gate_channels", [False, True])
+def test_backward_with_grouped_heads_and_channel_gates_matches_library_autograd(oracle_lib, gate_channels):
+    """A key/value head collects the gradients of every query head that reads it; per-channel
+    gates scale the incoming gradient channel by channel."""
+    cfg = I.small_config(n_obj=128, n_views=1, grid=16, heads=6, d=8, topk=2, window=48, seed=14, h_kv=2,
+                         gate_channels=gate_channels)
+    q, k, v = (I.bf16_bits_to_f32(a) for a in I.make_qkv(cfg))
+    gates, dout = I.make_gates(cfg), I.bf16_bits_to_f32(I.make_dout(cfg))
+    rng = np.random.default_rng(14)
+    idx = np.stack([rng.choice(cfg.nb, size=2, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[2, 1] = -1
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    dq, dk, dv = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout)
+    assert dq.shape == q.shape and dk.shape == k.shape == (cfg.n, 2, 8) and dv.shape == v.shape
+    rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout)
+    for a, b in ((dq, rq), (dk, rk), (dv, rv)):
+        assert np.abs(a - b).max() < 1e-5 * max(1.0, np.abs(b).max())
+
+
 def test_backward_finite_difference_of_dense_formulation():
     """Pins the autograd reference itself: central differences in float64."""
     cfg, q, k, v, gates, idx = _case(11, n_obj=64, grid=8, n_views=1, heads=1, d=4, topk=1, window=32)
