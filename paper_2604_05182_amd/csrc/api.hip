@@ -86,7 +86,7 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call) {
     switch (which_call) {
         case LSRM_WS_ROUTE: return route_ws_bytes(s);
         case LSRM_WS_FORWARD: return forward_ws_bytes(s);
-        case LSRM_WS_BACKWARD: return s.d == 64 && s.h_kv == s.h && !s.gate_channels && s.count == nullptr ? backward_ws_bytes(s) : 0;
+        case LSRM_WS_BACKWARD: return s.count == nullptr ? backward_ws_bytes(s) : 0;
         case LSRM_WS_ROUTE_3D: return route3d_ws_bytes(s);
         default: return 0;
     }
@@ -169,7 +169,7 @@ lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, con
     Shape s;
     lsrm_status rc = make_shape(p, &s);
     if (rc != LSRM_OK) return rc;
-    if (s.d != 64 || s.h_kv != s.h || s.gate_channels || s.count != nullptr) return LSRM_ERR_UNSUPPORTED;
+    if (s.count != nullptr) return LSRM_ERR_UNSUPPORTED;
     std::vector<int32_t> seg;
     rc = make_segments(p, s, &seg);
     if (rc != LSRM_OK) return rc;
@@ -178,6 +178,7 @@ lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, con
     for (const void *ptr : in)
         if (ptr == nullptr || !aligned(ptr, 16)) return LSRM_ERR_INVALID_ARG;
     if (d_gates == nullptr || d_lse == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (s.gate_channels && !aligned(d_gates, 16)) return LSRM_ERR_INVALID_ARG;
     if (s.topk > 0 && d_idx == nullptr) return LSRM_ERR_INVALID_ARG;
     if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < backward_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
     return launch_backward(s, seg.data(), (int)seg.size() - 1, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_lse,

@@ -5,7 +5,9 @@
 // Per branch, with P the softmax probabilities (recomputed from the saved log-sum-exp), g the
 // gate, D_i = dout_i . o_branch_i and dP = dout V^T:
 //     dV = (g P)^T dout        dS = (g P) o (dP - D)        dQ = scale dS K        dK = scale dS^T Q
-// The gate is folded into the exponent: g P = exp2(S scale log2e - (lse log2e - log2 g)).
+// A per-head gate is folded into the exponent: g P = exp2(S scale log2e - (lse log2e - log2 g)); with
+// per-channel gates the incoming gradient of each branch is gate o dout instead (three images of it).
+// With grouped-query heads a key/value head walks the query tiles of every query head that reads it.
 //
 // No floating-point atomics: the work is split into passes that each own their output rows.
 //   bwd_dq_kernel    one workgroup per (query block, head): walks the same key tiles as the forward
@@ -47,7 +49,11 @@ struct BwdArgs {
     const uint16_t *q, *k, *v, *kc, *vc, *dout, *out_branch;
     const int32_t *idx;
     const float *gates, *lse;
-    const char *img_q, *img_do, *img_k, *img_v, *img_kc, *img_vc;  // tile images
+    const char *img_q, *img_k, *img_v, *img_kc, *img_vc;  // tile images
+    const char *img_do[3];    // images of the gradient that reaches each branch: one shared image of dout with
+                              // per-head gates (the gate is folded into the exponent), gate o dout per branch
+                              // with per-channel gates
+    const uint16_t *gdo;      // per-channel gates only: [3][N][H][d] bf16, gate o dout (written by bwd_prep)
     float *aux;               // [3][N/32][H][64]: per query tile, 32 x (lse log2e - log2 g) then 32 x D, rows permuted
     float *part_k, *part_v;   // [n_split][nbp][H][d] fp32 partial gradients of the pooled keys / values
     int32_t *rev_cnt, *rev_ptr, *rev_cur, *rev_idx;  // reverse routing lists
@@ -56,6 +62,8 @@ struct BwdArgs {
     int64_t n;
     int nb, h, topk, window, n_seg;
     int own_block;  // window branch = the query's own block
+    int h_kv, group;    // key/value heads; query heads per key/value head
+    int gate_channels;  // gates are [N, 3, H, d]
     int nt;               // query / key tiles of 32 tokens
     int n_split, nbp, tiles_per_split;
     float scale, sl2;
@@ -161,18 +169,43 @@ __global__ __launch_bounds__(256) void bwd_prep(BwdArgs a) {
     for (int b = 0; b < 3; ++b) {
         const uint4 *obr = reinterpret_cast<const uint4 *>(a.out_branch + (((int64_t)b * a.n + row) * a.h + head) * D);
         float dl = 0.f;
+        if (a.gate_channels) {
+            // the gradient reaching this branch is gate o dout, channel by channel: D uses it, and its
+            // bf16 rounding is kept for the contractions
+            const float *gch = a.gates + ((row * 3 + b) * a.h + head) * D;
+            uint4 *gdo = reinterpret_cast<uint4 *>(const_cast<uint16_t *>(a.gdo) + (((int64_t)b * a.n + row) * a.h + head) * D);
 #pragma unroll
-        for (int c = 0; c < D / 8; ++c) {
-            uint4 w = obr[c];
-            uint32_t u[4] = {w.x, w.y, w.z, w.w};
+            for (int c = 0; c < D / 8; ++c) {
+                uint4 w = obr[c];
+                uint32_t u[4] = {w.x, w.y, w.z, w.w}, o4[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) dl += dov[8 * c + 2 * j] * bf16_lo(u[j]) + dov[8 * c + 2 * j + 1] * bf16_hi(u[j]);
+                for (int j = 0; j < 4; ++j) {
+                    const float g0 = gch[8 * c + 2 * j] * dov[8 * c + 2 * j];
+                    const float g1 = gch[8 * c + 2 * j + 1] * dov[8 * c + 2 * j + 1];
+                    dl += g0 * bf16_lo(u[j]) + g1 * bf16_hi(u[j]);
+                    o4[j] = pack_bf16(g0, g1);
+                }
+                gdo[c] = make_uint4(o4[0], o4[1], o4[2], o4[3]);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < D / 8; ++c) {
+                uint4 w = obr[c];
+                uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    dl += dov[8 * c + 2 * j] * bf16_lo(u[j]) + dov[8 * c + 2 * j + 1] * bf16_hi(u[j]);
+            }
         }
         const float lse = a.lse[((int64_t)b * a.n + row) * a.h + head];
-        const float g = a.gates[(row * a.h + head) * 3 + b];
         // an empty key set (lse = -inf) or a zero gate gives zero probabilities: offset +inf
         float l2 = __builtin_inff();
-        if (g > 0.f && lse > -__builtin_inff()) l2 = lse * kLog2e - __log2f(g);
+        if (a.gate_channels) {
+            if (lse > -__builtin_inff()) l2 = lse * kLog2e;
+        } else {
+            const float g = a.gates[(row * a.h + head) * 3 + b];
+            if (g > 0.f && lse > -__builtin_inff()) l2 = lse * kLog2e - __log2f(g);
+        }
         float *ax = a.aux + (((int64_t)b * a.nt + tile) * a.h + head) * 64;
         ax[pr] = l2;
         ax[32 + pr] = dl;
@@ -239,6 +272,7 @@ __global__ void rev_sort(BwdArgs a) {
 // dQ: one workgroup (2 wavefronts x 32 query rows) per (query block, head)
 template <int D>
 __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
+    // (at d = 128 the 256-register budget of two workgroups per SIMD still holds: 64 accumulator registers)
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int TILE = G::IMG + G::ROW;  // K rows | K^T | V rows
@@ -258,16 +292,21 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     const uint32_t lane16 = (uint32_t)lane * 16u;
     const int64_t row0 = (int64_t)qb * 64 + 32 * wave;
     const int half_w = a.window / 2;
+    const int kvh = head / a.group;  // key/value head of this query head
 
     bf16x8 qf[NS], dof[NS];
+    // the gradient rows of branch b: dout itself, or gate o dout with per-channel gates
+    auto load_dof = [&](int b) {
+        const uint16_t *src = a.gate_channels ? a.gdo + (int64_t)b * a.n * a.h * D : a.dout;
+        const uint16_t *drow = src + ((row0 + r) * a.h + head) * D + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks) dof[ks] = *reinterpret_cast<const bf16x8 *>(drow + 16 * ks);
+    };
     {
         const uint16_t *qrow = a.q + ((row0 + r) * a.h + head) * D + 8 * hh;
-        const uint16_t *drow = a.dout + ((row0 + r) * a.h + head) * D + 8 * hh;
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks) {
-            qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
-            dof[ks] = *reinterpret_cast<const bf16x8 *>(drow + 16 * ks);
-        }
+        for (int ks = 0; ks < NS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
+        load_dof(0);
     }
     float l2[3], dl[3];
 #pragma unroll
@@ -328,7 +367,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
             kimg = a.img_k;
             vimg = a.img_v;
         }
-        const int64_t off = (tile * a.h + head) * G::IMG;
+        const int64_t off = (tile * a.h_kv + kvh) * G::IMG;
         copy_kb<G::IMG / 1024>(kimg + off, buf, wave, lane16);
         copy_kb<G::ROW / 1024>(vimg + off, buf + G::IMG, wave, lane16);
     };
@@ -347,6 +386,8 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         wg_barrier();
         if (t + NBUF - 1 < T) issue(t + NBUF - 1, lds + ((t + NBUF - 1) % NBUF) * TILE);
         const int br = t < tc ? 0 : (t < tc + ts ? 1 : 2);
+        // tiles come branch by branch: with per-channel gates the gradient rows change at the two boundaries
+        if (a.gate_channels && (t == tc || t == tc + ts)) load_dof(br);
         const int j0 = br == 0 ? 32 * t : (br == 1 ? 0 : 32 * (st0 + t - tc - ts));
         const int lo = br == 0 ? 0 : (br == 1 ? -0x40000000 : wlo);
         const int hi = br == 0 ? a.nb : (br == 1 ? 0x7fffffff : whi);
@@ -403,14 +444,16 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 
 // ---------------------------------------------------------------------------------------------
 // dK, dV: one workgroup (2 wavefronts x 32 keys) per (key block, head[, query range])
+// blockIdx.y is the key/value head; the query tiles of each of its `group` query heads are walked in turn.
+// (d = 128: the two [128 x 32] accumulator sets alone take 128 registers, so one workgroup per SIMD.)
 template <int D, int MODE>
-__global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
+__global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArgs a) {
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int AUX = 2 * G::IMG;         // Q rows | Q^T | dO rows | dO^T | table (64 floats)
     constexpr int TILE = 2 * G::IMG + 1024;  // (table padded to keep the next buffer aligned)
     static_assert(2 * 32 * G::OUT_ROW <= 2 * TILE, "output staging fits in the tile buffers");
-    __shared__ __attribute__((aligned(1024))) char lds[2 * TILE];
+    extern __shared__ __attribute__((aligned(1024))) char lds[];  // 2 * TILE bytes
     const int n_kb = MODE == 0 ? a.nb : a.nbp / 64;
     const int per_xcd = (n_kb + 7) / 8;
     const int kb = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), head = blockIdx.y;  // (see bwd_dq_kernel)
@@ -428,8 +471,8 @@ __global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
     bf16x8 kB[NS], vB[NS];
     {
         const int64_t krow_i = key < limit ? key : limit - 1;  // (rows past the end are masked below)
-        const uint16_t *krow = (MODE == 0 ? a.k : a.kc) + (krow_i * a.h + head) * D + 8 * hh;
-        const uint16_t *vrow = (MODE == 0 ? a.v : a.vc) + (krow_i * a.h + head) * D + 8 * hh;
+        const uint16_t *krow = (MODE == 0 ? a.k : a.kc) + (krow_i * a.h_kv + head) * D + 8 * hh;
+        const uint16_t *vrow = (MODE == 0 ? a.v : a.vc) + (krow_i * a.h_kv + head) * D + 8 * hh;
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks) {
             kB[ks] = *reinterpret_cast<const bf16x8 *>(krow + 16 * ks);
@@ -480,26 +523,33 @@ __global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
         return 2 * (int64_t)__builtin_amdgcn_readlane(rev_held, e & 63) + (u & 1);
     };
     auto branch_of = [&](int t) { return MODE == 1 ? 0 : (t < tw ? 2 : 1); };
-    auto issue = [&](int t, char *buf) {
+    // step u of the walk: query tile u / group of query head head * group + u % group
+    const int grp = a.group;
+    const int U = T * grp;
+    auto issue = [&](int u, char *buf) {
+        const int t = u / grp, qh = head * grp + u % grp;
         const int64_t tile = tile_of(t);
-        const int64_t off = (tile * a.h + head) * G::IMG;
+        const int64_t off = (tile * a.h + qh) * G::IMG;
+        const int br = branch_of(t);
         copy_kb<G::IMG / 1024>(a.img_q + off, buf, wave, lane16);
-        copy_kb<G::IMG / 1024>(a.img_do + off, buf + G::IMG, wave, lane16);
+        copy_kb<G::IMG / 1024>((br == 0 ? a.img_do[0] : (br == 1 ? a.img_do[1] : a.img_do[2])) + off, buf + G::IMG, wave,
+                               lane16);
         if (wave == 0) {
-            const float *ax = a.aux + (((int64_t)branch_of(t) * a.nt + tile) * a.h + head) * 64;
+            const float *ax = a.aux + (((int64_t)br * a.nt + tile) * a.h + qh) * 64;
             __builtin_amdgcn_global_load_lds(GLB_PTR(ax + lane), LDS_PTR(buf + AUX), 4, 0, 0);
         }
     };
 
-    if (T > 0) issue(0, lds);
-    for (int t = 0; t < T; ++t) {
+    if (U > 0) issue(0, lds);
+    for (int u = 0; u < U; ++u) {
+        const int t = u / grp;
         // The barrier alone does not wait for copies in flight (they are counted by vmcnt, which a
         // workgroup-scope fence leaves alone): every wavefront first waits for its own share of tile t,
         // issued one iteration ago, then the barrier publishes all shares.
         __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         __syncthreads();
-        if (t + 1 < T) issue(t + 1, lds + ((t + 1) & 1) * TILE);
-        const char *buf = lds + (t & 1) * TILE;
+        if (u + 1 < U) issue(u + 1, lds + ((u + 1) & 1) * TILE);
+        const char *buf = lds + (u & 1) * TILE;
         const char *base = buf + lane16;
         const int q0 = 32 * (int)tile_of(t);
         // window tiles away from the band's edges (and all routed tiles) need no mask
@@ -569,7 +619,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
 
     if (MODE == 1) {
         // partial sums of this query range: [split][pooled key][head][channel] fp32
-        const int64_t o = (((int64_t)split * a.nbp + key) * a.h + head) * D;
+        const int64_t o = (((int64_t)split * a.nbp + key) * a.h_kv + head) * D;
 #pragma unroll
         for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
@@ -592,7 +642,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
             for (int g = 0; g < 4; ++g) {
                 f32x4 pk = {0.f, 0.f, 0.f, 0.f}, pv = {0.f, 0.f, 0.f, 0.f};
                 for (int sp = 0; sp < a.n_split; ++sp) {
-                    const int64_t o = (((int64_t)sp * a.nbp + kb) * a.h + head) * D + 32 * dt + 8 * g + 4 * hh;
+                    const int64_t o = (((int64_t)sp * a.nbp + kb) * a.h_kv + head) * D + 32 * dt + 8 * g + 4 * hh;
                     pk += *reinterpret_cast<const f32x4 *>(a.part_k + o);
                     pv += *reinterpret_cast<const f32x4 *>(a.part_v + o);
                 }
@@ -604,14 +654,14 @@ __global__ __launch_bounds__(128, 2) void bwd_dkv_kernel(BwdArgs a) {
             }
         __syncthreads();  // the tile buffers become the output staging
         char *stage = lds + wave * 32 * G::OUT_ROW;
-        store_rows_transposed<D>(xk, stage, a.dk + (key0 * a.h + head) * D, (int64_t)a.h * D, lane);
+        store_rows_transposed<D>(xk, stage, a.dk + (key0 * a.h_kv + head) * D, (int64_t)a.h_kv * D, lane);
         __builtin_amdgcn_s_waitcnt(0xC07F);  // staging reads of dK done before it is overwritten
-        store_rows_transposed<D>(xv, stage, a.dv + (key0 * a.h + head) * D, (int64_t)a.h * D, lane);
+        store_rows_transposed<D>(xv, stage, a.dv + (key0 * a.h_kv + head) * D, (int64_t)a.h_kv * D, lane);
     }
 }
 
 struct WsLayout {
-    size_t img_q, img_do, img_k, img_v, img_kc, img_vc, aux, part_k, part_v, rev_cnt, rev_ptr, rev_cur, rev_idx, total;
+    size_t img_q, img_do[3], gdo, img_k, img_v, img_kc, img_vc, aux, part_k, part_v, rev_cnt, rev_ptr, rev_cur, rev_idx, total;
     int n_split, nbp, tiles_per_split;
 };
 
@@ -626,28 +676,94 @@ WsLayout ws_layout(const Shape &s) {
         return at;
     };
     w.img_q = take(nt * s.h * img);
-    w.img_do = take(nt * s.h * img);
-    w.img_k = take(nt * s.h * img);
-    w.img_v = take(nt * s.h * img);
-    w.img_kc = take(ntc * s.h * img);
-    w.img_vc = take(ntc * s.h * img);
+    w.img_do[0] = take(nt * s.h * img);
+    if (s.gate_channels) {
+        // one image of gate o dout per branch, and the rows they are packed from
+        w.img_do[1] = take(nt * s.h * img);
+        w.img_do[2] = take(nt * s.h * img);
+        w.gdo = take((size_t)3 * s.n * s.h * s.d * 2);
+    } else {
+        w.img_do[1] = w.img_do[2] = w.img_do[0];
+        w.gdo = 0;
+    }
+    w.img_k = take(nt * s.h_kv * img);
+    w.img_v = take(nt * s.h_kv * img);
+    w.img_kc = take(ntc * s.h_kv * img);
+    w.img_vc = take(ntc * s.h_kv * img);
     w.aux = take((size_t)3 * nt * s.h * 64 * 4);
     // pooled keys: enough query ranges to fill the chip
     w.nbp = (s.nb + 63) / 64 * 64;
-    const int wgs = (w.nbp / 64) * s.h;
+    const int wgs = (w.nbp / 64) * s.h_kv;
     int n_split = (2048 + wgs - 1) / wgs;
     n_split = n_split < 1 ? 1 : (n_split > 16 ? 16 : n_split);
     w.tiles_per_split = (int)((nt + n_split - 1) / n_split);
     w.n_split = (int)((nt + w.tiles_per_split - 1) / (w.tiles_per_split > 0 ? w.tiles_per_split : 1));
     if (w.n_split < 1) w.n_split = 1;
-    w.part_k = take((size_t)w.n_split * w.nbp * s.h * s.d * 4);
-    w.part_v = take((size_t)w.n_split * w.nbp * s.h * s.d * 4);
+    w.part_k = take((size_t)w.n_split * w.nbp * s.h_kv * s.d * 4);
+    w.part_v = take((size_t)w.n_split * w.nbp * s.h_kv * s.d * 4);
     w.rev_cnt = take((size_t)s.nb * 4);
     w.rev_ptr = take((size_t)(s.nb + 1) * 4);
     w.rev_cur = take((size_t)s.nb * 4);
     w.rev_idx = take((size_t)s.nb * (s.topk > 0 ? s.topk : 1) * 4);
     w.total = off;
     return w;
+}
+
+template <int D>
+lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char *ws, hipStream_t st, hipEvent_t ev_start,
+                              hipEvent_t ev_stop) {
+    using G = BGeo<D>;
+    constexpr int DKV_LDS = 2 * (2 * G::IMG + 1024);
+    static bool attr_set = false;
+    if (!attr_set) {
+        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 0>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
+        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
+        attr_set = true;
+    }
+    if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
+    const int ntc = (s.nb + 31) / 32;
+    lsrm_status rc;
+    hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)((s.n * s.h + 255) / 256)), dim3(256), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    if ((rc = launch_pack_tiles(D, a.q, a.q, ws + w.img_q, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+    if (s.gate_channels) {
+        for (int b = 0; b < 3; ++b) {
+            const uint16_t *src = a.gdo + (size_t)b * s.n * s.h * D;
+            if ((rc = launch_pack_tiles(D, src, src, ws + w.img_do[b], s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+        }
+    } else {
+        if ((rc = launch_pack_tiles(D, a.dout, a.dout, ws + w.img_do[0], s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+    }
+    if ((rc = launch_pack_tiles(D, a.k, a.k, ws + w.img_k, s.n, s.h_kv, a.nt, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.v, a.v, ws + w.img_v, s.n, s.h_kv, a.nt, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.kc, a.kc, ws + w.img_kc, (int64_t)s.nb, s.h_kv, ntc, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.vc, a.vc, ws + w.img_vc, (int64_t)s.nb, s.h_kv, ntc, st)) != LSRM_OK) return rc;
+    // reverse routing lists
+    hipLaunchKernelGGL(fill_zero, dim3((s.nb + 255) / 256), dim3(256), 0, st, a.rev_cnt, s.nb);
+    LSRM_HIP_CHECK(hipGetLastError());
+    if (s.topk > 0) {
+        hipLaunchKernelGGL(rev_count, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
+        LSRM_HIP_CHECK(hipGetLastError());
+    }
+    hipLaunchKernelGGL(rev_scan, dim3(1), dim3(1024), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    if (s.topk > 0) {
+        hipLaunchKernelGGL(rev_fill, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
+        LSRM_HIP_CHECK(hipGetLastError());
+        hipLaunchKernelGGL(rev_sort, dim3((s.nb + 63) / 64), dim3(64), 0, st, a);
+        LSRM_HIP_CHECK(hipGetLastError());
+    }
+    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3((w.nbp / 64 + 7) / 8 * 8, s.h_kv, w.n_split), dim3(128), DKV_LDS, st,
+                       a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3((s.nb + 7) / 8 * 8, s.h_kv), dim3(128), DKV_LDS, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
+    return LSRM_OK;
 }
 
 }  // namespace
@@ -660,8 +776,7 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
                             const uint16_t *d_out_branch, const uint16_t *d_dout, uint16_t *d_dq, uint16_t *d_dk,
                             uint16_t *d_dv, void *d_ws, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
     if (s.nb == 0) return LSRM_OK;
-    if (n_seg > kMaxSeg || s.d != 64) return LSRM_ERR_UNSUPPORTED;
-    constexpr int D = 64;
+    if (n_seg > kMaxSeg) return LSRM_ERR_UNSUPPORTED;
     const WsLayout w = ws_layout(s);
     char *ws = reinterpret_cast<char *>(d_ws);
     BwdArgs a{};
@@ -676,7 +791,8 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     a.gates = d_gates;
     a.lse = d_lse;
     a.img_q = ws + w.img_q;
-    a.img_do = ws + w.img_do;
+    for (int b = 0; b < 3; ++b) a.img_do[b] = ws + w.img_do[b];
+    a.gdo = s.gate_channels ? reinterpret_cast<const uint16_t *>(ws + w.gdo) : nullptr;
     a.img_k = ws + w.img_k;
     a.img_v = ws + w.img_v;
     a.img_kc = ws + w.img_kc;
@@ -695,6 +811,9 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     a.n = s.n;
     a.nb = s.nb;
     a.h = s.h;
+    a.h_kv = s.h_kv;
+    a.group = s.h / s.h_kv;
+    a.gate_channels = s.gate_channels;
     a.topk = s.topk;
     a.window = s.window;
     a.own_block = s.own_block;
@@ -705,41 +824,9 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     a.tiles_per_split = w.tiles_per_split;
     a.scale = s.scale;
     a.sl2 = s.scale * kLog2e;
-
-    if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
-    const int ntc = (s.nb + 31) / 32;
-    lsrm_status rc;
-    if ((rc = launch_pack_tiles(D, d_q, d_q, ws + w.img_q, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, d_dout, d_dout, ws + w.img_do, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, d_k, d_k, ws + w.img_k, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, d_v, d_v, ws + w.img_v, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, d_kc, d_kc, ws + w.img_kc, (int64_t)s.nb, s.h, ntc, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, d_vc, d_vc, ws + w.img_vc, (int64_t)s.nb, s.h, ntc, st)) != LSRM_OK) return rc;
-    hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)((s.n * s.h + 255) / 256)), dim3(256), 0, st, a);
-    LSRM_HIP_CHECK(hipGetLastError());
-    // reverse routing lists
-    hipLaunchKernelGGL(fill_zero, dim3((s.nb + 255) / 256), dim3(256), 0, st, a.rev_cnt, s.nb);
-    LSRM_HIP_CHECK(hipGetLastError());
-    if (s.topk > 0) {
-        hipLaunchKernelGGL(rev_count, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
-        LSRM_HIP_CHECK(hipGetLastError());
-    }
-    hipLaunchKernelGGL(rev_scan, dim3(1), dim3(1024), 0, st, a);
-    LSRM_HIP_CHECK(hipGetLastError());
-    if (s.topk > 0) {
-        hipLaunchKernelGGL(rev_fill, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
-        LSRM_HIP_CHECK(hipGetLastError());
-        hipLaunchKernelGGL(rev_sort, dim3((s.nb + 63) / 64), dim3(64), 0, st, a);
-        LSRM_HIP_CHECK(hipGetLastError());
-    }
-    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
-    LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3((w.nbp / 64 + 7) / 8 * 8, s.h, w.n_split), dim3(128), 0, st, a);
-    LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
-    LSRM_HIP_CHECK(hipGetLastError());
-    if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
-    return LSRM_OK;
+    if (s.d == 32) return launch_backward_d<32>(s, a, w, ws, st, ev_start, ev_stop);
+    if (s.d == 64) return launch_backward_d<64>(s, a, w, ws, st, ev_start, ev_stop);
+    return launch_backward_d<128>(s, a, w, ws, st, ev_start, ev_stop);
 }
 
 }  // namespace lsrm

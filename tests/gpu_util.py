@@ -98,7 +98,7 @@ def run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offs
     ws = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
     B.lsrm_nsa_forward(p, dq_in, dk_in, dv_in, kc, vc, d_idx, d_g, out, lse, ob, ws)
     gq = torch.full_like(out, float("nan"))
-    gk, gv = torch.full_like(out, float("nan")), torch.full_like(out, float("nan"))
+    gk, gv = torch.full_like(dk_in, float("nan")), torch.full_like(dk_in, float("nan"))
     wsb = B.alloc_workspace(p, B.LSRM_WS_BACKWARD)
     B.lsrm_nsa_backward(p, dq_in, dk_in, dv_in, kc, vc, d_idx, d_g, lse, ob, ddo, gq, gk, gv, wsb)
     torch.cuda.synchronize()

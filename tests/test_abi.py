@@ -42,12 +42,12 @@ def test_host_side_argument_checks():
     # null pointers are rejected before anything is launched
     rc = B._lib.lsrm_nsa_compress(__import__("ctypes").byref(ok), None, None, None, None, None)
     assert rc == B.LSRM_ERR_INVALID_ARG
-    # the backward supports d = 64 only and says so before anything is launched
+    # the backward takes every head dimension the forward does; null pointers are rejected
     assert B.lsrm_workspace_bytes(ok, B.LSRM_WS_BACKWARD) > 0
     wide = B.make_params(512, 2, 16, 2, 128, 3, 128)
-    assert B.lsrm_workspace_bytes(wide, B.LSRM_WS_BACKWARD) == 0
+    assert B.lsrm_workspace_bytes(wide, B.LSRM_WS_BACKWARD) > 0
     rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(wide), *([None] * 14), 0, None, None, None)
-    assert rc == B.LSRM_ERR_UNSUPPORTED
+    assert rc == B.LSRM_ERR_INVALID_ARG
     rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(ok), *([None] * 14), 0, None, None, None)
     assert rc == B.LSRM_ERR_INVALID_ARG
     # four-rule routing: budgets must fit the row width; the budget struct is required
@@ -59,14 +59,12 @@ def test_host_side_argument_checks():
     assert call(__import__("ctypes").byref(ok), None, *([None] * 6), 0, None) == B.LSRM_ERR_INVALID_ARG
     assert call(__import__("ctypes").byref(ok), __import__("ctypes").byref(r_ok), *([None] * 6), 0, None) \
         == B.LSRM_ERR_INVALID_ARG          # null output table
-    # grouped-query heads and per-channel gates: forward only
+    # grouped-query heads and per-channel gates: forward and backward
     gqa = B.make_params(512, 2, 16, 4, 64, 3, 128, h_kv=2)
     chan = B.make_params(512, 2, 16, 2, 64, 3, 128, gate_channels=True)
     for p in (gqa, chan):
         assert B.lsrm_workspace_bytes(p, B.LSRM_WS_FORWARD) > 0
-        assert B.lsrm_workspace_bytes(p, B.LSRM_WS_BACKWARD) == 0
-        rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(p), *([None] * 14), 0, None, None, None)
-        assert rc == B.LSRM_ERR_UNSUPPORTED
+        assert B.lsrm_workspace_bytes(p, B.LSRM_WS_BACKWARD) > 0
     # fewer key/value heads need less room for the packed tiles
     assert B.lsrm_workspace_bytes(gqa, B.LSRM_WS_FORWARD) < B.lsrm_workspace_bytes(
         B.make_params(512, 2, 16, 4, 64, 3, 128), B.LSRM_WS_FORWARD)

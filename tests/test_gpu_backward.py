@@ -1,4 +1,4 @@
-"""GPU parity of lsrm_nsa_backward (d = 64) against the CPU oracle's analytic gradients, element by
+"""GPU parity of lsrm_nsa_backward against the CPU oracle's analytic gradients, element by
 element on small cases and on a sample of blocks and heads at the full size of config 5.
 Tolerance as for the forward: max-abs <= 2e-2 and relative L2 <= 5e-3 per gradient tensor."""
 import sys
@@ -74,6 +74,24 @@ def test_backward_own_block_window(B, oracle_lib):
     idx[rng.random(idx.shape) < 0.2] = -1
     got, args = _case(B, oracle_lib, cfg, idx=idx, window_mode=1)
     _assert_grads(got, oracle_lib.nsa_backward(*args, window_mode=1), cfg.name)
+
+
+@pytest.mark.parametrize("d,heads,h_kv,gate_channels", [(64, 6, 2, False), (64, 2, 2, True), (64, 4, 1, True),
+                                                        (32, 2, 2, False), (128, 2, 2, False), (128, 4, 2, True),
+                                                        # the paper's heads in small: 16 query heads per key/value head
+                                                        (32, 32, 2, True)])
+def test_backward_head_shapes_and_gates(B, oracle_lib, d, heads, h_kv, gate_channels):
+    """Head dimensions 32 / 64 / 128, query heads sharing key/value heads (a key/value head collects the
+    gradients of its whole group), one gate per output channel; ragged block count, holes in the table."""
+    cfg = I.small_config(name=f"b-d{d}-h{heads}-kv{h_kv}-ch{int(gate_channels)}", n_obj=576, n_views=2, grid=16,
+                         heads=heads, d=d, topk=4, window=160, seed=51, h_kv=h_kv, gate_channels=gate_channels)
+    _log(f"[backward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(11)
+    idx = np.stack([rng.choice(cfg.nb, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.2] = -1
+    got, args = _case(B, oracle_lib, cfg, idx=idx)
+    assert got[1].shape == (cfg.n, h_kv, d)
+    _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
 
 
 def test_backward_zero_window_and_topk_one(B, oracle_lib):
