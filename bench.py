@@ -96,7 +96,7 @@ def cpu_baseline_backward(cfg, arrays, idx, dout_bits, target_seconds=20.0):
     }
 
 
-def run_backward_bench(args, cfg, B, I, p, dev, tensors, workspaces, host):
+def run_backward_bench(args, cfg, B, I, p, dev, tensors, workspaces, host, route):
     import torch
     d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_pos, d_cams = tensors
     ws_route, ws_fwd = workspaces
@@ -105,10 +105,10 @@ def run_backward_bench(args, cfg, B, I, p, dev, tensors, workspaces, host):
     d_dout = torch.from_numpy(dout_bits.view(np.int16)).to(dev).view(torch.bfloat16)
     d_lse = torch.empty((3, cfg.n, cfg.heads), dtype=torch.float32, device=dev)
     d_ob = torch.empty((3, cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
-    d_dq, d_dk, d_dv = (torch.empty_like(d_q) for _ in range(3))
+    d_dq, d_dk, d_dv = torch.empty_like(d_q), torch.empty_like(d_k), torch.empty_like(d_k)
     ws_bwd = B.alloc_workspace(p, B.LSRM_WS_BACKWARD)
     # forward results the backward consumes (not timed)
-    B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route)
+    route()
     B.lsrm_nsa_compress(p, d_k, d_v, d_kc, d_vc)
     B.lsrm_nsa_forward(p, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_lse, d_ob, ws_fwd)
     torch.cuda.synchronize()
@@ -142,9 +142,11 @@ def run_backward_bench(args, cfg, B, I, p, dev, tensors, workspaces, host):
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {
-            "workload": f"config 5 ({cfg.name}): {cfg.n_obj} object + {cfg.n_views}x{cfg.grid}x{cfg.grid} image tokens = "
-                        f"{cfg.n}, {cfg.heads} heads, d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}; "
-                        f"gradients of q, k, v",
+            "workload": f"config {args.config} ({cfg.name}): {cfg.n_obj} object + {cfg.n_views}x{cfg.grid}x{cfg.grid} "
+                        f"image tokens = {cfg.n}, {cfg.heads} heads"
+                        + (f" on {cfg.kv_heads} key/value heads" if cfg.kv_heads != cfg.heads else "")
+                        + f", d {cfg.d}, block 64, top-k {cfg.topk}, window {cfg.window}"
+                        + (", per-channel gates" if cfg.gate_channels else "") + "; gradients of q, k, v",
             "effective_flops": flops,
             "pct_of_bf16_mfma_peak": round(100.0 * value / BF16_MFMA_PEAK_TFLOPS, 2),
         },
@@ -156,7 +158,7 @@ def run_backward_bench(args, cfg, B, I, p, dev, tensors, workspaces, host):
             "frac": round(call_tflops / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
         },
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and cfg.kv_heads == cfg.heads and not cfg.gate_channels:
         result["cpu_baseline"] = cpu_baseline_backward(cfg, {"qkv_bits": (q_bits, k_bits, v_bits), "gates": gates}, idx,
                                                        dout_bits)
     print(json.dumps(result), flush=True)
@@ -172,6 +174,9 @@ def main():
                          "6 forward with the paper's head shape (32 x 32 on 2 key/value heads, channel gates, "
                          "four-rule routing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="time lsrm_nsa_backward on the chosen config's shapes instead of the forward step (config 5 "
+                         "always does)")
     ap.add_argument("--topk", type=int, default=None, help="override the config's routed top-k (experiments)")
     ap.add_argument("--window", type=int, default=None, help="override the config's window (experiments)")
     ap.add_argument("--routing", choices=("projected", "four-rule"), default="projected",
@@ -231,12 +236,9 @@ def main():
         else:
             B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route)
 
-    if args.config == 5:
-        if four_rule:
-            print("bench.py: --routing four-rule is wired for the forward configs only", file=sys.stderr)
-            sys.exit(2)
+    if args.config == 5 or args.backward:
         run_backward_bench(args, cfg, B, I, p, dev, (d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_pos, d_cams),
-                           (ws_route, ws_fwd), (q_bits, k_bits, v_bits, gates))
+                           (ws_route, ws_fwd), (q_bits, k_bits, v_bits, gates), route)
         return
 
     n_ev = args.steps

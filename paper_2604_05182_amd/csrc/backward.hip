@@ -523,11 +523,12 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
         return 2 * (int64_t)__builtin_amdgcn_readlane(rev_held, e & 63) + (u & 1);
     };
     auto branch_of = [&](int t) { return MODE == 1 ? 0 : (t < tw ? 2 : 1); };
-    // step u of the walk: query tile u / group of query head head * group + u % group
+    // the walk: for every query tile t, the query heads gh of this key/value head's group in turn
+    // (counters instead of a division per step)
     const int grp = a.group;
     const int U = T * grp;
-    auto issue = [&](int u, char *buf) {
-        const int t = u / grp, qh = head * grp + u % grp;
+    auto issue = [&](int t, int gh, char *buf) {
+        const int qh = head * grp + gh;
         const int64_t tile = tile_of(t);
         const int64_t off = (tile * a.h + qh) * G::IMG;
         const int br = branch_of(t);
@@ -540,15 +541,27 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
         }
     };
 
-    if (U > 0) issue(0, lds);
-    for (int u = 0; u < U; ++u) {
-        const int t = u / grp;
+    int t = 0, gh = 0, t_nxt = 0, gh_nxt = 0;  // the step being computed, the step being copied
+    auto advance = [&](int &tt, int &gg) {
+        if (++gg == grp) {
+            gg = 0;
+            ++tt;
+        }
+    };
+    if (U > 0) {
+        issue(0, 0, lds);
+        advance(t_nxt, gh_nxt);
+    }
+    for (int u = 0; u < U; ++u, advance(t, gh)) {
         // The barrier alone does not wait for copies in flight (they are counted by vmcnt, which a
         // workgroup-scope fence leaves alone): every wavefront first waits for its own share of tile t,
         // issued one iteration ago, then the barrier publishes all shares.
         __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         __syncthreads();
-        if (u + 1 < U) issue(u + 1, lds + ((u + 1) & 1) * TILE);
+        if (u + 1 < U) {
+            issue(t_nxt, gh_nxt, lds + ((u + 1) & 1) * TILE);
+            advance(t_nxt, gh_nxt);
+        }
         const char *buf = lds + (u & 1) * TILE;
         const char *base = buf + lane16;
         const int q0 = 32 * (int)tile_of(t);

@@ -268,40 +268,58 @@ __device__ __forceinline__ float lane_max(const f32x16 &s) {
     return mx;
 }
 
-// Folds the maximum of a new score tile into the running maximum of row tile qt.
-//
-// The running maximum m is allowed to lag: it is raised (and O, l rescaled) only when a
-// new score exceeds it by more than kLag in the log2 domain, so probabilities stay
-// below 2^kLag -- harmless in fp32 and bf16, whose exponent ranges are the same -- and
-// the rescale of the O accumulators becomes a rare, wave-uniform branch.  m starts at
-// kMinusHuge (finite), so the first real score always raises it and no inf - inf ever
-// appears; a fully masked tile (maximum -inf) never does.
-constexpr float kLag = 8.0f;
+// The running maximum m of a row is kept optimistically: the exponentials of a tile are taken
+// against the current m without looking at the tile's own maximum first, and only their row sum
+// (which the softmax needs anyway) is examined afterwards.  If it exceeds kSumLimit -- some
+// probability would be above 2^10, or infinite: m starts at kMinusHuge, so the first real tile of
+// a branch always lands here -- the tile is redone: m is raised to the tile's maximum, O and l are
+// rescaled, the probabilities recomputed.  Otherwise every probability is at most 2^10, harmless in
+// fp32 and in bf16 (same exponent range), and the step has spent nothing on the maximum: no
+// in-lane reduction, no exchange between lane halves, no wait for the score MFMAs to retire.
+// A fully masked tile gives zeros and never redoes; a row whose keys are all masked so far keeps
+// m = kMinusHuge.
+constexpr float kSumLimit = 1024.0f;
 
-// `pending` (nullable) are probabilities that were computed against the old maximum but not
-// yet accumulated into O (the software pipeline keeps one tile of them): they are rescaled
-// together with O and l.
+// Wave-uniform: does any lane need its tile redone?  (written so that a NaN would also say yes)
+__device__ __forceinline__ bool sum_overflow(float psum) {
+    return __builtin_amdgcn_ballot_w64(!(psum <= kSumLimit)) != 0;
+}
+
+// Redoes the exponentials of one tile (scores s, already masked) of row tile qt after raising m to
+// the tile's maximum; O and l (which do not yet contain this tile) are rescaled.  Rare path.
 template <class G>
-__device__ __forceinline__ void update_max(WaveCtx<G> &c, int qt, float mx_lane, float sl2, uint32_t *pending) {
-    const float mx = half_max(mx_lane);
-    const bool raise = (mx - c.m[qt]) * sl2 > kLag;
-    if (__builtin_expect(__builtin_amdgcn_ballot_w64(raise) != 0, 0)) {
-        mfma_settle();  // the O accumulators may still be in flight
-        float m_new = raise ? mx : c.m[qt];
-        float alpha = raise ? __builtin_amdgcn_exp2f((c.m[qt] - m_new) * sl2) : 1.0f;
-        c.m[qt] = m_new;
-        c.l[qt] *= alpha;
+__device__ __forceinline__ void redo_tile(WaveCtx<G> &c, int qt, const f32x16 &s, uint32_t (&pu)[8], float &psum,
+                                          float sl2) {
+    mfma_settle();  // the O accumulators (and, at the start of a phase, s itself) may still be in flight
+    const float mx = half_max(lane_max(s));
+    const float m_new = fmaxf(c.m[qt], mx);
+    const float alpha = __builtin_amdgcn_exp2f((c.m[qt] - m_new) * sl2);
+    c.m[qt] = m_new;
+    c.l[qt] *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < G::ND; ++dt)
+    for (int dt = 0; dt < G::ND; ++dt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) c.o[qt][dt][i] *= alpha;
-        if (pending != nullptr) {
+        for (int i = 0; i < 16; ++i) c.o[qt][dt][i] *= alpha;
+    const float mc = m_new * sl2;
+    float p[16];
+    psum = 0.f;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                float lo = __uint_as_float(pending[k] << 16), hi = __uint_as_float(pending[k] & 0xffff0000u);
-                pending[k] = pack_bf16(lo * alpha, hi * alpha);
-            }
-        }
+    for (int e = 0; e < 16; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(s[e] * sl2 - mc);
+        psum += p[e];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) pu[k] = pack_bf16(p[2 * k], p[2 * k + 1]);
+}
+
+// After the exponentials of a tile: redo where needed, then add the row sums to l.
+template <class G>
+__device__ __forceinline__ void close_tile(WaveCtx<G> &c, const f32x16 (&s)[G::QT], uint32_t (&pu)[G::QT][8],
+                                           float (&psum)[G::QT], float sl2) {
+#pragma unroll
+    for (int qt = 0; qt < G::QT; ++qt) {
+        if (__builtin_expect(sum_overflow(psum[qt]), 0)) redo_tile<G>(c, qt, s[qt], pu[qt], psum[qt], sl2);
+        c.l[qt] += psum[qt];
     }
 }
 
@@ -319,6 +337,7 @@ union BFrag {
 // work only overlap when they alternate in program order: the QK and PV MFMAs are issued
 // alternately and every MFMA is followed by its share of the exponentials (one v_exp, its
 // fma and sum, half a bf16 pack at d = 128) -- about as many VALU cycles as the MFMA takes.
+// The row sums of the tile come back in psum (not yet added to l: see close_tile).
 // The empty asm statements pin each result to its place in the program (the compiler
 // otherwise sinks the arithmetic to its first use) and the scheduling barriers keep the
 // machine scheduler from regrouping; neither emits an instruction.
@@ -332,13 +351,13 @@ union BFrag {
 template <class G, bool QK, bool PV>
 __device__ __forceinline__ void mfma_block(WaveCtx<G> &c, const f32x16 (&s)[G::QT], bf16x8 (&kq)[G::KQ],
                                            f32x16 (&s_next)[G::QT], bf16x8 (&vq)[G::VQ],
-                                           const uint32_t (&pu_prev)[G::QT][8], uint32_t (&pu)[G::QT][8], float sl2,
-                                           const char *k_cur, const char *k_nxt, const char *v_cur,
-                                           const char *v_nxt) {
+                                           const uint32_t (&pu_prev)[G::QT][8], uint32_t (&pu)[G::QT][8],
+                                           float (&psum)[G::QT], float sl2, const char *k_cur, const char *k_nxt,
+                                           const char *v_cur, const char *v_nxt) {
     constexpr int QT = G::QT;
     constexpr int NQ = QK ? G::NS * QT : 0, NPV = PV ? 2 * G::ND * QT : 0, NG = NQ + NPV;
     constexpr int NE = 16 * QT;
-    float mc[QT], psum[QT], p[NE];
+    float mc[QT], p[NE];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         mc[qt] = c.m[qt] * sl2;
@@ -410,8 +429,6 @@ __device__ __forceinline__ void mfma_block(WaveCtx<G> &c, const f32x16 (&s)[G::Q
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) c.l[qt] += psum[qt];
 }
 
 // O^T += V^T P^T of the last tile (pipeline drain): the queue holds its first fragments.
@@ -440,8 +457,8 @@ __device__ __forceinline__ void pv_drain(WaveCtx<G> &c, bf16x8 (&vq)[G::VQ], con
 // First half: the QK^T MFMAs of the next tile (fragments kf) with the exponentials of the
 // current tile (scores s, already folded into the running maximum) in their shadow.
 template <class G, bool QK>
-__device__ __forceinline__ void own_qk_exp(WaveCtx<G> &c, const f32x16 &s, const bf16x8 (&kf)[G::NS], f32x16 &s_next,
-                                           uint32_t (&pu)[8], float sl2) {
+__device__ __forceinline__ float own_qk_exp(WaveCtx<G> &c, const f32x16 &s, const bf16x8 (&kf)[G::NS], f32x16 &s_next,
+                                            uint32_t (&pu)[8], float sl2) {
     static_assert(G::QT == 1, "");
     const float mc = c.m[0] * sl2;
     float psum = 0.f, p[16];
@@ -477,34 +494,24 @@ __device__ __forceinline__ void own_qk_exp(WaveCtx<G> &c, const f32x16 &s, const
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    c.l[0] += psum;
+    return psum;  // row sums of the tile, not yet added to l (see close_tile)
 }
 
-// Second half: the PV MFMAs of the current tile with the in-lane maximum of the next tile's
-// scores in their shadow (returned; folding it into the running maximum branches, so it
-// follows the MFMAs).
-template <class G, bool MAX>
-__device__ __forceinline__ float own_pv_max(WaveCtx<G> &c, const bf16x8 (&vf)[G::ND][2], const uint32_t (&pu)[8],
-                                            const f32x16 &s_next) {
-    constexpr int NG = 2 * G::ND, E = 16 / NG;
+// Second half: the PV MFMAs of the current tile.
+template <class G>
+__device__ __forceinline__ void own_pv(WaveCtx<G> &c, const bf16x8 (&vf)[G::ND][2], const uint32_t (&pu)[8]) {
+    constexpr int NG = 2 * G::ND;
     BFrag pb[2];
 #pragma unroll
     for (int k = 0; k < 8; ++k) pb[k / 4].u[k % 4] = pu[k];
-    float mx = -__builtin_inff();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         const int ks = g / G::ND, dt = g % G::ND;
         c.o[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pb[ks].v, c.o[0][dt], 0, 0, 0);
         asm volatile("" : "+v"(c.o[0][dt]));
-        if constexpr (MAX) {
-#pragma unroll
-            for (int e = g * E; e < (g + 1) * E; e += 2) mx = fmaxf(mx, fmaxf(s_next[e], s_next[e + 1]));
-            asm volatile("" : "+v"(mx));
-        }
         __builtin_amdgcn_sched_barrier(0);
     }
-    return mx;
 }
 
 // Shared phase (compressed and window branches): every tile is used by all query blocks of
@@ -516,8 +523,8 @@ __device__ __forceinline__ float own_pv_max(WaveCtx<G> &c, const bf16x8 (&vf)[G:
 // Step t runs mfma_block with QK of tile t+1, the exponentials of tile t and PV of tile t-1,
 // reloading its operand registers on the fly with the K fragments of tile t+2 and the V
 // fragments of tile t.  Once per step (one barrier) the slot of tile t-2 is refilled with
-// tile t-2+NSLOT, and after the block the maximum of tile t+1 is folded into the running
-// maximum.  Every wavefront runs every step: a tile outside a wavefront's own key range is
+// tile t-2+NSLOT, and after the block the row sums of tile t decide whether it must be redone
+// against a higher running maximum (close_tile).  Every wavefront runs every step: a tile outside a wavefront's own key range is
 // simply fully masked (the step body is kept unconditional on purpose -- a conditional
 // update of the accumulator tuples makes the compiler shuffle them through copies).
 // Scores and probabilities alternate between two register sets (index = tile parity), so
@@ -559,12 +566,12 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
 #pragma unroll
     for (int f = 0; f < G::VQ; ++f) vq[f] = *reinterpret_cast<const bf16x8 *>(lslot(0) + G::K_BYTES + f * 1024);
     msk(0, &j0, &need_mask, &cap);
-    mfma_settle();  // a branch follows the MFMAs that produced the scores
+    if (need_mask) {
+        mfma_settle();  // the mask reads the scores the MFMAs above produce
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        if (need_mask) mask_scores(c.lo[qt], min(c.hi[qt], cap), S[0][qt], j0, lane);
-        update_max<G>(c, qt, lane_max(S[0][qt]), sl2, nullptr);
+        for (int qt = 0; qt < QT; ++qt) mask_scores(c.lo[qt], min(c.hi[qt], cap), S[0][qt], j0, lane);
     }
+    float psum[QT];
 
     // One workgroup barrier per step keeps the ring consistent.  Before barrier t a wavefront has
     // finished (at least) MFMA block t-1 and waited for its own copies of tiles <= t+3; after it,
@@ -583,16 +590,16 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
         wg_barrier();
         if (t >= 2 && t - 2 + R < n_steps) issue_shared<G>(c, src(t - 2 + R), slot(t - 2), wave);
     };
-    // After an MFMA block: fold the maximum of the scores just produced (s_next) into the running
-    // maximum; pu are the probabilities still to be accumulated.
-    auto post = [&](int t, f32x16 (&s_next)[QT], uint32_t (&pu)[QT][8]) {
+    // After an MFMA block: mask the scores just produced (s_next, tile t+1) where the tile needs it,
+    // and close tile t (scores s, probabilities pu: redone if their row sums say so).
+    auto post = [&](int t, const f32x16 (&s)[QT], f32x16 (&s_next)[QT], uint32_t (&pu)[QT][8]) {
         msk(t + 1, &j0, &need_mask, &cap);
-        mfma_settle();  // s_next and O come from the MFMAs just issued; branches follow
+        if (__builtin_expect(need_mask, 0)) {
+            mfma_settle();  // s_next comes from the MFMAs just issued
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            if (__builtin_expect(need_mask, 0)) mask_scores(c.lo[qt], min(c.hi[qt], cap), s_next[qt], j0, lane);
-            update_max<G>(c, qt, lane_max(s_next[qt]), sl2, pu[qt]);
+            for (int qt = 0; qt < QT; ++qt) mask_scores(c.lo[qt], min(c.hi[qt], cap), s_next[qt], j0, lane);
         }
+        close_tile<G>(c, s, pu, psum, sl2);
     };
     // Scores and probabilities of tile t live in S[A], P[A]: with PAR, A is the parity of t and
     // nothing is copied from step to step; without, A = 0 and the sets are copied after a step.
@@ -613,11 +620,7 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
         wg_barrier();
         issue_shared<G>(c, src(t - 2 + R), slot(t - 2), wave);
     };
-    auto post_fast = [&](f32x16 (&s_next)[QT], uint32_t (&pu)[QT][8]) {
-        mfma_settle();
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) update_max<G>(c, qt, lane_max(s_next[qt]), sl2, pu[qt]);
-    };
+    auto post_fast = [&](const f32x16 (&s)[QT], uint32_t (&pu)[QT][8]) { close_tile<G>(c, s, pu, psum, sl2); };
     // QK(t+1) || exp(t) || PV(t-1); the queues move on to K(t+2) and V(t)  (stale slots past the end: unused)
     auto full_step = [&](auto par, auto fast, int t) {
         constexpr int A = PAR ? decltype(par)::value : 0;
@@ -625,19 +628,20 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
         if (lag) {
             if constexpr (FAST) sync_fast(t); else sync(t);
         }
-        mfma_block<G, true, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], sl2, lslot(t + 1), lslot(t + 2),
+        mfma_block<G, true, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], psum, sl2, lslot(t + 1), lslot(t + 2),
                                   lslot(t - 1), lslot(t));
         if (!lag) {
             if constexpr (FAST) sync_fast(t); else sync(t);
         }
-        if constexpr (FAST) post_fast(S[A ^ 1], P[A]); else post(t, S[A ^ 1], P[A]);
+        if constexpr (FAST) post_fast(S[A], P[A]); else post(t, S[A], S[A ^ 1], P[A]);
         rotate();
     };
     // exp(n-1) || PV(n-2); then the drain: PV of the last tile
     auto last_step = [&](auto par, int t) {
         constexpr int A = PAR ? decltype(par)::value : 0;
-        mfma_block<G, false, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], sl2, nullptr, nullptr, lslot(t - 1),
-                                   lslot(t));
+        mfma_block<G, false, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], psum, sl2, nullptr, nullptr,
+                                   lslot(t - 1), lslot(t));
+        close_tile<G>(c, S[A], P[A], psum, sl2);
         pv_drain<G>(c, vq, P[A], lslot(t));
     };
     using Even = std::integral_constant<int, 0>;
@@ -663,9 +667,9 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
     if (n_steps >= 2) {
         // QK(1) || exp(0)
         if (lag) sync(0);
-        mfma_block<G, true, false>(c, S[0], kq, S[1], vq, P[1], P[0], sl2, lslot(1), lslot(2), nullptr, nullptr);
+        mfma_block<G, true, false>(c, S[0], kq, S[1], vq, P[1], P[0], psum, sl2, lslot(1), lslot(2), nullptr, nullptr);
         if (!lag) sync(0);
-        post(0, S[1], P[0]);
+        post(0, S[0], S[1], P[0]);
         rotate();
         // full steps 1 .. n-2; those in [t_lo, t_hi) take the unconditional path
         const int t_end = n_steps - 1;
@@ -680,7 +684,8 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
         else
             last_step(Even{}, t_end);
     } else {
-        mfma_block<G, false, false>(c, S[0], kq, S[1], vq, P[1], P[0], sl2, nullptr, nullptr, nullptr, nullptr);
+        mfma_block<G, false, false>(c, S[0], kq, S[1], vq, P[1], P[0], psum, sl2, nullptr, nullptr, nullptr, nullptr);
+        close_tile<G>(c, S[0], P[0], psum, sl2);
         pv_drain<G>(c, vq, P[0], lslot(0));
     }
 }
@@ -688,7 +693,7 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
 // Selected phase: each query block streams its own routed blocks in 32-key steps through its
 // two tile slots; its two wavefronts split the copies and meet at a workgroup barrier every step.
 // CNT: blocks may hold fewer than 64 active tokens; valid(t) is the number of active keys of tile t
-// (0..32) and the scores of the others are masked (the in-shadow maximum is then taken afterwards).
+// (0..32) and the scores of the others are masked.
 template <class G, bool CNT, typename SrcFn, typename ValidFn>
 __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src, ValidFn valid, char *lds,
                                         int qbi, int sub, int lane, float sl2) {
@@ -740,36 +745,43 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
         wg_barrier();  // K(0) has been fetched by both wavefronts of the query block
         if (n > 2) issue_k(2);
         if (n > 0) {
-            mfma_settle();
             if constexpr (CNT) {
                 const int vld = valid(0);
-                if (vld < 32) mask_scores(0, vld, s_cur, 0, lane);
+                if (vld < 32) {
+                    mfma_settle();
+                    mask_scores(0, vld, s_cur, 0, lane);
+                }
             }
-            update_max<G>(c, 0, lane_max(s_cur), sl2, nullptr);
             read_v<G>(c, stage(0), vf);
         }
+        // the two halves of a step with the tile closed in between: [QK(t+1) || exp(t)], redo tile t if its
+        // row sums say so, [PV(t)]
+        auto close_own = [&](float psum) {
+            if (__builtin_expect(sum_overflow(psum), 0)) redo_tile<G>(c, 0, s_cur, pu, psum, sl2);
+            c.l[0] += psum;
+        };
         if (n > 1) read_k<G>(c, stage(1), kf);
         for (int t = 0; t + 1 < n; ++t) {
-            own_qk_exp<G, true>(c, s_cur, kf, s_next, pu, sl2);
-            float mx = own_pv_max<G, !CNT>(c, vf, pu, s_next);
+            close_own(own_qk_exp<G, true>(c, s_cur, kf, s_next, pu, sl2));
+            own_pv<G>(c, vf, pu);
             __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));  // K(t+2) and V(t+1) have landed
             wg_barrier();
             if (t + 3 < n) issue_k(t + 3);
             if (t + 2 < n) issue_v(t + 2);
             if (t + 2 < n) read_k<G>(c, stage(t + 2), kf);
             read_v<G>(c, stage(t + 1), vf);
-            mfma_settle();
             if constexpr (CNT) {
                 const int vld = valid(t + 1);
-                if (vld < 32) mask_scores(0, vld, s_next, 0, lane);
-                mx = lane_max(s_next);
+                if (vld < 32) {
+                    mfma_settle();
+                    mask_scores(0, vld, s_next, 0, lane);
+                }
             }
-            update_max<G>(c, 0, mx, sl2, nullptr);
             s_cur = s_next;
         }
         if (n > 0) {
-            own_qk_exp<G, false>(c, s_cur, kf, s_next, pu, sl2);
-            own_pv_max<G, false>(c, vf, pu, s_next);
+            close_own(own_qk_exp<G, false>(c, s_cur, kf, s_next, pu, sl2));
+            own_pv<G>(c, vf, pu);
         }
         // barriers 0 .. n_steps - 2 in total; n - 1 of them are behind us
         for (int t = (n > 0 ? n - 1 : 0); t + 1 < n_steps; ++t) {
