@@ -264,6 +264,56 @@ def test_forward_is_deterministic(B, oracle_lib):
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_forward_maximum_topk(B, oracle_lib, d):
+    """The largest routing row the kernels take: 64 blocks per query block (every lane of the
+    list holder is used), some rows full, some with holes."""
+    cfg = I.small_config(name=f"f-topk64-d{d}", n_obj=4096, n_views=2, grid=16, heads=1, d=d, topk=64, window=64,
+                         seed=61)
+    _log(f"[forward] {cfg.name}")
+    rng = np.random.default_rng(12)
+    idx = np.stack([rng.choice(cfg.nb, size=64, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[1::3][rng.random(idx[1::3].shape) < 0.3] = -1
+    _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx), cfg.name)
+
+
+@pytest.mark.parametrize("n_obj,n_views", [(0, 3), (640, 0)])
+def test_one_modality_only(B, oracle_lib, n_obj, n_views):
+    """Sequences without object tokens, or without views: routing finds no candidates of the other
+    modality (rows of -1), the selected branch is empty everywhere, the other two carry the layer."""
+    cfg = I.small_config(name=f"f-obj{n_obj}-views{n_views}", n_obj=n_obj, n_views=n_views, grid=16, heads=2, d=64,
+                         topk=3, window=96, seed=62)
+    _log(f"[route+forward] {cfg.name}")
+    pos = I.make_points(cfg) if n_obj else np.zeros((0, 3), dtype=np.float32)
+    cams = I.make_cameras(cfg) if n_views else np.zeros((0, 16), dtype=np.float32)
+    ref_idx, _ = oracle_lib.route(pos, cams, cfg.grid, cfg.topk)
+    assert (ref_idx == -1).all()
+    import torch
+    p = G.params_for(B, cfg)
+    d_idx = torch.full((cfg.nb, cfg.topk), -7, dtype=torch.int32, device="cuda")
+    ws = B.alloc_workspace(p, B.LSRM_WS_ROUTE)
+    dummy = torch.zeros(64, dtype=torch.float32, device="cuda")
+    B.lsrm_route_blocks(p, torch.from_numpy(pos).cuda() if n_obj else dummy,
+                        torch.from_numpy(cams).cuda() if n_views else dummy, d_idx, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_idx.cpu().numpy(), ref_idx)
+    res, ref_out, ref_lse, ref_ob = _forward_case(B, oracle_lib, cfg, idx=ref_idx)
+    _assert_forward(res, ref_out, ref_lse, ref_ob, cfg.name)
+    assert np.all(res["ob"][1] == 0) and np.all(np.isneginf(res["lse"][1]))
+
+
+def test_empty_problem_is_a_no_op(B):
+    import torch
+    p = B.make_params(0, 0, 16, 2, 64, 3, 128)
+    t = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    f = torch.zeros(64, dtype=torch.float32, device="cuda")
+    i = torch.zeros(64, dtype=torch.int32, device="cuda")
+    B.lsrm_route_blocks(p, f, f, i, None, f)
+    B.lsrm_nsa_compress(p, t, t, t, t)
+    B.lsrm_nsa_forward(p, t, t, t, t, t, i, f, t, None, None, f)
+    torch.cuda.synchronize()
+
+
 # ----------------------------------------------------------------------------- error paths
 def test_error_codes(B):
     import torch
