@@ -107,6 +107,32 @@ __device__ __forceinline__ void copy_kb(const char *src, char *dst, int wave, ui
 constexpr int vm_lgkm_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// A-operand fragment of the TRANSPOSE of a tile, read out of the tile's row-order fragments in LDS with
+// the transposing LDS load of gfx950 (ds_read_b64_tr_b16): within each group of 16 lanes, lane j receives
+// as element e the 16-bit element j % 4 of what lane 4 e + j / 4 of the group addressed.  So a lane of the
+// group addresses the four channels 4 (s % 4) .. + 3 of tile row s / 4 (s its index in the group), and
+// lane j ends up with one channel of four consecutive rows -- four of the eight K-values of a fragment
+// whose rows are channels.  Fragment (ks2, dt): channel 32 dt + (lane & 31), tile rows 16 ks2 + 8 hh + 0..7.
+// `tr_lane_offset` is the per-lane part of the address inside the row-order fragments; the fragment adds
+// dt * 2048 + ks2 * 256 and the second half of the rows another 128 (rows are stored permuted).
+// This halves what a step copies into LDS: the transposed halves of the tile images stay in memory.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t tr_lane_offset(int lane) {
+    const int s = lane & 15, grp = lane >> 4;
+    const int c = s & 3, k_local = s >> 2, hh = grp >> 1;
+    return (uint32_t)((grp & 1) * 1024 + (c >> 1) * 512 + (4 * hh + k_local) * 16 + (c & 1) * 8);
+}
+__device__ __forceinline__ bf16x8 read_tr(const char *rows, uint32_t lane_off, int dt, int ks2) {
+    const char *p = rows + lane_off + dt * 2048 + ks2 * 256;
+    union {
+        s16x4 h[2];
+        bf16x8 v;
+    } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 128));
+    return u.v;
+}
+
 template <int D>
 struct BGeo {
     static constexpr int NS = D / 16, ND = D / 32;
@@ -275,10 +301,10 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     // (at d = 128 the 256-register budget of two workgroups per SIMD still holds: 64 accumulator registers)
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
-    constexpr int TILE = G::IMG + G::ROW;  // K rows | K^T | V rows
-    constexpr int NBUF = LSRM_BWD_NBUF;    // tile buffers: copies run NBUF - 1 tiles ahead
-    constexpr int IPW = (G::IMG / 1024 + G::ROW / 1024) / 2;  // copy instructions per wavefront and tile
-    static_assert((G::IMG / 1024) % 2 == 0 && (G::ROW / 1024) % 2 == 0, "");
+    constexpr int TILE = 2 * G::ROW;     // K rows | V rows (K^T is read out of the K rows, see read_tr)
+    constexpr int NBUF = LSRM_BWD_NBUF;  // tile buffers: copies run NBUF - 1 tiles ahead
+    constexpr int IPW = G::ROW / 1024;   // copy instructions per wavefront and tile
+    static_assert((G::ROW / 1024) % 2 == 0, "");
     static_assert(2 * 32 * G::OUT_ROW <= NBUF * TILE, "output staging fits in the tile buffers");
     __shared__ __attribute__((aligned(1024))) char lds[NBUF * TILE];
     // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous range of
@@ -293,6 +319,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     const int64_t row0 = (int64_t)qb * 64 + 32 * wave;
     const int half_w = a.window / 2;
     const int kvh = head / a.group;  // key/value head of this query head
+    const uint32_t tr_off = tr_lane_offset(lane);
 
     bf16x8 qf[NS], dof[NS];
     // the gradient rows of branch b: dout itself, or gate o dout with per-channel gates
@@ -368,8 +395,8 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
             vimg = a.img_v;
         }
         const int64_t off = (tile * a.h_kv + kvh) * G::IMG;
-        copy_kb<G::IMG / 1024>(kimg + off, buf, wave, lane16);
-        copy_kb<G::ROW / 1024>(vimg + off, buf + G::IMG, wave, lane16);
+        copy_kb<G::ROW / 1024>(kimg + off, buf, wave, lane16);
+        copy_kb<G::ROW / 1024>(vimg + off, buf + G::ROW, wave, lane16);
     };
 
     for (int t = 0; t < NBUF - 1 && t < T; ++t) issue(t, lds + t * TILE);
@@ -397,7 +424,8 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
                     : (br == 2 && (j0 < max(seg_lo, (int)row0 + 31 - half_w) || j0 + 32 > min(seg_hi, (int)row0 + half_w)));
         const float lb = br == 0 ? l2[0] : (br == 1 ? l2[1] : l2[2]);
         const float db = br == 0 ? dl[0] : (br == 1 ? dl[1] : dl[2]);
-        const char *base = lds + (t % NBUF) * TILE + lane16;
+        const char *tile_k = lds + (t % NBUF) * TILE;
+        const char *base = tile_k + lane16;
 
         f32x16 s, dp;
 #pragma unroll
@@ -408,7 +436,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
                                                         0, 0);
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks)
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::IMG + ks * 1024),
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024),
                                                          dof[ks], dp, 0, 0, 0);
         float ds[16];
         if (__builtin_expect(need_mask, 0)) {
@@ -429,8 +457,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
             for (int dt = 0; dt < ND; ++dt)
-                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + (ks2 * ND + dt) * 1024), dsb[ks2].v, acc[dt], 0, 0, 0);
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(tile_k, tr_off, dt, ks2), dsb[ks2].v, acc[dt], 0, 0, 0);
     }
     __syncthreads();  // the tile buffers become the output staging
     static_assert(NBUF >= 2 && NBUF <= 4, "");
@@ -450,8 +477,8 @@ template <int D, int MODE>
 __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArgs a) {
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
-    constexpr int AUX = 2 * G::IMG;         // Q rows | Q^T | dO rows | dO^T | table (64 floats)
-    constexpr int TILE = 2 * G::IMG + 1024;  // (table padded to keep the next buffer aligned)
+    constexpr int AUX = 2 * G::ROW;          // Q rows | dO rows | table (64 floats); Q^T and dO^T: see read_tr
+    constexpr int TILE = 2 * G::ROW + 1024;  // (table padded to keep the next buffer aligned)
     static_assert(2 * 32 * G::OUT_ROW <= 2 * TILE, "output staging fits in the tile buffers");
     extern __shared__ __attribute__((aligned(1024))) char lds[];  // 2 * TILE bytes
     const int n_kb = MODE == 0 ? a.nb : a.nbp / 64;
@@ -463,6 +490,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, hh = lane >> 5;
     const uint32_t lane16 = (uint32_t)lane * 16u;
+    const uint32_t tr_off = tr_lane_offset(lane);
     const int64_t key0 = (int64_t)kb * 64 + 32 * wave;  // token index (MODE 0) or pooled-key index (MODE 1)
     const int64_t key = key0 + r;
     const int64_t limit = MODE == 0 ? a.n : (int64_t)a.nb;
@@ -532,8 +560,8 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
         const int64_t tile = tile_of(t);
         const int64_t off = (tile * a.h + qh) * G::IMG;
         const int br = branch_of(t);
-        copy_kb<G::IMG / 1024>(a.img_q + off, buf, wave, lane16);
-        copy_kb<G::IMG / 1024>((br == 0 ? a.img_do[0] : (br == 1 ? a.img_do[1] : a.img_do[2])) + off, buf + G::IMG, wave,
+        copy_kb<G::ROW / 1024>(a.img_q + off, buf, wave, lane16);
+        copy_kb<G::ROW / 1024>((br == 0 ? a.img_do[0] : (br == 1 ? a.img_do[1] : a.img_do[2])) + off, buf + G::ROW, wave,
                                lane16);
         if (wave == 0) {
             const float *ax = a.aux + (((int64_t)br * a.nt + tile) * a.h + qh) * 64;
@@ -607,15 +635,14 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
         for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
             for (int dt = 0; dt < ND; ++dt)
-                accv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    *reinterpret_cast<const bf16x8 *>(base + G::IMG + G::ROW + (ks2 * ND + dt) * 1024), pb[ks2].v, accv[dt], 0,
-                    0, 0);
+                accv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(buf + G::ROW, tr_off, dt, ks2), pb[ks2].v,
+                                                                   accv[dt], 0, 0, 0);
         f32x16 dp;
 #pragma unroll
         for (int i = 0; i < 16; ++i) dp[i] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks)
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::IMG + ks * 1024),
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024),
                                                          vB[ks], dp, 0, 0, 0);
         float ds[16];
 #pragma unroll
@@ -626,8 +653,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
         for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
             for (int dt = 0; dt < ND; ++dt)
-                acck[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + (ks2 * ND + dt) * 1024), dsb[ks2].v, acck[dt], 0, 0, 0);
+                acck[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(buf, tr_off, dt, ks2), dsb[ks2].v, acck[dt], 0, 0, 0);
     }
 
     if (MODE == 1) {
@@ -726,7 +752,7 @@ template <int D>
 lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char *ws, hipStream_t st, hipEvent_t ev_start,
                               hipEvent_t ev_stop) {
     using G = BGeo<D>;
-    constexpr int DKV_LDS = 2 * (2 * G::IMG + 1024);
+    constexpr int DKV_LDS = 2 * (2 * G::ROW + 1024);
     static bool attr_set = false;
     if (!attr_set) {
         LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 0>),
