@@ -29,6 +29,9 @@
 #ifndef LSRM_BWD_NBUF
 #define LSRM_BWD_NBUF 2
 #endif
+#ifndef LSRM_BWD_DKV_NBUF
+#define LSRM_BWD_DKV_NBUF 2  // (3, copies two steps ahead with counted waits, was measured: no faster)
+#endif
 
 namespace lsrm {
 
@@ -479,8 +482,8 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int AUX = 2 * G::ROW;          // Q rows | dO rows | table (64 floats); Q^T and dO^T: see read_tr
     constexpr int TILE = 2 * G::ROW + 1024;  // (table padded to keep the next buffer aligned)
-    static_assert(2 * 32 * G::OUT_ROW <= 2 * TILE, "output staging fits in the tile buffers");
-    extern __shared__ __attribute__((aligned(1024))) char lds[];  // 2 * TILE bytes
+    static_assert(2 * 32 * G::OUT_ROW <= LSRM_BWD_DKV_NBUF * TILE, "output staging fits in the tile buffers");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];  // LSRM_BWD_DKV_NBUF * TILE bytes
     const int n_kb = MODE == 0 ? a.nb : a.nbp / 64;
     const int per_xcd = (n_kb + 7) / 8;
     const int kb = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), head = blockIdx.y;  // (see bwd_dq_kernel)
@@ -576,21 +579,34 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
             ++tt;
         }
     };
-    if (U > 0) {
-        issue(0, 0, lds);
+    // NB tile buffers: the copies run NB - 1 steps ahead of the arithmetic
+    constexpr int NB = LSRM_BWD_DKV_NBUF;
+    constexpr int IPW = G::ROW / 1024;  // copy instructions per wavefront and step (wavefront 0: one more, the table)
+    static_assert(NB == 2 || NB == 3, "");
+    for (int i = 0; i < NB - 1 && i < U; ++i) {
+        issue(t_nxt, gh_nxt, lds + i * TILE);
         advance(t_nxt, gh_nxt);
     }
-    for (int u = 0; u < U; ++u, advance(t, gh)) {
+    for (int u = 0, slot = 0; u < U; ++u, advance(t, gh), slot = slot + 1 == NB ? 0 : slot + 1) {
         // The barrier alone does not wait for copies in flight (they are counted by vmcnt, which a
-        // workgroup-scope fence leaves alone): every wavefront first waits for its own share of tile t,
-        // issued one iteration ago, then the barrier publishes all shares.
-        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        // workgroup-scope fence leaves alone): every wavefront first waits for its own share of the
+        // step's tile -- the copies of the next step may stay in flight -- then the barrier publishes
+        // all shares; it also tells that everyone is done with the buffer refilled next.
+        if (NB == 3 && u + 1 < U) {
+            if (wave == 0)
+                __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW + 1));
+            else
+                __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW));
+        } else {
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        }
         __syncthreads();
-        if (u + 1 < U) {
-            issue(t_nxt, gh_nxt, lds + ((u + 1) & 1) * TILE);
+        if (u + NB - 1 < U) {
+            const int fill = slot == 0 ? NB - 1 : slot - 1;  // the buffer of step u - 1 = that of step u + NB - 1
+            issue(t_nxt, gh_nxt, lds + fill * TILE);
             advance(t_nxt, gh_nxt);
         }
-        const char *buf = lds + (u & 1) * TILE;
+        const char *buf = lds + slot * TILE;
         const char *base = buf + lane16;
         const int q0 = 32 * (int)tile_of(t);
         // window tiles away from the band's edges (and all routed tiles) need no mask
@@ -752,7 +768,7 @@ template <int D>
 lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char *ws, hipStream_t st, hipEvent_t ev_start,
                               hipEvent_t ev_stop) {
     using G = BGeo<D>;
-    constexpr int DKV_LDS = 2 * (2 * G::ROW + 1024);
+    constexpr int DKV_LDS = LSRM_BWD_DKV_NBUF * (2 * G::ROW + 1024);
     static bool attr_set = false;
     if (!attr_set) {
         LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 0>),
