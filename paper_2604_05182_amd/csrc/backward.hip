@@ -18,8 +18,8 @@
 //                    of the window and of the reverse routing list (query blocks in ascending order)
 //                    -- accumulates dK^T and dV^T in registers, adds the pooled gradients / 64.
 // Every operand tile is a "tile image" (see forward.hip): MFMA A-operand fragments in row order
-// (rows permuted so that an accumulator is directly the B operand of the next contraction)
-// followed by fragments of the transposed tile.  The transposed S^T = K Q^T form of the forward is
+// (rows permuted so that an accumulator is directly the B operand of the next contraction); the
+// fragments of the transposed tile are read out of the same bytes in LDS (see read_tr).  The transposed S^T = K Q^T form of the forward is
 // used in the dQ pass (one query per lane: lse and D are per-lane scalars); the dK/dV pass uses
 // S = Q K^T (one key per lane; lse and D of the 32 queries of the tile come from a small
 // per-tile table copied to LDS with the tile).
@@ -120,10 +120,19 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 // dt * 2048 + ks2 * 256 and the second half of the rows another 128 (rows are stored permuted).
 // This halves what a step copies into LDS: the transposed halves of the tile images stay in memory.
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+// In the backward's tile images the 16-byte slot of (row position r, channel half h) inside a fragment is
+// h * 32 + (r ^ 4 h): without the xor the two channel halves that a group of 16 lanes addresses in one
+// transposing load lie 512 bytes apart, i.e. in the same banks (measured: half the LDS cycles of these
+// kernels were bank conflicts); with it the group's 16 addresses cover 32 distinct banks.
 __device__ __forceinline__ uint32_t tr_lane_offset(int lane) {
     const int s = lane & 15, grp = lane >> 4;
     const int c = s & 3, k_local = s >> 2, hh = grp >> 1;
-    return (uint32_t)((grp & 1) * 1024 + (c >> 1) * 512 + (4 * hh + k_local) * 16 + (c & 1) * 8);
+    return (uint32_t)((grp & 1) * 1024 + (c >> 1) * 512 + (4 * (hh ^ (c >> 1)) + k_local) * 16 + (c & 1) * 8);
+}
+// per-lane offset of this lane's 16 bytes inside a row-order fragment of such an image
+__device__ __forceinline__ uint32_t row_lane_offset(int lane) {
+    const int r = lane & 31, hh = lane >> 5;
+    return (uint32_t)((hh * 32 + (r ^ (hh << 2))) * 16);
 }
 __device__ __forceinline__ bf16x8 read_tr(const char *rows, uint32_t lane_off, int dt, int ks2) {
     const char *p = rows + lane_off + dt * 2048 + ks2 * 256;
@@ -141,7 +150,7 @@ struct BGeo {
     static constexpr int NS = D / 16, ND = D / 32;
     static constexpr int ROW = 32 * D * 2;  // row-order fragments of a tile
     static constexpr int TB = D * 64;       // fragments of the transposed tile
-    static constexpr int IMG = ROW + TB;
+    static constexpr int IMG = ROW;         // the backward's images hold the row-order fragments only
     static constexpr int OUT_ROW = 2 * D + 8;  // padded bf16 row of the output staging (bytes)
 };
 
@@ -322,7 +331,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     const int64_t row0 = (int64_t)qb * 64 + 32 * wave;
     const int half_w = a.window / 2;
     const int kvh = head / a.group;  // key/value head of this query head
-    const uint32_t tr_off = tr_lane_offset(lane);
+    const uint32_t tr_off = tr_lane_offset(lane), row_off = row_lane_offset(lane);
 
     bf16x8 qf[NS], dof[NS];
     // the gradient rows of branch b: dout itself, or gate o dout with per-channel gates
@@ -428,7 +437,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         const float lb = br == 0 ? l2[0] : (br == 1 ? l2[1] : l2[2]);
         const float db = br == 0 ? dl[0] : (br == 1 ? dl[1] : dl[2]);
         const char *tile_k = lds + (t % NBUF) * TILE;
-        const char *base = tile_k + lane16;
+        const char *base = tile_k + row_off;
 
         f32x16 s, dp;
 #pragma unroll
@@ -493,7 +502,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, hh = lane >> 5;
     const uint32_t lane16 = (uint32_t)lane * 16u;
-    const uint32_t tr_off = tr_lane_offset(lane);
+    const uint32_t tr_off = tr_lane_offset(lane), row_off = row_lane_offset(lane);
     const int64_t key0 = (int64_t)kb * 64 + 32 * wave;  // token index (MODE 0) or pooled-key index (MODE 1)
     const int64_t key = key0 + r;
     const int64_t limit = MODE == 0 ? a.n : (int64_t)a.nb;
@@ -607,7 +616,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
             advance(t_nxt, gh_nxt);
         }
         const char *buf = lds + slot * TILE;
-        const char *base = buf + lane16;
+        const char *base = buf + row_off;
         const int q0 = 32 * (int)tile_of(t);
         // window tiles away from the band's edges (and all routed tiles) need no mask
         const bool win = MODE == 0 && t < tw &&
@@ -722,7 +731,7 @@ struct WsLayout {
 
 WsLayout ws_layout(const Shape &s) {
     WsLayout w;
-    const size_t img = (size_t)s.d * 128;  // bytes of one (tile, head) image
+    const size_t img = (size_t)s.d * 64;  // bytes of one (tile, head) image: row-order fragments only
     const size_t nt = (size_t)s.nb * 2, ntc = (size_t)(s.nb + 31) / 32;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -782,19 +791,19 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     lsrm_status rc;
     hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)((s.n * s.h + 255) / 256)), dim3(256), 0, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
-    if ((rc = launch_pack_tiles(D, a.q, a.q, ws + w.img_q, s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.q, a.q, ws + w.img_q, s.n, s.h, a.nt, st, true)) != LSRM_OK) return rc;
     if (s.gate_channels) {
         for (int b = 0; b < 3; ++b) {
             const uint16_t *src = a.gdo + (size_t)b * s.n * s.h * D;
-            if ((rc = launch_pack_tiles(D, src, src, ws + w.img_do[b], s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+            if ((rc = launch_pack_tiles(D, src, src, ws + w.img_do[b], s.n, s.h, a.nt, st, true)) != LSRM_OK) return rc;
         }
     } else {
-        if ((rc = launch_pack_tiles(D, a.dout, a.dout, ws + w.img_do[0], s.n, s.h, a.nt, st)) != LSRM_OK) return rc;
+        if ((rc = launch_pack_tiles(D, a.dout, a.dout, ws + w.img_do[0], s.n, s.h, a.nt, st, true)) != LSRM_OK) return rc;
     }
-    if ((rc = launch_pack_tiles(D, a.k, a.k, ws + w.img_k, s.n, s.h_kv, a.nt, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.v, a.v, ws + w.img_v, s.n, s.h_kv, a.nt, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.kc, a.kc, ws + w.img_kc, (int64_t)s.nb, s.h_kv, ntc, st)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.vc, a.vc, ws + w.img_vc, (int64_t)s.nb, s.h_kv, ntc, st)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.k, a.k, ws + w.img_k, s.n, s.h_kv, a.nt, st, true)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.v, a.v, ws + w.img_v, s.n, s.h_kv, a.nt, st, true)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.kc, a.kc, ws + w.img_kc, (int64_t)s.nb, s.h_kv, ntc, st, true)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.vc, a.vc, ws + w.img_vc, (int64_t)s.nb, s.h_kv, ntc, st, true)) != LSRM_OK) return rc;
     // reverse routing lists
     hipLaunchKernelGGL(fill_zero, dim3((s.nb + 255) / 256), dim3(256), 0, st, a.rev_cnt, s.nb);
     LSRM_HIP_CHECK(hipGetLastError());

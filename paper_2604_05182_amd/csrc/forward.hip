@@ -1053,11 +1053,14 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
 // Rows at or beyond n_rows read as zero (their scores are masked in the attention kernel).
 // One workgroup per (64-row block, head) = two tiles.
 // count (nullable, one entry per 64-row block): rows of a block at or beyond its count read as zero too.
-template <int D>
+// ROWS_ONLY (the backward's images): only the row-order fragments of k are written, img[tile][head] is
+// K_BYTES long, and inside a fragment the 16-byte slot of (row position r, channel half hh) is
+// hh * 32 + (r ^ 4 hh) instead of hh * 32 + r (keeps the backward's transposing LDS loads off shared banks).
+template <int D, bool ROWS_ONLY>
 __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
                                                   char *__restrict__ img, int64_t n_rows, int h, int n_tiles,
                                                   const int32_t *__restrict__ count) {
-    constexpr int K_BYTES = 32 * D * 2, TILE = K_BYTES + D * 64;
+    constexpr int K_BYTES = 32 * D * 2, TILE = ROWS_ONLY ? K_BYTES : K_BYTES + D * 64;
     constexpr int CH = D / 8;  // 16-byte chunks per row
     __shared__ uint16_t vt[64][D + 2];
     const int64_t blk = blockIdx.x;
@@ -1071,14 +1074,16 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
         uint4 kval = make_uint4(0, 0, 0, 0), vval = make_uint4(0, 0, 0, 0);
         if (row < n_rows && t < n_act) {
             kval = *reinterpret_cast<const uint4 *>(k + (row * h + head) * D + cc * 8);
-            vval = *reinterpret_cast<const uint4 *>(v + (row * h + head) * D + cc * 8);
+            if (!ROWS_ONLY) vval = *reinterpret_cast<const uint4 *>(v + (row * h + head) * D + cc * 8);
         }
         const int64_t tile = blk * 2 + t / 32;
         if (tile < n_tiles) {
             const int tt = t % 32;
-            const int r = (tt & ~12) | ((tt & 4) << 1) | ((tt & 8) >> 1);
+            int r = (tt & ~12) | ((tt & 4) << 1) | ((tt & 8) >> 1);
+            if (ROWS_ONLY) r ^= (cc & 1) << 2;
             *reinterpret_cast<uint4 *>(img + (tile * h + head) * TILE + (cc * 32 + r) * 16) = kval;
         }
+        if (ROWS_ONLY) continue;
         uint32_t w[4] = {vval.x, vval.y, vval.z, vval.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -1086,6 +1091,7 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
             vt[t][cc * 8 + 2 * j + 1] = (uint16_t)(w[j] >> 16);
         }
     }
+    if (ROWS_ONLY) return;
     __syncthreads();
     // V^T: chunk e of a tile = fragment f = e / 64 (ks2 = f / ND, dt = f % ND), lane = e % 64
     // (hh = lane / 32, r = lane % 32): channel 32 dt + r, keys 16 ks2 + 8 hh + 0..7.
@@ -1130,10 +1136,10 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     constexpr int D = G::D, NP = G::NP;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     const int tiles_c = (s.nb + 31) / 32;
-    hipLaunchKernelGGL(pack_tiles<D>, dim3(s.nb, s.h_kv), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h_kv,
+    hipLaunchKernelGGL((pack_tiles<D, false>), dim3(s.nb, s.h_kv), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h_kv,
                        2 * s.nb, a.count);
     LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(pack_tiles<D>, dim3((s.nb + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
+    hipLaunchKernelGGL((pack_tiles<D, false>), dim3((s.nb + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
                        (int64_t)s.nb, s.h_kv, tiles_c, (const int32_t *)nullptr);
     LSRM_HIP_CHECK(hipGetLastError());
     a.kv = ws + w.kv;
@@ -1165,18 +1171,20 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
 size_t forward_ws_bytes(const Shape &s) { return ws_layout(s).total; }
 
 lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t_src, char *img, int64_t n_rows, int h,
-                              int n_tiles, hipStream_t st) {
+                              int n_tiles, hipStream_t st, bool rows_only) {
     if (n_tiles <= 0) return LSRM_OK;
     const dim3 grid((n_tiles + 1) / 2, h);
-    if (d == 32)
-        hipLaunchKernelGGL(pack_tiles<32>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles,
-                           (const int32_t *)nullptr);
-    else if (d == 64)
-        hipLaunchKernelGGL(pack_tiles<64>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles,
-                           (const int32_t *)nullptr);
-    else
-        hipLaunchKernelGGL(pack_tiles<128>, grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles,
-                           (const int32_t *)nullptr);
+    const int32_t *no_count = nullptr;
+#define LSRM_PACK(DD, RO) \
+    hipLaunchKernelGGL((pack_tiles<DD, RO>), grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles, no_count)
+    if (d == 32) {
+        if (rows_only) LSRM_PACK(32, true); else LSRM_PACK(32, false);
+    } else if (d == 64) {
+        if (rows_only) LSRM_PACK(64, true); else LSRM_PACK(64, false);
+    } else {
+        if (rows_only) LSRM_PACK(128, true); else LSRM_PACK(128, false);
+    }
+#undef LSRM_PACK
     LSRM_HIP_CHECK(hipGetLastError());
     return LSRM_OK;
 }
