@@ -217,21 +217,23 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
  * implementation details); the paper gives no backward algorithm.  Reading: analytic gradients
  * of the three softmax branches with the routing table and the gate weights held constant, and
  * the average pooling differentiated: dk[t] += dk_cmp[t / 64] / 64, likewise dv.]
- *   d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates   as passed to lsrm_nsa_forward (gates must be >= 0)
+ *   d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates   as passed to lsrm_nsa_forward (per-head gates must be >= 0)
  *   d_lse        [3, N, h_q] fp32          as written by lsrm_nsa_forward (required)
  *   d_out_branch [3, N, h_q, d] bf16       as written by lsrm_nsa_forward (required)
  *   d_dout       [N, h_q, d] bf16          gradient of the loss with respect to d_out
- *   d_dq, d_dk, d_dv [N, h, d] bf16        OUT
+ *   d_dq [N, h_q, d], d_dk, d_dv [N, h_kv, d] bf16   OUT (a key/value head collects the gradients of
+ *           every query head that reads it)
  *   ev_start, ev_stop  nullable hipEvent_t (as void*): recorded on `stream` before the first and
  *           after the last kernel of the call.
  * With P = softmax probabilities recomputed from d_lse, D_i = dout_i . out_branch_i and
  * dP = dout V^T:  dV = g P^T dout,  dS = g P (dP - D),  dQ = scale dS K,  dK = scale dS^T Q
- * per branch (g the branch's gate), bf16 MFMA contractions with fp32 accumulation, P and dS
- * rounded to bf16 as MFMA operands.  No atomics on floating-point data: every gradient element
+ * per branch (g the branch's gate; with per-channel gates g P is P and dout is replaced by the
+ * channel-wise product gate * dout, rounded to bf16), bf16 MFMA contractions with fp32 accumulation,
+ * P and dS rounded to bf16 as MFMA operands.  No atomics on floating-point data: every gradient element
  * is summed in a fixed order (dK/dV go through reverse lists of the routing table, sorted by
  * query block), so results are reproducible bit for bit.
- * Only d = 64 with h_kv = h_q, per-head gates and full blocks (d_block_count NULL) is supported
- * (LSRM_ERR_UNSUPPORTED otherwise); both window modes are.
+ * Every head dimension, head grouping, gate layout and window mode of the forward is supported;
+ * blocks must be full (d_block_count NULL, LSRM_ERR_UNSUPPORTED otherwise).
  */
 lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k,
                               const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,
