@@ -158,7 +158,7 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
     return res[0] if len(res) == 1 else tuple(res)
 
 
-def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0, window_mode=0):
+def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0, window_mode=0, block_count=None):
     """-> (dq fp32 [N, H, d], dk, dv fp32 [N, h_kv, d]); single-threaded definition, small inputs only.
     Shapes and gate layouts as in nsa_forward."""
     q, k, v, kc, vc, gates, dout = map(_f32, (q, k, v, kc, vc, gates, dout))
@@ -171,7 +171,8 @@ def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0
     dk, dv = np.empty_like(k), np.empty_like(k)
     _load().oracle_nsa_backward(
         ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(h_kv), ctypes.c_int(d), ctypes.c_int(topk),
-        ctypes.c_int(window), ctypes.c_int(window_mode), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1),
+        ctypes.c_int(window), ctypes.c_int(window_mode), _p(_counts(block_count, n // 64), ctypes.c_int32),
+        ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1),
         _p(seg, ctypes.c_int32), _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float),
         _p(kc, ctypes.c_float), _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
         ctypes.c_int(1 if gates.ndim == 4 else 0), _p(dout, ctypes.c_float), _p(dq, ctypes.c_float),

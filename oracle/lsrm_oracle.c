@@ -422,10 +422,13 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
  * double, single-threaded over queries (this is a definition, not a fast path).
  * With grouped-query heads (h_kv < h) a key/value head collects the gradients of all the
  * query heads that read it; with per-channel gates `gate * dout` is a product per channel.
+ * With per-block counts (oracle_nsa_backward only) the padding slots of a block are neither
+ * queries nor keys: their gradients are zero, and a pooled pair passes its gradient to the
+ * count[b] active tokens of its block, divided by count[b].
  * dq is fp32 [N, H, d]; dk, dv are fp32 [N, h_kv, d].
  */
-void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window, int window_mode, float scale,
-                         int n_seg, const int32_t *seg, const float *q, const float *k, const float *v,
+void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window, int window_mode,
+                         const int32_t *count, float scale, int n_seg, const int32_t *seg, const float *q, const float *k, const float *v,
                          const float *kc, const float *vc, const int32_t *idx, const float *gates,
                          int gate_channels, const float *dout, float *dq, float *dk, float *dv) {
     int64_t nb = n / BLK;
@@ -450,7 +453,8 @@ void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window
     double *gd = (double *)malloc(sizeof(double) * (size_t)d); /* gate times dout: the gradient reaching one branch */
     for (int64_t i = 0; i < n; ++i) {
         int nc, ns, nw;
-        key_sets(i, nb, topk, window, window_mode, NULL, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+        if (count && (i % BLK) >= count[i / BLK]) continue; /* padding slot: no query lives here */
+        key_sets(i, nb, topk, window, window_mode, count, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
         for (int hh = 0; hh < h; ++hh) {
             size_t kvo = (size_t)(hh / group) * d; /* this query head's key/value head */
             const float *qv = q + (size_t)i * stride + (size_t)hh * d;
@@ -489,11 +493,14 @@ void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window
             }
         }
     }
-    for (int64_t j = 0; j < n; ++j)
+    for (int64_t j = 0; j < n; ++j) {
+        int cnt = count ? count[j / BLK] : BLK;
+        if ((j % BLK) >= cnt) continue; /* the mean was taken over the active tokens only */
         for (size_t c = 0; c < stride_kv; ++c) {
-            gk[(size_t)j * stride_kv + c] += gkc[(size_t)(j / BLK) * stride_kv + c] / 64.0;
-            gv[(size_t)j * stride_kv + c] += gvc[(size_t)(j / BLK) * stride_kv + c] / 64.0;
+            gk[(size_t)j * stride_kv + c] += gkc[(size_t)(j / BLK) * stride_kv + c] / (double)cnt;
+            gv[(size_t)j * stride_kv + c] += gvc[(size_t)(j / BLK) * stride_kv + c] / (double)cnt;
         }
+    }
     for (size_t e = 0; e < total; ++e) dq[e] = (float)gq[e];
     for (size_t e = 0; e < total_kv; ++e) { dk[e] = (float)gk[e]; dv[e] = (float)gv[e]; }
     free(gq); free(gk); free(gv); free(gkc); free(gvc);

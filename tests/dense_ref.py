@@ -80,7 +80,7 @@ def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None, window_mode=
     return out, ob, lse
 
 
-def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None, window_mode=0):
+def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None, window_mode=0, block_count=None):
     """Library autograd (float64) through the dense-mask formulation -> dq, dk, dv."""
     import torch
     tq, tk0, tv0 = (torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True) for a in (q, k, v))
@@ -93,10 +93,18 @@ def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=
     else:
         g = g[..., None]
     scale = 1.0 / np.sqrt(d) if not scale else scale
-    sel, win = masks(n, idx, seg_offsets, window, window_mode)
+    sel, win = masks(n, idx, seg_offsets, window, window_mode, block_count)
     sel, win = torch.tensor(sel), torch.tensor(win)
-    kc = tk.reshape(n // 64, 64, h, d).mean(1)
-    vc = tv.reshape(n // 64, 64, h, d).mean(1)
+    if block_count is None:
+        kc = tk.reshape(n // 64, 64, h, d).mean(1)
+        vc = tv.reshape(n // 64, 64, h, d).mean(1)
+        active_q = torch.ones(n, dtype=torch.float64)
+    else:
+        cnt = torch.tensor(np.asarray(block_count), dtype=torch.float64)
+        act = (torch.arange(64)[None, :] < cnt[:, None]).to(torch.float64)          # [NB, 64]
+        kc = (tk.reshape(n // 64, 64, h, d) * act[:, :, None, None]).sum(1) / cnt[:, None, None]
+        vc = (tv.reshape(n // 64, 64, h, d) * act[:, :, None, None]).sum(1) / cnt[:, None, None]
+        active_q = act.reshape(-1)     # padding slots are not queries: their outputs carry no loss
 
     def att(qh, kh, vh, mask):
         s = (qh @ kh.T) * scale
@@ -118,5 +126,5 @@ def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=
              + g[:, hh, 2] * att(tq[:, hh], tk[:, hh], tv[:, hh], win))
         outs.append(o)
     out = torch.stack(outs, dim=1)
-    (out * torch.tensor(np.asarray(dout, dtype=np.float64))).sum().backward()
+    (out * torch.tensor(np.asarray(dout, dtype=np.float64)) * active_q[:, None, None]).sum().backward()
     return tq.grad.numpy(), tk0.grad.numpy(), tv0.grad.numpy()

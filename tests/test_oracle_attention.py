@@ -330,6 +330,27 @@ def test_backward_with_grouped_heads_and_channel_gates_matches_library_autograd(
         assert np.abs(a - b).max() < 1e-5 * max(1.0, np.abs(b).max())
 
 
+@pytest.mark.parametrize("window_mode", [0, 1])
+def test_backward_with_active_counts_matches_library_autograd(oracle_lib, window_mode):
+    """Padding slots are neither queries nor keys; a pooled pair spreads its gradient over the active
+    tokens of its block."""
+    cfg, q, k, v, gates, idx = _case(23, n_obj=192, n_views=1, grid=16, heads=2, d=8, topk=2, window=48)
+    cnt = np.array([64, 1, 33, 20, 64, 7, 40][:cfg.nb], dtype=np.int32)
+    assert cfg.nb == 7
+    seg = cfg.seg_offsets()
+    rng = np.random.default_rng(4)
+    dout = rng.standard_normal(q.shape).astype(np.float32)
+    kc, vc = oracle_lib.pool(k, cnt), oracle_lib.pool(v, cnt)
+    dq, dk, dv = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout, window_mode=window_mode,
+                                         block_count=cnt)
+    rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout, window_mode=window_mode,
+                                         block_count=cnt)
+    for a, b in ((dq, rq), (dk, rk), (dv, rv)):
+        assert np.abs(a - b).max() < 1e-5 * max(1.0, np.abs(b).max())
+    inactive = (np.arange(cfg.n) % 64) >= np.repeat(cnt, 64)
+    assert np.all(dq[inactive] == 0) and np.all(dk[inactive] == 0) and np.all(dv[inactive] == 0)
+
+
 def test_backward_finite_difference_of_dense_formulation():
     """Pins the autograd reference itself: central differences in float64."""
     cfg, q, k, v, gates, idx = _case(11, n_obj=64, grid=8, n_views=1, heads=1, d=4, topk=1, window=32)
