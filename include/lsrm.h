@@ -87,8 +87,8 @@ typedef struct lsrm_nsa_params {
                               number of active tokens); the other slots are padding: never a key
                               in any branch, excluded from the block average, and their own
                               output rows are unspecified.  NULL: every block is full.
-                              Read by lsrm_nsa_compress and lsrm_nsa_forward (pass the same
-                              counts to both); lsrm_nsa_backward does not support it yet.      */
+                              Read by lsrm_nsa_compress, lsrm_nsa_forward and lsrm_nsa_backward
+                              (pass the same counts to all three).                            */
 } lsrm_nsa_params;
 
 enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2, LSRM_WS_ROUTE_3D = 3 };
@@ -232,8 +232,9 @@ lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, cons
  * P and dS rounded to bf16 as MFMA operands.  No atomics on floating-point data: every gradient element
  * is summed in a fixed order (dK/dV go through reverse lists of the routing table, sorted by
  * query block), so results are reproducible bit for bit.
- * Every head dimension, head grouping, gate layout and window mode of the forward is supported;
- * blocks must be full (d_block_count NULL, LSRM_ERR_UNSUPPORTED otherwise).
+ * Every head dimension, head grouping, gate layout, window mode and block-count setting of the
+ * forward is supported.  With d_block_count, padding slots are neither queries nor keys: their rows
+ * of d_dout (and of d_k, d_v) are never looked at, and their rows of d_dq, d_dk, d_dv are zero.
  */
 lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k,
                               const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,

@@ -86,7 +86,7 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call) {
     switch (which_call) {
         case LSRM_WS_ROUTE: return route_ws_bytes(s);
         case LSRM_WS_FORWARD: return forward_ws_bytes(s);
-        case LSRM_WS_BACKWARD: return s.count == nullptr ? backward_ws_bytes(s) : 0;
+        case LSRM_WS_BACKWARD: return backward_ws_bytes(s);
         case LSRM_WS_ROUTE_3D: return route3d_ws_bytes(s);
         default: return 0;
     }
@@ -169,7 +169,6 @@ lsrm_status lsrm_nsa_backward(const lsrm_nsa_params *p, const uint16_t *d_q, con
     Shape s;
     lsrm_status rc = make_shape(p, &s);
     if (rc != LSRM_OK) return rc;
-    if (s.count != nullptr) return LSRM_ERR_UNSUPPORTED;
     std::vector<int32_t> seg;
     rc = make_segments(p, s, &seg);
     if (rc != LSRM_OK) return rc;

@@ -67,6 +67,7 @@ struct BwdArgs {
     int own_block;  // window branch = the query's own block
     int h_kv, group;    // key/value heads; query heads per key/value head
     int gate_channels;  // gates are [N, 3, H, d]
+    const int32_t *count;  // nullable [NB]: active tokens per block; the other slots are neither queries nor keys
     int nt;               // query / key tiles of 32 tokens
     int n_split, nbp, tiles_per_split;
     float scale, sl2;
@@ -203,6 +204,8 @@ __global__ __launch_bounds__(256) void bwd_prep(BwdArgs a) {
     }
     const int64_t tile = row >> 5;
     const int pr = perm32((int)(row & 31));
+    // a padding slot is no query: zero probabilities (offset +inf) and a zero D in every branch
+    const bool padding = a.count != nullptr && (int)(row & 63) >= a.count[row >> 6];
 #pragma unroll
     for (int b = 0; b < 3; ++b) {
         const uint4 *obr = reinterpret_cast<const uint4 *>(a.out_branch + (((int64_t)b * a.n + row) * a.h + head) * D);
@@ -245,8 +248,8 @@ __global__ __launch_bounds__(256) void bwd_prep(BwdArgs a) {
             if (g > 0.f && lse > -__builtin_inff()) l2 = lse * kLog2e - __log2f(g);
         }
         float *ax = a.aux + (((int64_t)b * a.nt + tile) * a.h + head) * 64;
-        ax[pr] = l2;
-        ax[32 + pr] = dl;
+        ax[pr] = padding ? __builtin_inff() : l2;
+        ax[32 + pr] = padding ? 0.f : dl;
     }
 }
 
@@ -335,16 +338,19 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 
     bf16x8 qf[NS], dof[NS];
     // the gradient rows of branch b: dout itself, or gate o dout with per-channel gates
+    // (a padding slot reads as zeros: whatever the caller left there never reaches an MFMA)
+    const bool padding = a.count != nullptr && 32 * wave + r >= a.count[qb];
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     auto load_dof = [&](int b) {
         const uint16_t *src = a.gate_channels ? a.gdo + (int64_t)b * a.n * a.h * D : a.dout;
         const uint16_t *drow = src + ((row0 + r) * a.h + head) * D + 8 * hh;
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks) dof[ks] = *reinterpret_cast<const bf16x8 *>(drow + 16 * ks);
+        for (int ks = 0; ks < NS; ++ks) dof[ks] = padding ? zero8 : *reinterpret_cast<const bf16x8 *>(drow + 16 * ks);
     };
     {
         const uint16_t *qrow = a.q + ((row0 + r) * a.h + head) * D + 8 * hh;
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
+        for (int ks = 0; ks < NS; ++ks) qf[ks] = padding ? zero8 : *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
         load_dof(0);
     }
     float l2[3], dl[3];
@@ -372,6 +378,8 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         packed = __builtin_amdgcn_ds_permute((v >= 0 ? rank : 63) * 4, v);
         if (n_valid == 64) packed = v;
     }
+    // active tokens of the routed blocks, one per lane like the list itself
+    const int pcount = a.count != nullptr && lane < n_valid ? a.count[packed] : 64;
     const int ts = 2 * n_valid;
     int seg_lo = 0, seg_hi = 0;
     for (int s = 0; s < a.n_seg; ++s)
@@ -381,7 +389,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         }
     if (a.own_block) {  // window = the query's own block: the block is its own segment (a.window is 128)
         seg_lo = qb * 64;
-        seg_hi = qb * 64 + 64;
+        seg_hi = qb * 64 + 64;  // (padding slots at its end are masked per tile below)
     }
     const int k_start = max(seg_lo, qb * 64 - half_w), k_end = min(seg_hi, qb * 64 + 63 + half_w);
     const int st0 = k_start / 32;
@@ -429,11 +437,29 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         if (a.gate_channels && (t == tc || t == tc + ts)) load_dof(br);
         const int j0 = br == 0 ? 32 * t : (br == 1 ? 0 : 32 * (st0 + t - tc - ts));
         const int lo = br == 0 ? 0 : (br == 1 ? -0x40000000 : wlo);
-        const int hi = br == 0 ? a.nb : (br == 1 ? 0x7fffffff : whi);
+        int hi = br == 0 ? a.nb : (br == 1 ? 0x7fffffff : whi);
         // does any lane of this wavefront need the mask on this tile?  (pooled tail; window edges)
-        const bool need_mask =
+        bool need_mask =
             br == 0 ? (j0 + 32 > a.nb)
                     : (br == 2 && (j0 < max(seg_lo, (int)row0 + 31 - half_w) || j0 + 32 > min(seg_hi, (int)row0 + half_w)));
+        if (a.count != nullptr && br != 0) {
+            // padding slots at the end of the tile's block are no keys
+            int cnt, half;
+            if (br == 1) {
+                const int u = t - tc;
+                cnt = __builtin_amdgcn_readlane(pcount, u >> 1);
+                half = u & 1;
+            } else {
+                const int st = st0 + t - tc - ts;
+                cnt = a.count[st >> 1];
+                half = st & 1;
+            }
+            const int vld = min(32, max(0, cnt - 32 * half));
+            if (vld < 32) {
+                need_mask = true;
+                hi = min(hi, j0 + vld);
+            }
+        }
         const float lb = br == 0 ? l2[0] : (br == 1 ? l2[1] : l2[2]);
         const float db = br == 0 ? dl[0] : (br == 1 ? dl[1] : dl[2]);
         const char *tile_k = lds + (t % NBUF) * TILE;
@@ -507,6 +533,9 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
     const int64_t key = key0 + r;
     const int64_t limit = MODE == 0 ? a.n : (int64_t)a.nb;
     const int half_w = a.window / 2;
+    // MODE 0 with per-block counts: a padding slot is nobody's key (its probabilities are zeroed) and gets a zero gradient
+    const int n_act = MODE == 0 && a.count != nullptr ? a.count[kb] : 64;
+    const bool key_active = MODE == 1 || 32 * wave + r < n_act;
 
     bf16x8 kB[NS], vB[NS];
     {
@@ -517,6 +546,10 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
         for (int ks = 0; ks < NS; ++ks) {
             kB[ks] = *reinterpret_cast<const bf16x8 *>(krow + 16 * ks);
             vB[ks] = *reinterpret_cast<const bf16x8 *>(vrow + 16 * ks);
+            if (!key_active) {  // a padding slot reads as zeros, whatever the caller left there
+                const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+                kB[ks] = vB[ks] = zero8;
+            }
         }
     }
     f32x16 acck[ND], accv[ND];
@@ -647,6 +680,10 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
             float pi = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lv[i]);
             if (MODE == 1) {
                 pi = key < limit ? pi : 0.f;
+            } else if (n_act < 64) {
+                const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);
+                const int dj = (int)key - qi;
+                pi = key_active && (!win || (dj >= -half_w && dj < half_w)) ? pi : 0.f;
             } else if (win) {
                 const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);  // the query behind accumulator row i
                 const int dj = (int)key - qi;
@@ -712,8 +749,10 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    xk[dt][4 * g + j] = (acck[dt][4 * g + j] + pk[j] * (1.0f / 64.0f)) * a.scale;
-                    xv[dt][4 * g + j] = accv[dt][4 * g + j] + pv[j] * (1.0f / 64.0f);
+                    // the block average was taken over its n_act active tokens; a padding slot gets nothing
+                    const float inv_cnt = key_active ? 1.0f / (float)n_act : 0.f;
+                    xk[dt][4 * g + j] = (acck[dt][4 * g + j] + pk[j] * inv_cnt) * a.scale;
+                    xv[dt][4 * g + j] = accv[dt][4 * g + j] + pv[j] * inv_cnt;
                 }
             }
         __syncthreads();  // the tile buffers become the output staging
@@ -791,19 +830,19 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     lsrm_status rc;
     hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)((s.n * s.h + 255) / 256)), dim3(256), 0, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
-    if ((rc = launch_pack_tiles(D, a.q, a.q, ws + w.img_q, s.n, s.h, a.nt, st, true)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.q, a.q, ws + w.img_q, s.n, s.h, a.nt, st, true, a.count)) != LSRM_OK) return rc;
     if (s.gate_channels) {
         for (int b = 0; b < 3; ++b) {
             const uint16_t *src = a.gdo + (size_t)b * s.n * s.h * D;
-            if ((rc = launch_pack_tiles(D, src, src, ws + w.img_do[b], s.n, s.h, a.nt, st, true)) != LSRM_OK) return rc;
+            if ((rc = launch_pack_tiles(D, src, src, ws + w.img_do[b], s.n, s.h, a.nt, st, true, a.count)) != LSRM_OK) return rc;
         }
     } else {
-        if ((rc = launch_pack_tiles(D, a.dout, a.dout, ws + w.img_do[0], s.n, s.h, a.nt, st, true)) != LSRM_OK) return rc;
+        if ((rc = launch_pack_tiles(D, a.dout, a.dout, ws + w.img_do[0], s.n, s.h, a.nt, st, true, a.count)) != LSRM_OK) return rc;
     }
-    if ((rc = launch_pack_tiles(D, a.k, a.k, ws + w.img_k, s.n, s.h_kv, a.nt, st, true)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.v, a.v, ws + w.img_v, s.n, s.h_kv, a.nt, st, true)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.kc, a.kc, ws + w.img_kc, (int64_t)s.nb, s.h_kv, ntc, st, true)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.vc, a.vc, ws + w.img_vc, (int64_t)s.nb, s.h_kv, ntc, st, true)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.k, a.k, ws + w.img_k, s.n, s.h_kv, a.nt, st, true, a.count)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.v, a.v, ws + w.img_v, s.n, s.h_kv, a.nt, st, true, a.count)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.kc, a.kc, ws + w.img_kc, (int64_t)s.nb, s.h_kv, ntc, st, true, nullptr)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.vc, a.vc, ws + w.img_vc, (int64_t)s.nb, s.h_kv, ntc, st, true, nullptr)) != LSRM_OK) return rc;
     // reverse routing lists
     hipLaunchKernelGGL(fill_zero, dim3((s.nb + 255) / 256), dim3(256), 0, st, a.rev_cnt, s.nb);
     LSRM_HIP_CHECK(hipGetLastError());
@@ -878,6 +917,7 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     a.h_kv = s.h_kv;
     a.group = s.h / s.h_kv;
     a.gate_channels = s.gate_channels;
+    a.count = s.count;
     a.topk = s.topk;
     a.window = s.window;
     a.own_block = s.own_block;

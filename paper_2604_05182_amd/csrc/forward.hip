@@ -1171,12 +1171,11 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
 size_t forward_ws_bytes(const Shape &s) { return ws_layout(s).total; }
 
 lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t_src, char *img, int64_t n_rows, int h,
-                              int n_tiles, hipStream_t st, bool rows_only) {
+                              int n_tiles, hipStream_t st, bool rows_only, const int32_t *count) {
     if (n_tiles <= 0) return LSRM_OK;
     const dim3 grid((n_tiles + 1) / 2, h);
-    const int32_t *no_count = nullptr;
 #define LSRM_PACK(DD, RO) \
-    hipLaunchKernelGGL((pack_tiles<DD, RO>), grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles, no_count)
+    hipLaunchKernelGGL((pack_tiles<DD, RO>), grid, dim3(256), 0, st, rows_src, t_src, img, n_rows, h, n_tiles, count)
     if (d == 32) {
         if (rows_only) LSRM_PACK(32, true); else LSRM_PACK(32, false);
     } else if (d == 64) {

@@ -53,8 +53,9 @@ size_t forward_ws_bytes(const Shape &s);
 // Tile images (see forward.hip): img[tile][head] = row-order fragments of `rows_src`, then transposed
 // fragments of `t_src`, both [n_rows, H, d] bf16; n_tiles tiles of 32 rows.  rows_only: the backward's
 // flavour -- row-order fragments only (t_src unused), slots swizzled as backward.hip expects.
+// count (device, nullable, one entry per 64 rows): rows at or beyond their block's count read as zeros.
 lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t_src, char *img, int64_t n_rows, int h,
-                              int n_tiles, hipStream_t st, bool rows_only);
+                              int n_tiles, hipStream_t st, bool rows_only, const int32_t *count);
 
 lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, const uint16_t *d_q,
                             const uint16_t *d_k, const uint16_t *d_v, const uint16_t *d_kc, const uint16_t *d_vc,

@@ -84,12 +84,13 @@ def run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets="default
 
 
 def run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offsets="default", scale=0.0, window=None,
-                 window_mode=0):
+                 window_mode=0, block_count=None):
     """compress + forward (saving lse and branch outputs) + backward on the device -> dq, dk, dv as float32 numpy."""
     topk = idx.shape[1]
-    p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window, window_mode=window_mode)
+    p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window, window_mode=window_mode,
+                   block_count=block_count)
     dq_in, ddo = bf16_dev(q_bits), bf16_dev(dout_bits)
-    dk_in, dv_in, kc, vc = run_compress(B, cfg, k_bits, v_bits)
+    dk_in, dv_in, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count)
     d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
     d_g = torch.from_numpy(gates).cuda()
     out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")

@@ -68,13 +68,11 @@ def test_host_side_argument_checks():
     # fewer key/value heads need less room for the packed tiles
     assert B.lsrm_workspace_bytes(gqa, B.LSRM_WS_FORWARD) < B.lsrm_workspace_bytes(
         B.make_params(512, 2, 16, 4, 64, 3, 128), B.LSRM_WS_FORWARD)
-    # own-block window: everywhere; active counts: forward and compression only
+    # own-block window and active counts: everywhere
     own = B.make_params(512, 2, 16, 2, 64, 3, 128, window_mode=1)
     assert B.lsrm_workspace_bytes(own, B.LSRM_WS_BACKWARD) > 0
     assert B.lsrm_workspace_bytes(B.make_params(512, 2, 16, 2, 64, 3, 128, window_mode=2), B.LSRM_WS_FORWARD) == 0
     cnt = B.make_params(512, 2, 16, 2, 64, 3, 128)
     cnt.d_block_count = 256            # any non-null device address: only looked at on the device
     assert B.lsrm_workspace_bytes(cnt, B.LSRM_WS_FORWARD) > 0
-    assert B.lsrm_workspace_bytes(cnt, B.LSRM_WS_BACKWARD) == 0
-    rc = B._lib.lsrm_nsa_backward(__import__("ctypes").byref(cnt), *([None] * 14), 0, None, None, None)
-    assert rc == B.LSRM_ERR_UNSUPPORTED
+    assert B.lsrm_workspace_bytes(cnt, B.LSRM_WS_BACKWARD) > 0

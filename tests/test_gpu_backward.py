@@ -94,6 +94,35 @@ def test_backward_head_shapes_and_gates(B, oracle_lib, d, heads, h_kv, gate_chan
     _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
 
 
+@pytest.mark.parametrize("d,window_mode", [(64, 0), (64, 1), (128, 1), (32, 0)])
+def test_backward_with_active_counts(B, oracle_lib, d, window_mode):
+    """Blocks with fewer than 64 active tokens: padding slots are neither queries nor keys (whatever sits in
+    their rows of k, v and dout -- NaN here -- is never looked at) and get zero gradients."""
+    cfg = I.small_config(name=f"b-counts-d{d}-w{window_mode}", n_obj=576, n_views=2, grid=16, heads=3, d=d, topk=4,
+                         window=160, seed=71)
+    _log(f"[backward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(13)
+    cnt = rng.integers(1, 65, size=cfg.nb).astype(np.int32)
+    cnt[:6] = (64, 1, 33, 32, 31, 64)
+    idx = np.stack([rng.choice(cfg.nb, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.2] = -1
+    idx[:, 0] = np.minimum(np.arange(cfg.nb), 5)
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates, dout_bits = I.make_gates(cfg), I.make_dout(cfg)
+    q, k, v, dout = (I.bf16_bits_to_f32(a) for a in (q_bits, k_bits, v_bits, dout_bits))
+    inactive = (np.arange(cfg.n) % 64) >= np.repeat(cnt, 64)
+    k_bits, v_bits, dout_bits = k_bits.copy(), v_bits.copy(), dout_bits.copy()
+    for bits in (k_bits, v_bits, dout_bits):
+        bits[inactive] = 0x7FC0
+    got = G.run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, window_mode=window_mode, block_count=cnt)
+    kc, vc = oracle_lib.pool(k, cnt), oracle_lib.pool(v, cnt)
+    ref = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, cfg.seg_offsets(), cfg.window, dout,
+                                  window_mode=window_mode, block_count=cnt)
+    _assert_grads(got, ref, cfg.name)
+    for g in got:
+        assert np.all(g[inactive] == 0)
+
+
 def test_backward_zero_window_and_topk_one(B, oracle_lib):
     cfg = I.small_config(name="b-w0", n_obj=256, n_views=1, grid=16, heads=1, d=64, topk=1, window=0)
     got, args = _case(B, oracle_lib, cfg)
