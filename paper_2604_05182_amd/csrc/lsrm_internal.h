@@ -50,7 +50,7 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
                            float *d_lse, uint16_t *d_out_branch, void *d_ws, hipStream_t st, hipEvent_t ev_start,
                            hipEvent_t ev_stop);
 size_t forward_ws_bytes(const Shape &s);
-// Tile images (see forward.hip): img[tile][head] = row-order fragments of `rows_src`, then transposed
+// Tile images (see forward.hip): one image per (tile, head) = row-order fragments of `rows_src`, then transposed
 // fragments of `t_src`, both [n_rows, H, d] bf16; n_tiles tiles of 32 rows.  rows_only: the backward's
 // flavour -- row-order fragments only (t_src unused), slots swizzled as backward.hip expects.
 // count (device, nullable, one entry per 64 rows): rows at or beyond their block's count read as zeros.
