@@ -54,6 +54,9 @@
 #ifndef LSRM_QDEPTH
 #define LSRM_QDEPTH 2
 #endif
+#ifndef LSRM_NST
+#define LSRM_NST 2
+#endif
 #ifndef LSRM_PINGPONG
 #define LSRM_PINGPONG 1
 #endif
@@ -116,7 +119,11 @@ struct Geo {
     static constexpr int WAVES = NW * NP;
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int WAVES_PER_SIMD = WAVES / 4;
-    static constexpr int NSLOT = 2 * NP;        // tile slots in LDS
+    // tile slots in LDS: NST per query block; the selected phase copies NST - 1 steps ahead.  The 16 KB tiles of
+    // d = 128 fill the LDS with two stages; four stages for the smaller tiles of d <= 64 were measured: 0.7 %
+    // faster at d = 64 with 180 K tokens, 1 % slower with 57 K, 6 % slower at d = 32 -- hence two everywhere.
+    static constexpr int NST = D_ == 128 ? 2 : LSRM_NST;
+    static constexpr int NSLOT = NST * NP;
     static constexpr int T_INST = TILE / 1024;  // 1 KB copy instructions per tile
     // shared phases: copy instructions per wavefront and tile (a small tile, d = 32, has fewer
     // instructions than the workgroup has wavefronts: the first T_INST wavefronts issue one each
@@ -619,16 +626,15 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
     }
 }
 
-// Selected phase: each query block streams its own routed blocks in 32-key tiles through its two
+// Selected phase: each query block streams its own routed blocks in 32-key tiles through its NST
 // slots; its two wavefronts split the copies, and all wavefronts meet at a workgroup barrier every step.
 // CNT: blocks may hold fewer than 64 active tokens; valid(t) is the number of active keys of tile t
 // (0..32) and the scores of the others are masked.
 // Three tiles are in flight like in the shared phases: step t of a query block runs
 // mfma_block with QK of its tile t+1, the exponentials of tile t and PV of tile t-1, so every MFMA
-// has its share of the exponentials behind it.  Tile tau lives in stage tau & 1 of the block's two
+// has its share of the exponentials behind it.  Tile tau lives in stage tau mod NST of the block's NST
 // slots, K and V parts copied separately.  Barrier t comes before step t; behind it K(t) and
-// V(t-2) are dead, and K(t+2) and V(t) are copied over them, one step ahead of their use in step
-// t+1.  The operand queues are primed from LDS at the start of every step (the next tile's
+// V(t-2) are dead, and K(t+NST) and V(t+NST-2) are copied over them, NST-1 steps ahead of their use.  The operand queues are primed from LDS at the start of every step (the next tile's
 // fragments are still in flight while a step runs, so the queues cannot roll across tiles).
 // Steps 0 .. n (the last one is the PV of tile n-1); every wavefront meets barriers 0 .. n_steps.
 template <class G, bool CNT, typename SrcFn, typename ValidFn>
@@ -639,8 +645,10 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
     static_assert(G::NW == 2 && G::QT == 1, "two wavefronts per query block");
     constexpr int KI = G::K_BYTES / 1024 / G::NW, VI = G::V_BYTES / 1024 / G::NW;
     const int n = my_steps;
-    auto stage = [&](int tau) { return lds + ((tau & 1) * NP + qbi) * G::TILE; };
-    auto lstage = [&](int tau) { return lds + ((tau & 1) * NP + qbi) * G::TILE + c.lane16; };
+    constexpr int NST = G::NST;
+    static_assert((NST & (NST - 1)) == 0 && NST >= 2, "");
+    auto stage = [&](int tau) { return lds + ((tau & (NST - 1)) * NP + qbi) * G::TILE; };
+    auto lstage = [&](int tau) { return lds + ((tau & (NST - 1)) * NP + qbi) * G::TILE + c.lane16; };
     auto issue_part = [&](const char *tile, char *slot, int n_inst) {
 #pragma unroll 8
         for (int j = 0; j < n_inst; ++j) {
@@ -650,12 +658,16 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
     };
     auto issue_k = [&](int tau) { issue_part(src(tau), stage(tau), KI); };
     auto issue_v = [&](int tau) { issue_part(src(tau) + G::K_BYTES, stage(tau) + G::K_BYTES, VI); };
-    // barrier t: everything copied so far has landed and every LDS read of this wavefront is done
+    // barrier t: K(t+1) and V(t-1) have landed (both were issued behind barrier t+1-NST; what the NST-2
+    // barriers since then issued may stay in flight) and every LDS read of this wavefront is done
     auto sync = [&](int t) {
-        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        if (NST > 2 && t + NST - 1 < n)
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((NST - 2) * (KI + VI)));
+        else
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         wg_barrier();
-        if (t + 2 < n) issue_k(t + 2);
-        if (t < n) issue_v(t);
+        if (t + NST < n) issue_k(t + NST);
+        if (t + NST - 2 < n) issue_v(t + NST - 2);
     };
     bf16x8 kq[G::KQ], vq[G::VQ];
     f32x16 S[2][1];
@@ -682,8 +694,12 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
     };
     __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
     wg_barrier();  // every wavefront is done with the slots (previous phase)
-    if (n > 0) issue_k(0);
-    if (n > 1) issue_k(1);
+#pragma unroll
+    for (int tau = 0; tau < NST; ++tau)
+        if (tau < n) issue_k(tau);
+#pragma unroll
+    for (int tau = 0; tau < NST - 2; ++tau)
+        if (tau < n) issue_v(tau);
     __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
     wg_barrier();
     if (n > 0) {
