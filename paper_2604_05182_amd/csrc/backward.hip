@@ -26,6 +26,9 @@
 // Steps are not software pipelined: copy of tile t+1 (LDS DMA) overlaps the arithmetic of tile t.
 #include "lsrm_internal.h"
 
+#include <type_traits>
+#include <utility>
+
 #ifndef LSRM_BWD_NBUF
 #define LSRM_BWD_NBUF 2
 #endif
@@ -120,7 +123,6 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 // `tr_lane_offset` is the per-lane part of the address inside the row-order fragments; the fragment adds
 // dt * 2048 + ks2 * 256 and the second half of the rows another 128 (rows are stored permuted).
 // This halves what a step copies into LDS: the transposed halves of the tile images stay in memory.
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 // In the backward's tile images the 16-byte slot of (row position r, channel half h) inside a fragment is
 // h * 32 + (r ^ 4 h): without the xor the two channel halves that a group of 16 lanes addresses in one
 // transposing load lie 512 bytes apart, i.e. in the same banks (measured: half the LDS cycles of these
@@ -135,15 +137,50 @@ __device__ __forceinline__ uint32_t row_lane_offset(int lane) {
     const int r = lane & 31, hh = lane >> 5;
     return (uint32_t)((hh * 32 + (r ^ (hh << 2))) * 16);
 }
-__device__ __forceinline__ bf16x8 read_tr(const char *rows, uint32_t lane_off, int dt, int ks2) {
-    const char *p = rows + lane_off + dt * 2048 + ks2 * 256;
+// The loads are written as inline assembly on purpose.  The compiler cannot tell that a transposing load
+// (the builtin) does not touch the buffer that the global -> LDS copies of the next step are filling, and puts
+// an s_waitcnt vmcnt(0) before the first of them: every step then waits for the copies it has just issued,
+// and nothing is prefetched (seen in the assembly and in timestamps).  Loads it does not see get no such wait;
+// in exchange their results are waited for by hand: tr_take ties a counted lgkmcnt wait to the registers of a
+// fragment (LDS operations complete in order, so "at most n outstanding" covers all but the last n issued).
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+struct TrFrag {
+    i32x2 lo, hi;
+};
+template <int OFF>
+__device__ __forceinline__ void tr_issue(TrFrag &f, uint32_t addr) {
+    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                 : "=&v"(f.lo), "=&v"(f.hi)
+                 : "v"(addr), "n"(OFF), "n"(OFF + 128)
+                 : "memory");
+}
+template <int N>
+__device__ __forceinline__ bf16x8 tr_take(TrFrag &f) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(f.lo), "+v"(f.hi) : "n"(N) : "memory");
     union {
-        s16x4 h[2];
+        i32x2 h[2];
         bf16x8 v;
     } u;
-    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
-    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 128));
+    u.h[0] = f.lo;
+    u.h[1] = f.hi;
     return u.v;
+}
+
+// acc[dt] += (fragment (ks2, dt) of the transposed tile) x b[ks2] for every dt and ks2: all 2 ND fragments are
+// requested at once and each MFMA waits for its own.  rows: the tile's row-order fragments in LDS.
+template <int ND, int... I>
+__device__ __forceinline__ void mfma_tr_impl(f32x16 (&acc)[ND], uint32_t addr, const BFrag (&b)[2],
+                                             std::integer_sequence<int, I...>) {
+    TrFrag f[2 * ND];
+    (tr_issue<(I % ND) * 2048 + (I / ND) * 256>(f[I], addr), ...);
+    ((acc[I % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_take<2 * (2 * ND - 1 - I)>(f[I]), b[I / ND].v,
+                                                            acc[I % ND], 0, 0, 0)),
+     ...);
+}
+template <int ND>
+__device__ __forceinline__ void mfma_tr(f32x16 (&acc)[ND], const char *rows, uint32_t lane_off, const BFrag (&b)[2]) {
+    // (the low 32 bits of a generic pointer into LDS are the LDS address)
+    mfma_tr_impl<ND>(acc, (uint32_t)(uintptr_t)rows + lane_off, b, std::make_integer_sequence<int, 2 * ND>{});
 }
 
 template <int D>
@@ -393,6 +430,9 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     }
     const int k_start = max(seg_lo, qb * 64 - half_w), k_end = min(seg_hi, qb * 64 + 63 + half_w);
     const int st0 = k_start / 32;
+    // active tokens of the blocks of the window range, one per lane (a range of more than 64 blocks falls back to
+    // loading the count inside the loop)
+    const int wcount = a.count != nullptr && (st0 >> 1) + lane < a.nb ? a.count[(st0 >> 1) + lane] : 64;
     const int tw = k_end > k_start ? (k_end - 1) / 32 + 1 - st0 : 0;
     const int T = tc + ts + tw;
     const int wlo = max(seg_lo, (int)row0 + r - half_w), whi = min(seg_hi, (int)row0 + r + half_w);
@@ -421,6 +461,13 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 
     for (int t = 0; t < NBUF - 1 && t < T; ++t) issue(t, lds + t * TILE);
     for (int t = 0; t < T; ++t) {
+        // tiles come branch by branch: with per-channel gates the gradient rows change at the two boundaries.
+        // Loaded and waited for here, before this step's copies are issued: a wait for a register load placed
+        // after them would wait for the copies too (memory operations complete in order).
+        if (a.gate_channels && (t == tc || t == tc + ts)) {
+            load_dof(t == tc ? 1 : 2);
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        }
         // tile t has landed (this wavefront's share; the barrier covers the other's) while the
         // copies of the tiles after it stay in flight; both wavefronts are done with tile t-1
         const int ahead = min(T - 1, t + NBUF - 2) - t;  // tiles issued beyond t
@@ -433,8 +480,6 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         wg_barrier();
         if (t + NBUF - 1 < T) issue(t + NBUF - 1, lds + ((t + NBUF - 1) % NBUF) * TILE);
         const int br = t < tc ? 0 : (t < tc + ts ? 1 : 2);
-        // tiles come branch by branch: with per-channel gates the gradient rows change at the two boundaries
-        if (a.gate_channels && (t == tc || t == tc + ts)) load_dof(br);
         const int j0 = br == 0 ? 32 * t : (br == 1 ? 0 : 32 * (st0 + t - tc - ts));
         const int lo = br == 0 ? 0 : (br == 1 ? -0x40000000 : wlo);
         int hi = br == 0 ? a.nb : (br == 1 ? 0x7fffffff : whi);
@@ -451,7 +496,8 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
                 half = u & 1;
             } else {
                 const int st = st0 + t - tc - ts;
-                cnt = a.count[st >> 1];
+                const int wb = (st >> 1) - (st0 >> 1);  // block of the window range
+                cnt = wb < 64 ? __builtin_amdgcn_readlane(wcount, wb) : a.count[st >> 1];
                 half = st & 1;
             }
             const int vld = min(32, max(0, cnt - 32 * half));
@@ -491,11 +537,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         }
         BFrag dsb[2];
         to_b_operand(ds, dsb);
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-            for (int dt = 0; dt < ND; ++dt)
-                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(tile_k, tr_off, dt, ks2), dsb[ks2].v, acc[dt], 0, 0, 0);
+        mfma_tr<ND>(acc, tile_k, tr_off, dsb);
     }
     __syncthreads();  // the tile buffers become the output staging
     static_assert(NBUF >= 2 && NBUF <= 4, "");
@@ -583,139 +625,140 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
         ts = 2 * (a.rev_ptr[kb + 1] - e0);
         T = tw + ts;
     }
-    // the reverse list is held 64 entries at a time, one per lane (reloaded by whoever crosses a chunk)
-    int rev_chunk = -1, rev_held = 0;
-    auto tile_of = [&](int t) -> int64_t {
-        if (MODE == 1 || t < tw) return wt0 + t;
-        const int u = t - tw, e = u >> 1;
-        if ((e >> 6) != rev_chunk) {
-            rev_chunk = e >> 6;
-            const int at = e0 + rev_chunk * 64 + lane;
-            rev_held = at < e0 + (ts >> 1) ? a.rev_idx[at] : 0;
-        }
-        return 2 * (int64_t)__builtin_amdgcn_readlane(rev_held, e & 63) + (u & 1);
-    };
-    auto branch_of = [&](int t) { return MODE == 1 ? 0 : (t < tw ? 2 : 1); };
-    // the walk: for every query tile t, the query heads gh of this key/value head's group in turn
-    // (counters instead of a division per step)
+    // The walk is cut into segments with one pipelined loop each: the window tiles, then the routed tiles 64
+    // reverse-list entries at a time (one entry per lane, loaded before the loop).  Inside a loop nothing is loaded
+    // into registers from global memory: the wait for such a load would also wait for every tile copy in flight.
     const int grp = a.group;
-    const int U = T * grp;
-    auto issue = [&](int t, int gh, char *buf) {
-        const int qh = head * grp + gh;
-        const int64_t tile = tile_of(t);
-        const int64_t off = (tile * a.h + qh) * G::IMG;
-        const int br = branch_of(t);
-        copy_kb<G::ROW / 1024>(a.img_q + off, buf, wave, lane16);
-        copy_kb<G::ROW / 1024>((br == 0 ? a.img_do[0] : (br == 1 ? a.img_do[1] : a.img_do[2])) + off, buf + G::ROW, wave,
-                               lane16);
-        if (wave == 0) {
-            const float *ax = a.aux + (((int64_t)br * a.nt + tile) * a.h + qh) * 64;
-            __builtin_amdgcn_global_load_lds(GLB_PTR(ax + lane), LDS_PTR(buf + AUX), 4, 0, 0);
-        }
-    };
-
-    int t = 0, gh = 0, t_nxt = 0, gh_nxt = 0;  // the step being computed, the step being copied
-    auto advance = [&](int &tt, int &gg) {
-        if (++gg == grp) {
-            gg = 0;
-            ++tt;
-        }
-    };
-    // NB tile buffers: the copies run NB - 1 steps ahead of the arithmetic
-    constexpr int NB = LSRM_BWD_DKV_NBUF;
-    constexpr int IPW = G::ROW / 1024;  // copy instructions per wavefront and step (wavefront 0: one more, the table)
+    constexpr int NB = LSRM_BWD_DKV_NBUF;  // tile buffers: the copies run NB - 1 steps ahead of the arithmetic
+    constexpr int IPW = G::ROW / 1024;     // copy instructions per wavefront and step (wavefront 0: one more, the table)
     static_assert(NB == 2 || NB == 3, "");
-    for (int i = 0; i < NB - 1 && i < U; ++i) {
-        issue(t_nxt, gh_nxt, lds + i * TILE);
-        advance(t_nxt, gh_nxt);
-    }
-    for (int u = 0, slot = 0; u < U; ++u, advance(t, gh), slot = slot + 1 == NB ? 0 : slot + 1) {
-        // The barrier alone does not wait for copies in flight (they are counted by vmcnt, which a
-        // workgroup-scope fence leaves alone): every wavefront first waits for its own share of the
-        // step's tile -- the copies of the next step may stay in flight -- then the barrier publishes
-        // all shares; it also tells that everyone is done with the buffer refilled next.
-        if (NB == 3 && u + 1 < U) {
-            if (wave == 0)
-                __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW + 1));
-            else
-                __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW));
-        } else {
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
-        }
-        __syncthreads();
-        if (u + NB - 1 < U) {
-            const int fill = slot == 0 ? NB - 1 : slot - 1;  // the buffer of step u - 1 = that of step u + NB - 1
-            issue(t_nxt, gh_nxt, lds + fill * TILE);
+    // br_c: the branch whose probabilities these are (0 compressed, 1 selected, 2 window); tile_fn(t): the t-th query
+    // tile of the segment (arithmetic on registers only); every tile is met by the grp query heads of this key/value
+    // head in turn
+    auto run_segment = [&](int n_t, auto br_c, auto tile_fn) {
+        constexpr int BR = decltype(br_c)::value;
+        const int U = n_t * grp;
+        if (U <= 0) return;
+        const char *img_do = a.img_do[BR];
+        auto issue = [&](int t, int gh, char *buf) {
+            const int qh = head * grp + gh;
+            const int64_t tile = tile_fn(t);
+            const int64_t off = (tile * a.h + qh) * G::IMG;
+            copy_kb<G::ROW / 1024>(a.img_q + off, buf, wave, lane16);
+            copy_kb<G::ROW / 1024>(img_do + off, buf + G::ROW, wave, lane16);
+            if (wave == 0) {
+                const float *ax = a.aux + (((int64_t)BR * a.nt + tile) * a.h + qh) * 64;
+                __builtin_amdgcn_global_load_lds(GLB_PTR(ax + lane), LDS_PTR(buf + AUX), 4, 0, 0);
+            }
+        };
+        int t = 0, gh = 0, t_nxt = 0, gh_nxt = 0;  // the step being computed, the step being copied
+        auto advance = [&](int &tt, int &gg) {     // (counters instead of a division per step)
+            if (++gg == grp) {
+                gg = 0;
+                ++tt;
+            }
+        };
+        __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+        __syncthreads();  // both wavefronts are done with the buffers (previous segment)
+        for (int i = 0; i < NB - 1 && i < U; ++i) {
+            issue(t_nxt, gh_nxt, lds + i * TILE);
             advance(t_nxt, gh_nxt);
         }
-        const char *buf = lds + slot * TILE;
-        const char *base = buf + row_off;
-        const int q0 = 32 * (int)tile_of(t);
-        // window tiles away from the band's edges (and all routed tiles) need no mask
-        const bool win = MODE == 0 && t < tw &&
-                         ((int)key0 - (q0 + 31) < -half_w || (int)key0 + 31 - q0 >= half_w);
+        for (int u = 0, slot = 0; u < U; ++u, advance(t, gh), slot = slot + 1 == NB ? 0 : slot + 1) {
+            // The barrier alone does not wait for copies in flight (they are counted by vmcnt, which a
+            // workgroup-scope fence leaves alone): every wavefront first waits for its own share of the
+            // step's tile -- the copies of the next step may stay in flight -- then the barrier publishes
+            // all shares; it also tells that everyone is done with the buffer refilled next.
+            if (NB == 3 && u + 1 < U) {
+                if (wave == 0)
+                    __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW + 1));
+                else
+                    __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW));
+            } else {
+                __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+            }
+            wg_barrier();
+            if (u + NB - 1 < U) {
+                const int fill = slot == 0 ? NB - 1 : slot - 1;  // the buffer of step u - 1 = that of step u + NB - 1
+                issue(t_nxt, gh_nxt, lds + fill * TILE);
+                advance(t_nxt, gh_nxt);
+            }
+            const char *buf = lds + slot * TILE;
+            const char *base = buf + row_off;
+            const int q0 = 32 * (int)tile_fn(t);
+            // window tiles away from the band's edges (and all routed tiles) need no mask
+            const bool win = BR == 2 && ((int)key0 - (q0 + 31) < -half_w || (int)key0 + 31 - q0 >= half_w);
 
-        f32x16 s;
+            f32x16 s;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.f;
+            for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks)
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), kB[ks], s, 0,
-                                                        0, 0);
-        // table entries of the 16 query rows this lane holds: rows (i/4)*8 + hh*4 + i%4
-        float lv[16], dv_[16];
+            for (int ks = 0; ks < NS; ++ks)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), kB[ks], s,
+                                                            0, 0, 0);
+            // table entries of the 16 query rows this lane holds: rows (i/4)*8 + hh*4 + i%4
+            float lv[16], dv_[16];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(buf + AUX + (8 * g + 4 * hh) * 4);
-            const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(buf + AUX + (8 * g + 4 * hh) * 4);
+                const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                lv[4 * g + j] = x[j];
-                dv_[4 * g + j] = y[j];
+                for (int j = 0; j < 4; ++j) {
+                    lv[4 * g + j] = x[j];
+                    dv_[4 * g + j] = y[j];
+                }
             }
-        }
-        float p[16];
+            // Most tiles need no mask at all (wave-uniform test): routed tiles and window tiles inside the band, of
+            // blocks without padding; pooled keys before the last block.
+            const bool plain = MODE == 1 ? key0 + 32 <= limit : (!win && n_act == 64);
+            float p[16];
+            if (__builtin_expect(plain, 1)) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float pi = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lv[i]);
-            if (MODE == 1) {
-                pi = key < limit ? pi : 0.f;
-            } else if (n_act < 64) {
-                const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);
-                const int dj = (int)key - qi;
-                pi = key_active && (!win || (dj >= -half_w && dj < half_w)) ? pi : 0.f;
-            } else if (win) {
-                const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);  // the query behind accumulator row i
-                const int dj = (int)key - qi;
-                pi = (dj >= -half_w && dj < half_w) ? pi : 0.f;
+                for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lv[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float pi = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lv[i]);
+                    bool ok;
+                    if (MODE == 1) {
+                        ok = key < limit;
+                    } else {
+                        const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);  // the query behind accumulator row i
+                        const int dj = (int)key - qi;
+                        ok = key_active & (!win | ((dj >= -half_w) & (dj < half_w)));
+                    }
+                    p[i] = ok ? pi : 0.f;
+                }
             }
-            p[i] = pi;
+            BFrag pb[2];
+            to_b_operand(p, pb);
+            mfma_tr<ND>(accv, buf + G::ROW, tr_off, pb);
+            f32x16 dp;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dp[i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NS; ++ks)
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), vB[ks], dp, 0, 0, 0);
+            float ds[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ds[i] = p[i] * (dp[i] - dv_[i]);
+            BFrag dsb[2];
+            to_b_operand(ds, dsb);
+            mfma_tr<ND>(acck, buf, tr_off, dsb);
         }
-        BFrag pb[2];
-        to_b_operand(p, pb);
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-            for (int dt = 0; dt < ND; ++dt)
-                accv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(buf + G::ROW, tr_off, dt, ks2), pb[ks2].v,
-                                                                   accv[dt], 0, 0, 0);
-        f32x16 dp;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dp[i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < NS; ++ks)
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024),
-                                                         vB[ks], dp, 0, 0, 0);
-        float ds[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) ds[i] = p[i] * (dp[i] - dv_[i]);
-        BFrag dsb[2];
-        to_b_operand(ds, dsb);
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-            for (int dt = 0; dt < ND; ++dt)
-                acck[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr(buf, tr_off, dt, ks2), dsb[ks2].v, acck[dt], 0, 0, 0);
+    };
+    if (MODE == 1) {
+        run_segment(T, std::integral_constant<int, 0>{}, [&](int t) -> int64_t { return wt0 + t; });
+    } else {
+        run_segment(tw, std::integral_constant<int, 2>{}, [&](int t) -> int64_t { return wt0 + t; });
+        const int n_e = ts >> 1;  // entries of the reverse list: query blocks that route to this key block
+        for (int c0 = 0; c0 < n_e; c0 += 64) {
+            const int rev_held = c0 + lane < n_e ? a.rev_idx[e0 + c0 + lane] : 0;
+            run_segment(2 * min(64, n_e - c0), std::integral_constant<int, 1>{}, [&](int t) -> int64_t {
+                return 2 * (int64_t)__builtin_amdgcn_readlane(rev_held, t >> 1) + (t & 1);
+            });
+        }
     }
 
     if (MODE == 1) {
