@@ -554,7 +554,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 // blockIdx.y is the key/value head; the query tiles of each of its `group` query heads are walked in turn.
 // (d = 128: the two [128 x 32] accumulator sets alone take 128 registers, so one workgroup per SIMD.)
 template <int D, int MODE>
-__global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArgs a) {
+__global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArgs a) {
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int AUX = 2 * G::ROW;          // Q rows | dO rows | table (64 floats); Q^T and dO^T: see read_tr
@@ -696,17 +696,14 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
             for (int ks = 0; ks < NS; ++ks)
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), kB[ks], s,
                                                             0, 0, 0);
-            // table entries of the 16 query rows this lane holds: rows (i/4)*8 + hh*4 + i%4
-            float lv[16], dv_[16];
+            // table entries of the 16 query rows this lane holds: rows (i/4)*8 + hh*4 + i%4  (each half of the table
+            // is read right before its use: fewer registers live at once)
+            float lv[16];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const f32x4 x = *reinterpret_cast<const f32x4 *>(buf + AUX + (8 * g + 4 * hh) * 4);
-                const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    lv[4 * g + j] = x[j];
-                    dv_[4 * g + j] = y[j];
-                }
+                for (int j = 0; j < 4; ++j) lv[4 * g + j] = x[j];
             }
             // Most tiles need no mask at all (wave-uniform test): routed tiles and window tiles inside the band, of
             // blocks without padding; pooled keys before the last block.
@@ -733,6 +730,13 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 2)) void bwd_dkv_kernel(BwdArg
             BFrag pb[2];
             to_b_operand(p, pb);
             mfma_tr<ND>(accv, buf + G::ROW, tr_off, pb);
+            float dv_[16];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dv_[4 * g + j] = y[j];
+            }
             f32x16 dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) dp[i] = 0.f;
