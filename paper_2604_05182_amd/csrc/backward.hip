@@ -102,11 +102,12 @@ __device__ __forceinline__ void to_b_operand(const float (&x)[16], BFrag (&b)[2]
 // copies n_kb KB, contiguous on both sides, global -> LDS; the two wavefronts of the workgroup split it
 template <int N_KB>
 __device__ __forceinline__ void copy_kb(const char *src, char *dst, int wave, uint32_t lane16) {
+    static_assert(N_KB % 2 == 0, "");
+    src += wave * 1024;
+    dst += wave * 1024;
 #pragma unroll
     for (int i = 0; i < N_KB; i += 2)
-        if (i + wave < N_KB)
-            __builtin_amdgcn_global_load_lds(GLB_PTR(src + (i + wave) * 1024 + lane16), LDS_PTR(dst + (i + wave) * 1024),
-                                             16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLB_PTR(src + i * 1024 + lane16), LDS_PTR(dst + i * 1024), 16, 0, 0);
 }
 
 // s_waitcnt vmcnt <= n (and lgkmcnt == 0), and a raw barrier.  Neither this barrier nor __syncthreads() waits
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 
     auto issue = [&](int t, char *buf) {
         const char *kimg, *vimg;
-        int64_t tile;
+        int tile;
         if (t < tc) {
             tile = t;
             kimg = a.img_kc;
@@ -447,14 +448,14 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         } else {
             if (t < tc + ts) {
                 const int u = t - tc;
-                tile = 2 * (int64_t)__builtin_amdgcn_readlane(packed, u >> 1) + (u & 1);
+                tile = 2 * __builtin_amdgcn_readlane(packed, u >> 1) + (u & 1);
             } else {
                 tile = st0 + (t - tc - ts);
             }
             kimg = a.img_k;
             vimg = a.img_v;
         }
-        const int64_t off = (tile * a.h_kv + kvh) * G::IMG;
+        const int64_t off = (int64_t)((uint32_t)tile * (uint32_t)a.h_kv + (uint32_t)kvh) * G::IMG;
         copy_kb<G::ROW / 1024>(kimg + off, buf, wave, lane16);
         copy_kb<G::ROW / 1024>(vimg + off, buf + G::ROW, wave, lane16);
     };
@@ -640,16 +641,15 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
         const int U = n_t * grp;
         if (U <= 0) return;
         const char *img_do = a.img_do[BR];
+        const float *aux_br = a.aux + (int64_t)BR * a.nt * a.h * 64;  // table of this branch: [tile][head][64]
         auto issue = [&](int t, int gh, char *buf) {
-            const int qh = head * grp + gh;
-            const int64_t tile = tile_fn(t);
-            const int64_t off = (tile * a.h + qh) * G::IMG;
+            // (tile, head) index in 32 bits, byte offsets by shifts: a 64-bit multiply is several scalar instructions
+            const uint32_t ih = (uint32_t)tile_fn(t) * (uint32_t)a.h + (uint32_t)(head * grp + gh);
+            const int64_t off = (int64_t)ih * G::IMG;
             copy_kb<G::ROW / 1024>(a.img_q + off, buf, wave, lane16);
             copy_kb<G::ROW / 1024>(img_do + off, buf + G::ROW, wave, lane16);
-            if (wave == 0) {
-                const float *ax = a.aux + (((int64_t)BR * a.nt + tile) * a.h + qh) * 64;
-                __builtin_amdgcn_global_load_lds(GLB_PTR(ax + lane), LDS_PTR(buf + AUX), 4, 0, 0);
-            }
+            if (wave == 0)
+                __builtin_amdgcn_global_load_lds(GLB_PTR(aux_br + (int64_t)ih * 64 + lane), LDS_PTR(buf + AUX), 4, 0, 0);
         };
         int t = 0, gh = 0, t_nxt = 0, gh_nxt = 0;  // the step being computed, the step being copied
         auto advance = [&](int &tt, int &gg) {     // (counters instead of a division per step)
@@ -753,14 +753,14 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
         }
     };
     if (MODE == 1) {
-        run_segment(T, std::integral_constant<int, 0>{}, [&](int t) -> int64_t { return wt0 + t; });
+        run_segment(T, std::integral_constant<int, 0>{}, [&](int t) { return wt0 + t; });
     } else {
-        run_segment(tw, std::integral_constant<int, 2>{}, [&](int t) -> int64_t { return wt0 + t; });
+        run_segment(tw, std::integral_constant<int, 2>{}, [&](int t) { return wt0 + t; });
         const int n_e = ts >> 1;  // entries of the reverse list: query blocks that route to this key block
         for (int c0 = 0; c0 < n_e; c0 += 64) {
             const int rev_held = c0 + lane < n_e ? a.rev_idx[e0 + c0 + lane] : 0;
-            run_segment(2 * min(64, n_e - c0), std::integral_constant<int, 1>{}, [&](int t) -> int64_t {
-                return 2 * (int64_t)__builtin_amdgcn_readlane(rev_held, t >> 1) + (t & 1);
+            run_segment(2 * min(64, n_e - c0), std::integral_constant<int, 1>{}, [&](int t) {
+                return 2 * __builtin_amdgcn_readlane(rev_held, t >> 1) + (t & 1);
             });
         }
     }
