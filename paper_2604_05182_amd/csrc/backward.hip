@@ -438,110 +438,124 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     const int T = tc + ts + tw;
     const int wlo = max(seg_lo, (int)row0 + r - half_w), whi = min(seg_hi, (int)row0 + r + half_w);
 
-    auto issue = [&](int t, char *buf) {
-        const char *kimg, *vimg;
-        int tile;
-        if (t < tc) {
-            tile = t;
-            kimg = a.img_kc;
-            vimg = a.img_vc;
-        } else {
-            if (t < tc + ts) {
-                const int u = t - tc;
-                tile = 2 * __builtin_amdgcn_readlane(packed, u >> 1) + (u & 1);
-            } else {
-                tile = st0 + (t - tc - ts);
-            }
-            kimg = a.img_k;
-            vimg = a.img_v;
-        }
+    // Two tile buffers: the copy of tile t+1 is issued behind the barrier of step t and waited for before the
+    // barrier of step t+1.  The walk is one pipelined loop per branch, so that everything that depends on the
+    // branch (tile lookup, image, mask rule, table entries) is fixed inside a loop; the first tile of the next
+    // branch is requested in the last step of the one before it, so the pipeline never drains.
+    static_assert(NBUF == 2, "");
+    auto issue_tile = [&](const char *kimg, const char *vimg, int tile, char *buf) {
         const int64_t off = (int64_t)((uint32_t)tile * (uint32_t)a.h_kv + (uint32_t)kvh) * G::IMG;
         copy_kb<G::ROW / 1024>(kimg + off, buf, wave, lane16);
         copy_kb<G::ROW / 1024>(vimg + off, buf + G::ROW, wave, lane16);
     };
-
-    for (int t = 0; t < NBUF - 1 && t < T; ++t) issue(t, lds + t * TILE);
-    for (int t = 0; t < T; ++t) {
-        // tiles come branch by branch: with per-channel gates the gradient rows change at the two boundaries.
-        // Loaded and waited for here, before this step's copies are issued: a wait for a register load placed
-        // after them would wait for the copies too (memory operations complete in order).
-        if (a.gate_channels && (t == tc || t == tc + ts)) {
-            load_dof(t == tc ? 1 : 2);
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
-        }
-        // tile t has landed (this wavefront's share; the barrier covers the other's) while the
-        // copies of the tiles after it stay in flight; both wavefronts are done with tile t-1
-        const int ahead = min(T - 1, t + NBUF - 2) - t;  // tiles issued beyond t
-        if (ahead >= 2)
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(2 * IPW));
-        else if (ahead == 1)
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(IPW));
-        else
-            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
-        wg_barrier();
-        if (t + NBUF - 1 < T) issue(t + NBUF - 1, lds + ((t + NBUF - 1) % NBUF) * TILE);
-        const int br = t < tc ? 0 : (t < tc + ts ? 1 : 2);
-        const int j0 = br == 0 ? 32 * t : (br == 1 ? 0 : 32 * (st0 + t - tc - ts));
-        const int lo = br == 0 ? 0 : (br == 1 ? -0x40000000 : wlo);
-        int hi = br == 0 ? a.nb : (br == 1 ? 0x7fffffff : whi);
-        // does any lane of this wavefront need the mask on this tile?  (pooled tail; window edges)
-        bool need_mask =
-            br == 0 ? (j0 + 32 > a.nb)
-                    : (br == 2 && (j0 < max(seg_lo, (int)row0 + 31 - half_w) || j0 + 32 > min(seg_hi, (int)row0 + half_w)));
-        if (a.count != nullptr && br != 0) {
-            // padding slots at the end of the tile's block are no keys
-            int cnt, half;
-            if (br == 1) {
-                const int u = t - tc;
-                cnt = __builtin_amdgcn_readlane(pcount, u >> 1);
-                half = u & 1;
-            } else {
-                const int st = st0 + t - tc - ts;
-                const int wb = (st >> 1) - (st0 >> 1);  // block of the window range
-                cnt = wb < 64 ? __builtin_amdgcn_readlane(wcount, wb) : a.count[st >> 1];
-                half = st & 1;
-            }
-            const int vld = min(32, max(0, cnt - 32 * half));
-            if (vld < 32) {
-                need_mask = true;
-                hi = min(hi, j0 + vld);
-            }
-        }
-        const float lb = br == 0 ? l2[0] : (br == 1 ? l2[1] : l2[2]);
-        const float db = br == 0 ? dl[0] : (br == 1 ? dl[1] : dl[2]);
-        const char *tile_k = lds + (t % NBUF) * TILE;
-        const char *base = tile_k + row_off;
-
-        f32x16 s, dp;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < NS; ++ks)
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), qf[ks], s, 0,
-                                                        0, 0);
-#pragma unroll
-        for (int ks = 0; ks < NS; ++ks)
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024),
-                                                         dof[ks], dp, 0, 0, 0);
-        float ds[16];
-        if (__builtin_expect(need_mask, 0)) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
-                float p = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb);
-                p = (j >= lo && j < hi) ? p : 0.f;
-                ds[i] = p * (dp[i] - db);
-            }
+    // tile of step t of the whole walk (used at the branch boundaries only)
+    auto issue_any = [&](int t, char *buf) {
+        if (t < tc) {
+            issue_tile(a.img_kc, a.img_vc, t, buf);
+        } else if (t < tc + ts) {
+            const int u = t - tc;
+            issue_tile(a.img_k, a.img_v, 2 * __builtin_amdgcn_readlane(packed, u >> 1) + (u & 1), buf);
         } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb) * (dp[i] - db);
+            issue_tile(a.img_k, a.img_v, st0 + (t - tc - ts), buf);
         }
-        BFrag dsb[2];
-        to_b_operand(ds, dsb);
-        mfma_tr<ND>(acc, tile_k, tr_off, dsb);
-    }
+    };
+    // steps [t0, t1) of the walk, all of branch BR.  tile_fn(u): image tile of the u-th step of the branch;
+    // mask_fn(u, &j0, &lo, &hi) -> does this tile need a mask: key j0 + (position in the tile) is attended iff
+    // lo <= key < hi (per lane)
+    auto run_branch = [&](int t0, int t1, auto br_c, const char *kimg, const char *vimg, auto tile_fn, auto mask_fn) {
+        constexpr int BR = decltype(br_c)::value;
+        const float lb = l2[BR], db = dl[BR];
+        for (int t = t0; t < t1; ++t) {
+            // tile t has landed (this wavefront's share; the barrier covers the other's); both wavefronts are done
+            // with tile t-1, whose buffer takes tile t+1
+            __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+            wg_barrier();
+            char *nbuf = lds + ((t + 1) & 1) * TILE;
+            if (t + 1 < t1)
+                issue_tile(kimg, vimg, tile_fn(t + 1 - t0), nbuf);
+            else if (t + 1 < T)
+                issue_any(t + 1, nbuf);
+            int j0, lo, hi;
+            const bool need_mask = mask_fn(t - t0, &j0, &lo, &hi);
+            const char *tile_k = lds + (t & 1) * TILE;
+            const char *base = tile_k + row_off;
+
+            f32x16 s, dp;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NS; ++ks)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), qf[ks], s,
+                                                            0, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < NS; ++ks)
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), dof[ks], dp, 0, 0, 0);
+            // with per-channel gates the gradient rows change with the branch: the next branch's are requested
+            // once the last dP MFMAs of this one are issued, and have arrived by the wait at the top of the next step
+            if (BR < 2 && a.gate_channels && t + 1 == t1 && t + 1 < T) load_dof(t + 1 < tc + ts ? 1 : 2);
+            float ds[16];
+            if (__builtin_expect(need_mask, 0)) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
+                    float p = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb);
+                    p = ((j >= lo) & (j < hi)) ? p : 0.f;
+                    ds[i] = p * (dp[i] - db);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb) * (dp[i] - db);
+            }
+            BFrag dsb[2];
+            to_b_operand(ds, dsb);
+            mfma_tr<ND>(acc, tile_k, tr_off, dsb);
+        }
+    };
+    // padding slots at the end of a tile's block are no keys: valid keys of the tile, given its block's count
+    auto valid_keys = [&](int cnt, int half) { return min(32, max(0, cnt - 32 * half)); };
+
+    if (T > 0) issue_any(0, lds);
+    // pooled keys: only the last tile can reach past the end
+    run_branch(0, tc, std::integral_constant<int, 0>{}, a.img_kc, a.img_vc, [&](int u) { return u; },
+               [&](int u, int *j0, int *lo, int *hi) {
+                   *j0 = 32 * u;
+                   *lo = 0;
+                   *hi = a.nb;
+                   return 32 * u + 32 > a.nb;
+               });
+    // routed blocks: every key counts, except padding slots
+    run_branch(tc, tc + ts, std::integral_constant<int, 1>{}, a.img_k, a.img_v,
+               [&](int u) { return 2 * __builtin_amdgcn_readlane(packed, u >> 1) + (u & 1); },
+               [&](int u, int *j0, int *lo, int *hi) {
+                   *j0 = 0;
+                   *lo = 0;
+                   *hi = 32;
+                   if (a.count == nullptr) return false;
+                   *hi = valid_keys(__builtin_amdgcn_readlane(pcount, u >> 1), u & 1);
+                   return *hi < 32;
+               });
+    // window: the band's edges and the segment's ends, and padding slots
+    const int edge_lo = max(seg_lo, (int)row0 + 31 - half_w), edge_hi = min(seg_hi, (int)row0 + half_w);
+    run_branch(tc + ts, T, std::integral_constant<int, 2>{}, a.img_k, a.img_v, [&](int u) { return st0 + u; },
+               [&](int u, int *j0, int *lo, int *hi) {
+                   const int st = st0 + u;
+                   *j0 = 32 * st;
+                   *lo = wlo;
+                   *hi = whi;
+                   bool need = 32 * st < edge_lo || 32 * st + 32 > edge_hi;
+                   if (a.count != nullptr) {
+                       const int wb = (st >> 1) - (st0 >> 1);  // block of the window range
+                       const int cnt = wb < 64 ? __builtin_amdgcn_readlane(wcount, wb) : a.count[st >> 1];
+                       const int vld = valid_keys(cnt, st & 1);
+                       if (vld < 32) {
+                           need = true;
+                           *hi = min(*hi, 32 * st + vld);
+                       }
+                   }
+                   return need;
+               });
     __syncthreads();  // the tile buffers become the output staging
-    static_assert(NBUF >= 2 && NBUF <= 4, "");
     float x[ND][16];
 #pragma unroll
     for (int dt = 0; dt < ND; ++dt)
