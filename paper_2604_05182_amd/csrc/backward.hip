@@ -60,7 +60,7 @@ struct BwdArgs {
                               // per-head gates (the gate is folded into the exponent), gate o dout per branch
                               // with per-channel gates
     const uint16_t *gdo;      // per-channel gates only: [3][N][H][d] bf16, gate o dout (written by bwd_prep)
-    float *aux;               // [3][N/32][H][64]: per query tile, 32 x (lse log2e - log2 g) then 32 x D, rows permuted
+    float *aux;               // [3][N/32][H][64]: per query tile, 32 x (lse log2e - log2 g) then 32 x -D, rows permuted
     float *part_k, *part_v;   // [n_split][nbp][H][d] fp32 partial gradients of the pooled keys / values
     int32_t *rev_cnt, *rev_ptr, *rev_cur, *rev_idx;  // reverse routing lists
     uint16_t *dq, *dk, *dv;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void bwd_prep(BwdArgs a) {
         }
         float *ax = a.aux + (((int64_t)b * a.nt + tile) * a.h + head) * 64;
         ax[pr] = padding ? __builtin_inff() : l2;
-        ax[32 + pr] = padding ? 0.f : dl;
+        ax[32 + pr] = padding ? 0.f : -dl;  // negated: the kernels start the dP accumulators from it
     }
 }
 
@@ -464,7 +464,10 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     // lo <= key < hi (per lane)
     auto run_branch = [&](int t0, int t1, auto br_c, const char *kimg, const char *vimg, auto tile_fn, auto mask_fn) {
         constexpr int BR = decltype(br_c)::value;
-        const float lb = l2[BR], db = dl[BR];
+        const float lb = l2[BR];
+        f32x16 dp0;  // -D of this lane's query: the dP accumulator starts from it, so the MFMAs leave dP - D
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dp0[i] = dl[BR];
         for (int t = t0; t < t1; ++t) {
             // tile t has landed (this wavefront's share; the barrier covers the other's); both wavefronts are done
             // with tile t-1, whose buffer takes tile t+1
@@ -482,7 +485,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 
             f32x16 s, dp;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s[i] = dp[i] = 0.f;
+            for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < NS; ++ks)
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), qf[ks], s,
@@ -490,7 +493,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
             for (int ks = 0; ks < NS; ++ks)
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), dof[ks], dp, 0, 0, 0);
+                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), dof[ks], ks == 0 ? dp0 : dp, 0, 0, 0);
             // with per-channel gates the gradient rows change with the branch: the next branch's are requested
             // once the last dP MFMAs of this one are issued, and have arrived by the wait at the top of the next step
             if (BR < 2 && a.gate_channels && t + 1 == t1 && t + 1 < T) load_dof(t + 1 < tc + ts ? 1 : 2);
@@ -501,11 +504,11 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
                     const int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
                     float p = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb);
                     p = ((j >= lo) & (j < hi)) ? p : 0.f;
-                    ds[i] = p * (dp[i] - db);
+                    ds[i] = p * dp[i];
                 }
             } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb) * (dp[i] - db);
+                for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb) * dp[i];
             }
             BFrag dsb[2];
             to_b_operand(ds, dsb);
@@ -744,23 +747,20 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
             BFrag pb[2];
             to_b_operand(p, pb);
             mfma_tr<ND>(accv, buf + G::ROW, tr_off, pb);
-            float dv_[16];
+            f32x16 dp;  // starts from -D of the 16 query rows (second half of the table): the MFMAs leave dP - D
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) dv_[4 * g + j] = y[j];
+                for (int j = 0; j < 4; ++j) dp[4 * g + j] = y[j];
             }
-            f32x16 dp;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dp[i] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < NS; ++ks)
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), vB[ks], dp, 0, 0, 0);
             float ds[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) ds[i] = p[i] * (dp[i] - dv_[i]);
+            for (int i = 0; i < 16; ++i) ds[i] = p[i] * dp[i];
             BFrag dsb[2];
             to_b_operand(ds, dsb);
             mfma_tr<ND>(acck, buf, tr_off, dsb);
