@@ -332,7 +332,58 @@ __global__ void rev_fill(BwdArgs a) {
     int v = a.idx[e];
     if (v >= 0 && v < a.nb) a.rev_idx[atomicAdd(&a.rev_cur[v], 1)] = e / a.topk;
 }
-__global__ void rev_sort(BwdArgs a) {
+// Puts every list in ascending order (the fill order is whatever the atomics gave; a fixed order makes the
+// gradients reproducible, and ascending keeps consecutive query tiles together).  The entries of a list are
+// block numbers, distinct unless a row of the table repeats a block: one wavefront per key block marks them in
+// a bitmap of nb bits in LDS and reads the bitmap back in order.
+__global__ __launch_bounds__(64) void rev_sort(BwdArgs a) {
+    extern __shared__ uint32_t bits[];  // (nb + 31) / 32 words
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int words = (a.nb + 31) >> 5;
+    int32_t *x = a.rev_idx + a.rev_ptr[b];
+    const int len = a.rev_ptr[b + 1] - a.rev_ptr[b];
+    if (len <= 1) return;
+    for (int w = lane; w < words; w += 64) bits[w] = 0u;
+    __syncthreads();
+    for (int i = lane; i < len; i += 64) atomicOr(&bits[x[i] >> 5], 1u << (x[i] & 31));
+    __syncthreads();
+    // a table may list a block twice in one row (it is then attended twice): the bitmap would drop the repeat,
+    // so such a list is sorted the slow way
+    int marked = 0;
+    for (int w = lane; w < words; w += 64) marked += __popc(bits[w]);
+    for (int off = 32; off > 0; off >>= 1) marked += __shfl_xor(marked, off);
+    if (marked != len) {
+        if (lane == 0)
+            for (int i = 1; i < len; ++i) {
+                int v = x[i], j = i - 1;
+                while (j >= 0 && x[j] > v) {
+                    x[j + 1] = x[j];
+                    --j;
+                }
+                x[j + 1] = v;
+            }
+        return;
+    }
+    int base = 0;
+    for (int w0 = 0; w0 < words; w0 += 64) {
+        const int w = w0 + lane;
+        uint32_t m = w < words ? bits[w] : 0u;
+        const int c = __popc(m);
+        int pre = c;  // inclusive prefix sum over the lanes
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(pre, off);
+            if (lane >= off) pre += t;
+        }
+        int at = base + pre - c;
+        while (m != 0u) {
+            x[at++] = (w << 5) + (__ffs(m) - 1);
+            m &= m - 1u;
+        }
+        base += __shfl(pre, 63);
+    }
+}
+// the same for sequences too long for the bitmap: insertion sort, one thread per list
+__global__ void rev_sort_serial(BwdArgs a) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= a.nb) return;
     int32_t *x = a.rev_idx + a.rev_ptr[b];
@@ -916,7 +967,11 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     if (s.topk > 0) {
         hipLaunchKernelGGL(rev_fill, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
         LSRM_HIP_CHECK(hipGetLastError());
-        hipLaunchKernelGGL(rev_sort, dim3((s.nb + 63) / 64), dim3(64), 0, st, a);
+        const size_t bitmap = (size_t)((s.nb + 31) / 32) * 4;
+        if (bitmap <= 48 * 1024)
+            hipLaunchKernelGGL(rev_sort, dim3(s.nb), dim3(64), bitmap, st, a);
+        else
+            hipLaunchKernelGGL(rev_sort_serial, dim3((s.nb + 63) / 64), dim3(64), 0, st, a);
         LSRM_HIP_CHECK(hipGetLastError());
     }
     hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);

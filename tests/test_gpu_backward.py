@@ -65,6 +65,29 @@ def test_backward_ragged_and_holes(B, oracle_lib):
     _assert_grads(got, oracle_lib.nsa_backward(*args, scale=0.2), cfg.name)
 
 
+def test_backward_repeated_and_popular_blocks(B, oracle_lib):
+    """Rows that list a block twice (it is attended twice) and one block that every row lists (a reverse list
+    longer than one 64-entry chunk), with a top-k of zero windows' worth and per-channel gates on grouped heads
+    (the gradient rows change between branches even where a branch is empty)."""
+    cfg = I.small_config(name="b-repeat", n_obj=4096, n_views=2, grid=16, heads=4, d=64, topk=4, window=128, seed=27,
+                         h_kv=2, gate_channels=True)
+    _log(f"[backward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(11)
+    idx = np.stack([rng.choice(cfg.nb, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[:, 0] = 5                      # a popular block: nb entries in its reverse list
+    idx[3::7, 2] = idx[3::7, 1]        # repeats inside a row
+    idx[4::9, 3] = 5                   # the popular block twice in a row
+    idx[6] = -1
+    got, args = _case(B, oracle_lib, cfg, idx=idx)
+    _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
+    # no routed blocks and no window at all: only the compressed branch is left
+    cfg0 = I.small_config(name="b-cmp-only", n_obj=512, n_views=2, grid=16, heads=4, d=64, topk=2, window=0, seed=28,
+                          h_kv=2, gate_channels=True)
+    idx0 = np.full((cfg0.nb, cfg0.topk), -1, dtype=np.int32)
+    got, args = _case(B, oracle_lib, cfg0, idx=idx0)
+    _assert_grads(got, oracle_lib.nsa_backward(*args), cfg0.name)
+
+
 def test_backward_own_block_window(B, oracle_lib):
     """The window branch over the query's own block (App. A) instead of the sliding window."""
     cfg = I.small_config(name="b-ownblock", n_obj=1088, n_views=3, grid=24, heads=3, d=64, topk=5, window=200, seed=23)
