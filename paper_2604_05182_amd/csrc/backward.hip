@@ -32,6 +32,9 @@
 #ifndef LSRM_BWD_NBUF
 #define LSRM_BWD_NBUF 2
 #endif
+#ifndef LSRM_BWD_EARLY_DP
+#define LSRM_BWD_EARLY_DP 1
+#endif
 #ifndef LSRM_BWD_DKV_NBUF
 #define LSRM_BWD_DKV_NBUF 2  // (3, copies two steps ahead with counted waits, was measured: no faster)
 #endif
@@ -773,6 +776,25 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
 #pragma unroll
                 for (int j = 0; j < 4; ++j) lv[4 * g + j] = x[j];
             }
+            // dP = dout V^T does not depend on the probabilities.  With one wavefront per SIMD (d = 128) nothing else
+            // runs under the exponentials, so its MFMAs are issued before them (LSRM_BWD_EARLY_DP); with three
+            // wavefronts per SIMD the extra live accumulator would cost the third one, and the other wavefronts
+            // fill the gap anyway.
+            constexpr bool EARLY_DP = D == 128 && LSRM_BWD_EARLY_DP;
+            f32x16 dp;  // starts from -D of the 16 query rows (second half of the table): the MFMAs leave dP - D
+            auto dp_mfmas = [&]() {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dp[4 * g + j] = y[j];
+                }
+#pragma unroll
+                for (int ks = 0; ks < NS; ++ks)
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), vB[ks], dp, 0, 0, 0);
+            };
+            if constexpr (EARLY_DP) dp_mfmas();
             // Most tiles need no mask at all (wave-uniform test): routed tiles and window tiles inside the band, of
             // blocks without padding; pooled keys before the last block.
             const bool plain = MODE == 1 ? key0 + 32 <= limit : (!win && n_act == 64);
@@ -798,17 +820,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
             BFrag pb[2];
             to_b_operand(p, pb);
             mfma_tr<ND>(accv, buf + G::ROW, tr_off, pb);
-            f32x16 dp;  // starts from -D of the 16 query rows (second half of the table): the MFMAs leave dP - D
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) dp[4 * g + j] = y[j];
-            }
-#pragma unroll
-            for (int ks = 0; ks < NS; ++ks)
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), vB[ks], dp, 0, 0, 0);
+            if constexpr (!EARLY_DP) dp_mfmas();
             float ds[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) ds[i] = p[i] * dp[i];
