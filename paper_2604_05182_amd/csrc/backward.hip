@@ -32,8 +32,8 @@
 #ifndef LSRM_BWD_NBUF
 #define LSRM_BWD_NBUF 2
 #endif
-#ifndef LSRM_BWD_EARLY_DP
-#define LSRM_BWD_EARLY_DP 1
+#ifndef LSRM_BWD_VGPR_CHAINS
+#define LSRM_BWD_VGPR_CHAINS 1
 #endif
 #ifndef LSRM_BWD_DKV_NBUF
 #define LSRM_BWD_DKV_NBUF 2  // (3, copies two steps ahead with counted waits, was measured: no faster)
@@ -101,6 +101,20 @@ __device__ __forceinline__ void to_b_operand(const float (&x)[16], BFrag (&b)[2]
 #pragma unroll
     for (int k = 0; k < 8; ++k) b[k / 4].u[k % 4] = pack_bf16(x[2 * k], x[2 * k + 1]);
 }
+
+// MFMAs whose accumulator stays in ordinary VGPRs, written as inline assembly.  A kernel compiled for one wavefront
+// per SIMD (more than 256 registers) gets every MFMA builtin in the form that accumulates in AGPRs; results that the
+// vector ALU must read (scores, dP) then travel through v_accvgpr_read/write, and the register allocator was seen to
+// park them in the AGPRs of the long-lived dK/dV accumulators, saving and restoring those around every chain (about
+// 100 register moves per step).  The hardware does not interlock "MFMA result read by a VALU instruction" and the
+// compiler cannot pad what it does not see, so a chain ends with mfma_v_settle (24 wait states cover the 8 passes).
+__device__ __forceinline__ void mfma_v_first(f32x16 &d, bf16x8 a, bf16x8 b) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_v(f32x16 &d, bf16x8 a, bf16x8 b) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_v_settle(f32x16 &d) { asm volatile("s_nop 15\n\ts_nop 7" : "+v"(d)); }
 
 // copies n_kb KB, contiguous on both sides, global -> LDS; the two wavefronts of the workgroup split it
 template <int N_KB>
@@ -701,8 +715,9 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     // reverse-list entries at a time (one entry per lane, loaded before the loop).  Inside a loop nothing is loaded
     // into registers from global memory: the wait for such a load would also wait for every tile copy in flight.
     const int grp = a.group;
+    constexpr bool VGPR_CHAINS = D == 128 && LSRM_BWD_VGPR_CHAINS;  // (the kernel has one wavefront per SIMD: see mfma_v)
     constexpr int NB = LSRM_BWD_DKV_NBUF;  // tile buffers: the copies run NB - 1 steps ahead of the arithmetic
-    constexpr int IPW = G::ROW / 1024;     // copy instructions per wavefront and step (wavefront 0: one more, the table)
+    constexpr int IPW = G::ROW / 1024;    // copy instructions per wavefront and step (wavefront 0: one more, the table)
     static_assert(NB == 2 || NB == 3, "");
     // br_c: the branch whose probabilities these are (0 compressed, 1 selected, 2 window); tile_fn(t): the t-th query
     // tile of the segment (arithmetic on registers only); every tile is met by the grp query heads of this key/value
@@ -729,6 +744,103 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
                 ++tt;
             }
         };
+        // ---- the pieces of a step (one 32-query tile against this wavefront's 32 keys)
+        struct Tile {
+            const char *buf;  // its buffer: Q rows | dO rows | table
+            int q0;           // first query of the tile
+            bool win;         // a window tile at the band's edge: positions outside the band are masked
+            f32x16 s, dp;
+            float p[16];
+        };
+        // S = Q K^T
+        auto ph_scores = [&](Tile &x, const char *buf, int tile) {
+            x.buf = buf;
+            x.q0 = 32 * tile;
+            // window tiles away from the band's edges (and all routed tiles) need no mask
+            x.win = BR == 2 && ((int)key0 - (x.q0 + 31) < -half_w || (int)key0 + 31 - x.q0 >= half_w);
+            const char *base = buf + row_off;
+            if constexpr (VGPR_CHAINS) {
+                mfma_v_first(x.s, *reinterpret_cast<const bf16x8 *>(base), kB[0]);
+#pragma unroll
+                for (int ks = 1; ks < NS; ++ks) mfma_v(x.s, *reinterpret_cast<const bf16x8 *>(base + ks * 1024), kB[ks]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x.s[i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < NS; ++ks)
+                    x.s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024),
+                                                                  kB[ks], x.s, 0, 0, 0);
+            }
+        };
+        // dP - D = dout V^T - D: the accumulator starts from -D of the 16 query rows this lane holds (second half
+        // of the table, rows (i/4)*8 + hh*4 + i%4)
+        auto ph_dp = [&](Tile &x) {
+            const char *base = x.buf + row_off;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 y = *reinterpret_cast<const f32x4 *>(x.buf + AUX + 128 + (8 * g + 4 * hh) * 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) x.dp[4 * g + j] = y[j];
+            }
+#pragma unroll
+            for (int ks = 0; ks < NS; ++ks) {
+                const bf16x8 rows = *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024);
+                if constexpr (VGPR_CHAINS)
+                    mfma_v(x.dp, rows, vB[ks]);
+                else
+                    x.dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows, vB[ks], x.dp, 0, 0, 0);
+            }
+        };
+        // P = exp2(S scale log2e - offset), the offsets of the query rows from the first half of the table
+        // (read right before their use: fewer registers live at once)
+        auto ph_exp = [&](Tile &x) {
+            float lv[16];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 y = *reinterpret_cast<const f32x4 *>(x.buf + AUX + (8 * g + 4 * hh) * 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) lv[4 * g + j] = y[j];
+            }
+            // Most tiles need no mask at all (wave-uniform test): routed tiles and window tiles inside the band, of
+            // blocks without padding; pooled keys before the last block.
+            const bool plain = MODE == 1 ? key0 + 32 <= limit : (!x.win && n_act == 64);
+            if constexpr (VGPR_CHAINS) mfma_v_settle(x.s);
+            if (__builtin_expect(plain, 1)) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x.p[i] = __builtin_amdgcn_exp2f(x.s[i] * a.sl2 - lv[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float pi = __builtin_amdgcn_exp2f(x.s[i] * a.sl2 - lv[i]);
+                    bool ok;
+                    if (MODE == 1) {
+                        ok = key < limit;
+                    } else {
+                        const int qi = x.q0 + (i % 8) + 8 * hh + 16 * (i / 8);  // the query behind accumulator row i
+                        const int dj = (int)key - qi;
+                        ok = key_active & (!x.win | ((dj >= -half_w) & (dj < half_w)));
+                    }
+                    x.p[i] = ok ? pi : 0.f;
+                }
+            }
+        };
+        // dV^T += dout^T P
+        auto ph_dv = [&](Tile &x) {
+            BFrag pb[2];
+            to_b_operand(x.p, pb);
+            mfma_tr<ND>(accv, x.buf + G::ROW, tr_off, pb);
+        };
+        // dS = P o (dP - D), dK^T += Q^T dS
+        auto ph_dk = [&](Tile &x) {
+            if constexpr (VGPR_CHAINS) mfma_v_settle(x.dp);
+            float ds[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ds[i] = x.p[i] * x.dp[i];
+            BFrag dsb[2];
+            to_b_operand(ds, dsb);
+            mfma_tr<ND>(acck, x.buf, tr_off, dsb);
+        };
+
         __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         __syncthreads();  // both wavefronts are done with the buffers (previous segment)
         for (int i = 0; i < NB - 1 && i < U; ++i) {
@@ -754,79 +866,15 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
                 issue(t_nxt, gh_nxt, lds + fill * TILE);
                 advance(t_nxt, gh_nxt);
             }
-            const char *buf = lds + slot * TILE;
-            const char *base = buf + row_off;
-            const int q0 = 32 * (int)tile_fn(t);
-            // window tiles away from the band's edges (and all routed tiles) need no mask
-            const bool win = BR == 2 && ((int)key0 - (q0 + 31) < -half_w || (int)key0 + 31 - q0 >= half_w);
-
-            f32x16 s;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[i] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < NS; ++ks)
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), kB[ks], s,
-                                                            0, 0, 0);
-            // table entries of the 16 query rows this lane holds: rows (i/4)*8 + hh*4 + i%4  (each half of the table
-            // is read right before its use: fewer registers live at once)
-            float lv[16];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 x = *reinterpret_cast<const f32x4 *>(buf + AUX + (8 * g + 4 * hh) * 4);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) lv[4 * g + j] = x[j];
-            }
-            // dP = dout V^T does not depend on the probabilities.  With one wavefront per SIMD (d = 128) nothing else
-            // runs under the exponentials, so its MFMAs are issued before them (LSRM_BWD_EARLY_DP); with three
-            // wavefronts per SIMD the extra live accumulator would cost the third one, and the other wavefronts
-            // fill the gap anyway.
-            constexpr bool EARLY_DP = D == 128 && LSRM_BWD_EARLY_DP;
-            f32x16 dp;  // starts from -D of the 16 query rows (second half of the table): the MFMAs leave dP - D
-            auto dp_mfmas = [&]() {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) dp[4 * g + j] = y[j];
-                }
-#pragma unroll
-                for (int ks = 0; ks < NS; ++ks)
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), vB[ks], dp, 0, 0, 0);
-            };
-            if constexpr (EARLY_DP) dp_mfmas();
-            // Most tiles need no mask at all (wave-uniform test): routed tiles and window tiles inside the band, of
-            // blocks without padding; pooled keys before the last block.
-            const bool plain = MODE == 1 ? key0 + 32 <= limit : (!win && n_act == 64);
-            float p[16];
-            if (__builtin_expect(plain, 1)) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lv[i]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float pi = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lv[i]);
-                    bool ok;
-                    if (MODE == 1) {
-                        ok = key < limit;
-                    } else {
-                        const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);  // the query behind accumulator row i
-                        const int dj = (int)key - qi;
-                        ok = key_active & (!win | ((dj >= -half_w) & (dj < half_w)));
-                    }
-                    p[i] = ok ? pi : 0.f;
-                }
-            }
-            BFrag pb[2];
-            to_b_operand(p, pb);
-            mfma_tr<ND>(accv, buf + G::ROW, tr_off, pb);
-            if constexpr (!EARLY_DP) dp_mfmas();
-            float ds[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) ds[i] = p[i] * dp[i];
-            BFrag dsb[2];
-            to_b_operand(ds, dsb);
-            mfma_tr<ND>(acck, buf, tr_off, dsb);
+            // (dP does not depend on the probabilities, but issuing its MFMAs before the exponentials measured no
+            // faster, and its accumulator live across them would cost the third wavefront per SIMD at d <= 64;
+            // working on two steps at once at d = 128 was slower: the registers no longer fit)
+            Tile x;
+            ph_scores(x, lds + slot * TILE, tile_fn(t));
+            ph_exp(x);
+            ph_dv(x);
+            ph_dp(x);
+            ph_dk(x);
         }
     };
     if (MODE == 1) {
