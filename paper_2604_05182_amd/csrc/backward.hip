@@ -76,6 +76,10 @@ struct BwdArgs {
     const int32_t *count;  // nullable [NB]: active tokens per block; the other slots are neither queries nor keys
     int nt;               // query / key tiles of 32 tokens
     int n_split, nbp, tiles_per_split;
+    // token keys with grouped-query heads: the query heads of a group are dealt to hsplit workgroups, hpw heads each,
+    // whose fp32 sums [hsplit][NB * 64][H_kv][d] a last pass adds up in order (hsplit == 1: no such pass)
+    int hsplit, hpw;
+    float *hpart_k, *hpart_v;
     float scale, sl2;
 };
 
@@ -647,7 +651,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     constexpr int TILE = 2 * G::ROW + 1024;  // (table padded to keep the next buffer aligned)
     static_assert(2 * 32 * G::OUT_ROW <= LSRM_BWD_DKV_NBUF * TILE, "output staging fits in the tile buffers");
     extern __shared__ __attribute__((aligned(1024))) char lds[];  // LSRM_BWD_DKV_NBUF * TILE bytes
-    const int n_kb = MODE == 0 ? a.nb : a.nbp / 64;
+    const int n_kb = MODE != 1 ? a.nb : a.nbp / 64;
     const int per_xcd = (n_kb + 7) / 8;
     const int kb = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), head = blockIdx.y;  // (see bwd_dq_kernel)
     if (kb >= n_kb) return;
@@ -659,17 +663,17 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     const uint32_t tr_off = tr_lane_offset(lane), row_off = row_lane_offset(lane);
     const int64_t key0 = (int64_t)kb * 64 + 32 * wave;  // token index (MODE 0) or pooled-key index (MODE 1)
     const int64_t key = key0 + r;
-    const int64_t limit = MODE == 0 ? a.n : (int64_t)a.nb;
+    const int64_t limit = MODE != 1 ? a.n : (int64_t)a.nb;
     const int half_w = a.window / 2;
     // MODE 0 with per-block counts: a padding slot is nobody's key (its probabilities are zeroed) and gets a zero gradient
-    const int n_act = MODE == 0 && a.count != nullptr ? a.count[kb] : 64;
+    const int n_act = MODE != 1 && a.count != nullptr ? a.count[kb] : 64;
     const bool key_active = MODE == 1 || 32 * wave + r < n_act;
 
     bf16x8 kB[NS], vB[NS];
     {
         const int64_t krow_i = key < limit ? key : limit - 1;  // (rows past the end are masked below)
-        const uint16_t *krow = (MODE == 0 ? a.k : a.kc) + (krow_i * a.h_kv + head) * D + 8 * hh;
-        const uint16_t *vrow = (MODE == 0 ? a.v : a.vc) + (krow_i * a.h_kv + head) * D + 8 * hh;
+        const uint16_t *krow = (MODE != 1 ? a.k : a.kc) + (krow_i * a.h_kv + head) * D + 8 * hh;
+        const uint16_t *vrow = (MODE != 1 ? a.v : a.vc) + (krow_i * a.h_kv + head) * D + 8 * hh;
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks) {
             kB[ks] = *reinterpret_cast<const bf16x8 *>(krow + 16 * ks);
@@ -714,7 +718,10 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     // The walk is cut into segments with one pipelined loop each: the window tiles, then the routed tiles 64
     // reverse-list entries at a time (one entry per lane, loaded before the loop).  Inside a loop nothing is loaded
     // into registers from global memory: the wait for such a load would also wait for every tile copy in flight.
-    const int grp = a.group;
+    // the query heads of the group this workgroup walks: all of them, or (token keys, heads dealt to hsplit
+    // workgroups) its share
+    const int gh0 = MODE == 0 && a.hsplit > 1 ? (int)blockIdx.z * a.hpw : 0;
+    const int grp = MODE == 0 && a.hsplit > 1 ? min(a.group, gh0 + a.hpw) - gh0 : a.group;
     constexpr bool VGPR_CHAINS = D == 128 && LSRM_BWD_VGPR_CHAINS;  // (the kernel has one wavefront per SIMD: see mfma_v)
     constexpr int NB = LSRM_BWD_DKV_NBUF;  // tile buffers: the copies run NB - 1 steps ahead of the arithmetic
     constexpr int IPW = G::ROW / 1024;    // copy instructions per wavefront and step (wavefront 0: one more, the table)
@@ -730,7 +737,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
         const float *aux_br = a.aux + (int64_t)BR * a.nt * a.h * 64;  // table of this branch: [tile][head][64]
         auto issue = [&](int t, int gh, char *buf) {
             // (tile, head) index in 32 bits, byte offsets by shifts: a 64-bit multiply is several scalar instructions
-            const uint32_t ih = (uint32_t)tile_fn(t) * (uint32_t)a.h + (uint32_t)(head * grp + gh);
+            const uint32_t ih = (uint32_t)tile_fn(t) * (uint32_t)a.h + (uint32_t)(head * a.group + gh0 + gh);
             const int64_t off = (int64_t)ih * G::IMG;
             copy_kb<G::ROW / 1024>(a.img_q + off, buf, wave, lane16);
             copy_kb<G::ROW / 1024>(img_do + off, buf + G::ROW, wave, lane16);
@@ -879,7 +886,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     };
     if (MODE == 1) {
         run_segment(T, std::integral_constant<int, 0>{}, [&](int t) { return wt0 + t; });
-    } else {
+    } else if (MODE == 0) {
         run_segment(tw, std::integral_constant<int, 2>{}, [&](int t) { return wt0 + t; });
         const int n_e = ts >> 1;  // entries of the reverse list: query blocks that route to this key block
         for (int c0 = 0; c0 < n_e; c0 += 64) {
@@ -890,6 +897,42 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
         }
     }
 
+    if (MODE == 0 && a.hsplit > 1) {
+        // the sums over this workgroup's heads: [head range][key][head][channel] fp32; the last pass finishes the rows
+        const int64_t o = ((((int64_t)blockIdx.z * a.nb * 64) + key) * a.h_kv + head) * D;
+#pragma unroll
+        for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 xk, xv;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    xk[j] = acck[dt][4 * g + j];
+                    xv[j] = accv[dt][4 * g + j];
+                }
+                *reinterpret_cast<f32x4 *>(a.hpart_k + o + 32 * dt + 8 * g + 4 * hh) = xk;
+                *reinterpret_cast<f32x4 *>(a.hpart_v + o + 32 * dt + 8 * g + 4 * hh) = xv;
+            }
+        return;
+    }
+    if (MODE == 2) {
+        // last pass: the sums of the head ranges, added in order
+        for (int z = 0; z < a.hsplit; ++z) {
+            const int64_t o = ((((int64_t)z * a.nb * 64) + key) * a.h_kv + head) * D;
+#pragma unroll
+            for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 xk = *reinterpret_cast<const f32x4 *>(a.hpart_k + o + 32 * dt + 8 * g + 4 * hh);
+                    const f32x4 xv = *reinterpret_cast<const f32x4 *>(a.hpart_v + o + 32 * dt + 8 * g + 4 * hh);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        acck[dt][4 * g + j] += xk[j];
+                        accv[dt][4 * g + j] += xv[j];
+                    }
+                }
+        }
+    }
     if (MODE == 1) {
         // partial sums of this query range: [split][pooled key][head][channel] fp32
         const int64_t o = (((int64_t)split * a.nbp + key) * a.h_kv + head) * D;
@@ -937,7 +980,8 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
 
 struct WsLayout {
     size_t img_q, img_do[3], gdo, img_k, img_v, img_kc, img_vc, aux, part_k, part_v, rev_cnt, rev_ptr, rev_cur, rev_idx, total;
-    int n_split, nbp, tiles_per_split;
+    int n_split, nbp, tiles_per_split, hsplit, hpw;
+    size_t hpart_k, hpart_v;
 };
 
 WsLayout ws_layout(const Shape &s) {
@@ -970,12 +1014,23 @@ WsLayout ws_layout(const Shape &s) {
     w.nbp = (s.nb + 63) / 64 * 64;
     const int wgs = (w.nbp / 64) * s.h_kv;
     int n_split = (2048 + wgs - 1) / wgs;
-    n_split = n_split < 1 ? 1 : (n_split > 16 ? 16 : n_split);
+    n_split = n_split < 1 ? 1 : (n_split > 64 ? 64 : n_split);
     w.tiles_per_split = (int)((nt + n_split - 1) / n_split);
     w.n_split = (int)((nt + w.tiles_per_split - 1) / (w.tiles_per_split > 0 ? w.tiles_per_split : 1));
     if (w.n_split < 1) w.n_split = 1;
     w.part_k = take((size_t)w.n_split * w.nbp * s.h_kv * s.d * 4);
     w.part_v = take((size_t)w.n_split * w.nbp * s.h_kv * s.d * 4);
+    // token keys: with grouped-query heads a workgroup would walk group x as many steps while there are group x
+    // fewer workgroups, and the longest reverse list sets the kernel's time -- deal the heads of a group to
+    // up to 8 workgroups
+    const int grp = s.h / s.h_kv;
+    w.hpw = (grp + 7) / 8;
+    w.hsplit = (grp + w.hpw - 1) / w.hpw;
+    w.hpart_k = w.hpart_v = 0;
+    if (w.hsplit > 1) {
+        w.hpart_k = take((size_t)w.hsplit * s.nb * 64 * s.h_kv * s.d * 4);
+        w.hpart_v = take((size_t)w.hsplit * s.nb * 64 * s.h_kv * s.d * 4);
+    }
     w.rev_cnt = take((size_t)s.nb * 4);
     w.rev_ptr = take((size_t)(s.nb + 1) * 4);
     w.rev_cur = take((size_t)s.nb * 4);
@@ -994,6 +1049,8 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
         LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 0>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
         LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
+        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 2>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
         attr_set = true;
     }
@@ -1039,8 +1096,12 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3((w.nbp / 64 + 7) / 8 * 8, s.h_kv, w.n_split), dim3(128), DKV_LDS, st,
                        a);
     LSRM_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3((s.nb + 7) / 8 * 8, s.h_kv), dim3(128), DKV_LDS, st, a);
+    hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3((s.nb + 7) / 8 * 8, s.h_kv, a.hsplit), dim3(128), DKV_LDS, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
+    if (a.hsplit > 1) {  // add up the per-head-range sums, in order, and finish the rows
+        hipLaunchKernelGGL((bwd_dkv_kernel<D, 2>), dim3((s.nb + 7) / 8 * 8, s.h_kv), dim3(128), DKV_LDS, st, a);
+        LSRM_HIP_CHECK(hipGetLastError());
+    }
     if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;
 }
@@ -1100,6 +1161,10 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     a.n_seg = n_seg;
     a.nt = s.nb * 2;
     a.n_split = w.n_split;
+    a.hsplit = w.hsplit;
+    a.hpw = w.hpw;
+    a.hpart_k = reinterpret_cast<float *>(ws + w.hpart_k);
+    a.hpart_v = reinterpret_cast<float *>(ws + w.hpart_v);
     a.nbp = w.nbp;
     a.tiles_per_split = w.tiles_per_split;
     a.scale = s.scale;
