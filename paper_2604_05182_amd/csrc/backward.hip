@@ -80,6 +80,7 @@ struct BwdArgs {
     // whose fp32 sums [hsplit][NB * 64][H_kv][d] a last pass adds up in order (hsplit == 1: no such pass)
     int hsplit, hpw;
     float *hpart_k, *hpart_v;
+    const int32_t *order;  // [NB] key blocks, longest reverse list first: the order the token-key workgroups start in
     float scale, sl2;
 };
 
@@ -346,6 +347,29 @@ __global__ __launch_bounds__(1024) void rev_scan(BwdArgs a) {
         run += a.rev_cnt[i];
     }
     if (t == 1023) a.rev_ptr[a.nb] = part[1023];
+}
+// The key blocks in order of falling reverse-list length (within 1024 length classes; equal lengths in any
+// order -- it only decides which workgroup starts when).  The token-key dK/dV workgroups take their block from
+// this list: the long walks start first instead of forming the tail of the kernel, and the round-robin of
+// workgroups over the XCDs spreads them, where a contiguous range of blocks per XCD left the popular blocks
+// (say, all image blocks) to one or two XCDs.
+__global__ __launch_bounds__(1024) void rev_order(BwdArgs a, int32_t *order) {
+    __shared__ int bin[1024];
+    const int t = threadIdx.x;
+    bin[t] = 0;
+    __syncthreads();
+    for (int b = t; b < a.nb; b += 1024) atomicAdd(&bin[min(a.rev_cnt[b], 1023)], 1);
+    __syncthreads();
+    if (t == 0) {  // start of each class, longest first
+        int run = 0;
+        for (int c = 1023; c >= 0; --c) {
+            const int n = bin[c];
+            bin[c] = run;
+            run += n;
+        }
+    }
+    __syncthreads();
+    for (int b = t; b < a.nb; b += 1024) order[atomicAdd(&bin[min(a.rev_cnt[b], 1023)], 1)] = b;
 }
 __global__ void rev_fill(BwdArgs a) {
     int e = blockIdx.x * blockDim.x + threadIdx.x;
@@ -653,8 +677,15 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     extern __shared__ __attribute__((aligned(1024))) char lds[];  // LSRM_BWD_DKV_NBUF * TILE bytes
     const int n_kb = MODE != 1 ? a.nb : a.nbp / 64;
     const int per_xcd = (n_kb + 7) / 8;
-    const int kb = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), head = blockIdx.y;  // (see bwd_dq_kernel)
-    if (kb >= n_kb) return;
+    const int head = blockIdx.y;
+    int kb;
+    if (MODE == 0) {  // token keys: longest walk first (see rev_order)
+        if ((int)blockIdx.x >= n_kb) return;
+        kb = a.order[blockIdx.x];
+    } else {
+        kb = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);  // (see bwd_dq_kernel)
+        if (kb >= n_kb) return;
+    }
     const int split = MODE == 1 ? blockIdx.z : 0;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -981,7 +1012,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
 struct WsLayout {
     size_t img_q, img_do[3], gdo, img_k, img_v, img_kc, img_vc, aux, part_k, part_v, rev_cnt, rev_ptr, rev_cur, rev_idx, total;
     int n_split, nbp, tiles_per_split, hsplit, hpw;
-    size_t hpart_k, hpart_v;
+    size_t hpart_k, hpart_v, order;
 };
 
 WsLayout ws_layout(const Shape &s) {
@@ -1032,6 +1063,7 @@ WsLayout ws_layout(const Shape &s) {
         w.hpart_v = take((size_t)w.hsplit * s.nb * 64 * s.h_kv * s.d * 4);
     }
     w.rev_cnt = take((size_t)s.nb * 4);
+    w.order = take((size_t)s.nb * 4);
     w.rev_ptr = take((size_t)(s.nb + 1) * 4);
     w.rev_cur = take((size_t)s.nb * 4);
     w.rev_idx = take((size_t)s.nb * (s.topk > 0 ? s.topk : 1) * 4);
@@ -1080,6 +1112,8 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
         LSRM_HIP_CHECK(hipGetLastError());
     }
     hipLaunchKernelGGL(rev_scan, dim3(1), dim3(1024), 0, st, a);
+    LSRM_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(rev_order, dim3(1), dim3(1024), 0, st, a, const_cast<int32_t *>(a.order));
     LSRM_HIP_CHECK(hipGetLastError());
     if (s.topk > 0) {
         hipLaunchKernelGGL(rev_fill, dim3((s.nb * s.topk + 255) / 256), dim3(256), 0, st, a);
@@ -1165,6 +1199,7 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     a.hpw = w.hpw;
     a.hpart_k = reinterpret_cast<float *>(ws + w.hpart_k);
     a.hpart_v = reinterpret_cast<float *>(ws + w.hpart_v);
+    a.order = reinterpret_cast<const int32_t *>(ws + w.order);
     a.nbp = w.nbp;
     a.tiles_per_split = w.tiles_per_split;
     a.scale = s.scale;
