@@ -244,60 +244,66 @@ __device__ __forceinline__ void store_rows_transposed(const float (&x)[D / 32][1
 
 // ---------------------------------------------------------------------------------------------
 // per (token, head): the per-branch exponent offset and D = dout . o_branch, in tile-image row order
+// Threads: 8 channels each.  A workgroup takes one query tile and PREP_HB heads: thread = (head, row of the tile,
+// 16-byte chunk of the row), chunks fastest, so a row's d channels are read by d / 8 neighbouring lanes (16-byte
+// loads, contiguous per row) and the 32 table entries of a (tile, head) are written from one wavefront, side by side.
 template <int D>
-__global__ __launch_bounds__(256) void bwd_prep(BwdArgs a) {
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= a.n * a.h) return;
-    const int64_t row = e / a.h;
-    const int head = (int)(e % a.h);
-    const uint4 *dor = reinterpret_cast<const uint4 *>(a.dout + (row * a.h + head) * D);
-    float dov[D];
-#pragma unroll
-    for (int c = 0; c < D / 8; ++c) {
-        uint4 w = dor[c];
-        uint32_t u[4] = {w.x, w.y, w.z, w.w};
+struct PrepGeo {
+    static constexpr int CH = D / 8;                            // chunks = lanes per (row, head)
+    static constexpr int HB = CH * 32 >= 256 ? 1 : 256 / (CH * 32);  // heads per workgroup
+    static constexpr int THREADS = HB * 32 * CH;
+};
+template <int D>
+__global__ __launch_bounds__(PrepGeo<D>::THREADS) void bwd_prep(BwdArgs a) {
+    using P = PrepGeo<D>;
+    constexpr int CH = P::CH;
+    const int c = threadIdx.x % CH, r = (threadIdx.x / CH) % 32;
+    const int heads_x = (a.h + P::HB - 1) / P::HB;
+    const int64_t tile = blockIdx.x / heads_x;
+    const int head = (int)(blockIdx.x % heads_x) * P::HB + threadIdx.x / (CH * 32);
+    if (head >= a.h) return;  // (whole groups of CH lanes leave together)
+    const int64_t row = tile * 32 + r;
+    float dov[8];
+    {
+        const uint4 w = *reinterpret_cast<const uint4 *>(a.dout + (row * a.h + head) * D + 8 * c);
+        const uint32_t u[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            dov[8 * c + 2 * j] = bf16_lo(u[j]);
-            dov[8 * c + 2 * j + 1] = bf16_hi(u[j]);
+            dov[2 * j] = bf16_lo(u[j]);
+            dov[2 * j + 1] = bf16_hi(u[j]);
         }
     }
-    const int64_t tile = row >> 5;
-    const int pr = perm32((int)(row & 31));
+    const int pr = perm32(r);
     // a padding slot is no query: zero probabilities (offset +inf) and a zero D in every branch
     const bool padding = a.count != nullptr && (int)(row & 63) >= a.count[row >> 6];
 #pragma unroll
     for (int b = 0; b < 3; ++b) {
-        const uint4 *obr = reinterpret_cast<const uint4 *>(a.out_branch + (((int64_t)b * a.n + row) * a.h + head) * D);
+        const uint4 w = *reinterpret_cast<const uint4 *>(a.out_branch + (((int64_t)b * a.n + row) * a.h + head) * D + 8 * c);
+        const uint32_t u[4] = {w.x, w.y, w.z, w.w};
         float dl = 0.f;
         if (a.gate_channels) {
             // the gradient reaching this branch is gate o dout, channel by channel: D uses it, and its
             // bf16 rounding is kept for the contractions
-            const float *gch = a.gates + ((row * 3 + b) * a.h + head) * D;
-            uint4 *gdo = reinterpret_cast<uint4 *>(const_cast<uint16_t *>(a.gdo) + (((int64_t)b * a.n + row) * a.h + head) * D);
+            const f32x4 *gch = reinterpret_cast<const f32x4 *>(a.gates + ((row * 3 + b) * a.h + head) * D + 8 * c);
+            const f32x4 g_lo = gch[0], g_hi = gch[1];
+            const float g[8] = {g_lo[0], g_lo[1], g_lo[2], g_lo[3], g_hi[0], g_hi[1], g_hi[2], g_hi[3]};
+            uint32_t o4[4];
 #pragma unroll
-            for (int c = 0; c < D / 8; ++c) {
-                uint4 w = obr[c];
-                uint32_t u[4] = {w.x, w.y, w.z, w.w}, o4[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float g0 = gch[8 * c + 2 * j] * dov[8 * c + 2 * j];
-                    const float g1 = gch[8 * c + 2 * j + 1] * dov[8 * c + 2 * j + 1];
-                    dl += g0 * bf16_lo(u[j]) + g1 * bf16_hi(u[j]);
-                    o4[j] = pack_bf16(g0, g1);
-                }
-                gdo[c] = make_uint4(o4[0], o4[1], o4[2], o4[3]);
+            for (int j = 0; j < 4; ++j) {
+                const float g0 = g[2 * j] * dov[2 * j], g1 = g[2 * j + 1] * dov[2 * j + 1];
+                dl += g0 * bf16_lo(u[j]) + g1 * bf16_hi(u[j]);
+                o4[j] = pack_bf16(g0, g1);
             }
+            *reinterpret_cast<uint4 *>(const_cast<uint16_t *>(a.gdo) + (((int64_t)b * a.n + row) * a.h + head) * D + 8 * c) =
+                make_uint4(o4[0], o4[1], o4[2], o4[3]);
         } else {
 #pragma unroll
-            for (int c = 0; c < D / 8; ++c) {
-                uint4 w = obr[c];
-                uint32_t u[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    dl += dov[8 * c + 2 * j] * bf16_lo(u[j]) + dov[8 * c + 2 * j + 1] * bf16_hi(u[j]);
-            }
+            for (int j = 0; j < 4; ++j) dl += dov[2 * j] * bf16_lo(u[j]) + dov[2 * j + 1] * bf16_hi(u[j]);
         }
+        // D of the row: the sum over its CH lanes, in a fixed order
+#pragma unroll
+        for (int m = 1; m < CH; m <<= 1) dl += __shfl_xor(dl, m);
+        if (c != 0) continue;
         const float lse = a.lse[((int64_t)b * a.n + row) * a.h + head];
         // an empty key set (lse = -inf) or a zero gate gives zero probabilities: offset +inf
         float l2 = __builtin_inff();
@@ -1089,7 +1095,8 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
     const int ntc = (s.nb + 31) / 32;
     lsrm_status rc;
-    hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)((s.n * s.h + 255) / 256)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)(a.nt * ((s.h + PrepGeo<D>::HB - 1) / PrepGeo<D>::HB))),
+                       dim3(PrepGeo<D>::THREADS), 0, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     if ((rc = launch_pack_tiles(D, a.q, a.q, ws + w.img_q, s.n, s.h, a.nt, st, true, a.count)) != LSRM_OK) return rc;
     if (s.gate_channels) {
