@@ -35,6 +35,9 @@
 #ifndef LSRM_BWD_VGPR_CHAINS
 #define LSRM_BWD_VGPR_CHAINS 1
 #endif
+#ifndef LSRM_BWD_SPLIT_TARGET
+#define LSRM_BWD_SPLIT_TARGET 2048
+#endif
 #ifndef LSRM_BWD_DKV_NBUF
 #define LSRM_BWD_DKV_NBUF 2  // (3, copies two steps ahead with counted waits, was measured: no faster)
 #endif
@@ -1050,7 +1053,10 @@ WsLayout ws_layout(const Shape &s) {
     // pooled keys: enough query ranges to fill the chip
     w.nbp = (s.nb + 63) / 64 * 64;
     const int wgs = (w.nbp / 64) * s.h_kv;
-    int n_split = (2048 + wgs - 1) / wgs;
+    // (more ranges mean more partial sums to write; with grouped-query heads a workgroup's walk is group x as long
+    // and twice as many ranges measured faster, without them slower)
+    const int target = s.h > s.h_kv ? 2 * LSRM_BWD_SPLIT_TARGET : LSRM_BWD_SPLIT_TARGET;
+    int n_split = (target + wgs - 1) / wgs;
     n_split = n_split < 1 ? 1 : (n_split > 64 ? 64 : n_split);
     w.tiles_per_split = (int)((nt + n_split - 1) / n_split);
     w.n_split = (int)((nt + w.tiles_per_split - 1) / (w.tiles_per_split > 0 ? w.tiles_per_split : 1));
