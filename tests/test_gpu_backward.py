@@ -102,7 +102,9 @@ def test_backward_own_block_window(B, oracle_lib):
 @pytest.mark.parametrize("d,heads,h_kv,gate_channels", [(64, 6, 2, False), (64, 2, 2, True), (64, 4, 1, True),
                                                         (32, 2, 2, False), (128, 2, 2, False), (128, 4, 2, True),
                                                         # the paper's heads in small: 16 query heads per key/value head
-                                                        (32, 32, 2, True)])
+                                                        (32, 32, 2, True),
+                                                        # 9 query heads per key/value head: head ranges of 2, 2, 2, 2, 1
+                                                        (32, 18, 2, False)])
 def test_backward_head_shapes_and_gates(B, oracle_lib, d, heads, h_kv, gate_channels):
     """Head dimensions 32 / 64 / 128, query heads sharing key/value heads (a key/value head collects the
     gradients of its whole group), one gate per output channel; ragged block count, holes in the table."""
