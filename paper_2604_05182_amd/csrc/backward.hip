@@ -12,18 +12,22 @@
 // No floating-point atomics: the work is split into passes that each own their output rows.
 //   bwd_dq_kernel    one workgroup per (query block, head): walks the same key tiles as the forward
 //                    (pooled, routed, window) and accumulates dQ^T in registers.
-//   bwd_dkv_kernel   one workgroup per (key block, head): walks the query tiles that attend it --
+//   bwd_dkv_kernel   one workgroup per (key block, key/value head): walks the query tiles that attend it --
 //                    MODE 1: pooled keys, every query tile of the sequence (split into ranges whose
 //                    partial sums are added in order by MODE 0); MODE 0: token keys, the query tiles
-//                    of the window and of the reverse routing list (query blocks in ascending order)
-//                    -- accumulates dK^T and dV^T in registers, adds the pooled gradients / 64.
+//                    of the window and of the reverse routing list (query blocks in ascending order),
+//                    key blocks taken longest list first -- accumulates dK^T and dV^T in registers, adds
+//                    the pooled gradients / 64.  With grouped-query heads the heads of a group are dealt to
+//                    several workgroups, whose sums MODE 2 adds in order before finishing the rows.
 // Every operand tile is a "tile image" (see forward.hip): MFMA A-operand fragments in row order
 // (rows permuted so that an accumulator is directly the B operand of the next contraction); the
-// fragments of the transposed tile are read out of the same bytes in LDS (see read_tr).  The transposed S^T = K Q^T form of the forward is
+// fragments of the transposed tile are read out of the same bytes in LDS (see mfma_tr).  The
+// transposed S^T = K Q^T form of the forward is
 // used in the dQ pass (one query per lane: lse and D are per-lane scalars); the dK/dV pass uses
 // S = Q K^T (one key per lane; lse and D of the 32 queries of the tile come from a small
 // per-tile table copied to LDS with the tile).
-// Steps are not software pipelined: copy of tile t+1 (LDS DMA) overlaps the arithmetic of tile t.
+// Steps are not software pipelined: the copy of tile t+1 (global -> LDS) overlaps the arithmetic of tile t, and
+// nothing inside a loop may make the compiler wait for all memory operations (see tr_issue, run_segment).
 #include "lsrm_internal.h"
 
 #include <type_traits>
