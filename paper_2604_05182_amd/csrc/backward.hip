@@ -463,7 +463,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     // (at d = 128 the 256-register budget of two workgroups per SIMD still holds: 64 accumulator registers)
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
-    constexpr int TILE = 2 * G::ROW;     // K rows | V rows (K^T is read out of the K rows, see read_tr)
+    constexpr int TILE = 2 * G::ROW;     // K rows | V rows (K^T is read out of the K rows, see mfma_tr)
     constexpr int NBUF = LSRM_BWD_NBUF;  // tile buffers: copies run NBUF - 1 tiles ahead
     constexpr int IPW = G::ROW / 1024;   // copy instructions per wavefront and tile
     static_assert((G::ROW / 1024) % 2 == 0, "");
@@ -684,7 +684,7 @@ template <int D, int MODE>
 __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArgs a) {
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
-    constexpr int AUX = 2 * G::ROW;          // Q rows | dO rows | table (64 floats); Q^T and dO^T: see read_tr
+    constexpr int AUX = 2 * G::ROW;          // Q rows | dO rows | table (64 floats); Q^T and dO^T: see mfma_tr
     constexpr int TILE = 2 * G::ROW + 1024;  // (table padded to keep the next buffer aligned)
     static_assert(2 * 32 * G::OUT_ROW <= LSRM_BWD_DKV_NBUF * TILE, "output staging fits in the tile buffers");
     extern __shared__ __attribute__((aligned(1024))) char lds[];  // LSRM_BWD_DKV_NBUF * TILE bytes
