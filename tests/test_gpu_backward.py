@@ -65,12 +65,13 @@ def test_backward_ragged_and_holes(B, oracle_lib):
     _assert_grads(got, oracle_lib.nsa_backward(*args, scale=0.2), cfg.name)
 
 
-def test_backward_repeated_and_popular_blocks(B, oracle_lib):
+@pytest.mark.parametrize("d", [64, 128, 32])
+def test_backward_repeated_and_popular_blocks(B, oracle_lib, d):
     """Rows that list a block twice (it is attended twice) and one block that every row lists (a reverse list
-    longer than one 64-entry chunk), with a top-k of zero windows' worth and per-channel gates on grouped heads
+    longer than one 64-entry chunk, and by far the longest walk), with per-channel gates on grouped heads
     (the gradient rows change between branches even where a branch is empty)."""
-    cfg = I.small_config(name="b-repeat", n_obj=4096, n_views=2, grid=16, heads=4, d=64, topk=4, window=128, seed=27,
-                         h_kv=2, gate_channels=True)
+    cfg = I.small_config(name=f"b-repeat-d{d}", n_obj=4096, n_views=2, grid=16, heads=4, d=d, topk=4, window=128,
+                         seed=27, h_kv=2, gate_channels=True)
     _log(f"[backward] {cfg.name} nb={cfg.nb}")
     rng = np.random.default_rng(11)
     idx = np.stack([rng.choice(cfg.nb, size=cfg.topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
