@@ -182,6 +182,29 @@ def test_backward_config5_full_size_sampled(B, oracle_lib):
     assert all(np.isfinite(g).all() for g in got)
 
 
+def test_backward_wide_heads_many_tiles_sampled(B, oracle_lib):
+    """Head dimension 128 (the shape of config 4's heads) on a sequence long enough for thousands of workgroups,
+    several window tiles per key block and reverse lists of uneven length: sampled like the test above, plus
+    two runs compared bit for bit."""
+    cfg = I.small_config(name="b-d128-mid", n_obj=32768, n_views=4, grid=64, heads=2, d=128, topk=16, window=512,
+                         seed=61)
+    qblocks = I.sample_query_blocks(cfg, 3)
+    kblocks = I.sample_query_blocks(cfg, 2, seed=5)[::2]
+    heads = [0, 1]
+    _log(f"[backward] {cfg.name}: N {cfg.n}; oracle on {len(qblocks)} query blocks, {len(kblocks)} key blocks")
+    got, args = _case(B, oracle_lib, cfg)
+    (q, k, v, kc, vc, idx, gates, seg_arr, window, dout) = args
+    ref = oracle_lib.nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg_arr, window, dout, qblocks, kblocks, heads)
+    rows_q = (np.asarray(qblocks)[:, None] * 64 + np.arange(64)[None]).reshape(-1)
+    rows_k = (np.asarray(kblocks)[:, None] * 64 + np.arange(64)[None]).reshape(-1)
+    sub = (got[0][rows_q][:, heads], got[1][rows_k][:, heads], got[2][rows_k][:, heads])
+    _assert_grads(sub, ref, cfg.name)
+    assert all(np.isfinite(g).all() for g in got)
+    again, _ = _case(B, oracle_lib, cfg)
+    for x, y in zip(got, again):
+        assert np.array_equal(x, y)
+
+
 def test_backward_is_deterministic(B, oracle_lib):
     cfg = I.small_config(name="b-det", n_obj=1024, n_views=2, grid=16, heads=2, d=64, topk=4, window=256)
     q_bits, k_bits, v_bits = I.make_qkv(cfg)
