@@ -290,6 +290,45 @@ def test_lse_normalises_scores(oracle_lib):
     assert abs(np.exp(s - lse[0, i, hh]).sum() - 1.0) < 1e-6
 
 
+def test_a_block_listed_twice_counts_twice(oracle_lib):
+    """A routing row may repeat a block; its keys then enter the selected softmax twice.  Closed forms:
+    a row [a, a] gives the output of [a] with the log-sum-exp raised by ln 2 (all weights doubled), and
+    a row [a, a, b] equals a softmax over a and b in which a's scores carry an extra ln 2 -- checked here
+    by comparing with [a, b] after that bias is folded into the keys of a copy of block a.  Gradients of
+    [a, a] equal those of [a] (each copy gets half the weight, the two add up)."""
+    cfg, q, k, v, gates, _ = _case(21, n_obj=256, n_views=0, grid=0, heads=1, d=8, topk=3, window=0)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    nb = cfg.nb
+    once = np.full((nb, 3), -1, dtype=np.int32)
+    twice = np.full((nb, 3), -1, dtype=np.int32)
+    once[:, 0] = (np.arange(nb) + 1) % nb
+    twice[:, 0] = twice[:, 1] = once[:, 0]
+    o1, l1, b1 = oracle_lib.nsa_forward(q, k, v, kc, vc, once, gates, seg, 0, want_lse=True, want_branches=True)
+    o2, l2, b2 = oracle_lib.nsa_forward(q, k, v, kc, vc, twice, gates, seg, 0, want_lse=True, want_branches=True)
+    assert np.abs(o1 - o2).max() < 1e-6
+    assert np.abs(l2[1] - l1[1] - np.log(2.0)).max() < 1e-6
+    dout = I.bf16_bits_to_f32(I.make_dout(cfg))
+    g1 = oracle_lib.nsa_backward(q, k, v, kc, vc, once, gates, seg, 0, dout)
+    g2 = oracle_lib.nsa_backward(q, k, v, kc, vc, twice, gates, seg, 0, dout)
+    for x, y in zip(g1, g2):
+        assert np.abs(x - y).max() < 1e-5 * max(1.0, np.abs(x).max())
+    # [a, a, b]: block a counted twice against block b counted once = a weight of 2 on a's probabilities
+    mixed = twice.copy()
+    mixed[:, 2] = (np.arange(nb) + 2) % nb
+    om = oracle_lib.nsa_forward(q, k, v, kc, vc, mixed, gates, seg, 0, want_lse=True, want_branches=True)[2][1]
+    scale = 1.0 / np.sqrt(cfg.d)
+    for i in (0, 70, 200):
+        a, b = mixed[i // 64, 0], mixed[i // 64, 2]
+        ka = k[64 * a:64 * a + 64, 0].astype(np.float64)
+        kb = k[64 * b:64 * b + 64, 0].astype(np.float64)
+        sa, sb = ka @ q[i, 0] * scale, kb @ q[i, 0] * scale
+        m = max(sa.max(), sb.max())
+        wa, wb = 2.0 * np.exp(sa - m), np.exp(sb - m)
+        ref = (wa @ v[64 * a:64 * a + 64, 0] + wb @ v[64 * b:64 * b + 64, 0]) / (wa.sum() + wb.sum())
+        assert np.abs(om[i, 0] - ref).max() < 1e-6
+
+
 def test_explicit_scale_is_used(oracle_lib):
     cfg, q, k, v, gates, idx = _case(9)
     seg = cfg.seg_offsets()
