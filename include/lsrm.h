@@ -191,7 +191,8 @@ lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, con
  *   d_q [N, h_q, d], d_k, d_v [N, h_kv, d], d_kc, d_vc [N/64, h_kv, d]   bf16
  *   d_idx   [NB, topk] int32  any routing table: block ids in [0, NB) or -1 (skipped);
  *           all queries of block b attend every token of the listed blocks.  A row
- *           of -1 gives a zero selected branch.
+ *           of -1 gives a zero selected branch.  A block listed twice in a row enters
+ *           that row's softmax twice (its tokens weigh double against the others).
  *   d_gates [N, h_q, 3] fp32  gate weights (cmp, sel, win), already passed through
  *           the sigmoid of Eq. (nsa_2); [N, 3, h_q, d] fp32, 16-byte aligned, when
  *           params.gate_channels is 1 (the sum of Eq. (nsa_1) is then taken per channel)
