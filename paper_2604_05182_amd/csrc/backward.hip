@@ -1070,8 +1070,12 @@ WsLayout ws_layout(const Shape &s) {
     // token keys: with grouped-query heads a workgroup would walk group x as many steps while there are group x
     // fewer workgroups, and the longest reverse list sets the kernel's time -- deal the heads of a group to
     // up to 8 workgroups
+    // (as long as their fp32 sums stay within 2 GiB of workspace)
     const int grp = s.h / s.h_kv;
-    w.hpw = (grp + 7) / 8;
+    const size_t per_range = (size_t)s.nb * 64 * s.h_kv * s.d * 4 * 2;
+    const size_t fit = per_range > 0 ? ((size_t)2 << 30) / per_range : 8;
+    const int ranges = (int)(fit < 8 ? (fit < 1 ? 1 : fit) : 8);
+    w.hpw = (grp + ranges - 1) / ranges;
     w.hsplit = (grp + w.hpw - 1) / w.hpw;
     w.hpart_k = w.hpart_v = 0;
     if (w.hsplit > 1) {
