@@ -120,12 +120,14 @@ def test_backward_head_shapes_and_gates(B, oracle_lib, d, heads, h_kv, gate_chan
     _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
 
 
-@pytest.mark.parametrize("d,window_mode", [(64, 0), (64, 1), (128, 1), (32, 0)])
-def test_backward_with_active_counts(B, oracle_lib, d, window_mode):
+@pytest.mark.parametrize("d,window_mode,heads,h_kv", [(64, 0, 3, 3), (64, 1, 3, 3), (128, 1, 3, 3), (32, 0, 3, 3),
+                                                       # grouped heads: the pass that adds the head ranges finishes the rows
+                                                       (64, 0, 4, 2), (32, 1, 16, 2)])
+def test_backward_with_active_counts(B, oracle_lib, d, window_mode, heads, h_kv):
     """Blocks with fewer than 64 active tokens: padding slots are neither queries nor keys (whatever sits in
     their rows of k, v and dout -- NaN here -- is never looked at) and get zero gradients."""
-    cfg = I.small_config(name=f"b-counts-d{d}-w{window_mode}", n_obj=576, n_views=2, grid=16, heads=3, d=d, topk=4,
-                         window=160, seed=71)
+    cfg = I.small_config(name=f"b-counts-d{d}-w{window_mode}-h{heads}-kv{h_kv}", n_obj=576, n_views=2, grid=16,
+                         heads=heads, d=d, topk=4, window=160, seed=71, h_kv=h_kv)
     _log(f"[backward] {cfg.name} nb={cfg.nb}")
     rng = np.random.default_rng(13)
     cnt = rng.integers(1, 65, size=cfg.nb).astype(np.int32)
@@ -135,6 +137,10 @@ def test_backward_with_active_counts(B, oracle_lib, d, window_mode):
     idx[:, 0] = np.minimum(np.arange(cfg.nb), 5)
     q_bits, k_bits, v_bits = I.make_qkv(cfg)
     gates, dout_bits = I.make_gates(cfg), I.make_dout(cfg)
+    if heads != h_kv:
+        # a key/value head sums the gradients of its group: dout / group (a power of two, exact in bf16) keeps
+        # dk, dv at the magnitude the absolute tolerance was set for
+        dout_bits = I.f32_to_bf16_bits(I.bf16_bits_to_f32(dout_bits) * np.float32(h_kv / heads))
     q, k, v, dout = (I.bf16_bits_to_f32(a) for a in (q_bits, k_bits, v_bits, dout_bits))
     inactive = (np.arange(cfg.n) % 64) >= np.repeat(cnt, 64)
     k_bits, v_bits, dout_bits = k_bits.copy(), v_bits.copy(), dout_bits.copy()
