@@ -634,8 +634,9 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
 // mfma_block with QK of its tile t+1, the exponentials of tile t and PV of tile t-1, so every MFMA
 // has its share of the exponentials behind it.  Tile tau lives in stage tau mod NST of the block's NST
 // slots, K and V parts copied separately.  Barrier t comes before step t; behind it K(t) and
-// V(t-2) are dead, and K(t+NST) and V(t+NST-2) are copied over them, NST-1 steps ahead of their use.  The operand queues are primed from LDS at the start of every step (the next tile's
-// fragments are still in flight while a step runs, so the queues cannot roll across tiles).
+// V(t-2) are dead, and K(t+NST) and V(t+NST-2) are copied over them, NST-1 steps ahead of their use.
+// The operand queues are primed from LDS at the start of every step (the next tile's fragments are
+// still in flight while a step runs, so the queues cannot roll across tiles).
 // Steps 0 .. n (the last one is the PV of tile n-1); every wavefront meets barriers 0 .. n_steps.
 template <class G, bool CNT, typename SrcFn, typename ValidFn>
 __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src, ValidFn valid, char *lds,
