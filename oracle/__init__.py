@@ -180,24 +180,34 @@ def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0
     return dq, dk, dv
 
 
-def nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, qblocks, kblocks, heads, scale=0.0,
-                         window_mode=0):
-    """Gradients for a sample: dq [len(qblocks)*64, len(heads), d] of the listed query blocks and
-    dk, dv [len(kblocks)*64, len(heads), d] of the listed key blocks (all queries contribute)."""
+def nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, qblocks, kblocks, heads,
+                         kv_heads=None, scale=0.0, window_mode=0):
+    """Gradients for a sample: dq [len(qblocks)*64, len(heads), d] of the listed query blocks and query
+    heads, and dk, dv [len(kblocks)*64, len(kv_heads), d] of the listed key blocks and key/value heads (all
+    queries contribute, through every query head of the key/value head's group).  kv_heads defaults to
+    `heads` when every query head has its own key/value head.  Shapes and gate layouts as in nsa_forward."""
     q, k, v, kc, vc, gates, dout = map(_f32, (q, k, v, kc, vc, gates, dout))
     idx, seg = _i32(idx), _i32(seg_offsets)
-    qb, kb, hs = _i32(np.asarray(qblocks)), _i32(np.asarray(kblocks)), _i32(np.asarray(heads))
     n, h, d = q.shape
+    h_kv = k.shape[1]
+    assert h % h_kv == 0 and gates.shape in ((n, h, 3), (n, 3, h, d))
+    if kv_heads is None:
+        assert h_kv == h, "grouped heads: say which key/value heads dk, dv are wanted for"
+        kv_heads = heads
+    qb, kb, hs, kvs = (_i32(np.asarray(a)) for a in (qblocks, kblocks, heads, kv_heads))
+    assert hs.size == 0 or (hs.min() >= 0 and hs.max() < h)
+    assert kvs.size == 0 or (kvs.min() >= 0 and kvs.max() < h_kv)
     topk = idx.shape[1] if idx.ndim == 2 else 0
     dq = np.empty((qb.shape[0] * 64, hs.shape[0], d), dtype=np.float32)
-    dk = np.empty((kb.shape[0] * 64, hs.shape[0], d), dtype=np.float32)
+    dk = np.empty((kb.shape[0] * 64, kvs.shape[0], d), dtype=np.float32)
     dv = np.empty_like(dk)
     _load().oracle_nsa_backward_sampled(
-        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), ctypes.c_int(topk), ctypes.c_int(window),
-        ctypes.c_int(window_mode), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
-        _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
-        _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float), _p(dout, ctypes.c_float),
+        ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(h_kv), ctypes.c_int(d), ctypes.c_int(topk),
+        ctypes.c_int(window), ctypes.c_int(window_mode), ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1),
+        _p(seg, ctypes.c_int32), _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float),
+        _p(kc, ctypes.c_float), _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
+        ctypes.c_int(1 if gates.ndim == 4 else 0), _p(dout, ctypes.c_float),
         _p(qb, ctypes.c_int32), ctypes.c_int(qb.shape[0]), _p(kb, ctypes.c_int32), ctypes.c_int(kb.shape[0]),
-        _p(hs, ctypes.c_int32), ctypes.c_int(hs.shape[0]), _p(dq, ctypes.c_float), _p(dk, ctypes.c_float),
-        _p(dv, ctypes.c_float))
+        _p(hs, ctypes.c_int32), ctypes.c_int(hs.shape[0]), _p(kvs, ctypes.c_int32), ctypes.c_int(kvs.shape[0]),
+        _p(dq, ctypes.c_float), _p(dk, ctypes.c_float), _p(dv, ctypes.c_float))
     return dq, dk, dv

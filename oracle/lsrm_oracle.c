@@ -509,35 +509,46 @@ void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window
 
 /*
  * Gradients of the same layer for a sample of blocks and heads (full-size parity checks).
- * The arithmetic per (query, head, branch) is that of oracle_nsa_backward; only what is
- * accumulated differs:
- *   dq  [n_qb*64, n_hs, d]  rows of the listed query blocks,
- *   dk, dv [n_kb*64, n_hs, d]  rows of the listed key blocks -- every query of the sequence
- *           that attends them contributes (pooled keys of the listed blocks included, spread
- *           back over their 64 tokens as in the full function).
- * A (query, branch) whose key set meets none of the listed key blocks is skipped unless its
- * dq is wanted.  OpenMP over queries with per-thread accumulators, summed in thread order.
+ * The arithmetic per (query, head, branch) is that of oracle_nsa_backward (grouped-query heads
+ * and per-channel gates included); only what is accumulated differs:
+ *   dq  [n_qb*64, n_hs, d]  rows of the listed query blocks, listed query heads `heads`;
+ *   dk, dv [n_kb*64, n_kvs, d]  rows of the listed key blocks, listed key/value heads `kvheads`
+ *           -- every query of the sequence that attends them contributes, through every query
+ *           head of the key/value head's group (pooled keys of the listed blocks included,
+ *           spread back over their 64 tokens as in the full function).
+ * A (query, branch, head) that feeds neither a wanted dq row nor a listed key block and
+ * key/value head is skipped.  OpenMP over queries with per-thread accumulators.
+ * Full blocks only (no per-block counts).
  */
-void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, int window_mode, float scale,
-                                 int n_seg,
-                                 const int32_t *seg, const float *q, const float *k, const float *v,
-                                 const float *kc, const float *vc, const int32_t *idx, const float *gates,
-                                 const float *dout, const int32_t *qblocks, int n_qb, const int32_t *kblocks,
-                                 int n_kb, const int32_t *heads, int n_hs, float *dq, float *dk, float *dv) {
+void oracle_nsa_backward_sampled(int64_t n, int h, int h_kv, int d, int topk, int window, int window_mode,
+                                 float scale, int n_seg, const int32_t *seg, const float *q, const float *k,
+                                 const float *v, const float *kc, const float *vc, const int32_t *idx,
+                                 const float *gates, int gate_channels, const float *dout,
+                                 const int32_t *qblocks, int n_qb, const int32_t *kblocks, int n_kb,
+                                 const int32_t *heads, int n_hs, const int32_t *kvheads, int n_kvs, float *dq,
+                                 float *dk, float *dv) {
     int64_t nb = n / BLK;
-    size_t stride = (size_t)h * d;
+    size_t stride = (size_t)h * d;        /* rows of q, dout */
+    size_t stride_kv = (size_t)h_kv * d;  /* rows of k, v, kc, vc */
+    int group = h / h_kv;
     double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
     size_t maxkeys = (size_t)nb;
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
     if ((size_t)window + BLK > maxkeys) maxkeys = (size_t)window + BLK;
-    /* position of a block in the sample lists, or -1 */
+    /* position of a block / head in the sample lists, or -1 */
     int32_t *qpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nb > 0 ? nb : 1));
     int32_t *kpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nb > 0 ? nb : 1));
+    int32_t *hpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)h);
+    int32_t *kvpos = (int32_t *)malloc(sizeof(int32_t) * (size_t)h_kv);
     for (int64_t b = 0; b < nb; ++b) qpos[b] = kpos[b] = -1;
+    for (int a = 0; a < h; ++a) hpos[a] = -1;
+    for (int a = 0; a < h_kv; ++a) kvpos[a] = -1;
     for (int a = 0; a < n_qb; ++a) qpos[qblocks[a]] = a;
     for (int a = 0; a < n_kb; ++a) kpos[kblocks[a]] = a;
-    size_t ostride = (size_t)n_hs * d;
-    size_t tot_q = (size_t)n_qb * BLK * ostride, tot_k = (size_t)n_kb * BLK * ostride, tot_c = (size_t)n_kb * ostride;
+    for (int a = 0; a < n_hs; ++a) hpos[heads[a]] = a;
+    for (int a = 0; a < n_kvs; ++a) kvpos[kvheads[a]] = a;
+    size_t qstride = (size_t)n_hs * d, kstride = (size_t)n_kvs * d;
+    size_t tot_q = (size_t)n_qb * BLK * qstride, tot_k = (size_t)n_kb * BLK * kstride, tot_c = (size_t)n_kb * kstride;
     double *gq = (double *)calloc(tot_q > 0 ? tot_q : 1, sizeof(double));
     double *gk = (double *)calloc(tot_k > 0 ? tot_k : 1, sizeof(double));
     double *gv = (double *)calloc(tot_k > 0 ? tot_k : 1, sizeof(double));
@@ -554,6 +565,7 @@ void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, 
         int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + BLK));
         double *p = (double *)malloc(sizeof(double) * maxkeys);
         double *o = (double *)malloc(sizeof(double) * (size_t)d);
+        double *gd = (double *)malloc(sizeof(double) * (size_t)d); /* gate times dout for one branch */
 #pragma omp for schedule(dynamic, 16)
         for (int64_t i = 0; i < n; ++i) {
             int nc, ns, nw;
@@ -568,43 +580,49 @@ void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, 
                     int64_t blk = br == 0 ? rows[j] : rows[j] / BLK;
                     if (kpos[blk] >= 0) touches = 1;
                 }
-                if (!touches && qa < 0) continue;
-                for (int a = 0; a < n_hs; ++a) {
-                    int hh = heads[a];
+                for (int hh = 0; hh < h; ++hh) {
+                    int ha = qa >= 0 ? hpos[hh] : -1;               /* column of dq fed by this head, or -1 */
+                    int kva = touches ? kvpos[hh / group] : -1;      /* column of dk, dv fed by this head, or -1 */
+                    if (ha < 0 && kva < 0) continue;
+                    size_t kvo = (size_t)(hh / group) * d;
                     const float *qv = q + (size_t)i * stride + (size_t)hh * d;
                     const float *dor = dout + (size_t)i * stride + (size_t)hh * d;
-                    double g = (double)gates[((size_t)i * h + hh) * 3 + br];
-                    const float *kb = (br == 0 ? kc : k) + (size_t)hh * d;
-                    const float *vb = (br == 0 ? vc : v) + (size_t)hh * d;
-                    attend(qv, d, sc, kb, vb, stride, rows, cnt, p, o);
+                    for (int c = 0; c < d; ++c) {
+                        double g = gate_channels ? (double)gates[(((size_t)i * 3 + br) * h + hh) * d + c]
+                                                 : (double)gates[((size_t)i * h + hh) * 3 + br];
+                        gd[c] = g * (double)dor[c];
+                    }
+                    const float *kb = (br == 0 ? kc : k) + kvo;
+                    const float *vb = (br == 0 ? vc : v) + kvo;
+                    attend(qv, d, sc, kb, vb, stride_kv, rows, cnt, p, o);
                     double delta = 0.0;
-                    for (int c = 0; c < d; ++c) delta += g * (double)dor[c] * o[c];
+                    for (int c = 0; c < d; ++c) delta += gd[c] * o[c];
                     for (int j = 0; j < cnt; ++j) {
                         int64_t blk = br == 0 ? rows[j] : rows[j] / BLK;
-                        int ka = kpos[blk];
-                        if (ka < 0 && qa < 0) continue;
-                        const float *kr = kb + (size_t)rows[j] * stride;
-                        const float *vr = vb + (size_t)rows[j] * stride;
+                        int ka = kva >= 0 ? kpos[blk] : -1;
+                        if (ka < 0 && ha < 0) continue;
+                        const float *kr = kb + (size_t)rows[j] * stride_kv;
+                        const float *vr = vb + (size_t)rows[j] * stride_kv;
                         double dp = 0.0;
-                        for (int c = 0; c < d; ++c) dp += g * (double)dor[c] * (double)vr[c];
+                        for (int c = 0; c < d; ++c) dp += gd[c] * (double)vr[c];
                         double ds = p[j] * (dp - delta) * sc;
-                        if (qa >= 0) {
-                            double *gqr = gq + ((size_t)qa * BLK + (size_t)(i % BLK)) * ostride + (size_t)a * d;
+                        if (ha >= 0) {
+                            double *gqr = gq + ((size_t)qa * BLK + (size_t)(i % BLK)) * qstride + (size_t)ha * d;
                             for (int c = 0; c < d; ++c) gqr[c] += ds * (double)kr[c];
                         }
                         if (ka >= 0) {
                             double *gkr, *gvr;
                             if (br == 0) {
-                                gkr = tkc + (size_t)ka * ostride + (size_t)a * d;
-                                gvr = tvc + (size_t)ka * ostride + (size_t)a * d;
+                                gkr = tkc + (size_t)ka * kstride + (size_t)kva * d;
+                                gvr = tvc + (size_t)ka * kstride + (size_t)kva * d;
                             } else {
                                 size_t row = (size_t)ka * BLK + (size_t)(rows[j] % BLK);
-                                gkr = tk + row * ostride + (size_t)a * d;
-                                gvr = tv + row * ostride + (size_t)a * d;
+                                gkr = tk + row * kstride + (size_t)kva * d;
+                                gvr = tv + row * kstride + (size_t)kva * d;
                             }
                             for (int c = 0; c < d; ++c) {
                                 gkr[c] += ds * (double)qv[c];
-                                gvr[c] += p[j] * g * (double)dor[c];
+                                gvr[c] += p[j] * gd[c];
                             }
                         }
                     }
@@ -617,15 +635,15 @@ void oracle_nsa_backward_sampled(int64_t n, int h, int d, int topk, int window, 
             for (size_t e = 0; e < tot_c; ++e) { gkc[e] += tkc[e]; gvc[e] += tvc[e]; }
         }
         free(tk); free(tv); free(tkc); free(tvc);
-        free(rc); free(rs); free(rw); free(p); free(o);
+        free(rc); free(rs); free(rw); free(p); free(o); free(gd);
     }
     for (size_t e = 0; e < tot_q; ++e) dq[e] = (float)gq[e];
     for (int a = 0; a < n_kb; ++a)
         for (int t = 0; t < BLK; ++t)
-            for (size_t c = 0; c < ostride; ++c) {
-                size_t e = ((size_t)a * BLK + (size_t)t) * ostride + c;
-                dk[e] = (float)(gk[e] + gkc[(size_t)a * ostride + c] / 64.0);
-                dv[e] = (float)(gv[e] + gvc[(size_t)a * ostride + c] / 64.0);
+            for (size_t c = 0; c < kstride; ++c) {
+                size_t e = ((size_t)a * BLK + (size_t)t) * kstride + c;
+                dk[e] = (float)(gk[e] + gkc[(size_t)a * kstride + c] / 64.0);
+                dv[e] = (float)(gv[e] + gvc[(size_t)a * kstride + c] / 64.0);
             }
-    free(gq); free(gk); free(gv); free(gkc); free(gvc); free(qpos); free(kpos);
+    free(gq); free(gk); free(gv); free(gkc); free(gvc); free(qpos); free(kpos); free(hpos); free(kvpos);
 }

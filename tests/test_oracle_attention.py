@@ -432,3 +432,43 @@ def test_backward_sampled_matches_autograd_and_full(oracle_lib):
         assert got.shape == want.shape
         assert np.abs(got - want).max() < 1e-5 * max(1.0, np.abs(want).max())
         assert np.abs(got - full[rows][:, heads]).max() < 1e-6 * max(1.0, np.abs(want).max())
+
+
+@pytest.mark.parametrize("gate_channels,window_mode", [(False, 0), (True, 0), (True, 1), (False, 1)])
+def test_backward_sampled_with_grouped_heads_channel_gates_and_own_block_window(oracle_lib, gate_channels,
+                                                                                 window_mode):
+    """The sampled function on 6 query heads sharing 2 key/value heads, with per-head and per-channel gates and
+    with both window modes: dq on listed query heads, dk and dv on listed key/value heads (the whole group
+    of a key/value head contributes), against library autograd of the dense formulation and the full function.
+    Dropping a head of the group, reading the wrong key/value head, a gate taken per head where it is per
+    channel, or the sliding window where the own block is asked for, each fails it."""
+    cfg = I.small_config(n_obj=192, n_views=2, grid=8, heads=6, d=8, topk=2, window=80, seed=15, h_kv=2,
+                         gate_channels=gate_channels)
+    q, k, v = (I.bf16_bits_to_f32(a) for a in I.make_qkv(cfg))
+    gates, dout = I.make_gates(cfg), I.bf16_bits_to_f32(I.make_dout(cfg))
+    rng = np.random.default_rng(15)
+    idx = np.stack([rng.choice(cfg.nb, size=2, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[1, 0] = -1
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k), oracle_lib.pool(v)
+    rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout, window_mode=window_mode)
+    fq, fk, fv = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout, window_mode=window_mode)
+    qblocks, kblocks, heads, kv_heads = [4, 0], [1, 3, 2], [5, 0, 3], [1]
+    dq, dk, dv = oracle_lib.nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout, qblocks, kblocks,
+                                                 heads, kv_heads=kv_heads, window_mode=window_mode)
+    rows_q = np.concatenate([np.arange(64 * b, 64 * b + 64) for b in qblocks])
+    rows_k = np.concatenate([np.arange(64 * b, 64 * b + 64) for b in kblocks])
+    for got, ref, full, rows, cols in ((dq, rq, fq, rows_q, heads), (dk, rk, fk, rows_k, kv_heads),
+                                       (dv, rv, fv, rows_k, kv_heads)):
+        want = ref[rows][:, cols]
+        assert got.shape == want.shape
+        assert np.abs(got - want).max() < 1e-5 * max(1.0, np.abs(want).max())
+        assert np.abs(got - full[rows][:, cols]).max() < 1e-6 * max(1.0, np.abs(want).max())
+    # both key/value heads at once, no dq wanted
+    _, dk2, dv2 = oracle_lib.nsa_backward_sampled(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout, [], kblocks,
+                                                  [], kv_heads=[0, 1], window_mode=window_mode)
+    assert np.abs(dk2 - rk[rows_k]).max() < 1e-5 * max(1.0, np.abs(rk).max())
+    assert np.abs(dv2 - rv[rows_k]).max() < 1e-5 * max(1.0, np.abs(rv).max())
+    if window_mode == 1:   # the two window readings really differ on this case
+        sq, _, _ = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout, window_mode=0)
+        assert np.abs(sq - rq).max() > 1e-3
