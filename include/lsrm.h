@@ -18,7 +18,8 @@
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the call returns without synchronising;
  *   - the library allocates no device memory: scratch comes from the caller
- *     (d_ws / ws_bytes, size from lsrm_workspace_bytes, 256-byte aligned);
+ *     (d_ws / ws_bytes, size from lsrm_workspace_bytes, 256-byte aligned), except in
+ *     lsrm_route_blocks_static, which uses a fixed array inside the library;
  *   - nothing throws or aborts: the return value is LSRM_OK or a negative code,
  *     and on error no kernel has been launched.
  */
@@ -38,7 +39,9 @@ enum {
     LSRM_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, misaligned segment, ... */
     LSRM_ERR_UNSUPPORTED = -2, /* block != 64, d not in {32,64,128}, topk > 64, ...         */
     LSRM_ERR_WORKSPACE = -3,   /* d_ws null / too small / misaligned                        */
-    LSRM_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed                */
+    LSRM_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed                */
+    LSRM_ERR_TOO_LARGE = -5    /* lsrm_route_blocks_static: the problem needs more than the
+                                  library's fixed scratch                                   */
 };
 
 /* Human-readable text for a status code (static storage). */
@@ -121,6 +124,24 @@ size_t lsrm_workspace_bytes(const lsrm_nsa_params *p, int which_call);
  */
 lsrm_status lsrm_route_blocks(const lsrm_nsa_params *p, const float *d_pos, const lsrm_camera *d_cams,
                               int32_t *d_idx, float *d_dist2, void *d_ws, size_t ws_bytes, void *stream);
+
+/*
+ * lsrm_route_blocks for callers that cannot allocate device memory or own no workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels
+ * and results as lsrm_route_blocks, without d_ws: the projections pass through a fixed array of
+ * LSRM_STATIC_ROUTE_SCRATCH_BYTES that the library's code object holds on every GPU it runs on until
+ * the process ends.  The call itself allocates nothing (no hipMalloc / hipFree, no allocating
+ * library routine); on its first use on a device it looks the array's address up and keeps it
+ * (the one piece of state this library holds, guarded by a mutex).
+ * LSRM_ERR_TOO_LARGE when (n_obj / 64) * n_views * 8 bytes exceed the array (131072 block-view pairs;
+ * the largest benchmark configuration needs 73728).
+ * All calls on one GPU share the array: calls that overlap in time on the same GPU (different
+ * streams, or threads) race on it and must be serialised by the caller; calls on one stream are
+ * ordered.  Nothing in it needs to start at zero: every element read is written earlier in the same call.
+ */
+#define LSRM_STATIC_ROUTE_SCRATCH_BYTES (1u << 20)
+lsrm_status lsrm_route_blocks_static(const lsrm_nsa_params *p, const float *d_pos, const lsrm_camera *d_cams,
+                                     int32_t *d_idx, float *d_dist2, void *stream);
 
 /*
  * Budgets of the four geometric selection rules.  [Sec. 3.3, paragraphs "Image/Volume to Image

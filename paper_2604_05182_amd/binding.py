@@ -19,6 +19,8 @@ LSRM_ERR_INVALID_ARG = -1
 LSRM_ERR_UNSUPPORTED = -2
 LSRM_ERR_WORKSPACE = -3
 LSRM_ERR_HIP = -4
+LSRM_ERR_TOO_LARGE = -5
+LSRM_STATIC_ROUTE_SCRATCH_BYTES = 1 << 20
 LSRM_WS_ROUTE, LSRM_WS_FORWARD, LSRM_WS_BACKWARD, LSRM_WS_ROUTE_3D = 0, 1, 2, 3
 
 
@@ -54,6 +56,8 @@ _lib.lsrm_workspace_bytes.restype = _sz
 _lib.lsrm_workspace_bytes.argtypes = [_pp, ctypes.c_int]
 _lib.lsrm_route_blocks.restype = ctypes.c_int32
 _lib.lsrm_route_blocks.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.lsrm_route_blocks_static.restype = ctypes.c_int32
+_lib.lsrm_route_blocks_static.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
 _lib.lsrm_route_blocks_3d.restype = ctypes.c_int32
 _lib.lsrm_route_blocks_3d.argtypes = [_pp, ctypes.POINTER(lsrm_route3d_params), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.lsrm_nsa_compress.restype = ctypes.c_int32
@@ -118,6 +122,12 @@ def lsrm_route_blocks(p, pos, cams, idx, dist2=None, ws=None, stream=None):
     nbytes = ws.numel() * ws.element_size() if ws is not None else 0
     _check(_lib.lsrm_route_blocks(ctypes.byref(p), _ptr(pos), _ptr(cams), _ptr(idx), _ptr(dist2), _ptr(ws),
                                   nbytes, _stream(stream)), "lsrm_route_blocks")
+
+
+def lsrm_route_blocks_static(p, pos, cams, idx, dist2=None, stream=None):
+    """lsrm_route_blocks without a workspace: the library's fixed per-GPU scratch is used (no allocation)."""
+    _check(_lib.lsrm_route_blocks_static(ctypes.byref(p), _ptr(pos), _ptr(cams), _ptr(idx), _ptr(dist2),
+                                         _stream(stream)), "lsrm_route_blocks_static")
 
 
 def lsrm_route_blocks_3d(p, r, pos, pos_img, cams, idx, dist2=None, ws=None, stream=None):

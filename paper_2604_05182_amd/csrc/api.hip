@@ -76,6 +76,7 @@ const char *lsrm_strerror(lsrm_status s) {
         case LSRM_ERR_UNSUPPORTED: return "unsupported configuration";
         case LSRM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case LSRM_ERR_HIP: return "HIP runtime error";
+        case LSRM_ERR_TOO_LARGE: return "problem exceeds the fixed scratch of the allocation-free entry point";
         default: return "unknown status";
     }
 }
@@ -103,6 +104,18 @@ lsrm_status lsrm_route_blocks(const lsrm_nsa_params *p, const float *d_pos, cons
     if (s.n_views > 0 && d_cams == nullptr) return LSRM_ERR_INVALID_ARG;
     if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < route_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
     return launch_route(s, d_pos, d_cams, d_idx, d_dist2, d_ws, static_cast<hipStream_t>(stream));
+}
+
+lsrm_status lsrm_route_blocks_static(const lsrm_nsa_params *p, const float *d_pos, const lsrm_camera *d_cams,
+                                     int32_t *d_idx, float *d_dist2, void *stream) {
+    Shape s;
+    lsrm_status rc = make_shape(p, &s);
+    if (rc != LSRM_OK) return rc;
+    if (s.nb == 0 || s.topk == 0) return LSRM_OK;
+    if (d_idx == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (s.n_obj > 0 && d_pos == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (s.n_views > 0 && d_cams == nullptr) return LSRM_ERR_INVALID_ARG;
+    return launch_route_static(s, d_pos, d_cams, d_idx, d_dist2, static_cast<hipStream_t>(stream));
 }
 
 lsrm_status lsrm_route_blocks_3d(const lsrm_nsa_params *p, const lsrm_route3d_params *r, const float *d_pos,

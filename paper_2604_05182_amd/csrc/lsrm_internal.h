@@ -36,6 +36,9 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 lsrm_status launch_route(const Shape &s, const float *d_pos, const lsrm_camera *d_cams, int32_t *d_idx,
                          float *d_dist2, void *d_ws, hipStream_t st);
 size_t route_ws_bytes(const Shape &s);
+// Same kernels, the projections going through the library's fixed per-GPU scratch; calls nothing that allocates.
+lsrm_status launch_route_static(const Shape &s, const float *d_pos, const lsrm_camera *d_cams, int32_t *d_idx,
+                                float *d_dist2, hipStream_t st);
 
 lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const float *d_pos, const float *d_pos_img,
                             const lsrm_camera *d_cams, int32_t *d_idx, float *d_dist2, void *d_ws, hipStream_t st);

@@ -19,6 +19,14 @@
 // reproducible bit for bit.  Plain ALU work, latency bound and tiny next to attention.
 #include "lsrm_internal.h"
 
+#include <mutex>
+
+// Fixed scratch of lsrm_route_blocks_static, the entry point for callers that cannot allocate: the
+// projections project_blocks hands to select_topk ([n_obj/64, n_views] float2).  One copy per GPU, held
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress -- never a
+// device address; kernels receive the address looked up in static_scratch() below.
+static __device__ __align__(256) unsigned char scratch[LSRM_STATIC_ROUTE_SCRATCH_BYTES];
+
 namespace lsrm {
 
 namespace {
@@ -381,6 +389,37 @@ lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const 
                        d_dist2);
     LSRM_HIP_CHECK(hipGetLastError());
     return LSRM_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device (every GPU holds its
+// own copy of the array at its own address).
+static lsrm_status static_scratch(void **out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *addr[kMaxDevices] = {};
+    int dev = -1;
+    LSRM_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return LSRM_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (addr[dev] == nullptr) {
+        void *ptr = nullptr;
+        LSRM_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr) return LSRM_ERR_HIP;
+        addr[dev] = ptr;
+    }
+    *out = addr[dev];
+    return LSRM_OK;
+}
+
+lsrm_status launch_route_static(const Shape &s, const float *d_pos, const lsrm_camera *d_cams, int32_t *d_idx,
+                                float *d_dist2, hipStream_t st) {
+    if (route_ws_bytes(s) > (size_t)LSRM_STATIC_ROUTE_SCRATCH_BYTES) return LSRM_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    lsrm_status rc = static_scratch(&ws);
+    if (rc != LSRM_OK) return rc;
+    // project_blocks writes every projection select_topk reads, so nothing of the previous call's
+    // contents needs clearing.
+    return launch_route(s, d_pos, d_cams, d_idx, d_dist2, ws, st);
 }
 
 size_t route_ws_bytes(const Shape &s) {

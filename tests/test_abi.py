@@ -15,7 +15,7 @@ def _declared():
 
 def test_header_declares_the_entry_points():
     names = _declared()
-    for must in ("lsrm_route_blocks", "lsrm_route_blocks_3d", "lsrm_nsa_compress", "lsrm_nsa_forward",
+    for must in ("lsrm_route_blocks", "lsrm_route_blocks_static", "lsrm_route_blocks_3d", "lsrm_nsa_compress", "lsrm_nsa_forward",
                  "lsrm_nsa_backward", "lsrm_workspace_bytes", "lsrm_strerror"):
         assert must in names
 
