@@ -348,3 +348,26 @@ def sample_query_blocks(cfg: NSAConfig, n_random: int, seed: int = 0) -> np.ndar
     rng = _rng(cfg.seed + 77 + seed, 40)
     extra = rng.choice(cfg.nb, size=min(n_random, cfg.nb), replace=False)
     return np.array(sorted(edge | set(int(e) for e in extra)), dtype=np.int32)
+
+
+def sample_query_blocks_stratified(cfg: NSAConfig, per_stratum: int, slots: int = 4, ranges: int = 8,
+                                   seed: int = 0) -> np.ndarray:
+    """First and last block of every segment, `per_stratum` random blocks for every combination of
+    (block id mod `slots`, which of `ranges` equal contiguous ranges of block groups the block falls in), and
+    the blocks on either side of every range boundary (sorted, unique).  A group is `slots` consecutive
+    blocks; the ranges are ceil(groups / ranges) groups long."""
+    groups = (cfg.nb + slots - 1) // slots
+    per_range = (groups + ranges - 1) // ranges
+    blocks = np.arange(cfg.nb)
+    slot, rng_id = blocks % slots, (blocks // slots) // per_range
+    picked = set(int(b) for b in sample_query_blocks(cfg, 0))
+    rng = _rng(cfg.seed + 91 + seed, 41)
+    for s in range(slots):
+        for r in range(ranges):
+            pool = blocks[(slot == s) & (rng_id == r)]
+            if pool.size:
+                picked.update(int(b) for b in rng.choice(pool, size=min(per_stratum, pool.size), replace=False))
+    for r in range(1, ranges):
+        edge = r * per_range * slots
+        picked.update(b for b in (edge - 1, edge) if 0 <= b < cfg.nb)
+    return np.array(sorted(picked), dtype=np.int32)

@@ -120,14 +120,18 @@ def test_backward_head_shapes_and_gates(B, oracle_lib, d, heads, h_kv, gate_chan
     _assert_grads(got, oracle_lib.nsa_backward(*args), cfg.name)
 
 
-@pytest.mark.parametrize("d,window_mode,heads,h_kv", [(64, 0, 3, 3), (64, 1, 3, 3), (128, 1, 3, 3), (32, 0, 3, 3),
-                                                       # grouped heads: the pass that adds the head ranges finishes the rows
-                                                       (64, 0, 4, 2), (32, 1, 16, 2)])
-def test_backward_with_active_counts(B, oracle_lib, d, window_mode, heads, h_kv):
+@pytest.mark.parametrize("d,window_mode,heads,h_kv,gate_channels",
+                         [(64, 0, 3, 3, False), (64, 1, 3, 3, False), (128, 1, 3, 3, False), (32, 0, 3, 3, False),
+                          # grouped heads: the pass that adds the head ranges finishes the rows
+                          (64, 0, 4, 2, False), (32, 1, 16, 2, False),
+                          # per-channel gates: the gate * dout rows of padding slots (NaN dout) must never be read
+                          (64, 0, 3, 3, True), (128, 1, 2, 2, True), (32, 0, 4, 2, True)])
+def test_backward_with_active_counts(B, oracle_lib, d, window_mode, heads, h_kv, gate_channels):
     """Blocks with fewer than 64 active tokens: padding slots are neither queries nor keys (whatever sits in
     their rows of k, v and dout -- NaN here -- is never looked at) and get zero gradients."""
-    cfg = I.small_config(name=f"b-counts-d{d}-w{window_mode}-h{heads}-kv{h_kv}", n_obj=576, n_views=2, grid=16,
-                         heads=heads, d=d, topk=4, window=160, seed=71, h_kv=h_kv)
+    cfg = I.small_config(name=f"b-counts-d{d}-w{window_mode}-h{heads}-kv{h_kv}-ch{int(gate_channels)}", n_obj=576,
+                         n_views=2, grid=16, heads=heads, d=d, topk=4, window=160, seed=71, h_kv=h_kv,
+                         gate_channels=gate_channels)
     _log(f"[backward] {cfg.name} nb={cfg.nb}")
     rng = np.random.default_rng(13)
     cnt = rng.integers(1, 65, size=cfg.nb).astype(np.int32)
