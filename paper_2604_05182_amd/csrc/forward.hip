@@ -85,7 +85,8 @@ constexpr float kMinusHuge = -1.0e30f;  // initial running maximum: finite, so n
 struct FwdArgs {
     const uint16_t *q;
     const char *kv, *kvc;  // packed tile images of (k, v) and of the pooled (kc, vc)
-    const int32_t *idx;
+    const int32_t *idx;    // routing table [NB, topk]
+    const int32_t *sched;  // d = 128: the routing rows in step order, block id | owner << 28 (schedule.hip)
     const float *gates;
     int32_t seg[kMaxSeg + 1];  // window segment offsets (tokens)
     uint16_t *out;
@@ -638,9 +639,9 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src
 // The operand queues are primed from LDS at the start of every step (the next tile's fragments are
 // still in flight while a step runs, so the queues cannot roll across tiles).
 // Steps 0 .. n (the last one is the PV of tile n-1); every wavefront meets barriers 0 .. n_steps.
-template <class G, bool CNT, typename SrcFn, typename ValidFn>
-__device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src, ValidFn valid, char *lds,
-                                         int qbi, int sub, int lane, float sl2) {
+template <class G, bool CNT, typename SrcFn, typename OwnFn, typename ValidFn>
+__device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps, SrcFn src, OwnFn own, ValidFn valid,
+                                         char *lds, int qbi, int sub, int lane, float sl2) {
     constexpr int NP = G::NP;
     if (n_steps <= 0) return;
     static_assert(G::NW == 2 && G::QT == 1, "two wavefronts per query block");
@@ -648,8 +649,11 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
     const int n = my_steps;
     constexpr int NST = G::NST;
     static_assert((NST & (NST - 1)) == 0 && NST >= 2, "");
-    auto stage = [&](int tau) { return lds + ((tau & (NST - 1)) * NP + qbi) * G::TILE; };
-    auto lstage = [&](int tau) { return lds + ((tau & (NST - 1)) * NP + qbi) * G::TILE + c.lane16; };
+    // tile tau of this query block lives in the slot of its owner: the query block of the group that copies it (this
+    // one, unless the step schedule lets a lower-numbered query block of the group meet the same key block at the
+    // same step: the tile is then copied once and read by all of them)
+    auto stage = [&](int tau) { return lds + ((tau & (NST - 1)) * NP + own(tau)) * G::TILE; };
+    auto lstage = [&](int tau) { return stage(tau) + c.lane16; };
     auto issue_part = [&](const char *tile, char *slot, int n_inst) {
 #pragma unroll 8
         for (int j = 0; j < n_inst; ++j) {
@@ -657,10 +661,17 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
             __builtin_amdgcn_global_load_lds(GLB_PTR(tile + i * 1024 + c.lane16), LDS_PTR(slot + i * 1024), 16, 0, 0);
         }
     };
-    auto issue_k = [&](int tau) { issue_part(src(tau), stage(tau), KI); };
-    auto issue_v = [&](int tau) { issue_part(src(tau) + G::K_BYTES, stage(tau) + G::K_BYTES, VI); };
+    auto issue_k = [&](int tau) {
+        if (own(tau) == qbi) issue_part(src(tau), stage(tau), KI);
+    };
+    auto issue_v = [&](int tau) {
+        if (own(tau) == qbi) issue_part(src(tau) + G::K_BYTES, stage(tau) + G::K_BYTES, VI);
+    };
     // barrier t: K(t+1) and V(t-1) have landed (both were issued behind barrier t+1-NST; what the NST-2
-    // barriers since then issued may stay in flight) and every LDS read of this wavefront is done
+    // barriers since then issued may stay in flight) and every LDS read of this wavefront is done.  Every
+    // wavefront waits for its own copies before the barrier, so behind it the tiles are there for all
+    // wavefronts, whoever copied them; all wavefronts are at the same step, so the slots overwritten behind
+    // barrier t (K of step t, V of step t-2) are dead for all of them.
     auto sync = [&](int t) {
         if (NST > 2 && t + NST - 1 < n)
             __builtin_amdgcn_s_waitcnt(vm_lgkm_imm((NST - 2) * (KI + VI)));
@@ -674,13 +685,13 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
     f32x16 S[2][1];
     uint32_t P[2][1][8];
     float psum[1];
-    auto prime_k = [&](int tau) {
+    auto prime_k = [&](const char *ls) {
 #pragma unroll
-        for (int i = 0; i < G::KQ; ++i) kq[i] = *reinterpret_cast<const bf16x8 *>(lstage(tau) + i * 1024);
+        for (int i = 0; i < G::KQ; ++i) kq[i] = *reinterpret_cast<const bf16x8 *>(ls + i * 1024);
     };
-    auto prime_v = [&](int tau) {
+    auto prime_v = [&](const char *ls) {
 #pragma unroll
-        for (int f = 0; f < G::VQ; ++f) vq[f] = *reinterpret_cast<const bf16x8 *>(lstage(tau) + G::K_BYTES + f * 1024);
+        for (int f = 0; f < G::VQ; ++f) vq[f] = *reinterpret_cast<const bf16x8 *>(ls + G::K_BYTES + f * 1024);
     };
     auto mask_next = [&](int t, f32x16 &s_next) {
         if constexpr (CNT) {
@@ -712,31 +723,33 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
     auto full_step = [&](auto par, int t) {
         constexpr int A = decltype(par)::value;
         sync(t);
-        prime_k(t + 1);
-        prime_v(t - 1);
-        mfma_block<G, true, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], psum, sl2, lstage(t + 1), lstage(t + 1),
-                                  lstage(t - 1), lstage(t - 1));
+        const char *k_nx = lstage(t + 1), *v_pv = lstage(t - 1);
+        prime_k(k_nx);
+        prime_v(v_pv);
+        mfma_block<G, true, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], psum, sl2, k_nx, k_nx, v_pv, v_pv);
         mask_next(t, S[A ^ 1][0]);
         close_tile<G>(c, S[A], P[A], psum, sl2);
     };
     auto last_steps = [&](auto par, int t) {  // t = n - 1 >= 1: exp(t) || PV(t-1), then the PV of tile t
         constexpr int A = decltype(par)::value;
         sync(t);
-        prime_v(t - 1);
-        mfma_block<G, false, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], psum, sl2, nullptr, nullptr, lstage(t - 1),
-                                   lstage(t - 1));
+        const char *v_pv = lstage(t - 1);
+        prime_v(v_pv);
+        mfma_block<G, false, true>(c, S[A], kq, S[A ^ 1], vq, P[A ^ 1], P[A], psum, sl2, nullptr, nullptr, v_pv, v_pv);
         close_tile<G>(c, S[A], P[A], psum, sl2);
         sync(t + 1);
-        prime_v(t);
-        pv_drain<G>(c, vq, P[A], lstage(t));
+        const char *v_last = lstage(t);
+        prime_v(v_last);
+        pv_drain<G>(c, vq, P[A], v_last);
     };
     using Even = std::integral_constant<int, 0>;
     using Odd = std::integral_constant<int, 1>;
     int done = 0;  // barriers 0 .. done-1 are behind us
     if (n >= 2) {
         sync(0);
-        prime_k(1);
-        mfma_block<G, true, false>(c, S[0], kq, S[1], vq, P[1], P[0], psum, sl2, lstage(1), lstage(1), nullptr, nullptr);
+        const char *k1 = lstage(1);
+        prime_k(k1);
+        mfma_block<G, true, false>(c, S[0], kq, S[1], vq, P[1], P[0], psum, sl2, k1, k1, nullptr, nullptr);
         mask_next(0, S[1][0]);
         close_tile<G>(c, S[0], P[0], psum, sl2);
         int t = 1;
@@ -758,8 +771,9 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
         mfma_block<G, false, false>(c, S[0], kq, S[1], vq, P[1], P[0], psum, sl2, nullptr, nullptr, nullptr, nullptr);
         close_tile<G>(c, S[0], P[0], psum, sl2);
         sync(1);
-        prime_v(0);
-        pv_drain<G>(c, vq, P[0], lstage(0));
+        const char *v_last = lstage(0);
+        prime_v(v_last);
+        pv_drain<G>(c, vq, P[0], v_last);
         done = 2;
     }
     for (int t = done; t <= n_steps; ++t) {
@@ -943,33 +957,49 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
     {
         reset_branch<G>(c);
         int packed = -1, pcount = 0, my_valid = 0, max_valid = 0;
+        if constexpr (D == 128) {
+            // rows of the step schedule (schedule.hip): valid entries first, block id | owner << 28
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            const int qbp = group * NP + p;
-            int v = (qbp < a.nb && lane < a.topk) ? a.idx[(int64_t)qbp * a.topk + lane] : -1;
-            if (v >= a.nb) v = -1;
-            const unsigned long long valid = __ballot(v >= 0);
-            const int n_valid = __popcll(valid);
-            max_valid = max(max_valid, n_valid);
-            if (p == qbi) {
-                // compact the valid entries of this block's row to lanes 0..n_valid-1
-                const int rank = __popcll(valid & ((1ull << lane) - 1ull));
-                packed = __builtin_amdgcn_ds_permute((v >= 0 ? rank : 63) * 4, v);
-                if (n_valid == 64) packed = v;
-                my_valid = n_valid;
+            for (int p = 0; p < NP; ++p) {
+                const int v = lane < a.topk ? a.sched[((int64_t)group * NP + p) * a.topk + lane] : -1;
+                const int n_valid = __popcll(__ballot(v >= 0));
+                max_valid = max(max_valid, n_valid);
+                if (p == qbi) {
+                    packed = v;
+                    my_valid = n_valid;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int qbp = group * NP + p;
+                int v = (qbp < a.nb && lane < a.topk) ? a.idx[(int64_t)qbp * a.topk + lane] : -1;
+                if (v >= a.nb) v = -1;
+                const unsigned long long valid = __ballot(v >= 0);
+                const int n_valid = __popcll(valid);
+                max_valid = max(max_valid, n_valid);
+                if (p == qbi) {
+                    // compact the valid entries of this block's row to lanes 0..n_valid-1
+                    const int rank = __popcll(valid & ((1ull << lane) - 1ull));
+                    packed = __builtin_amdgcn_ds_permute((v >= 0 ? rank : 63) * 4, v);
+                    if (n_valid == 64) packed = v;
+                    my_valid = n_valid;
+                }
             }
         }
-        if constexpr (CNT) pcount = lane < my_valid ? a.count[packed] : 0;
+        if constexpr (CNT) pcount = lane < my_valid ? a.count[packed & 0xFFFFFF] : 0;
         const char *base = a.kv + head_kv;
         auto src = [&](int t) {
-            int kb = __builtin_amdgcn_readlane(packed, t >> 1);
+            const int kb = __builtin_amdgcn_readlane(packed, t >> 1) & 0xFFFFFF;
             return base + (2 * kb + (t & 1)) * tile_stride;
         };
+        // the query block whose wavefronts copy this query block's tile of step t (always itself without a schedule)
+        auto own = [&](int t) { return D == 128 ? (__builtin_amdgcn_readlane(packed, t >> 1) >> 28) & 3 : qbi; };
         auto valid = [&](int t) {  // active keys of tile t of this query block's list
             int cnt = __builtin_amdgcn_readlane(pcount, t >> 1);
             return min(32, max(0, cnt - 32 * (t & 1)));
         };
-        run_own<G, CNT>(c, 2 * max_valid, 2 * my_valid, src, valid, lds, qbi, sub, lane, sl2);
+        run_own<G, CNT>(c, 2 * max_valid, 2 * my_valid, src, own, valid, lds, qbi, sub, lane, sl2);
         if (active) finish_branch<G>(c, a, 1, row0, head, wave, lane, lds);
     }
 
@@ -1100,7 +1130,7 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
 }
 
 struct WsLayout {
-    size_t kv, kvc, gsum, total;
+    size_t kv, kvc, gsum, sched, total;
 };
 
 WsLayout ws_layout(const Shape &s) {
@@ -1113,6 +1143,8 @@ WsLayout ws_layout(const Shape &s) {
     off += align_up((size_t)((s.nb + 31) / 32) * s.h_kv * tile, 256);
     w.gsum = off;
     off += align_up((size_t)s.nb * 64 * s.h * s.d * 4, 256);
+    w.sched = off;
+    off += s.d == 128 ? sel_schedule_bytes(s) : 0;
     w.total = off > 0 ? off : 256;
     return w;
 }
@@ -1130,6 +1162,11 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     hipLaunchKernelGGL((pack_tiles<D, false>), dim3((s.nb + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
                        (int64_t)s.nb, s.h_kv, tiles_c, (const int32_t *)nullptr);
     LSRM_HIP_CHECK(hipGetLastError());
+    if (D == 128) {
+        lsrm_status rc = launch_sel_schedule(s, a.idx, reinterpret_cast<int32_t *>(ws + w.sched), st);
+        if (rc != LSRM_OK) return rc;
+    }
+    a.sched = reinterpret_cast<const int32_t *>(ws + w.sched);
     a.kv = ws + w.kv;
     a.kvc = ws + w.kvc;
     a.gsum = (float *)(ws + w.gsum);

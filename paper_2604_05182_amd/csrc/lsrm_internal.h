@@ -53,6 +53,11 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
                            float *d_lse, uint16_t *d_out_branch, void *d_ws, hipStream_t st, hipEvent_t ev_start,
                            hipEvent_t ev_stop);
 size_t forward_ws_bytes(const Shape &s);
+// Step schedule of the selected branch (schedule.hip): the rows of d_idx reordered so that the four query blocks of
+// an attention workgroup meet a block they share at the same step; d_sched [ceil(nb / 4) * 4, topk] int32, an entry
+// is block id | owner << 28.
+size_t sel_schedule_bytes(const Shape &s);
+lsrm_status launch_sel_schedule(const Shape &s, const int32_t *d_idx, int32_t *d_sched, hipStream_t st);
 // Tile images (see forward.hip): one image per (tile, head) = row-order fragments of `rows_src`, then transposed
 // fragments of `t_src`, both [n_rows, H, d] bf16; n_tiles tiles of 32 rows.  rows_only: the backward's
 // flavour -- row-order fragments only (t_src unused), slots swizzled as backward.hip expects.

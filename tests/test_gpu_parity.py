@@ -277,6 +277,45 @@ def test_forward_maximum_topk(B, oracle_lib, d):
     _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx), cfg.name)
 
 
+@pytest.mark.parametrize("d,topk", [(64, 6), (128, 9), (32, 5)])
+def test_forward_rows_that_share_and_repeat_blocks(B, oracle_lib, d, topk):
+    """Routing rows built to stress the step schedule of the selected branch: the four rows of a workgroup
+    identical, overlapping in part (pairs, triples), disjoint, a block listed twice or three times in a row
+    (it is attended that many times) while its neighbours list it once, holes in the middle of rows, rows of
+    different lengths, an empty row."""
+    cfg = I.small_config(name=f"f-share-d{d}", n_obj=1088, n_views=3, grid=24, heads=2, d=d, topk=topk, window=64,
+                         seed=81)
+    _log(f"[forward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(17)
+    idx = np.full((cfg.nb, topk), -1, dtype=np.int32)
+    for g in range(0, cfg.nb, 4):
+        rows = range(g, min(g + 4, cfg.nb))
+        kind = (g // 4) % 6
+        common = rng.choice(cfg.nb, size=topk, replace=False)
+        for r in rows:
+            if kind == 0:      # identical rows (in a different order each)
+                idx[r] = rng.permutation(common)
+            elif kind == 1:    # half shared, half private
+                own = rng.choice(cfg.nb, size=topk, replace=False)
+                idx[r] = np.where(np.arange(topk) % 2 == 0, common, own)
+            elif kind == 2:    # disjoint random rows
+                idx[r] = rng.choice(cfg.nb, size=topk, replace=False)
+            elif kind == 3:    # repeats: the first block twice or three times in odd rows, once in even rows
+                idx[r] = common
+                if r % 2:
+                    idx[r, 1] = common[0]
+                    if topk > 4:
+                        idx[r, 4] = common[0]
+            elif kind == 4:    # holes in the middle, rows of different lengths
+                idx[r] = rng.permutation(common)
+                idx[r, rng.random(topk) < 0.25 * (1 + r % 4)] = -1
+            else:              # pairs share: rows 0, 1 one list, rows 2, 3 another, one row empty
+                idx[r] = common if (r - g) < 2 else rng.choice(cfg.nb, size=topk, replace=False)
+                if r - g == 3:
+                    idx[r] = -1
+    _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx), cfg.name)
+
+
 @pytest.mark.parametrize("n_obj,n_views", [(0, 3), (640, 0)])
 def test_one_modality_only(B, oracle_lib, n_obj, n_views):
     """Sequences without object tokens, or without views: routing finds no candidates of the other
