@@ -183,6 +183,9 @@ def main():
                     help="routing table: the configs' projected-centroid rule (default) or the four geometric "
                          "selection rules (lsrm_route_blocks_3d: B^i = 4, a quarter of top-k volume blocks, the "
                          "rest image blocks)")
+    ap.add_argument("--two-pass", action="store_true",
+                    help="lsrm_nsa_compress, then a forward that repacks k and v itself, instead of the default "
+                         "lsrm_nsa_compress_pack + forward with kv_packed (one pass over k and v for both)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings against)")
@@ -223,6 +226,8 @@ def main():
     d_out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device=dev)
     ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE)
     ws_fwd = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
+    if not (args.two_pass or args.config == 5 or args.backward):
+        p.kv_packed = 1
     four_rule = args.routing == "four-rule" or args.config in I.ROUTE3D
     if four_rule:
         k_vol = I.ROUTE3D[args.config]["k_v2v"] if args.config in I.ROUTE3D else cfg.topk // 4
@@ -254,7 +259,10 @@ def main():
         route()
         if i is not None:
             e[1].record()
-        B.lsrm_nsa_compress(p, d_k, d_v, d_kc, d_vc)
+        if args.two_pass:
+            B.lsrm_nsa_compress(p, d_k, d_v, d_kc, d_vc)
+        else:
+            B.lsrm_nsa_compress_pack(p, d_k, d_v, d_kc, d_vc, ws_fwd)
         if i is not None:
             e[2].record()
         B.lsrm_nsa_forward(p, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, None, None, ws_fwd,

@@ -92,6 +92,11 @@ typedef struct lsrm_nsa_params {
                               output rows are unspecified.  NULL: every block is full.
                               Read by lsrm_nsa_compress, lsrm_nsa_forward and lsrm_nsa_backward
                               (pass the same counts to all three).                            */
+    int32_t kv_packed;     /* lsrm_nsa_forward only.  0: the call repacks d_k, d_v into its workspace
+                              itself.  1: d_ws already holds their repacked form, written by
+                              lsrm_nsa_compress_pack with the same params, d_k, d_v and d_ws (and not
+                              touched since by anything but lsrm_nsa_forward): the repacking pass is
+                              skipped.  Other calls ignore the field.                          */
 } lsrm_nsa_params;
 
 enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2, LSRM_WS_ROUTE_3D = 3 };
@@ -204,6 +209,20 @@ lsrm_status lsrm_route_blocks_3d(const lsrm_nsa_params *p, const lsrm_route3d_pa
  */
 lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, const uint16_t *d_v,
                               uint16_t *d_kc, uint16_t *d_vc, void *stream);
+
+/*
+ * Block compression and the forward's repacking of K and V in one pass over K and V.  [Sec. 3.2,
+ * App. A "Compressed", as lsrm_nsa_compress.]  The layer needs K and V twice before attention starts:
+ * averaged per block, and rearranged into the order the matrix units read them; both are bound by
+ * the same HBM reads, so a caller that runs compress and forward back to back saves one pass.
+ *   d_k, d_v, d_kc, d_vc   as in lsrm_nsa_compress.  The averages are the same means; the fp32
+ *              partial sums are added in a different (fixed) order, so single values may differ
+ *              from lsrm_nsa_compress by one rounding of the bf16 result.
+ *   d_ws, ws_bytes   the workspace of the lsrm_nsa_forward call that follows
+ *              (lsrm_workspace_bytes(p, LSRM_WS_FORWARD)); that call must set params.kv_packed = 1.
+ */
+lsrm_status lsrm_nsa_compress_pack(const lsrm_nsa_params *p, const uint16_t *d_k, const uint16_t *d_v,
+                                   uint16_t *d_kc, uint16_t *d_vc, void *d_ws, size_t ws_bytes, void *stream);
 
 /*
  * NSA forward.  [App. A, Eq. (nsa_1): o_i = w_cmp CmpAttn(q_i, k_cmp, v_cmp)

@@ -36,7 +36,7 @@ class lsrm_nsa_params(ctypes.Structure):
                 ("d", ctypes.c_int32), ("topk", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("n_seg", ctypes.c_int32), ("seg_offsets", ctypes.POINTER(ctypes.c_int32)),
                 ("scale", ctypes.c_float), ("gate_channels", ctypes.c_int32), ("window_mode", ctypes.c_int32),
-                ("d_block_count", ctypes.c_void_p)]
+                ("d_block_count", ctypes.c_void_p), ("kv_packed", ctypes.c_int32)]
 
 
 class lsrm_route3d_params(ctypes.Structure):
@@ -62,6 +62,8 @@ _lib.lsrm_route_blocks_3d.restype = ctypes.c_int32
 _lib.lsrm_route_blocks_3d.argtypes = [_pp, ctypes.POINTER(lsrm_route3d_params), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.lsrm_nsa_compress.restype = ctypes.c_int32
 _lib.lsrm_nsa_compress.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
+_lib.lsrm_nsa_compress_pack.restype = ctypes.c_int32
+_lib.lsrm_nsa_compress_pack.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.lsrm_nsa_forward.restype = ctypes.c_int32
 _lib.lsrm_nsa_forward.argtypes = [_pp] + [_vp] * 11 + [_sz, _vp, _vp, _vp]
 _lib.lsrm_nsa_backward.restype = ctypes.c_int32
@@ -142,6 +144,14 @@ def lsrm_nsa_compress(p, k, v, kc, vc, stream=None):
     """k, v bf16 [N,H,d] -> kc, vc bf16 [N/64,H,d]."""
     _check(_lib.lsrm_nsa_compress(ctypes.byref(p), _ptr(k), _ptr(v), _ptr(kc), _ptr(vc), _stream(stream)),
            "lsrm_nsa_compress")
+
+
+def lsrm_nsa_compress_pack(p, k, v, kc, vc, ws, stream=None):
+    """lsrm_nsa_compress that also leaves the repacked k, v in the forward workspace `ws`; the forward call that
+    follows takes params with kv_packed = 1."""
+    nbytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(_lib.lsrm_nsa_compress_pack(ctypes.byref(p), _ptr(k), _ptr(v), _ptr(kc), _ptr(vc), _ptr(ws), nbytes,
+                                       _stream(stream)), "lsrm_nsa_compress_pack")
 
 
 def _event(ev):

@@ -15,6 +15,7 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     if (!(p->scale >= 0.0f) || __builtin_isinf(p->scale)) return LSRM_ERR_INVALID_ARG;
     if (p->h_q % p->h_kv != 0 || (p->gate_channels != 0 && p->gate_channels != 1)) return LSRM_ERR_INVALID_ARG;
     if (p->window_mode != 0 && p->window_mode != 1) return LSRM_ERR_INVALID_ARG;
+    if (p->kv_packed != 0 && p->kv_packed != 1) return LSRM_ERR_INVALID_ARG;
     if (p->block != kBlock || (p->d != 32 && p->d != 64 && p->d != 128) || p->topk > 64) return LSRM_ERR_UNSUPPORTED;
     int64_t n_img = (int64_t)p->n_views * p->grid * p->grid;
     int64_t n = (int64_t)p->n_obj + n_img;
@@ -30,6 +31,7 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     s->own_block = p->window_mode == 1;
     s->window = s->own_block ? 128 : p->window;
     s->count = p->d_block_count;
+    s->kv_packed = p->kv_packed;
     s->nb_obj = p->n_obj / kBlock;
     s->tiles_per_view = (p->grid / 8) * (p->grid / 8);
     s->n_tiles = p->n_views * s->tiles_per_view;
@@ -147,6 +149,18 @@ lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, con
     if (d_k == nullptr || d_v == nullptr || d_kc == nullptr || d_vc == nullptr) return LSRM_ERR_INVALID_ARG;
     if (!aligned(d_k, 16) || !aligned(d_v, 16) || !aligned(d_kc, 16) || !aligned(d_vc, 16)) return LSRM_ERR_INVALID_ARG;
     return launch_compress(s, d_k, d_v, d_kc, d_vc, static_cast<hipStream_t>(stream));
+}
+
+lsrm_status lsrm_nsa_compress_pack(const lsrm_nsa_params *p, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
+                                   uint16_t *d_vc, void *d_ws, size_t ws_bytes, void *stream) {
+    Shape s;
+    lsrm_status rc = make_shape(p, &s);
+    if (rc != LSRM_OK) return rc;
+    if (s.nb == 0) return LSRM_OK;
+    if (d_k == nullptr || d_v == nullptr || d_kc == nullptr || d_vc == nullptr) return LSRM_ERR_INVALID_ARG;
+    if (!aligned(d_k, 16) || !aligned(d_v, 16) || !aligned(d_kc, 16) || !aligned(d_vc, 16)) return LSRM_ERR_INVALID_ARG;
+    if (d_ws == nullptr || !aligned(d_ws, 256) || ws_bytes < forward_ws_bytes(s)) return LSRM_ERR_WORKSPACE;
+    return launch_compress_pack(s, d_k, d_v, d_kc, d_vc, d_ws, static_cast<hipStream_t>(stream));
 }
 
 lsrm_status lsrm_nsa_forward(const lsrm_nsa_params *p, const uint16_t *d_q, const uint16_t *d_k, const uint16_t *d_v,

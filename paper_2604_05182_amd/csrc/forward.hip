@@ -1074,26 +1074,46 @@ __device__ __forceinline__ int64_t image_index(int64_t tile, int head, int h, in
     return ROWS_ONLY ? tile * h + head : (int64_t)head * n_tiles + tile;
 }
 
-template <int D, bool ROWS_ONLY>
+// POOL (with the full images only): the block averages of k and v are written as well (kc, vc [n_rows / 64, H, D]
+// bf16: Sec. 3.2, the compressed pair of the block), so that one pass over K and V serves both the pooling and
+// the packing.  A thread sums its rows in fp32 in token order (rows t, t + 2048 / D, ...); the partial sums of
+// the 2048 / D threads that share a channel group are added in thread order; one rounding to bf16.
+template <int D, bool ROWS_ONLY, bool POOL = false>
 __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k, const uint16_t *__restrict__ v,
                                                   char *__restrict__ img, int64_t n_rows, int h, int n_tiles,
-                                                  const int32_t *__restrict__ count) {
+                                                  const int32_t *__restrict__ count, uint16_t *__restrict__ kc = nullptr,
+                                                  uint16_t *__restrict__ vc = nullptr) {
+    static_assert(!(POOL && ROWS_ONLY), "");
     constexpr int K_BYTES = 32 * D * 2, TILE = ROWS_ONLY ? K_BYTES : K_BYTES + D * 64;
     constexpr int CH = D / 8;  // 16-byte chunks per row
     __shared__ uint16_t vt[64][D + 2];
+    __shared__ float psum[POOL ? 2 : 1][POOL ? 256 / CH : 1][POOL ? D + 1 : 1];  // [k, v][thread group][channel]
     const int64_t blk = blockIdx.x;
     const int head = blockIdx.y;
     const int n_act = count != nullptr ? count[blk] : 64;
+    float ak[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, av[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // K: a permutation of 16-byte chunks.  Source chunk (row t, chunk cc) goes to fragment
     // ks = cc / 2, lane (hh = cc % 2, r = perm(t % 32)) of tile t / 32.
-    for (int e = threadIdx.x; e < 64 * CH; e += 256) {
+    // all loads of the thread first (64 CH / 256 chunks of k and as many of v), so that they are in flight together
+    constexpr int NIT = 64 * CH / 256;
+    uint4 kin[NIT], vin[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int e = threadIdx.x + 256 * it;
         const int t = e / CH, cc = e % CH;
         const int64_t row = blk * 64 + t;
-        uint4 kval = make_uint4(0, 0, 0, 0), vval = make_uint4(0, 0, 0, 0);
+        kin[it] = make_uint4(0, 0, 0, 0);
+        vin[it] = make_uint4(0, 0, 0, 0);
         if (row < n_rows && t < n_act) {
-            kval = *reinterpret_cast<const uint4 *>(k + (row * h + head) * D + cc * 8);
-            if (!ROWS_ONLY) vval = *reinterpret_cast<const uint4 *>(v + (row * h + head) * D + cc * 8);
+            kin[it] = *reinterpret_cast<const uint4 *>(k + (row * h + head) * D + cc * 8);
+            if (!ROWS_ONLY) vin[it] = *reinterpret_cast<const uint4 *>(v + (row * h + head) * D + cc * 8);
         }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int e = threadIdx.x + 256 * it;
+        const int t = e / CH, cc = e % CH;
+        const uint4 kval = kin[it], vval = vin[it];
         const int64_t tile = blk * 2 + t / 32;
         if (tile < n_tiles) {
             const int tt = t % 32;
@@ -1108,9 +1128,39 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
             vt[t][cc * 8 + 2 * j] = (uint16_t)(w[j] & 0xffffu);
             vt[t][cc * 8 + 2 * j + 1] = (uint16_t)(w[j] >> 16);
         }
+        if (POOL) {
+            const uint32_t kw[4] = {kval.x, kval.y, kval.z, kval.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ak[2 * j] += __uint_as_float(kw[j] << 16);
+                ak[2 * j + 1] += __uint_as_float(kw[j] & 0xffff0000u);
+                av[2 * j] += __uint_as_float(w[j] << 16);
+                av[2 * j + 1] += __uint_as_float(w[j] & 0xffff0000u);
+            }
+        }
     }
     if (ROWS_ONLY) return;
+    if (POOL) {
+        // (every thread keeps one chunk column cc = threadIdx.x % CH: 256 is a multiple of CH)
+        const int grp = threadIdx.x / CH, cc = threadIdx.x % CH;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            psum[0][grp][cc * 8 + j] = ak[j];
+            psum[1][grp][cc * 8 + j] = av[j];
+        }
+    }
     __syncthreads();
+    if (POOL) {
+        if (threadIdx.x < 2 * D) {
+            const int which = threadIdx.x / D, c = threadIdx.x % D;
+            float sum = 0.f;
+            for (int g = 0; g < 256 / CH; ++g) sum += psum[which][g][c];
+            const float mean = sum / (float)n_act;
+            uint32_t u = __float_as_uint(mean);
+            u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
+            (which == 0 ? kc : vc)[(blk * h + head) * D + c] = (uint16_t)(u >> 16);
+        }
+    }
     // V^T: chunk e of a tile = fragment f = e / 64 (ks2 = f / ND, dt = f % ND), lane = e % 64
     // (hh = lane / 32, r = lane % 32): channel 32 dt + r, keys 16 ks2 + 8 hh + 0..7.
     constexpr int ND = D / 32;
@@ -1156,9 +1206,11 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     constexpr int D = G::D, NP = G::NP;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     const int tiles_c = (s.nb + 31) / 32;
-    hipLaunchKernelGGL((pack_tiles<D, false>), dim3(s.nb, s.h_kv), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h_kv,
-                       2 * s.nb, a.count);
-    LSRM_HIP_CHECK(hipGetLastError());
+    if (!s.kv_packed) {
+        hipLaunchKernelGGL((pack_tiles<D, false>), dim3(s.nb, s.h_kv), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h_kv,
+                           2 * s.nb, a.count);
+        LSRM_HIP_CHECK(hipGetLastError());
+    }
     hipLaunchKernelGGL((pack_tiles<D, false>), dim3((s.nb + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
                        (int64_t)s.nb, s.h_kv, tiles_c, (const int32_t *)nullptr);
     LSRM_HIP_CHECK(hipGetLastError());
@@ -1194,6 +1246,25 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
 }  // namespace
 
 size_t forward_ws_bytes(const Shape &s) { return ws_layout(s).total; }
+
+lsrm_status launch_compress_pack(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
+                                 uint16_t *d_vc, void *d_ws, hipStream_t st) {
+    if (s.nb == 0) return LSRM_OK;
+    char *img = reinterpret_cast<char *>(d_ws) + ws_layout(s).kv;
+    const dim3 grid(s.nb, s.h_kv);
+#define LSRM_POOL_PACK(DD) \
+    hipLaunchKernelGGL((pack_tiles<DD, false, true>), grid, dim3(256), 0, st, d_k, d_v, img, s.n, s.h_kv, 2 * s.nb, s.count, \
+                       d_kc, d_vc)
+    if (s.d == 32)
+        LSRM_POOL_PACK(32);
+    else if (s.d == 64)
+        LSRM_POOL_PACK(64);
+    else
+        LSRM_POOL_PACK(128);
+#undef LSRM_POOL_PACK
+    LSRM_HIP_CHECK(hipGetLastError());
+    return LSRM_OK;
+}
 
 lsrm_status launch_pack_tiles(int d, const uint16_t *rows_src, const uint16_t *t_src, char *img, int64_t n_rows, int h,
                               int n_tiles, hipStream_t st, bool rows_only, const int32_t *count) {

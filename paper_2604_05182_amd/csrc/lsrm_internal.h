@@ -15,6 +15,7 @@ struct Shape {
     int gate_channels;  // 0: gates [N, H, 3]; 1: gates [N, 3, H, d]
     int own_block;      // window branch = the query's own block; `window` is then 128 (every slot of the block
                         // within reach) and the kernels treat the block as its own segment
+    int kv_packed;      // the forward workspace already holds the tile images of k and v (lsrm_nsa_compress_pack)
     const int32_t *count;  // device, nullable [nb]: active tokens per block
     int nb_obj, tiles_per_view, n_tiles, nb;
     int64_t n;
@@ -53,6 +54,10 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
                            float *d_lse, uint16_t *d_out_branch, void *d_ws, hipStream_t st, hipEvent_t ev_start,
                            hipEvent_t ev_stop);
 size_t forward_ws_bytes(const Shape &s);
+// Pooling and packing in one pass over k and v: kc, vc as launch_compress writes them (same mean, fp32 partial sums
+// added in a different order) and the tile images of (k, v) in the forward workspace d_ws.
+lsrm_status launch_compress_pack(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
+                                 uint16_t *d_vc, void *d_ws, hipStream_t st);
 // Step schedule of the selected branch (schedule.hip): the rows of d_idx reordered so that the four query blocks of
 // an attention workgroup meet a block they share at the same step; d_sched [ceil(nb / 4) * 4, topk] int32, an entry
 // is block id | owner << 28.

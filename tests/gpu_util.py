@@ -61,19 +61,30 @@ def run_compress(B, cfg, k_bits, v_bits, block_count=None):
 
 
 def run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets="default", scale=0.0,
-                want_aux=False, window=None, window_mode=0, block_count=None):
-    """compress + forward on the device.  Returns dict of numpy results (+ device kc, vc)."""
+                want_aux=False, window=None, window_mode=0, block_count=None, fused_pack=False):
+    """compress + forward on the device.  Returns dict of numpy results (+ device kc, vc).
+    fused_pack: lsrm_nsa_compress_pack, then the forward with kv_packed = 1 (one pass over k and v for both)."""
     topk = idx.shape[1]
     p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window, window_mode=window_mode,
                    block_count=block_count)
     dq = bf16_dev(q_bits)
-    dk, dv, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count)
+    if fused_pack:
+        dk, dv = bf16_dev(k_bits), bf16_dev(v_bits)
+        kc = torch.empty((cfg.nb, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device="cuda")
+        vc = torch.empty_like(kc)
+        ws = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
+        ws.fill_(0xFF)   # NaN patterns: an image the fused pass fails to write shows
+        B.lsrm_nsa_compress_pack(p, dk, dv, kc, vc, ws)
+        p.kv_packed = 1
+    else:
+        dk, dv, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count)
     d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
     d_g = torch.from_numpy(gates).cuda()
     out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((3, cfg.n, cfg.heads), dtype=torch.float32, device="cuda") if want_aux else None
     ob = torch.empty((3, cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda") if want_aux else None
-    ws = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
+    if not fused_pack:
+        ws = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
     B.lsrm_nsa_forward(p, dq, dk, dv, kc, vc, d_idx, d_g, out, lse, ob, ws)
     torch.cuda.synchronize()
     res = {"out": bf16_host(out), "kc": bf16_host(kc), "vc": bf16_host(vc)}

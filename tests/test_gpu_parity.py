@@ -205,6 +205,47 @@ def test_compress_with_active_counts(B, oracle_lib):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-6)
 
 
+@pytest.mark.parametrize("d,heads,h_kv,with_counts", [(64, 2, 2, False), (128, 3, 3, False), (32, 8, 2, False),
+                                                      (128, 2, 2, True), (64, 4, 1, True)])
+def test_compress_pack_then_forward(B, oracle_lib, d, heads, h_kv, with_counts):
+    """lsrm_nsa_compress_pack (pooling and repacking in one pass over k and v) followed by the forward with
+    kv_packed = 1: the pooled pairs against the oracle's means, the attention outputs against the oracle, and
+    bit for bit against the two-pass route when both are given the same pooled pairs."""
+    cfg = I.small_config(name=f"f-fused-d{d}-h{heads}-kv{h_kv}-cnt{int(with_counts)}", n_obj=1088, n_views=3, grid=24,
+                         heads=heads, d=d, topk=5, window=200, seed=43, h_kv=h_kv)
+    _log(f"[compress_pack + forward] {cfg.name} nb={cfg.nb}")
+    cnt = _block_counts(cfg, 9) if with_counts else None
+    q_bits, k_bits, v_bits = I.make_qkv(cfg)
+    gates = I.make_gates(cfg)
+    idx, _ = oracle_lib.route(I.make_points(cfg), I.make_cameras(cfg), cfg.grid, cfg.topk)
+    if cnt is not None:
+        inactive = (np.arange(cfg.n) % 64) >= np.repeat(cnt, 64)
+        k_bits, v_bits = k_bits.copy(), v_bits.copy()
+        k_bits[inactive] = 0x7FC0
+        v_bits[inactive] = 0x7FC0
+    res = G.run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, want_aux=True, block_count=cnt, fused_pack=True)
+    q, k, v = (I.bf16_bits_to_f32(a) for a in (q_bits, k_bits, v_bits))
+    kc, vc = oracle_lib.pool(k, cnt), oracle_lib.pool(v, cnt)
+    for got, ref in ((res["kc"], kc), (res["vc"], vc)):
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-6)
+    ref_out, ref_lse, ref_ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, cfg.seg_offsets(), cfg.window,
+                                                      want_lse=True, want_branches=True, block_count=cnt)
+    sel = slice(None) if cnt is None else (np.arange(cfg.n) % 64) < np.repeat(cnt, 64)
+    got = {"out": res["out"][sel], "lse": res["lse"][:, sel], "ob": res["ob"][:, sel]}
+    _assert_forward(got, ref_out[sel], ref_lse[:, sel], ref_ob[:, sel], cfg.name)
+    # the images of the fused pass are those of the forward's own packing: same pooled pairs in, same bits out
+    import torch
+    p = G.params_for(B, cfg, block_count=cnt)
+    dq, dk, dv = (G.bf16_dev(a) for a in (q_bits, k_bits, v_bits))
+    kc_d, vc_d = (torch.from_numpy(I.f32_to_bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+                  for a in (res["kc"], res["vc"]))
+    out2 = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
+    B.lsrm_nsa_forward(p, dq, dk, dv, kc_d, vc_d, torch.from_numpy(idx).cuda(), torch.from_numpy(gates).cuda(), out2,
+                       None, None, B.alloc_workspace(p, B.LSRM_WS_FORWARD))
+    torch.cuda.synchronize()
+    assert np.array_equal(G.bf16_host(out2)[sel], res["out"][sel])
+
+
 def test_forward_dense_equivalence(B, oracle_lib):
     """Single segment, window covering the sequence, every block routed: the selected and
     window branches both equal plain full attention (compared with the oracle's)."""
