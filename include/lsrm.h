@@ -37,7 +37,7 @@ typedef int32_t lsrm_status;
 enum {
     LSRM_OK = 0,
     LSRM_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, misaligned segment, ... */
-    LSRM_ERR_UNSUPPORTED = -2, /* block != 64, d not in {32,64,128}, topk > 64, ...         */
+    LSRM_ERR_UNSUPPORTED = -2, /* block != 64, d not in {32,64,128}, topk > 128, ..         */
     LSRM_ERR_WORKSPACE = -3,   /* d_ws null / too small / misaligned                        */
     LSRM_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed                */
     LSRM_ERR_TOO_LARGE = -5    /* lsrm_route_blocks_static: the problem needs more than the
@@ -72,7 +72,7 @@ typedef struct lsrm_nsa_params {
     int32_t h_kv;     /* key/value heads, a divisor of h_q: query head i reads key/value
                          head i / (h_q / h_kv) (grouped-query heads, App. A)               */
     int32_t d;        /* head dimension: 32, 64 or 128                                     */
-    int32_t topk;     /* K routed key blocks per query block (<= 64)                       */
+    int32_t topk;     /* K routed key blocks per query block (<= 128)                      */
     int32_t window;   /* W, even: query i sees keys j with -W/2 <= j - i < W/2             */
     int32_t n_seg;    /* number of window segments                                         */
     const int32_t *seg_offsets; /* HOST, n_seg + 1 ascending token offsets, multiples of 64,

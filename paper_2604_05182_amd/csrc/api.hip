@@ -16,7 +16,7 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     if (p->h_q % p->h_kv != 0 || (p->gate_channels != 0 && p->gate_channels != 1)) return LSRM_ERR_INVALID_ARG;
     if (p->window_mode != 0 && p->window_mode != 1) return LSRM_ERR_INVALID_ARG;
     if (p->kv_packed != 0 && p->kv_packed != 1) return LSRM_ERR_INVALID_ARG;
-    if (p->block != kBlock || (p->d != 32 && p->d != 64 && p->d != 128) || p->topk > 64) return LSRM_ERR_UNSUPPORTED;
+    if (p->block != kBlock || (p->d != 32 && p->d != 64 && p->d != 128) || p->topk > 128) return LSRM_ERR_UNSUPPORTED;
     int64_t n_img = (int64_t)p->n_views * p->grid * p->grid;
     int64_t n = (int64_t)p->n_obj + n_img;
     if (n > (int64_t)1 << 30) return LSRM_ERR_UNSUPPORTED;

@@ -458,7 +458,8 @@ __global__ void rev_sort_serial(BwdArgs a) {
 
 // ---------------------------------------------------------------------------------------------
 // dQ: one workgroup (2 wavefronts x 32 query rows) per (query block, head)
-template <int D>
+// WIDE: routing rows of 65..128 entries (two per lane of the list holder instead of one).
+template <int D, bool WIDE>
 __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     // (at d = 128 the 256-register budget of two workgroups per SIMD still holds: 64 accumulator registers)
     using G = BGeo<D>;
@@ -515,18 +516,41 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
 
     // ---- the tiles of this query block: pooled, routed, window
     const int tc = (a.nb + 31) / 32;
-    int packed = -1, n_valid = 0;
+    // the routing row, valid entries first: entry u sits in lane u % 64 of register u / 64 (compacted through LDS;
+    // the LDS operations of a wavefront complete in order, so the reads see the writes)
+    constexpr int NR = WIDE ? 2 : 1;
+    __shared__ int row_scratch[2][128];
+    int packed[NR], pcount[NR], n_valid = 0;
     {
-        int v = lane < a.topk ? a.idx[(int64_t)qb * a.topk + lane] : -1;
-        if (v >= a.nb) v = -1;
-        const unsigned long long valid = __ballot(v >= 0);
-        n_valid = __popcll(valid);
-        const int rank = __popcll(valid & ((1ull << lane) - 1ull));
-        packed = __builtin_amdgcn_ds_permute((v >= 0 ? rank : 63) * 4, v);
-        if (n_valid == 64) packed = v;
+        int v[NR], before = 0;
+        unsigned long long bal[NR];
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int col = lane + 64 * j;
+            v[j] = col < a.topk ? a.idx[(int64_t)qb * a.topk + col] : -1;
+            if (v[j] >= a.nb) v[j] = -1;
+            bal[j] = __ballot(v[j] >= 0);
+            n_valid += __popcll(bal[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            if (v[j] >= 0) row_scratch[wave][before + __popcll(bal[j] & ((1ull << lane) - 1ull))] = v[j];
+            before += __popcll(bal[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < NR; ++j) packed[j] = lane + 64 * j < n_valid ? row_scratch[wave][lane + 64 * j] : -1;
     }
-    // active tokens of the routed blocks, one per lane like the list itself
-    const int pcount = a.count != nullptr && lane < n_valid ? a.count[packed] : 64;
+    // active tokens of the routed blocks, held like the list itself
+#pragma unroll
+    for (int j = 0; j < NR; ++j) pcount[j] = a.count != nullptr && lane + 64 * j < n_valid ? a.count[packed[j]] : 64;
+    auto entry = [&](const int (&reg)[NR], int u) {  // wave-uniform u
+        if constexpr (WIDE) {
+            const int e0 = __builtin_amdgcn_readlane(reg[0], u & 63), e1 = __builtin_amdgcn_readlane(reg[NR - 1], u & 63);
+            return u < 64 ? e0 : e1;
+        } else {
+            return __builtin_amdgcn_readlane(reg[0], u);
+        }
+    };
     const int ts = 2 * n_valid;
     int seg_lo = 0, seg_hi = 0;
     for (int s = 0; s < a.n_seg; ++s)
@@ -563,7 +587,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
             issue_tile(a.img_kc, a.img_vc, t, buf);
         } else if (t < tc + ts) {
             const int u = t - tc;
-            issue_tile(a.img_k, a.img_v, 2 * __builtin_amdgcn_readlane(packed, u >> 1) + (u & 1), buf);
+            issue_tile(a.img_k, a.img_v, 2 * entry(packed, u >> 1) + (u & 1), buf);
         } else {
             issue_tile(a.img_k, a.img_v, st0 + (t - tc - ts), buf);
         }
@@ -638,13 +662,13 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
                });
     // routed blocks: every key counts, except padding slots
     run_branch(tc, tc + ts, std::integral_constant<int, 1>{}, a.img_k, a.img_v,
-               [&](int u) { return 2 * __builtin_amdgcn_readlane(packed, u >> 1) + (u & 1); },
+               [&](int u) { return 2 * entry(packed, u >> 1) + (u & 1); },
                [&](int u, int *j0, int *lo, int *hi) {
                    *j0 = 0;
                    *lo = 0;
                    *hi = 32;
                    if (a.count == nullptr) return false;
-                   *hi = valid_keys(__builtin_amdgcn_readlane(pcount, u >> 1), u & 1);
+                   *hi = valid_keys(entry(pcount, u >> 1), u & 1);
                    return *hi < 32;
                });
     // window: the band's edges and the segment's ends, and padding slots
@@ -1096,16 +1120,13 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
                               hipEvent_t ev_stop) {
     using G = BGeo<D>;
     constexpr int DKV_LDS = LSRM_BWD_DKV_NBUF * (2 * G::ROW + 1024);
-    static bool attr_set = false;
-    if (!attr_set) {
-        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 0>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
-        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
-        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 2>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
-        attr_set = true;
-    }
+    // (set on every call: cheap, and right whichever device is current and whichever thread calls)
+    LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 0>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
+    LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
+    LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 2>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
     const int ntc = (s.nb + 31) / 32;
     lsrm_status rc;
@@ -1146,7 +1167,10 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
             hipLaunchKernelGGL(rev_sort_serial, dim3((s.nb + 63) / 64), dim3(64), 0, st, a);
         LSRM_HIP_CHECK(hipGetLastError());
     }
-    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
+    if (s.topk > 64)
+        hipLaunchKernelGGL((bwd_dq_kernel<D, true>), dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
+    else
+        hipLaunchKernelGGL((bwd_dq_kernel<D, false>), dim3((s.nb + 7) / 8 * 8, s.h), dim3(128), 0, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3((w.nbp / 64 + 7) / 8 * 8, s.h_kv, w.n_split), dim3(128), DKV_LDS, st,
                        a);

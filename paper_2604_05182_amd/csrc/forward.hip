@@ -891,7 +891,8 @@ __device__ __forceinline__ WinRange window_range(const FwdArgs &a, int qb) {
 }
 
 // CNT: a.count is given (variable number of active tokens per block).
-template <class G, bool CNT>
+// WIDE: routing rows of 65..128 entries (two per lane of the list holder instead of one).
+template <class G, bool CNT, bool WIDE>
 __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward_kernel(FwdArgs a) {
     constexpr int D = G::D, NP = G::NP;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -956,47 +957,83 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
     // ---------------- selected branch: every token of the routed blocks
     {
         reset_branch<G>(c);
-        int packed = -1, pcount = 0, my_valid = 0, max_valid = 0;
+        // this query block's routing row, valid entries first: entry u sits in lane u % 64 of register u / 64
+        constexpr int NR = WIDE ? 2 : 1;
+        int packed[NR], pcount[NR], my_valid = 0, max_valid = 0;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) packed[j] = -1, pcount[j] = 0;
         if constexpr (D == 128) {
-            // rows of the step schedule (schedule.hip): valid entries first, block id | owner << 28
+            // rows of the step schedule (schedule.hip): already compact, block id | owner << 28
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
-                const int v = lane < a.topk ? a.sched[((int64_t)group * NP + p) * a.topk + lane] : -1;
-                const int n_valid = __popcll(__ballot(v >= 0));
-                max_valid = max(max_valid, n_valid);
-                if (p == qbi) {
-                    packed = v;
-                    my_valid = n_valid;
+                int n_valid = 0;
+#pragma unroll
+                for (int j = 0; j < NR; ++j) {
+                    const int col = lane + 64 * j;
+                    const int v = col < a.topk ? a.sched[((int64_t)group * NP + p) * a.topk + col] : -1;
+                    n_valid += __popcll(__ballot(v >= 0));
+                    if (p == qbi) packed[j] = v;
                 }
+                max_valid = max(max_valid, n_valid);
+                if (p == qbi) my_valid = n_valid;
             }
         } else {
+            // rows of the routing table: compacted through this wavefront's 512 bytes behind the tile slots
+            int *scratch = reinterpret_cast<int *>(lds + G::LDS_BYTES) + wave * 128;
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
                 const int qbp = group * NP + p;
-                int v = (qbp < a.nb && lane < a.topk) ? a.idx[(int64_t)qbp * a.topk + lane] : -1;
-                if (v >= a.nb) v = -1;
-                const unsigned long long valid = __ballot(v >= 0);
-                const int n_valid = __popcll(valid);
+                int v[NR], n_valid = 0;
+                unsigned long long bal[NR];
+#pragma unroll
+                for (int j = 0; j < NR; ++j) {
+                    const int col = lane + 64 * j;
+                    v[j] = (qbp < a.nb && col < a.topk) ? a.idx[(int64_t)qbp * a.topk + col] : -1;
+                    if (v[j] >= a.nb) v[j] = -1;
+                    bal[j] = __ballot(v[j] >= 0);
+                    n_valid += __popcll(bal[j]);
+                }
                 max_valid = max(max_valid, n_valid);
                 if (p == qbi) {
-                    // compact the valid entries of this block's row to lanes 0..n_valid-1
-                    const int rank = __popcll(valid & ((1ull << lane) - 1ull));
-                    packed = __builtin_amdgcn_ds_permute((v >= 0 ? rank : 63) * 4, v);
-                    if (n_valid == 64) packed = v;
+                    int before = 0;
+#pragma unroll
+                    for (int j = 0; j < NR; ++j) {
+                        if (v[j] >= 0) scratch[before + __popcll(bal[j] & ((1ull << lane) - 1ull))] = v[j];
+                        before += __popcll(bal[j]);
+                    }
+                    // (LDS operations of a wavefront complete in order: the reads below see the writes above)
+#pragma unroll
+                    for (int j = 0; j < NR; ++j) packed[j] = lane + 64 * j < n_valid ? scratch[lane + 64 * j] : -1;
                     my_valid = n_valid;
                 }
             }
         }
-        if constexpr (CNT) pcount = lane < my_valid ? a.count[packed & 0xFFFFFF] : 0;
-        const char *base = a.kv + head_kv;
-        auto src = [&](int t) {
-            const int kb = __builtin_amdgcn_readlane(packed, t >> 1) & 0xFFFFFF;
-            return base + (2 * kb + (t & 1)) * tile_stride;
+        if constexpr (CNT) {
+#pragma unroll
+            for (int j = 0; j < NR; ++j) pcount[j] = lane + 64 * j < my_valid ? a.count[packed[j] & 0xFFFFFF] : 0;
+        }
+        // entry u of the row / of the counts (wave-uniform u)
+        auto entry = [&](int u) {
+            if constexpr (WIDE) {
+                const int e0 = __builtin_amdgcn_readlane(packed[0], u & 63), e1 = __builtin_amdgcn_readlane(packed[NR - 1], u & 63);
+                return u < 64 ? e0 : e1;
+            } else {
+                return __builtin_amdgcn_readlane(packed[0], u);
+            }
         };
+        const char *base = a.kv + head_kv;
+        auto src = [&](int t) { return base + (2 * (entry(t >> 1) & 0xFFFFFF) + (t & 1)) * tile_stride; };
         // the query block whose wavefronts copy this query block's tile of step t (always itself without a schedule)
-        auto own = [&](int t) { return D == 128 ? (__builtin_amdgcn_readlane(packed, t >> 1) >> 28) & 3 : qbi; };
+        auto own = [&](int t) { return D == 128 ? (entry(t >> 1) >> 28) & 3 : qbi; };
         auto valid = [&](int t) {  // active keys of tile t of this query block's list
-            int cnt = __builtin_amdgcn_readlane(pcount, t >> 1);
+            const int u = t >> 1;
+            int cnt;
+            if constexpr (WIDE) {
+                const int c0 = __builtin_amdgcn_readlane(pcount[0], u & 63), c1 = __builtin_amdgcn_readlane(pcount[NR - 1], u & 63);
+                cnt = u < 64 ? c0 : c1;
+            } else {
+                cnt = __builtin_amdgcn_readlane(pcount[0], u);
+            }
             return min(32, max(0, cnt - 32 * (t & 1)));
         };
         run_own<G, CNT>(c, 2 * max_valid, 2 * my_valid, src, own, valid, lds, qbi, sub, lane, sl2);
@@ -1224,20 +1261,19 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     a.gsum = (float *)(ws + w.gsum);
     a.groups_per_head = (s.nb + NP - 1) / NP;
     a.groups_per_xcd = (a.groups_per_head + 7) / 8;
-    static bool attr_set = false;
-    if (!attr_set) {
-        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<G, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
-        LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&nsa_forward_kernel<G, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
-        attr_set = true;
-    }
+    // dynamic LDS: the tile slots, then 512 bytes per wavefront for compacting a routing row
+    constexpr int kLds = G::LDS_BYTES + G::WAVES * 512;
+    const bool cnt = a.count != nullptr, wide = s.topk > 64;
+    const void *kern = cnt ? (wide ? reinterpret_cast<const void *>(&nsa_forward_kernel<G, true, true>)
+                                   : reinterpret_cast<const void *>(&nsa_forward_kernel<G, true, false>))
+                           : (wide ? reinterpret_cast<const void *>(&nsa_forward_kernel<G, false, true>)
+                                   : reinterpret_cast<const void *>(&nsa_forward_kernel<G, false, false>));
+    // (set on every launch: cheap, and right whichever device is current and whichever thread calls)
+    LSRM_HIP_CHECK(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
     const dim3 grid(8 * a.groups_per_xcd * s.h);
-    if (a.count != nullptr)
-        hipLaunchKernelGGL((nsa_forward_kernel<G, true>), grid, dim3(G::THREADS), G::LDS_BYTES, st, a);
-    else
-        hipLaunchKernelGGL((nsa_forward_kernel<G, false>), grid, dim3(G::THREADS), G::LDS_BYTES, st, a);
+    void *kargs[] = {&a};
+    LSRM_HIP_CHECK(hipLaunchKernel(kern, grid, dim3(G::THREADS), kargs, kLds, st));
     LSRM_HIP_CHECK(hipGetLastError());
     if (ev_stop != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_stop, st));
     return LSRM_OK;

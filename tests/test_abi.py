@@ -36,7 +36,7 @@ def test_host_side_argument_checks():
     assert B.lsrm_workspace_bytes(ok, B.LSRM_WS_FORWARD) >= 1024 * 2 * 64 * 2
     for bad in (B.make_params(500, 2, 16, 2, 64, 3, 128), B.make_params(512, 2, 12, 2, 64, 3, 128),
                 B.make_params(512, 2, 16, 2, 64, 3, 127), B.make_params(512, 2, 16, 2, 96, 3, 128),
-                B.make_params(512, 2, 16, 2, 64, 65, 128), B.make_params(512, 2, 16, 3, 64, 3, 128, h_kv=2)):
+                B.make_params(512, 2, 16, 2, 64, 129, 128), B.make_params(512, 2, 16, 3, 64, 3, 128, h_kv=2)):
         assert B.lsrm_workspace_bytes(bad, B.LSRM_WS_FORWARD) == 0
     assert B.strerror(B.LSRM_ERR_WORKSPACE).startswith("workspace")
     # null pointers are rejected before anything is launched

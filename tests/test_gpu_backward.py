@@ -89,6 +89,23 @@ def test_backward_repeated_and_popular_blocks(B, oracle_lib, d):
     _assert_grads(got, oracle_lib.nsa_backward(*args), cfg0.name)
 
 
+@pytest.mark.parametrize("d,topk", [(64, 128), (128, 80), (32, 100)])
+def test_backward_wide_routing_rows(B, oracle_lib, d, topk):
+    """Routing rows of 65..128 entries (the paper's stage-3 budgets at 16 views need 80), with holes on either
+    side of entry 64 and a row whose valid entries all sit past it."""
+    cfg = I.small_config(name=f"b-topk{topk}-d{d}", n_obj=8192, n_views=2, grid=16, heads=2, d=d, topk=topk, window=64,
+                         seed=63)
+    _log(f"[backward] {cfg.name} nb={cfg.nb}")
+    rng = np.random.default_rng(14)
+    idx = np.stack([rng.choice(cfg.nb, size=topk, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[1::3][rng.random(idx[1::3].shape) < 0.3] = -1
+    idx[5, :70] = -1
+    got, args = _case(B, oracle_lib, cfg, idx=idx)
+    # every block and head through the sampled function (the same arithmetic, spread over the host's threads)
+    every = np.arange(cfg.nb, dtype=np.int32)
+    _assert_grads(got, oracle_lib.nsa_backward_sampled(*args, every, every, list(range(cfg.heads))), cfg.name)
+
+
 def test_backward_own_block_window(B, oracle_lib):
     """The window branch over the query's own block (App. A) instead of the sliding window."""
     cfg = I.small_config(name="b-ownblock", n_obj=1088, n_views=3, grid=24, heads=3, d=64, topk=5, window=200, seed=23)

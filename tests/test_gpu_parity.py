@@ -305,17 +305,22 @@ def test_forward_is_deterministic(B, oracle_lib):
     assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("d", [64, 128])
-def test_forward_maximum_topk(B, oracle_lib, d):
-    """The largest routing row the kernels take: 64 blocks per query block (every lane of the
-    list holder is used), some rows full, some with holes."""
-    cfg = I.small_config(name=f"f-topk64-d{d}", n_obj=4096, n_views=2, grid=16, heads=1, d=d, topk=64, window=64,
-                         seed=61)
+@pytest.mark.parametrize("d,topk,with_counts", [(64, 64, False), (128, 64, False), (32, 128, False), (64, 128, False),
+                                                 (128, 128, False), (128, 80, False), (32, 80, True), (128, 100, True)])
+def test_forward_wide_routing_rows(B, oracle_lib, d, topk, with_counts):
+    """Routing rows of 64 entries (every lane of the list holder is used) and of 65..128 (two registers: the
+    paper's stage-3 budget is 16 volume + 4 blocks per view, 80 at 16 views), some rows full, some with holes
+    on either side of entry 64, neighbouring rows overlapping as routed rows do."""
+    cfg = I.small_config(name=f"f-topk{topk}-d{d}-cnt{int(with_counts)}", n_obj=8192, n_views=2, grid=16, heads=1, d=d,
+                         topk=topk, window=64, seed=61)
     _log(f"[forward] {cfg.name}")
     rng = np.random.default_rng(12)
-    idx = np.stack([rng.choice(cfg.nb, size=64, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx = np.stack([(rng.choice(cfg.nb - 8, size=topk, replace=False) + (r // 4) % 8) for r in range(cfg.nb)]).astype(np.int32)
+    idx[0::4] = idx[1::4]                               # pairs of identical rows inside a workgroup's group
     idx[1::3][rng.random(idx[1::3].shape) < 0.3] = -1
-    _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx), cfg.name)
+    idx[5, :70] = -1                                     # a row whose valid entries all sit past entry 64
+    cnt = _block_counts(cfg, 10) if with_counts else None
+    _assert_forward(*_forward_case(B, oracle_lib, cfg, idx=idx, block_count=cnt), cfg.name)
 
 
 @pytest.mark.parametrize("d,topk", [(64, 6), (128, 9), (32, 5)])
