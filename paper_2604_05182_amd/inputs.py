@@ -103,11 +103,11 @@ CONFIGS = {
     4: NSAConfig("extreme", 262144, 18, 96, 16, 128, 32, 1024, "ellipsoids", near_views=2, seed=1004),
     5: NSAConfig("mid-backward", 32768, 6, 64, 16, 64, 16, 512, "uniform", seed=1002),
     # The paper's attention heads (App. A: 32 query heads of 32 channels on 2 key/value heads, one gate
-    # per output channel) with its stage-3 routing budgets (16 volume + 4 M image blocks, M = 8 views of
-    # 512 / 8 = 64 patches a side); routed with the four geometric rules.
-    6: NSAConfig("paper-heads", 131072, 8, 64, 32, 32, 48, 512, "ellipsoids", seed=1006, h_kv=2, gate_channels=True),
+    # per output channel) with its stage-3 routing budgets (hyper-parameter table of the appendix: 16 volume
+    # + 4 M image blocks, M = 16 views of 512 / 8 = 64 patches a side); routed with the four geometric rules.
+    6: NSAConfig("paper-heads", 131072, 16, 64, 32, 32, 80, 512, "ellipsoids", seed=1006, h_kv=2, gate_channels=True),
 }
-ROUTE3D = {6: dict(prefilter=4, k_v2v=16, k_v2i=32, k_i2v=16, k_i2i=32)}  # four-rule budgets of such configs
+ROUTE3D = {6: dict(prefilter=4, k_v2v=16, k_v2i=64, k_i2v=16, k_i2i=64)}  # four-rule budgets of such configs
 
 
 def small_config(name="unit", n_obj=512, n_views=2, grid=16, heads=2, d=64, topk=3, window=128,

@@ -45,6 +45,8 @@ CASES = [
     # the full-size scene with the paper's stage-2 budgets (volume 8, image 2M)
     (I.CONFIGS[3], 32, 4, 8, 24, 8, 24),
     (I.CONFIGS[4], 44, 4, 8, 36, 8, 36),
+    # the paper's stage-3 budgets at 16 views: 16 volume + 64 image blocks, rows of 80
+    (I.CONFIGS[6], 80, 4, 16, 64, 16, 64),
 ]
 
 
