@@ -17,6 +17,8 @@
  *     brain-float bit pattern (uint16_t here);
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the call returns without synchronising;
+ *   - no global state apart from lsrm_route_blocks_static's address lookup; calls may come from any
+ *     thread and any device may be current;
  *   - the library allocates no device memory: scratch comes from the caller
  *     (d_ws / ws_bytes, size from lsrm_workspace_bytes, 256-byte aligned), except in
  *     lsrm_route_blocks_static, which uses a fixed array inside the library;
@@ -77,7 +79,9 @@ typedef struct lsrm_nsa_params {
     int32_t n_seg;    /* number of window segments                                         */
     const int32_t *seg_offsets; /* HOST, n_seg + 1 ascending token offsets, multiples of 64,
                                    first 0, last N; the window never crosses a boundary.
-                                   NULL means the default: [objects], [view 0], [view 1]... */
+                                   NULL means the default: [objects], [view 0], [view 1]...
+                                   At most 63 segments (explicit or default: 62 views with object
+                                   tokens); more returns LSRM_ERR_UNSUPPORTED from the attention calls. */
     float scale;      /* softmax scale; 0 selects 1/sqrt(d)                                */
     int32_t gate_channels; /* 0: d_gates is [N, h_q, 3], one weight per head and branch;
                               1: d_gates is [N, 3, h_q, d], one weight per output channel
@@ -234,7 +238,8 @@ lsrm_status lsrm_nsa_compress_pack(const lsrm_nsa_params *p, const uint16_t *d_k
  *           of -1 gives a zero selected branch.  A block listed twice in a row enters
  *           that row's softmax twice (its tokens weigh double against the others).
  *   d_gates [N, h_q, 3] fp32  gate weights (cmp, sel, win), already passed through
- *           the sigmoid of Eq. (nsa_2); [N, 3, h_q, d] fp32, 16-byte aligned, when
+ *           the sigmoid of Eq. (nsa_2), hence in [0, 1] (the forward is linear in them whatever their
+ *           sign; lsrm_nsa_backward treats a negative per-head gate as zero); [N, 3, h_q, d] fp32, 16-byte aligned, when
  *           params.gate_channels is 1 (the sum of Eq. (nsa_1) is then taken per channel)
  *   d_out   [N, h_q, d] bf16  OUT
  *   d_lse   [3, N, h_q] fp32  OUT, nullable: natural-log sum-exp of the scaled scores

@@ -15,15 +15,20 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lsrm_oracle.c")
-_LIB = os.path.join(_HERE, "liblsrm_oracle.so")
+# LSRM_ORACLE_SANITIZE=1 selects a build with AddressSanitizer and UndefinedBehaviorSanitizer (the process must
+# have been started with the AddressSanitizer runtime preloaded: see tests/test_oracle_sanitizers.py)
+_SANITIZE = os.environ.get("LSRM_ORACLE_SANITIZE", "0") == "1"
+_LIB = os.path.join(_HERE, "liblsrm_oracle_asan.so" if _SANITIZE else "liblsrm_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile lsrm_oracle.c with gcc (no fused multiply-add: routing is compared bit for bit)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-fno-fast-math", "-o", _LIB, _SRC, "-lm"]
+        extra = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"] \
+            if _SANITIZE else []
+        cmd = ["gcc", "-O1" if _SANITIZE else "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", *extra, "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

@@ -33,18 +33,9 @@
 #include <type_traits>
 #include <utility>
 
-#ifndef LSRM_BWD_NBUF
-#define LSRM_BWD_NBUF 2
-#endif
-#ifndef LSRM_BWD_VGPR_CHAINS
-#define LSRM_BWD_VGPR_CHAINS 1
-#endif
-#ifndef LSRM_BWD_SPLIT_TARGET
-#define LSRM_BWD_SPLIT_TARGET 2048
-#endif
-#ifndef LSRM_BWD_DKV_NBUF
-#define LSRM_BWD_DKV_NBUF 2  // (3, copies two steps ahead with counted waits, was measured: no faster)
-#endif
+constexpr int kBwdNbuf = 2;         // tile buffers of the dQ kernel
+constexpr int kBwdDkvNbuf = 2;      // tile buffers of the dK/dV kernels (three, copies two steps ahead: no faster)
+constexpr int kBwdSplitTarget = 2048;  // pooled-key workgroups aimed at when the query range is split
 
 namespace lsrm {
 
@@ -465,7 +456,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     using G = BGeo<D>;
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int TILE = 2 * G::ROW;     // K rows | V rows (K^T is read out of the K rows, see mfma_tr)
-    constexpr int NBUF = LSRM_BWD_NBUF;  // tile buffers: copies run NBUF - 1 tiles ahead
+    constexpr int NBUF = kBwdNbuf;  // tile buffers: copies run NBUF - 1 tiles ahead
     constexpr int IPW = G::ROW / 1024;   // copy instructions per wavefront and tile
     static_assert((G::ROW / 1024) % 2 == 0, "");
     static_assert(2 * 32 * G::OUT_ROW <= NBUF * TILE, "output staging fits in the tile buffers");
@@ -710,8 +701,8 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int AUX = 2 * G::ROW;          // Q rows | dO rows | table (64 floats); Q^T and dO^T: see mfma_tr
     constexpr int TILE = 2 * G::ROW + 1024;  // (table padded to keep the next buffer aligned)
-    static_assert(2 * 32 * G::OUT_ROW <= LSRM_BWD_DKV_NBUF * TILE, "output staging fits in the tile buffers");
-    extern __shared__ __attribute__((aligned(1024))) char lds[];  // LSRM_BWD_DKV_NBUF * TILE bytes
+    static_assert(2 * 32 * G::OUT_ROW <= kBwdDkvNbuf * TILE, "output staging fits in the tile buffers");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];  // kBwdDkvNbuf * TILE bytes
     const int n_kb = MODE != 1 ? a.nb : a.nbp / 64;
     const int per_xcd = (n_kb + 7) / 8;
     const int head = blockIdx.y;
@@ -790,8 +781,8 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     // workgroups) its share
     const int gh0 = MODE == 0 && a.hsplit > 1 ? (int)blockIdx.z * a.hpw : 0;
     const int grp = MODE == 0 && a.hsplit > 1 ? min(a.group, gh0 + a.hpw) - gh0 : a.group;
-    constexpr bool VGPR_CHAINS = D == 128 && LSRM_BWD_VGPR_CHAINS;  // (the kernel has one wavefront per SIMD: see mfma_v)
-    constexpr int NB = LSRM_BWD_DKV_NBUF;  // tile buffers: the copies run NB - 1 steps ahead of the arithmetic
+    constexpr bool VGPR_CHAINS = D == 128;  // (the kernel has one wavefront per SIMD: see mfma_v)
+    constexpr int NB = kBwdDkvNbuf;  // tile buffers: the copies run NB - 1 steps ahead of the arithmetic
     constexpr int IPW = G::ROW / 1024;    // copy instructions per wavefront and step (wavefront 0: one more, the table)
     static_assert(NB == 2 || NB == 3, "");
     // br_c: the branch whose probabilities these are (0 compressed, 1 selected, 2 window); tile_fn(t): the t-th query
@@ -1083,7 +1074,7 @@ WsLayout ws_layout(const Shape &s) {
     const int wgs = (w.nbp / 64) * s.h_kv;
     // (more ranges mean more partial sums to write; with grouped-query heads a workgroup's walk is group x as long
     // and twice as many ranges measured faster, without them slower)
-    const int target = s.h > s.h_kv ? 2 * LSRM_BWD_SPLIT_TARGET : LSRM_BWD_SPLIT_TARGET;
+    const int target = s.h > s.h_kv ? 2 * kBwdSplitTarget : kBwdSplitTarget;
     int n_split = (target + wgs - 1) / wgs;
     n_split = n_split < 1 ? 1 : (n_split > 64 ? 64 : n_split);
     w.tiles_per_split = (int)((nt + n_split - 1) / n_split);
@@ -1119,7 +1110,7 @@ template <int D>
 lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char *ws, hipStream_t st, hipEvent_t ev_start,
                               hipEvent_t ev_stop) {
     using G = BGeo<D>;
-    constexpr int DKV_LDS = LSRM_BWD_DKV_NBUF * (2 * G::ROW + 1024);
+    constexpr int DKV_LDS = kBwdDkvNbuf * (2 * G::ROW + 1024);
     // (set on every call: cheap, and right whichever device is current and whichever thread calls)
     LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 0>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));

@@ -45,28 +45,6 @@
 
 #include <type_traits>
 
-#ifndef LSRM_QT64
-#define LSRM_QT64 1  // (two row tiles per wavefront were measured slower at d = 64 and do not fit the registers at d = 128)
-#endif
-#ifndef LSRM_QT128
-#define LSRM_QT128 1
-#endif
-#ifndef LSRM_QDEPTH
-#define LSRM_QDEPTH 2
-#endif
-#ifndef LSRM_NST
-#define LSRM_NST 2
-#endif
-#ifndef LSRM_PINGPONG
-#define LSRM_PINGPONG 1
-#endif
-#ifndef LSRM_PAR64
-#define LSRM_PAR64 1
-#endif
-#ifndef LSRM_PAR128
-#define LSRM_PAR128 1
-#endif
-
 namespace lsrm {
 
 namespace {
@@ -123,15 +101,14 @@ struct Geo {
     // tile slots in LDS: NST per query block; the selected phase copies NST - 1 steps ahead.  The 16 KB tiles of
     // d = 128 fill the LDS with two stages; four stages for the smaller tiles of d <= 64 were measured: 0.7 %
     // faster at d = 64 with 180 K tokens, 1 % slower with 57 K, 6 % slower at d = 32 -- hence two everywhere.
-    static constexpr int NST = D_ == 128 ? 2 : LSRM_NST;
+    static constexpr int NST = 2;
     static constexpr int NSLOT = NST * NP;
     static constexpr int T_INST = TILE / 1024;  // 1 KB copy instructions per tile
     // shared phases: copy instructions per wavefront and tile (a small tile, d = 32, has fewer
     // instructions than the workgroup has wavefronts: the first T_INST wavefronts issue one each
     // and the others none, whose waits for SH_IPT copies per tile are then trivially met)
     static constexpr int SH_IPT = T_INST >= WAVES ? T_INST / WAVES : 1;
-    static constexpr int KQ = NS < LSRM_QDEPTH ? NS : LSRM_QDEPTH;  // operand fragments kept in registers (rolling queues)
-    static constexpr int VQ = 2 * ND < LSRM_QDEPTH ? 2 * ND : LSRM_QDEPTH;
+    static constexpr int KQ = 2, VQ = 2;        // operand fragments kept in registers (rolling queues)
     static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output staging (bytes)
     static constexpr int LDS_BYTES = NSLOT * TILE;
     static_assert(QT == 1 || QT == 2, "");
@@ -278,7 +255,7 @@ __device__ __forceinline__ float lane_max(const f32x16 &s) {
 // m = kMinusHuge.
 constexpr float kSumLimit = 1024.0f;
 
-// Wave-uniform: does any lane need its tile redone?  (written so that a NaN would also say yes)
+// Wave-uniform: does any lane need its tile redone?  (psum is a sum of exponentials of finite or -inf arguments: never NaN)
 __device__ __forceinline__ bool sum_overflow(float psum) {
     return __builtin_amdgcn_ballot_w64(!(psum <= kSumLimit)) != 0;
 }
@@ -470,14 +447,14 @@ template <class G, typename SrcFn, typename MaskFn>
 __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, SrcFn src, MaskFn msk, int mf_lo, int mf_hi,
                                            char *lds, int wave, int lane, float sl2) {
     constexpr int R = G::NSLOT, QT = G::QT;
-    constexpr bool PAR = G::D == 128 ? LSRM_PAR128 : LSRM_PAR64;
+    constexpr bool PAR = true;  // scores and probabilities alternate between two register sets by tile parity
     if (n_steps <= 0) return;
     auto slot = [&](int t) { return lds + (t % R) * G::TILE; };
     auto lslot = [&](int t) { return lds + (t % R) * G::TILE + c.lane16; };  // this lane's fragment base
     // The two wavefronts that share a SIMD (w and w + 4 of an 8-wavefront workgroup) run half a
     // step apart: one meets the step's barrier before its MFMA block, the other after it, so
     // one's latency-bound work between blocks coincides with the other's MFMA block.
-    const bool lag = LSRM_PINGPONG && G::WAVES == 8 && wave >= 4;
+    const bool lag = G::WAVES == 8 && wave >= 4;
     __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
     wg_barrier();  // every wavefront is done with the slots (previous phase)
     for (int t = 0; t < R && t < n_steps; ++t) issue_shared<G>(c, src(t), slot(t), wave);
@@ -1350,8 +1327,8 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     WsLayout w = ws_layout(s);
     char *ws = reinterpret_cast<char *>(d_ws);
     if (s.d == 32) return launch_forward_d<Geo<32, 4, 1>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
-    if (s.d == 64) return launch_forward_d<Geo<64, 4, LSRM_QT64>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
-    return launch_forward_d<Geo<128, 4, LSRM_QT128>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
+    if (s.d == 64) return launch_forward_d<Geo<64, 4, 1>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
+    return launch_forward_d<Geo<128, 4, 1>>(s, seg_host, n_seg, a, d_k, d_v, d_kc, d_vc, ws, w, st, ev_start, ev_stop);
 }
 
 }  // namespace lsrm
