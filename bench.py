@@ -2,7 +2,9 @@
 """Benchmark of the NSA layer hot path on one MI355X.
 
 A step is one pass of the whole path over one synthetic batch: lsrm_route_blocks ->
-lsrm_nsa_compress -> lsrm_nsa_forward, inputs already resident in HBM.  The metric is
+lsrm_nsa_compress_pack (block averages and the forward's repacking of k, v in one pass) ->
+lsrm_nsa_forward, inputs already resident in HBM (--two-pass: lsrm_nsa_compress and a forward that
+repacks k, v itself).  The metric is
 effective attention TFLOP/s (4 d h x attended (query, key) pairs; masked or padded work
 does not count) and ms per layer.  Prints one JSON line.
 
@@ -29,7 +31,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per launch of the attention kernel (fetched + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs of this script scaled by the same counters of a plain 1 GiB copy; the readings and the commands are
 # in profiles/nsa_forward_kernel_config4_hbm_traffic.txt.  Only the workloads that were profiled appear.
-MEASURED_HBM_BYTES = {4: 73.6e9 + 8.8e9}
+MEASURED_HBM_BYTES = {4: 66.6e9 + 8.8e9}
 
 
 def cpu_baseline(cfg, arrays, idx, target_seconds=20.0):
@@ -336,6 +338,12 @@ def main():
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
         },
     }
+    # the whole lsrm_nsa_forward call (step schedule, packing of the pooled pairs, attention kernel; with --two-pass also
+    # the packing of k and v) against the same peak
+    call_tflops = flops / (ms_fwd_call * 1e-3) / 1e12
+    result["roofline_call"] = {"call": "lsrm_nsa_forward", "bound": "mfma", "achieved": round(call_tflops, 3),
+                               "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                               "frac": round(call_tflops / BF16_MFMA_PEAK_TFLOPS, 4)}
     if cfg.d == 32:
         # At d = 32 a 32 x 32 score tile costs 4 MFMAs but still 1024 exponentials: the softmax arithmetic,
         # not the matrix pipe, bounds the kernel.  Per score element and head: scale-and-subtract, running
