@@ -38,9 +38,9 @@
 //   contiguous on both sides per instruction, the copy instructions of a tile split over
 //   the wavefronts that share it, s_waitcnt vmcnt placed by hand, and read back as
 //   conflict-free ds_read_b128 MFMA fragments.
-//   The gated sum of the branches is carried between branches in an fp32 scratch tile in
-//   MFMA-fragment order (fully coalesced) instead of in registers; the final tile goes
-//   through LDS so that the bf16 output rows are written as whole 16-byte chunks.
+//   The gated sum of the branches is carried between branches in registers at d <= 64 and, at d = 128,
+//   where they do not suffice, in a bf16 scratch tile in MFMA-fragment order (fully coalesced); the
+//   final tile goes through LDS so that the bf16 output rows are written as whole 16-byte chunks.
 #include "lsrm_internal.h"
 
 #include <type_traits>
@@ -70,7 +70,7 @@ struct FwdArgs {
     uint16_t *out;
     float *lse;
     uint16_t *out_branch;
-    float *gsum;  // scratch: running gated sum, fragment order
+    uint16_t *gsum;  // d = 128: scratch for the running gated sum, bf16 in accumulator-fragment order
     int64_t n;
     int nb, h, topk, window, n_seg;
     int h_kv, group;    // key/value heads; query heads per key/value head (query head i reads head i / group)
@@ -110,6 +110,7 @@ struct Geo {
     static constexpr int SH_IPT = T_INST >= WAVES ? T_INST / WAVES : 1;
     static constexpr int KQ = 2, VQ = 2;        // operand fragments kept in registers (rolling queues)
     static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output staging (bytes)
+    static constexpr bool GSUM_REGS = D_ <= 64; // the running gated sum fits the registers beside the accumulators
     static constexpr int LDS_BYTES = NSLOT * TILE;
     static_assert(QT == 1 || QT == 2, "");
     static_assert(WAVES % 4 == 0 && WAVES * ROWS * OUT_ROW <= LDS_BYTES, "output staging must fit in the tile slots");
@@ -157,6 +158,10 @@ struct WaveCtx {
     bf16x8 qf[G::QT][G::NS];
     f32x16 o[G::QT][G::ND];
     float m[G::QT], l[G::QT];
+    // running gated sum of the branches, kept in registers where they suffice (d <= 64); at d = 128 it goes
+    // through a bf16 scratch tile in global memory instead (fp32 there cost 1.8 % of the kernel for 7 % less
+    // rounding error in `out`, whose own bf16 rounding and that of the probabilities dominate either way)
+    f32x16 g[G::QT][G::GSUM_REGS ? G::ND : 1];
     int lo[G::QT], hi[G::QT];   // valid key range of this lane's queries in mask coordinates
     uint32_t lane16;            // lane * 16: byte offset of this lane inside any 1 KB fragment or copy instruction
 };
@@ -760,7 +765,7 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
 }
 
 // Ends a branch: normalises, applies the gate and folds the result into the running
-// gated sum kept in the fp32 scratch tile (written by branch 0, updated by branch 1,
+// gated sum (registers, or the scratch tile: written by branch 0, updated by branch 1,
 // consumed by branch 2, which converts to bf16 and stores the output rows through LDS).
 // Optionally stores the un-gated branch output and its log-sum-exp.
 template <class G>
@@ -794,8 +799,6 @@ __device__ __forceinline__ void finish_branch(WaveCtx<G> &c, const FwdArgs &a, i
                 }
             }
         }
-        // scratch tile of this (32-row tile, head): [ND][4][64 lanes] float4
-        f32x4 *gs = reinterpret_cast<f32x4 *>(a.gsum) + ((((row0 >> 5) + qt) * a.h + head) * (G::ND * 4)) * 64 + lane;
 #pragma unroll
         for (int dt = 0; dt < G::ND; ++dt) {
 #pragma unroll
@@ -804,13 +807,34 @@ __device__ __forceinline__ void finish_branch(WaveCtx<G> &c, const FwdArgs &a, i
 #pragma unroll
                 for (int j = 0; j < 4; ++j) v[j] = w * c.o[qt][dt][4 * gq + j];
                 if (a.gate_channels) v *= gch[8 * dt + 2 * gq];  // channels 32 dt + 8 gq + 4 hh + 0..3
-                if (branch > 0) {
-                    f32x4 prev = gs[(dt * 4 + gq) * 64];
-                    v += prev;
-                }
-                if (branch < 2) {
-                    gs[(dt * 4 + gq) * 64] = v;
+                if constexpr (G::GSUM_REGS) {
+                    if (branch > 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] += c.g[qt][dt][4 * gq + j];
+                    }
+                    if (branch < 2) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) c.g[qt][dt][4 * gq + j] = v[j];
+                    }
                 } else {
+                    // bf16 pairs in accumulator order: 8 bytes per lane and fragment, fully coalesced
+                    uint2 *slot = reinterpret_cast<uint2 *>(a.gsum) +
+                                  ((((row0 >> 5) + qt) * a.h + head) * (G::ND * 4) + dt * 4 + gq) * 64 + lane;
+                    if (branch > 0) {
+                        const uint2 pv = *slot;
+                        v[0] += __uint_as_float(pv.x << 16);
+                        v[1] += __uint_as_float(pv.x & 0xffff0000u);
+                        v[2] += __uint_as_float(pv.y << 16);
+                        v[3] += __uint_as_float(pv.y & 0xffff0000u);
+                    }
+                    if (branch < 2) {
+                        uint2 w2;
+                        w2.x = pack_bf16(v[0], v[1]);
+                        w2.y = pack_bf16(v[2], v[3]);
+                        *slot = w2;
+                    }
+                }
+                if (branch == 2) {
                     uint2 w2;
                     w2.x = pack_bf16(v[0], v[1]);
                     w2.y = pack_bf16(v[2], v[3]);
@@ -1206,7 +1230,7 @@ WsLayout ws_layout(const Shape &s) {
     w.kvc = off;
     off += align_up((size_t)((s.nb + 31) / 32) * s.h_kv * tile, 256);
     w.gsum = off;
-    off += align_up((size_t)s.nb * 64 * s.h * s.d * 4, 256);
+    off += s.d == 128 ? align_up((size_t)s.nb * 64 * s.h * s.d * 2, 256) : 0;  // (kept in registers at d <= 64)
     w.sched = off;
     off += s.d == 128 ? sel_schedule_bytes(s) : 0;
     w.total = off > 0 ? off : 256;
@@ -1235,7 +1259,7 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     a.sched = reinterpret_cast<const int32_t *>(ws + w.sched);
     a.kv = ws + w.kv;
     a.kvc = ws + w.kvc;
-    a.gsum = (float *)(ws + w.gsum);
+    a.gsum = reinterpret_cast<uint16_t *>(ws + w.gsum);
     a.groups_per_head = (s.nb + NP - 1) / NP;
     a.groups_per_xcd = (a.groups_per_head + 7) / 8;
     // dynamic LDS: the tile slots, then 512 bytes per wavefront for compacting a routing row
