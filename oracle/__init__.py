@@ -109,26 +109,38 @@ def _counts(block_count, nb):
     return cnt
 
 
-def pool(x: np.ndarray, block_count=None) -> np.ndarray:
+def _groups(group_offsets, nb):
+    """Spatial blocks as runs of 64-slot blocks: ascending offsets [ng + 1], first 0, last nb; None = no groups."""
+    if group_offsets is None:
+        return 0, None
+    off = _i32(group_offsets)
+    assert off.ndim == 1 and off.shape[0] >= 2 and off[0] == 0 and off[-1] == nb and np.all(np.diff(off) >= 1)
+    return off.shape[0] - 1, off
+
+
+def pool(x: np.ndarray, block_count=None, group_offsets=None) -> np.ndarray:
     """x fp32 [N, H, d] -> block means fp32 [N/64, H, d] (over the first block_count[b] tokens of
-    block b when block_count is given, 1..64 each)."""
+    block b when block_count is given, 1..64 each); with group_offsets one mean per spatial block, [ng, H, d]."""
     x = _f32(x)
     n, h, d = x.shape
-    out = np.empty((n // 64, h, d), dtype=np.float32)
+    ng, off = _groups(group_offsets, n // 64)
+    out = np.empty((ng if ng else n // 64, h, d), dtype=np.float32)
     cnt = _counts(block_count, n // 64)
     _load().oracle_pool(ctypes.c_int64(n), ctypes.c_int(h), ctypes.c_int(d), _p(x, ctypes.c_float),
-                        _p(cnt, ctypes.c_int32), _p(out, ctypes.c_float))
+                        _p(cnt, ctypes.c_int32), ctypes.c_int(ng), _p(off, ctypes.c_int32), _p(out, ctypes.c_float))
     return out
 
 
 def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qblocks=None,
-                want_lse=False, want_branches=False, window_mode=0, block_count=None):
+                want_lse=False, want_branches=False, window_mode=0, block_count=None, group_offsets=None):
     """NSA forward for the query blocks in `qblocks` (all blocks if None).
 
     q [N, H, d]; k, v [N, h_kv, d] and kc, vc [NB, h_kv, d] with h_kv dividing H (grouped-query
     heads); gates [N, H, 3] (per head) or [N, 3, H, d] (per channel).
     window_mode 0: sliding window of `window` tokens inside the segment; 1: the query's own block.
     block_count [NB] (optional): active tokens per block (kc, vc pooled with the same counts).
+    group_offsets [ng + 1] (optional): spatial blocks as runs of 64-slot blocks; kc, vc are then [ng, h_kv, d] (pooled
+    with the same groups), the compressed branch sees one pair per group and the own-block window the whole group.
     Returns out fp32 [nq*64, H, d] (compact over the listed blocks) and, on request,
     lse fp32 [3, nq*64, H] and the three branch outputs fp32 [3, nq*64, H, d].
     """
@@ -138,6 +150,8 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
     h_kv = k.shape[1]
     assert h % h_kv == 0 and v.shape == k.shape and kc.shape[1] == h_kv and vc.shape == kc.shape
     assert gates.shape in ((n, h, 3), (n, 3, h, d))
+    ng, goff = _groups(group_offsets, n // 64)
+    assert kc.shape[0] == (ng if ng else n // 64)
     gate_channels = 1 if gates.ndim == 4 else 0
     topk = idx.shape[1] if idx.ndim == 2 else 0
     if qblocks is None:
@@ -153,8 +167,8 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
         ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1), _p(seg, ctypes.c_int32),
         _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float), _p(kc, ctypes.c_float),
         _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float), ctypes.c_int(gate_channels),
-        _p(qblocks, ctypes.c_int32), ctypes.c_int(nq), _p(out, ctypes.c_float),
-        _p(lse, ctypes.c_float), _p(ob, ctypes.c_float))
+        _p(qblocks, ctypes.c_int32), ctypes.c_int(nq), ctypes.c_int(ng), _p(goff, ctypes.c_int32),
+        _p(out, ctypes.c_float), _p(lse, ctypes.c_float), _p(ob, ctypes.c_float))
     res = [out]
     if want_lse:
         res.append(lse)
@@ -163,7 +177,8 @@ def nsa_forward(q, k, v, kc, vc, idx, gates, seg_offsets, window, scale=0.0, qbl
     return res[0] if len(res) == 1 else tuple(res)
 
 
-def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0, window_mode=0, block_count=None):
+def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0.0, window_mode=0, block_count=None,
+                 group_offsets=None):
     """-> (dq fp32 [N, H, d], dk, dv fp32 [N, h_kv, d]); single-threaded definition, small inputs only.
     Shapes and gate layouts as in nsa_forward."""
     q, k, v, kc, vc, gates, dout = map(_f32, (q, k, v, kc, vc, gates, dout))
@@ -171,6 +186,8 @@ def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0
     n, h, d = q.shape
     h_kv = k.shape[1]
     assert h % h_kv == 0 and gates.shape in ((n, h, 3), (n, 3, h, d))
+    ng, goff = _groups(group_offsets, n // 64)
+    assert kc.shape[0] == (ng if ng else n // 64)
     topk = idx.shape[1] if idx.ndim == 2 else 0
     dq = np.empty_like(q)
     dk, dv = np.empty_like(k), np.empty_like(k)
@@ -180,8 +197,8 @@ def nsa_backward(q, k, v, kc, vc, idx, gates, seg_offsets, window, dout, scale=0
         ctypes.c_float(scale), ctypes.c_int(seg.shape[0] - 1),
         _p(seg, ctypes.c_int32), _p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float),
         _p(kc, ctypes.c_float), _p(vc, ctypes.c_float), _p(idx, ctypes.c_int32), _p(gates, ctypes.c_float),
-        ctypes.c_int(1 if gates.ndim == 4 else 0), _p(dout, ctypes.c_float), _p(dq, ctypes.c_float),
-        _p(dk, ctypes.c_float), _p(dv, ctypes.c_float))
+        ctypes.c_int(1 if gates.ndim == 4 else 0), _p(dout, ctypes.c_float), ctypes.c_int(ng), _p(goff, ctypes.c_int32),
+        _p(dq, ctypes.c_float), _p(dk, ctypes.c_float), _p(dv, ctypes.c_float))
     return dq, dk, dv
 
 

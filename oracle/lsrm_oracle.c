@@ -247,13 +247,54 @@ void oracle_route_3d(int n_obj, int n_views, int grid, int width, int prefilter,
 /* ------------------------------------------------------------------ pooling */
 
 /*
+ * Spatial blocks larger than 64 tokens (Sec. 3.2: 8 x 8 x 8 volume blocks with a variable number of active
+ * tokens, up to 512): a spatial block is a run of consecutive 64-slot blocks, group g = 64-slot blocks
+ * off[g] .. off[g+1]-1 (off ascending, off[0] = 0, off[ng] = N / 64).  With groups the compressed pair is one
+ * per spatial block (the average of all its active tokens) and the own-block window (App. A) is the whole
+ * spatial block; routing tables keep listing 64-slot blocks.  NULL / ng = 0: every 64-slot block is its own
+ * spatial block.
+ */
+typedef struct { int ng; const int32_t *off; } groups_t;
+
+static int group_of(const groups_t *g, int64_t blk) {
+    for (int a = 0; a < g->ng; ++a)
+        if (blk >= g->off[a] && blk < g->off[a + 1]) return a;
+    return -1;
+}
+
+static int max_group_blocks(const groups_t *g) {
+    int m = 1;
+    for (int a = 0; g && a < g->ng; ++a)
+        if (g->off[a + 1] - g->off[a] > m) m = g->off[a + 1] - g->off[a];
+    return m;
+}
+
+/*
  * out[b, h, :] = mean over the active tokens t of block b of x[64 b + t, h, :];  x is [N, H, d],
  * out is [N/64, H, d].  count (nullable) [N/64]: block b has count[b] active tokens (1..64), held in
  * its first slots (Sec. 3.2: blocks hold a variable number of active tokens); NULL = all 64.
+ * With groups (ng > 0): out is [ng, H, d], row g the mean over the active tokens of all 64-slot blocks of group g.
  */
-void oracle_pool(int64_t n, int h, int d, const float *x, const int32_t *count, float *out) {
+void oracle_pool(int64_t n, int h, int d, const float *x, const int32_t *count, int ng, const int32_t *goff,
+                 float *out) {
     int64_t nb = n / BLK;
     size_t row = (size_t)h * d;
+    if (ng > 0) {
+#pragma omp parallel for schedule(static)
+        for (int g = 0; g < ng; ++g) {
+            for (size_t c = 0; c < row; ++c) {
+                double s = 0.0;
+                int64_t tot = 0;
+                for (int64_t b = goff[g]; b < goff[g + 1]; ++b) {
+                    int cnt = count ? count[b] : BLK;
+                    for (int t = 0; t < cnt; ++t) s += (double)x[((size_t)(BLK * b + t)) * row + c];
+                    tot += cnt;
+                }
+                out[(size_t)g * row + c] = (float)(s / (double)tot);
+            }
+        }
+        return;
+    }
 #pragma omp parallel for schedule(static)
     for (int64_t b = 0; b < nb; ++b) {
         int cnt = count ? count[b] : BLK;
@@ -307,13 +348,18 @@ static int segment_of(const int32_t *seg, int n_seg, int64_t i) {
  *   window_mode 0: keys j with -W/2 <= j - i < W/2 inside the query's segment (the configs' sliding window);
  *   window_mode 1: the tokens of the query's own block (App. A, "Window").
  *   count (nullable): active tokens per block (its first count[b] slots); inactive slots are nobody's key.
+ *   grp (nullable): spatial blocks as groups of 64-slot blocks: the compressed keys are the groups' pairs and
+ *   the own-block window is the query's whole group.
  */
-static void key_sets(int64_t i, int64_t nb, int topk, int window, int window_mode, const int32_t *count, int n_seg,
-                     const int32_t *seg, const int32_t *idx, int64_t *rc, int *nc, int64_t *rs, int *ns,
-                     int64_t *rw, int *nw) {
+static void key_sets(int64_t i, int64_t nb, int topk, int window, int window_mode, const int32_t *count,
+                     const groups_t *grp, int n_seg, const int32_t *seg, const int32_t *idx, int64_t *rc, int *nc,
+                     int64_t *rs, int *ns, int64_t *rw, int *nw) {
     int64_t qb = i / BLK;
     *nc = 0;
-    for (int64_t b = 0; b < nb; ++b) rc[(*nc)++] = b;
+    if (grp)
+        for (int g = 0; g < grp->ng; ++g) rc[(*nc)++] = g;
+    else
+        for (int64_t b = 0; b < nb; ++b) rc[(*nc)++] = b;
     *ns = 0;
     for (int k = 0; k < topk; ++k) {
         int32_t kb = idx[qb * topk + k];
@@ -323,8 +369,16 @@ static void key_sets(int64_t i, int64_t nb, int topk, int window, int window_mod
     }
     *nw = 0;
     if (window_mode == 1) {
-        int cnt = count ? count[qb] : BLK;
-        for (int t = 0; t < cnt; ++t) rw[(*nw)++] = qb * BLK + t;
+        int64_t b0 = qb, b1 = qb + 1;
+        if (grp) {
+            int g = group_of(grp, qb);
+            b0 = grp->off[g];
+            b1 = grp->off[g + 1];
+        }
+        for (int64_t b = b0; b < b1; ++b) {
+            int cnt = count ? count[b] : BLK;
+            for (int t = 0; t < cnt; ++t) rw[(*nw)++] = b * BLK + t;
+        }
         return;
     }
     int sg = segment_of(seg, n_seg, i);
@@ -354,8 +408,11 @@ static void key_sets(int64_t i, int64_t nb, int topk, int window, int window_mod
 void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window, int window_mode,
                         const int32_t *count, float scale, int n_seg, const int32_t *seg, const float *q, const float *k, const float *v,
                         const float *kc, const float *vc, const int32_t *idx, const float *gates,
-                        int gate_channels, const int32_t *qblocks, int nq, float *out, float *lse, float *ob) {
+                        int gate_channels, const int32_t *qblocks, int nq, int ng, const int32_t *goff, float *out,
+                        float *lse, float *ob) {
     int64_t nb = n / BLK;
+    groups_t gst = {ng, goff};
+    const groups_t *grp = ng > 0 ? &gst : NULL;
     size_t stride = (size_t)h * d;        /* row stride of q and the outputs */
     size_t stride_kv = (size_t)h_kv * d;  /* row stride of k, v, kc, vc */
     int group = h / h_kv;
@@ -364,11 +421,13 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
     if ((size_t)window + BLK > maxkeys) maxkeys = (size_t)window + BLK;
     int64_t rows_out = (int64_t)nq * BLK;
+    size_t maxwin = (size_t)window + (size_t)BLK * max_group_blocks(grp);
+    if (maxwin > maxkeys) maxkeys = maxwin;
 #pragma omp parallel
     {
         int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
         int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
-        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + BLK));
+        int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * maxwin);
         double *s = (double *)malloc(sizeof(double) * maxkeys);
         double *o = (double *)malloc(sizeof(double) * (size_t)d * 3);
 #pragma omp for schedule(dynamic, 1) collapse(2)
@@ -379,7 +438,7 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
                     int64_t i = (int64_t)qblocks[iq] * BLK + t;
                     int64_t r = (int64_t)iq * BLK + t;
                     int nc, ns, nw;
-                    key_sets(i, nb, topk, window, window_mode, count, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+                    key_sets(i, nb, topk, window, window_mode, count, grp, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
                     const float *qv = q + (size_t)i * stride + (size_t)hh * d;
                     double l0 = attend(qv, d, sc, kc + kvo, vc + kvo, stride_kv, rc, nc, s, o);
                     double l1 = attend(qv, d, sc, k + kvo, v + kvo, stride_kv, rs, ns, s, o + d);
@@ -430,12 +489,16 @@ void oracle_nsa_forward(int64_t n, int h, int h_kv, int d, int topk, int window,
 void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window, int window_mode,
                          const int32_t *count, float scale, int n_seg, const int32_t *seg, const float *q, const float *k, const float *v,
                          const float *kc, const float *vc, const int32_t *idx, const float *gates,
-                         int gate_channels, const float *dout, float *dq, float *dk, float *dv) {
+                         int gate_channels, const float *dout, int ng, const int32_t *goff, float *dq, float *dk,
+                         float *dv) {
     int64_t nb = n / BLK;
+    groups_t gst = {ng, goff};
+    const groups_t *grp = ng > 0 ? &gst : NULL;
     size_t stride = (size_t)h * d;        /* rows of q, dout, dq */
     size_t stride_kv = (size_t)h_kv * d;  /* rows of k, v, kc, vc, dk, dv */
     int group = h / h_kv;
-    size_t total = (size_t)n * stride, total_kv = (size_t)n * stride_kv, totalc = (size_t)nb * stride_kv;
+    size_t total = (size_t)n * stride, total_kv = (size_t)n * stride_kv;
+    size_t totalc = (size_t)(grp ? ng : nb) * stride_kv;  /* pooled pairs: one per spatial block */
     double sc = scale > 0.0f ? (double)scale : 1.0 / sqrt((double)d);
     size_t maxkeys = (size_t)nb;
     if ((size_t)topk * BLK > maxkeys) maxkeys = (size_t)topk * BLK;
@@ -447,14 +510,16 @@ void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window
     double *gvc = (double *)calloc(totalc > 0 ? totalc : 1, sizeof(double));
     int64_t *rc = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb > 0 ? nb : 1));
     int64_t *rs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(topk > 0 ? topk : 1) * BLK);
-    int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * ((size_t)window + BLK));
+    size_t maxwin = (size_t)window + (size_t)BLK * max_group_blocks(grp);
+    if (maxwin > maxkeys) maxkeys = maxwin;
+    int64_t *rw = (int64_t *)malloc(sizeof(int64_t) * maxwin);
     double *p = (double *)malloc(sizeof(double) * maxkeys);
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
     double *gd = (double *)malloc(sizeof(double) * (size_t)d); /* gate times dout: the gradient reaching one branch */
     for (int64_t i = 0; i < n; ++i) {
         int nc, ns, nw;
         if (count && (i % BLK) >= count[i / BLK]) continue; /* padding slot: no query lives here */
-        key_sets(i, nb, topk, window, window_mode, count, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+        key_sets(i, nb, topk, window, window_mode, count, grp, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
         for (int hh = 0; hh < h; ++hh) {
             size_t kvo = (size_t)(hh / group) * d; /* this query head's key/value head */
             const float *qv = q + (size_t)i * stride + (size_t)hh * d;
@@ -496,9 +561,16 @@ void oracle_nsa_backward(int64_t n, int h, int h_kv, int d, int topk, int window
     for (int64_t j = 0; j < n; ++j) {
         int cnt = count ? count[j / BLK] : BLK;
         if ((j % BLK) >= cnt) continue; /* the mean was taken over the active tokens only */
+        int64_t pair = j / BLK; /* the pooled pair this token went into, and how many tokens it averaged */
+        double tokens = (double)cnt;
+        if (grp) {
+            pair = group_of(grp, j / BLK);
+            tokens = 0.0;
+            for (int64_t b = grp->off[pair]; b < grp->off[pair + 1]; ++b) tokens += count ? count[b] : BLK;
+        }
         for (size_t c = 0; c < stride_kv; ++c) {
-            gk[(size_t)j * stride_kv + c] += gkc[(size_t)(j / BLK) * stride_kv + c] / (double)cnt;
-            gv[(size_t)j * stride_kv + c] += gvc[(size_t)(j / BLK) * stride_kv + c] / (double)cnt;
+            gk[(size_t)j * stride_kv + c] += gkc[(size_t)pair * stride_kv + c] / tokens;
+            gv[(size_t)j * stride_kv + c] += gvc[(size_t)pair * stride_kv + c] / tokens;
         }
     }
     for (size_t e = 0; e < total; ++e) dq[e] = (float)gq[e];
@@ -569,7 +641,7 @@ void oracle_nsa_backward_sampled(int64_t n, int h, int h_kv, int d, int topk, in
 #pragma omp for schedule(dynamic, 16)
         for (int64_t i = 0; i < n; ++i) {
             int nc, ns, nw;
-            key_sets(i, nb, topk, window, window_mode, NULL, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
+            key_sets(i, nb, topk, window, window_mode, NULL, NULL, n_seg, seg, idx, rc, &nc, rs, &ns, rw, &nw);
             int qa = qpos[i / BLK];
             for (int br = 0; br < 3; ++br) {
                 const int64_t *rows = br == 0 ? rc : (br == 1 ? rs : rw);

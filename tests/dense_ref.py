@@ -8,18 +8,27 @@ usable for small N.
 import numpy as np
 
 
-def pooled(x, block_count=None):
+def group_ids(n, group_offsets):
+    """Spatial block (group) of every token; group_offsets [ng + 1] in 64-slot blocks, None: one group per block."""
+    if group_offsets is None:
+        return np.arange(n) // 64
+    off = np.asarray(group_offsets)
+    return np.repeat(np.repeat(np.arange(len(off) - 1), np.diff(off)), 64)
+
+
+def pooled(x, block_count=None, group_offsets=None):
+    """Mean over the active tokens of every spatial block: a membership matrix times x, over its row sums."""
     n, h, d = x.shape
-    xb = x.reshape(n // 64, 64, h, d)
-    if block_count is None:
-        return xb.mean(axis=1)
-    act = (np.arange(64)[None, :] < np.asarray(block_count)[:, None]).astype(x.dtype)
-    return (xb * act[:, :, None, None]).sum(axis=1) / np.asarray(block_count, dtype=x.dtype)[:, None, None]
+    active = np.ones(n, dtype=bool) if block_count is None else (np.arange(n) % 64) < np.repeat(np.asarray(block_count), 64)
+    gid = group_ids(n, group_offsets)
+    member = ((gid[None, :] == np.arange(gid.max() + 1)[:, None]) & active[None, :]).astype(x.dtype)   # [groups, n]
+    return np.einsum("gn,nhc->ghc", member, x) / member.sum(axis=1)[:, None, None]
 
 
-def masks(n, idx, seg_offsets, window, window_mode=0, block_count=None):
+def masks(n, idx, seg_offsets, window, window_mode=0, block_count=None, group_offsets=None):
     """Boolean [n, n] masks of the selected and window branches.  window_mode 1: the window is the
-    query's own block.  block_count: slots at or beyond a block's count are nobody's key."""
+    query's own block (its whole spatial block with group_offsets).  block_count: slots at or beyond a
+    block's count are nobody's key."""
     nb = n // 64
     sel = np.zeros((n, n), dtype=bool)
     for qb in range(nb):
@@ -33,7 +42,8 @@ def masks(n, idx, seg_offsets, window, window_mode=0, block_count=None):
     j = np.arange(n)[None, :]
     win = (seg_id[:, None] == seg_id[None, :]) & (seg_id[:, None] >= 0) & (j - i >= -(window // 2)) & (j - i < window // 2)
     if window_mode == 1:
-        win = (i // 64) == (j // 64)
+        gid = group_ids(n, group_offsets)
+        win = gid[:, None] == gid[None, :]
     if block_count is not None:
         active = (np.arange(n) % 64) < np.repeat(np.asarray(block_count), 64)
         sel = sel & active[None, :]
@@ -55,7 +65,8 @@ def masked_attention(q, k, v, mask, scale):
     return p @ v, lse, p
 
 
-def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None, window_mode=0, block_count=None):
+def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None, window_mode=0, block_count=None,
+              group_offsets=None):
     """All float64.  Returns out [N,H,d], branches [3,N,H,d], lse [3,N,H].
     Grouped-query heads (k, v with fewer heads than q) are expanded to one key/value head per
     query head first; gates are [N,H,3] or, per channel, [N,3,H,d]."""
@@ -64,9 +75,9 @@ def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None, window_mode=
     if k.shape[1] != h:
         k, v = (np.repeat(a, h // a.shape[1], axis=1) for a in (k, v))
     scale = 1.0 / np.sqrt(d) if not scale else scale
-    kc, vc = pooled(k, block_count), pooled(v, block_count)
-    sel, win = masks(n, idx, seg_offsets, window, window_mode, block_count)
-    allc = np.ones((n, n // 64), dtype=bool)
+    kc, vc = pooled(k, block_count, group_offsets), pooled(v, block_count, group_offsets)
+    sel, win = masks(n, idx, seg_offsets, window, window_mode, block_count, group_offsets)
+    allc = np.ones((n, kc.shape[0]), dtype=bool)
     ob = np.zeros((3, n, h, d))
     lse = np.zeros((3, n, h))
     for hh in range(h):
@@ -80,7 +91,8 @@ def dense_nsa(q, k, v, idx, gates, seg_offsets, window, scale=None, window_mode=
     return out, ob, lse
 
 
-def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None, window_mode=0, block_count=None):
+def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=None, window_mode=0, block_count=None,
+                          group_offsets=None):
     """Library autograd (float64) through the dense-mask formulation -> dq, dk, dv."""
     import torch
     tq, tk0, tv0 = (torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True) for a in (q, k, v))
@@ -93,9 +105,16 @@ def dense_nsa_torch_grads(q, k, v, idx, gates, seg_offsets, window, dout, scale=
     else:
         g = g[..., None]
     scale = 1.0 / np.sqrt(d) if not scale else scale
-    sel, win = masks(n, idx, seg_offsets, window, window_mode, block_count)
+    sel, win = masks(n, idx, seg_offsets, window, window_mode, block_count, group_offsets)
     sel, win = torch.tensor(sel), torch.tensor(win)
-    if block_count is None:
+    if group_offsets is not None:
+        act_tok = np.ones(n, dtype=bool) if block_count is None else (np.arange(n) % 64) < np.repeat(np.asarray(block_count), 64)
+        gid = group_ids(n, group_offsets)
+        member = torch.tensor(((gid[None, :] == np.arange(gid.max() + 1)[:, None]) & act_tok[None, :]).astype(np.float64))
+        kc = torch.einsum("gn,nhc->ghc", member, tk) / member.sum(1)[:, None, None]
+        vc = torch.einsum("gn,nhc->ghc", member, tv) / member.sum(1)[:, None, None]
+        active_q = torch.tensor(act_tok.astype(np.float64))
+    elif block_count is None:
         kc = tk.reshape(n // 64, 64, h, d).mean(1)
         vc = tv.reshape(n // 64, 64, h, d).mean(1)
         active_q = torch.ones(n, dtype=torch.float64)

@@ -472,3 +472,78 @@ def test_backward_sampled_with_grouped_heads_channel_gates_and_own_block_window(
     if window_mode == 1:   # the two window readings really differ on this case
         sq, _, _ = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout, window_mode=0)
         assert np.abs(sq - rq).max() > 1e-3
+
+
+def _grouped_case(seed, with_counts):
+    """14 blocks of 64 slots in 6 spatial blocks of 1, 3, 2, 5, 1 and 2 blocks (64 .. 320 slots)."""
+    cfg = I.small_config(n_obj=640, n_views=1, grid=16, heads=2, d=8, topk=3, window=96, seed=seed)
+    assert cfg.nb == 14
+    goff = np.array([0, 1, 4, 6, 11, 12, 14], dtype=np.int32)
+    q, k, v = (I.bf16_bits_to_f32(a) for a in I.make_qkv(cfg))
+    gates = I.make_gates(cfg)
+    rng = np.random.default_rng(seed)
+    idx = np.stack([rng.choice(cfg.nb, size=3, replace=False) for _ in range(cfg.nb)]).astype(np.int32)
+    idx[2, 1] = -1
+    cnt = None
+    if with_counts:
+        cnt = np.full(cfg.nb, 64, dtype=np.int32)
+        cnt[[0, 3, 5, 10, 13]] = (17, 40, 1, 33, 64)    # partly filled last (and one middle) block of a spatial block
+    return cfg, goff, q, k, v, gates, idx, cnt
+
+
+@pytest.mark.parametrize("with_counts", [False, True])
+@pytest.mark.parametrize("window_mode", [0, 1])
+def test_spatial_blocks_of_several_64_slot_blocks_match_dense_formulation(oracle_lib, window_mode, with_counts):
+    """Spatial blocks larger than 64 tokens (Sec. 3.2: up to 8 x 8 x 8 active tokens per volume block), given as
+    groups of 64-slot blocks: one compressed pair per spatial block (the mean of all its active tokens) and, with the
+    own-block window, all of the query's spatial block as window keys -- against the dense formulation (membership
+    matrix for the pooling, a group-diagonal window mask) and the library attention.  Pooling per 64-slot block,
+    a window over the 64-slot block only, or a mean that counts padding slots each fails it."""
+    cfg, goff, q, k, v, gates, idx, cnt = _grouped_case(31, with_counts)
+    seg = cfg.seg_offsets()
+    kc, vc = oracle_lib.pool(k, cnt, goff), oracle_lib.pool(v, cnt, goff)
+    assert kc.shape == (6, 2, 8)
+    assert np.abs(kc - D.pooled(k.astype(np.float64), cnt, goff)).max() < 1e-6
+    # a spatial block of one full 64-slot block is the plain block mean; a group mean is the count-weighted mean of its blocks
+    if cnt is None:
+        assert np.allclose(kc[0], k[:64].mean(0), atol=1e-6) and np.allclose(kc[3], k[6 * 64:11 * 64].mean(0), atol=1e-6)
+    out, lse, ob = oracle_lib.nsa_forward(q, k, v, kc, vc, idx, gates, seg, cfg.window, want_lse=True, want_branches=True,
+                                          window_mode=window_mode, block_count=cnt, group_offsets=goff)
+    ref_out, ref_ob, ref_lse = D.dense_nsa(q, k, v, idx, gates, seg, cfg.window, window_mode=window_mode, block_count=cnt,
+                                           group_offsets=goff)
+    act = np.ones(cfg.n, dtype=bool) if cnt is None else (np.arange(cfg.n) % 64) < np.repeat(cnt, 64)
+    assert np.abs(out[act] - ref_out[act]).max() < 1e-5
+    assert np.abs(ob[:, act] - ref_ob[:, act]).max() < 1e-5
+    assert np.abs(lse[:, act] - ref_lse[:, act]).max() < 1e-5
+    # compressed branch: exactly 6 keys, so with q = 0 its lse is log 6
+    z = oracle_lib.nsa_forward(np.zeros_like(q), k, v, kc, vc, idx, gates, seg, cfg.window, want_lse=True,
+                               window_mode=window_mode, block_count=cnt, group_offsets=goff)[1]
+    assert np.abs(z[0] - np.log(6.0)).max() < 1e-6
+    if window_mode == 1:
+        # window keys of a query in the 5-block spatial block: all its active tokens
+        n_keys = 5 * 64 if cnt is None else int(cnt[6:11].sum())
+        assert np.abs(z[2, 6 * 64:11 * 64] - np.log(n_keys)).max() < 1e-5
+        # library attention with the group-diagonal mask
+        import torch
+        gid = D.group_ids(cfg.n, goff)
+        mask = torch.tensor((gid[:, None] == gid[None, :]) & act[None, :])
+        tq, tk, tv = (torch.tensor(a.astype(np.float64)).permute(1, 0, 2) for a in (q, k, v))
+        sd = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask).permute(1, 0, 2).numpy()
+        assert np.abs(ob[2][act] - sd[act]).max() < 1e-5
+
+
+@pytest.mark.parametrize("with_counts", [False, True])
+def test_backward_with_spatial_blocks_matches_library_autograd(oracle_lib, with_counts):
+    """Gradients with grouped blocks: a pooled pair hands its gradient to all active tokens of its spatial block,
+    divided by their number; the own-block window spans the spatial block."""
+    cfg, goff, q, k, v, gates, idx, cnt = _grouped_case(33, with_counts)
+    seg = cfg.seg_offsets()
+    dout = I.bf16_bits_to_f32(I.make_dout(cfg))
+    kc, vc = oracle_lib.pool(k, cnt, goff), oracle_lib.pool(v, cnt, goff)
+    for window_mode in (0, 1):
+        dq, dk, dv = oracle_lib.nsa_backward(q, k, v, kc, vc, idx, gates, seg, cfg.window, dout, window_mode=window_mode,
+                                             block_count=cnt, group_offsets=goff)
+        rq, rk, rv = D.dense_nsa_torch_grads(q, k, v, idx, gates, seg, cfg.window, dout, window_mode=window_mode,
+                                             block_count=cnt, group_offsets=goff)
+        for a, b in ((dq, rq), (dk, rk), (dv, rv)):
+            assert np.abs(a - b).max() < 1e-5 * max(1.0, np.abs(b).max())
