@@ -101,6 +101,19 @@ typedef struct lsrm_nsa_params {
                               lsrm_nsa_compress_pack with the same params, d_k, d_v and d_ws (and not
                               touched since by anything but lsrm_nsa_forward): the repacking pass is
                               skipped.  Other calls ignore the field.                          */
+    const int32_t *d_group_offsets; /* DEVICE, nullable, [n_groups + 1]: spatial blocks larger than 64 tokens
+                              (Sec. 3.2: 8 x 8 x 8 volume blocks hold up to 512 active tokens).  Spatial block g
+                              is the run of 64-slot blocks d_group_offsets[g] .. d_group_offsets[g+1] - 1
+                              (ascending, first 0, last N / 64; the caller lays a spatial block's tokens out in
+                              consecutive 64-slot blocks, the last one padded, with d_block_count giving the
+                              fill).  Then: d_kc, d_vc are [n_groups, h_kv, d], one compressed pair per spatial
+                              block, the average of all its active tokens (lsrm_nsa_compress*); the compressed
+                              branch attends those n_groups pairs; with window_mode 1 the window of a query is
+                              its whole spatial block; lsrm_nsa_backward differentiates accordingly.  Routing
+                              tables keep listing 64-slot blocks (a caller that selects a spatial block lists
+                              its 64-slot blocks; rows hold up to 128).  NULL: every 64-slot block is its own
+                              spatial block.                                                    */
+    int32_t n_groups;      /* number of spatial blocks when d_group_offsets is given (1 .. N / 64), else 0   */
 } lsrm_nsa_params;
 
 enum { LSRM_WS_ROUTE = 0, LSRM_WS_FORWARD = 1, LSRM_WS_BACKWARD = 2, LSRM_WS_ROUTE_3D = 3 };
@@ -209,7 +222,8 @@ lsrm_status lsrm_route_blocks_3d(const lsrm_nsa_params *p, const lsrm_route3d_pa
  *   d_k, d_v   [N, h_kv, d] bf16
  *   d_kc, d_vc [N/64, h_kv, d] bf16  OUT: mean over the 64 tokens of each block (over its
  *              d_block_count[b] active tokens when counts are given), accumulated in fp32 in
- *              token order, rounded to nearest-even bf16.
+ *              token order, rounded to nearest-even bf16.  With d_group_offsets: [n_groups, h_kv, d],
+ *              the mean over all active tokens of each spatial block.
  */
 lsrm_status lsrm_nsa_compress(const lsrm_nsa_params *p, const uint16_t *d_k, const uint16_t *d_v,
                               uint16_t *d_kc, uint16_t *d_vc, void *stream);

@@ -36,7 +36,8 @@ class lsrm_nsa_params(ctypes.Structure):
                 ("d", ctypes.c_int32), ("topk", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("n_seg", ctypes.c_int32), ("seg_offsets", ctypes.POINTER(ctypes.c_int32)),
                 ("scale", ctypes.c_float), ("gate_channels", ctypes.c_int32), ("window_mode", ctypes.c_int32),
-                ("d_block_count", ctypes.c_void_p), ("kv_packed", ctypes.c_int32)]
+                ("d_block_count", ctypes.c_void_p), ("kv_packed", ctypes.c_int32),
+                ("d_group_offsets", ctypes.c_void_p), ("n_groups", ctypes.c_int32)]
 
 
 class lsrm_route3d_params(ctypes.Structure):
@@ -75,9 +76,15 @@ def strerror(status: int) -> str:
 
 
 def make_params(n_obj, n_views, grid, heads, d, topk, window, seg_offsets=None, scale=0.0, h_kv=None,
-                block=64, gate_channels=False, window_mode=0, block_count=None) -> lsrm_nsa_params:
-    """block_count: int32 device tensor [N/64] of active tokens per block, or None (kept alive by the struct)."""
+                block=64, gate_channels=False, window_mode=0, block_count=None, group_offsets=None) -> lsrm_nsa_params:
+    """block_count: int32 device tensor [N/64] of active tokens per block, or None; group_offsets: int32 device tensor
+    [n_groups + 1] (spatial blocks as runs of 64-slot blocks), or None (both kept alive by the struct)."""
     p = lsrm_nsa_params()
+    if group_offsets is not None:
+        assert group_offsets.is_cuda and group_offsets.dtype == torch.int32 and group_offsets.is_contiguous()
+        p._group_keepalive = group_offsets
+        p.d_group_offsets = group_offsets.data_ptr()
+        p.n_groups = group_offsets.numel() - 1
     p.gate_channels = 1 if gate_channels else 0
     p.window_mode = window_mode
     if block_count is not None:

@@ -32,10 +32,21 @@ lsrm_status make_shape(const lsrm_nsa_params *p, Shape *s) {
     s->window = s->own_block ? 128 : p->window;
     s->count = p->d_block_count;
     s->kv_packed = p->kv_packed;
+    s->goff = p->d_group_offsets;
+    s->ng = p->d_group_offsets != nullptr ? p->n_groups : 0;
+    s->group_window = 0;
+    if (s->ng > 0 && p->window_mode == 1) {
+        // the window is the query's spatial block: a sliding window without reach limit inside per-block segments
+        s->own_block = 0;
+        s->group_window = 1;
+        s->window = 1 << 30;
+    }
     s->nb_obj = p->n_obj / kBlock;
     s->tiles_per_view = (p->grid / 8) * (p->grid / 8);
     s->n_tiles = p->n_views * s->tiles_per_view;
     s->nb = s->nb_obj + s->n_tiles;
+    if (p->d_group_offsets != nullptr ? (p->n_groups < 1 || p->n_groups > s->nb) : p->n_groups != 0) return LSRM_ERR_INVALID_ARG;
+    s->nbc = s->ng > 0 ? s->ng : s->nb;
     s->n = n;
     s->scale = p->scale > 0.0f ? p->scale : 1.0f / __builtin_sqrtf((float)p->d);
     return LSRM_OK;

@@ -68,6 +68,10 @@ struct BwdArgs {
     int32_t seg[kMaxSeg + 1];
     int64_t n;
     int nb, h, topk, window, n_seg;
+    int nbc;        // compressed pairs (spatial blocks): nb unless blocks are grouped
+    // spatial blocks of several 64-slot blocks (nullable): group of every block, its token range as the window
+    // segment of the block (given only when the window is the spatial block), active tokens per group
+    const int32_t *blk_grp, *blk_seg, *grp_tok;
     int own_block;  // window branch = the query's own block
     int h_kv, group;    // key/value heads; query heads per key/value head
     int gate_channels;  // gates are [N, 3, H, d]
@@ -506,7 +510,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
         for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
 
     // ---- the tiles of this query block: pooled, routed, window
-    const int tc = (a.nb + 31) / 32;
+    const int tc = (a.nbc + 31) / 32;
     // the routing row, valid entries first: entry u sits in lane u % 64 of register u / 64 (compacted through LDS;
     // the LDS operations of a wavefront complete in order, so the reads see the writes)
     constexpr int NR = WIDE ? 2 : 1;
@@ -544,11 +548,16 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     };
     const int ts = 2 * n_valid;
     int seg_lo = 0, seg_hi = 0;
-    for (int s = 0; s < a.n_seg; ++s)
-        if (qb * 64 >= a.seg[s] && qb * 64 < a.seg[s + 1]) {
-            seg_lo = a.seg[s];
-            seg_hi = a.seg[s + 1];
-        }
+    if (a.blk_seg != nullptr) {  // the query's spatial block
+        seg_lo = a.blk_seg[2 * qb];
+        seg_hi = a.blk_seg[2 * qb + 1];
+    } else {
+        for (int s = 0; s < a.n_seg; ++s)
+            if (qb * 64 >= a.seg[s] && qb * 64 < a.seg[s + 1]) {
+                seg_lo = a.seg[s];
+                seg_hi = a.seg[s + 1];
+            }
+    }
     if (a.own_block) {  // window = the query's own block: the block is its own segment (a.window is 128)
         seg_lo = qb * 64;
         seg_hi = qb * 64 + 64;  // (padding slots at its end are masked per tile below)
@@ -648,8 +657,8 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
                [&](int u, int *j0, int *lo, int *hi) {
                    *j0 = 32 * u;
                    *lo = 0;
-                   *hi = a.nb;
-                   return 32 * u + 32 > a.nb;
+                   *hi = a.nbc;
+                   return 32 * u + 32 > a.nbc;
                });
     // routed blocks: every key counts, except padding slots
     run_branch(tc, tc + ts, std::integral_constant<int, 1>{}, a.img_k, a.img_v,
@@ -722,7 +731,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     const uint32_t tr_off = tr_lane_offset(lane), row_off = row_lane_offset(lane);
     const int64_t key0 = (int64_t)kb * 64 + 32 * wave;  // token index (MODE 0) or pooled-key index (MODE 1)
     const int64_t key = key0 + r;
-    const int64_t limit = MODE != 1 ? a.n : (int64_t)a.nb;
+    const int64_t limit = MODE != 1 ? a.n : (int64_t)a.nbc;
     const int half_w = a.window / 2;
     // MODE 0 with per-block counts: a padding slot is nobody's key (its probabilities are zeroed) and gets a zero gradient
     const int n_act = MODE != 1 && a.count != nullptr ? a.count[kb] : 64;
@@ -757,11 +766,16 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     } else {
         const int k0 = kb * 64;
         int seg_lo = 0, seg_hi = 0;
-        for (int s = 0; s < a.n_seg; ++s)
-            if (k0 >= a.seg[s] && k0 < a.seg[s + 1]) {
-                seg_lo = a.seg[s];
-                seg_hi = a.seg[s + 1];
-            }
+        if (a.blk_seg != nullptr) {  // the key's spatial block
+            seg_lo = a.blk_seg[2 * kb];
+            seg_hi = a.blk_seg[2 * kb + 1];
+        } else {
+            for (int s = 0; s < a.n_seg; ++s)
+                if (k0 >= a.seg[s] && k0 < a.seg[s + 1]) {
+                    seg_lo = a.seg[s];
+                    seg_hi = a.seg[s + 1];
+                }
+        }
         if (a.own_block) {
             seg_lo = k0;
             seg_hi = k0 + 64;
@@ -1009,7 +1023,10 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
                 *reinterpret_cast<f32x4 *>(a.part_v + o + 32 * dt + 8 * g + 4 * hh) = xv;
             }
     } else {
-        // add the gradient of the pooled key / value of this block (its query ranges in order), / 64
+        // add the gradient of the pooled key / value this block went into (its query ranges in order), divided by
+        // the number of tokens that pair averaged: the block's, or its whole spatial block's
+        const int pair = a.blk_grp != nullptr ? a.blk_grp[kb] : kb;
+        const float pooled_tokens = a.grp_tok != nullptr ? (float)a.grp_tok[pair] : (float)n_act;
         float xk[ND][16], xv[ND][16];
 #pragma unroll
         for (int dt = 0; dt < ND; ++dt)
@@ -1017,14 +1034,14 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
             for (int g = 0; g < 4; ++g) {
                 f32x4 pk = {0.f, 0.f, 0.f, 0.f}, pv = {0.f, 0.f, 0.f, 0.f};
                 for (int sp = 0; sp < a.n_split; ++sp) {
-                    const int64_t o = (((int64_t)sp * a.nbp + kb) * a.h_kv + head) * D + 32 * dt + 8 * g + 4 * hh;
+                    const int64_t o = (((int64_t)sp * a.nbp + pair) * a.h_kv + head) * D + 32 * dt + 8 * g + 4 * hh;
                     pk += *reinterpret_cast<const f32x4 *>(a.part_k + o);
                     pv += *reinterpret_cast<const f32x4 *>(a.part_v + o);
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     // the block average was taken over its n_act active tokens; a padding slot gets nothing
-                    const float inv_cnt = key_active ? 1.0f / (float)n_act : 0.f;
+                    const float inv_cnt = key_active ? 1.0f / pooled_tokens : 0.f;
                     xk[dt][4 * g + j] = (acck[dt][4 * g + j] + pk[j] * inv_cnt) * a.scale;
                     xv[dt][4 * g + j] = accv[dt][4 * g + j] + pv[j] * inv_cnt;
                 }
@@ -1040,13 +1057,13 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
 struct WsLayout {
     size_t img_q, img_do[3], gdo, img_k, img_v, img_kc, img_vc, aux, part_k, part_v, rev_cnt, rev_ptr, rev_cur, rev_idx, total;
     int n_split, nbp, tiles_per_split, hsplit, hpw;
-    size_t hpart_k, hpart_v, order;
+    size_t hpart_k, hpart_v, order, gtab;
 };
 
 WsLayout ws_layout(const Shape &s) {
     WsLayout w;
     const size_t img = (size_t)s.d * 64;  // bytes of one (tile, head) image: row-order fragments only
-    const size_t nt = (size_t)s.nb * 2, ntc = (size_t)(s.nb + 31) / 32;
+    const size_t nt = (size_t)s.nb * 2, ntc = (size_t)(s.nbc + 31) / 32;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         size_t at = off;
@@ -1070,7 +1087,7 @@ WsLayout ws_layout(const Shape &s) {
     w.img_vc = take(ntc * s.h_kv * img);
     w.aux = take((size_t)3 * nt * s.h * 64 * 4);
     // pooled keys: enough query ranges to fill the chip
-    w.nbp = (s.nb + 63) / 64 * 64;
+    w.nbp = (s.nbc + 63) / 64 * 64;
     const int wgs = (w.nbp / 64) * s.h_kv;
     // (more ranges mean more partial sums to write; with grouped-query heads a workgroup's walk is group x as long
     // and twice as many ranges measured faster, without them slower)
@@ -1102,6 +1119,7 @@ WsLayout ws_layout(const Shape &s) {
     w.rev_ptr = take((size_t)(s.nb + 1) * 4);
     w.rev_cur = take((size_t)s.nb * 4);
     w.rev_idx = take((size_t)s.nb * (s.topk > 0 ? s.topk : 1) * 4);
+    w.gtab = take(group_tables_bytes(s));
     w.total = off;
     return w;
 }
@@ -1119,7 +1137,7 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     LSRM_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D, 2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, DKV_LDS));
     if (ev_start != nullptr) LSRM_HIP_CHECK(hipEventRecord(ev_start, st));
-    const int ntc = (s.nb + 31) / 32;
+    const int ntc = (s.nbc + 31) / 32;
     lsrm_status rc;
     hipLaunchKernelGGL(bwd_prep<D>, dim3((unsigned)(a.nt * ((s.h + PrepGeo<D>::HB - 1) / PrepGeo<D>::HB))),
                        dim3(PrepGeo<D>::THREADS), 0, st, a);
@@ -1135,8 +1153,8 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     }
     if ((rc = launch_pack_tiles(D, a.k, a.k, ws + w.img_k, s.n, s.h_kv, a.nt, st, true, a.count)) != LSRM_OK) return rc;
     if ((rc = launch_pack_tiles(D, a.v, a.v, ws + w.img_v, s.n, s.h_kv, a.nt, st, true, a.count)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.kc, a.kc, ws + w.img_kc, (int64_t)s.nb, s.h_kv, ntc, st, true, nullptr)) != LSRM_OK) return rc;
-    if ((rc = launch_pack_tiles(D, a.vc, a.vc, ws + w.img_vc, (int64_t)s.nb, s.h_kv, ntc, st, true, nullptr)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.kc, a.kc, ws + w.img_kc, (int64_t)s.nbc, s.h_kv, ntc, st, true, nullptr)) != LSRM_OK) return rc;
+    if ((rc = launch_pack_tiles(D, a.vc, a.vc, ws + w.img_vc, (int64_t)s.nbc, s.h_kv, ntc, st, true, nullptr)) != LSRM_OK) return rc;
     // reverse routing lists
     hipLaunchKernelGGL(fill_zero, dim3((s.nb + 255) / 256), dim3(256), 0, st, a.rev_cnt, s.nb);
     LSRM_HIP_CHECK(hipGetLastError());
@@ -1220,6 +1238,16 @@ lsrm_status launch_backward(const Shape &s, const int32_t *seg_host, int n_seg, 
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
     a.n = s.n;
     a.nb = s.nb;
+    a.nbc = s.nbc;
+    a.blk_grp = a.blk_seg = a.grp_tok = nullptr;
+    if (s.ng > 0) {
+        GroupTables gt;
+        lsrm_status rc = launch_group_tables(s, reinterpret_cast<int32_t *>(ws + w.gtab), &gt, st);
+        if (rc != LSRM_OK) return rc;
+        a.blk_grp = gt.blk_grp;
+        a.grp_tok = gt.grp_tok;
+        if (s.group_window) a.blk_seg = gt.blk_seg;
+    }
     a.h = s.h;
     a.h_kv = s.h_kv;
     a.group = s.h / s.h_kv;

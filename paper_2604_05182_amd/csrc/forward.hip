@@ -73,6 +73,8 @@ struct FwdArgs {
     uint16_t *gsum;  // d = 128: scratch for the running gated sum, bf16 in accumulator-fragment order
     int64_t n;
     int nb, h, topk, window, n_seg;
+    int nbc;                 // compressed pairs (spatial blocks): nb unless blocks are grouped
+    const int32_t *blk_seg;  // nullable [nb][2]: window segment (first and end token) of every block, instead of `seg`
     int h_kv, group;    // key/value heads; query heads per key/value head (query head i reads head i / group)
     int gate_channels;  // gates are [N, 3, H, d] (one per output channel) instead of [N, H, 3]
     int own_block;      // the window branch sees the query's own block (App. A) instead of a sliding window
@@ -868,11 +870,16 @@ __device__ __forceinline__ WinRange window_range(const FwdArgs &a, int qb) {
     const int q0 = qb * 64;
     w.seg_lo = 0;
     w.seg_hi = 0;
-    for (int s = 0; s < a.n_seg; ++s) {
-        int lo = a.seg[s], hi = a.seg[s + 1];
-        if (q0 >= lo && q0 < hi) {
-            w.seg_lo = lo;
-            w.seg_hi = hi;
+    if (a.blk_seg != nullptr) {  // segments per block (the query's spatial block), looked up instead of scanned
+        w.seg_lo = a.blk_seg[2 * qb];
+        w.seg_hi = a.blk_seg[2 * qb + 1];
+    } else {
+        for (int s = 0; s < a.n_seg; ++s) {
+            int lo = a.seg[s], hi = a.seg[s + 1];
+            if (q0 >= lo && q0 < hi) {
+                w.seg_lo = lo;
+                w.seg_hi = hi;
+            }
         }
     }
     if (a.own_block) {
@@ -916,7 +923,7 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
     const int kvh = head / a.group;                         // key/value head of this query head
     // images are stored head-major: the tiles of one head are contiguous
     const int64_t tile_stride = G::TILE;
-    const int64_t head_kv = (int64_t)kvh * (2 * a.nb) * G::TILE, head_kvc = (int64_t)kvh * ((a.nb + 31) / 32) * G::TILE;
+    const int64_t head_kv = (int64_t)kvh * (2 * a.nb) * G::TILE, head_kvc = (int64_t)kvh * ((a.nbc + 31) / 32) * G::TILE;
     const float sl2 = a.scale_log2e;
 
     WaveCtx<G> c;
@@ -941,17 +948,17 @@ __global__ __launch_bounds__((G::THREADS), (G::WAVES_PER_SIMD)) void nsa_forward
 #pragma unroll
         for (int qt = 0; qt < G::QT; ++qt) {
             c.lo[qt] = 0;
-            c.hi[qt] = a.nb;
+            c.hi[qt] = a.nbc;
         }
-        const int n_steps = (a.nb + 31) / 32;
+        const int n_steps = (a.nbc + 31) / 32;
         const char *base = a.kvc + head_kvc;
         auto src = [&](int t) { return base + t * tile_stride; };
         auto msk = [&](int t, int *j0, bool *need, int *cap) {
             *j0 = 32 * t;
-            *need = 32 * t + 32 > a.nb;
+            *need = 32 * t + 32 > a.nbc;
             *cap = 0x7fffffff;
         };
-        run_shared<G>(c, n_steps, src, msk, 0, a.nb / 32, lds, wave, lane, sl2);
+        run_shared<G>(c, n_steps, src, msk, 0, a.nbc / 32, lds, wave, lane, sl2);
         if (active) finish_branch<G>(c, a, 0, row0, head, wave, lane, lds);
     }
 
@@ -1218,7 +1225,7 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
 }
 
 struct WsLayout {
-    size_t kv, kvc, gsum, sched, total;
+    size_t kv, kvc, gsum, sched, gtab, total;
 };
 
 WsLayout ws_layout(const Shape &s) {
@@ -1228,11 +1235,13 @@ WsLayout ws_layout(const Shape &s) {
     w.kv = off;
     off += align_up((size_t)s.nb * 2 * s.h_kv * tile, 256);
     w.kvc = off;
-    off += align_up((size_t)((s.nb + 31) / 32) * s.h_kv * tile, 256);
+    off += align_up((size_t)((s.nbc + 31) / 32) * s.h_kv * tile, 256);
     w.gsum = off;
     off += s.d == 128 ? align_up((size_t)s.nb * 64 * s.h * s.d * 2, 256) : 0;  // (kept in registers at d <= 64)
     w.sched = off;
     off += s.d == 128 ? sel_schedule_bytes(s) : 0;
+    w.gtab = off;
+    off += group_tables_bytes(s);
     w.total = off > 0 ? off : 256;
     return w;
 }
@@ -1243,14 +1252,20 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
                              const WsLayout &w, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
     constexpr int D = G::D, NP = G::NP;
     for (int i = 0; i <= n_seg; ++i) a.seg[i] = seg_host[i];
-    const int tiles_c = (s.nb + 31) / 32;
+    const int tiles_c = (s.nbc + 31) / 32;
+    if (s.group_window) {
+        GroupTables gt;
+        lsrm_status rc = launch_group_tables(s, reinterpret_cast<int32_t *>(ws + w.gtab), &gt, st);
+        if (rc != LSRM_OK) return rc;
+        a.blk_seg = gt.blk_seg;
+    }
     if (!s.kv_packed) {
         hipLaunchKernelGGL((pack_tiles<D, false>), dim3(s.nb, s.h_kv), dim3(256), 0, st, d_k, d_v, ws + w.kv, s.n, s.h_kv,
                            2 * s.nb, a.count);
         LSRM_HIP_CHECK(hipGetLastError());
     }
-    hipLaunchKernelGGL((pack_tiles<D, false>), dim3((s.nb + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
-                       (int64_t)s.nb, s.h_kv, tiles_c, (const int32_t *)nullptr);
+    hipLaunchKernelGGL((pack_tiles<D, false>), dim3((s.nbc + 63) / 64, s.h_kv), dim3(256), 0, st, d_kc, d_vc, ws + w.kvc,
+                       (int64_t)s.nbc, s.h_kv, tiles_c, (const int32_t *)nullptr);
     LSRM_HIP_CHECK(hipGetLastError());
     if (D == 128) {
         lsrm_status rc = launch_sel_schedule(s, a.idx, reinterpret_cast<int32_t *>(ws + w.sched), st);
@@ -1289,6 +1304,13 @@ lsrm_status launch_compress_pack(const Shape &s, const uint16_t *d_k, const uint
     if (s.nb == 0) return LSRM_OK;
     char *img = reinterpret_cast<char *>(d_ws) + ws_layout(s).kv;
     const dim3 grid(s.nb, s.h_kv);
+    if (s.ng > 0) {
+        // a spatial block's average spans several 64-slot blocks, i.e. several workgroups of the packing pass: the
+        // two are separate passes here
+        lsrm_status rc = launch_pack_tiles(s.d, d_k, d_v, img, s.n, s.h_kv, 2 * s.nb, st, false, s.count);
+        if (rc != LSRM_OK) return rc;
+        return launch_compress(s, d_k, d_v, d_kc, d_vc, st);
+    }
 #define LSRM_POOL_PACK(DD) \
     hipLaunchKernelGGL((pack_tiles<DD, false, true>), grid, dim3(256), 0, st, d_k, d_v, img, s.n, s.h_kv, 2 * s.nb, s.count, \
                        d_kc, d_vc)
@@ -1337,6 +1359,8 @@ lsrm_status launch_forward(const Shape &s, const int32_t *seg_host, int n_seg, c
     a.out_branch = d_out_branch;
     a.n = s.n;
     a.nb = s.nb;
+    a.nbc = s.nbc;
+    a.blk_seg = nullptr;
     a.h = s.h;
     a.h_kv = s.h_kv;
     a.group = s.h / s.h_kv;

@@ -16,6 +16,11 @@ struct Shape {
     int own_block;      // window branch = the query's own block; `window` is then 128 (every slot of the block
                         // within reach) and the kernels treat the block as its own segment
     int kv_packed;      // the forward workspace already holds the tile images of k and v (lsrm_nsa_compress_pack)
+    const int32_t *goff;   // device, nullable [ng + 1]: spatial blocks as runs of 64-slot blocks
+    int ng;                // number of spatial blocks (0 without goff)
+    int nbc;               // compressed pairs: ng with groups, else nb
+    int group_window;      // window branch = the query's spatial block (groups with window_mode 1): the kernels take the
+                           // window segment of a block from the blk_seg table and `window` is 2^30
     const int32_t *count;  // device, nullable [nb]: active tokens per block
     int nb_obj, tiles_per_view, n_tiles, nb;
     int64_t n;
@@ -44,6 +49,16 @@ lsrm_status launch_route_static(const Shape &s, const float *d_pos, const lsrm_c
 lsrm_status launch_route_3d(const Shape &s, const lsrm_route3d_params &r, const float *d_pos, const float *d_pos_img,
                             const lsrm_camera *d_cams, int32_t *d_idx, float *d_dist2, void *d_ws, hipStream_t st);
 size_t route3d_ws_bytes(const Shape &s);
+
+// Tables derived from the group offsets, for the attention kernels (tab: 3 nb + ng int32 of workspace):
+//   blk_grp [nb]     spatial block of every 64-slot block
+//   blk_seg [nb][2]  first token and end token of that spatial block
+//   grp_tok [ng]     active tokens of every spatial block
+struct GroupTables {
+    const int32_t *blk_grp, *blk_seg, *grp_tok;
+};
+inline size_t group_tables_bytes(const Shape &s) { return s.ng > 0 ? align_up(((size_t)3 * s.nb + s.ng) * 4, 256) : 0; }
+lsrm_status launch_group_tables(const Shape &s, int32_t *tab, GroupTables *out, hipStream_t st);
 
 lsrm_status launch_compress(const Shape &s, const uint16_t *d_k, const uint16_t *d_v, uint16_t *d_kc,
                             uint16_t *d_vc, hipStream_t st);  // honours s.count

@@ -15,13 +15,15 @@ def bf16_host(t: torch.Tensor) -> np.ndarray:
     return t.float().cpu().numpy()
 
 
-def params_for(B, cfg, seg_offsets="default", scale=0.0, topk=None, window=None, window_mode=0, block_count=None):
+def params_for(B, cfg, seg_offsets="default", scale=0.0, topk=None, window=None, window_mode=0, block_count=None,
+               group_offsets=None):
     seg = None if isinstance(seg_offsets, str) else seg_offsets
     cnt = None if block_count is None else torch.from_numpy(np.ascontiguousarray(block_count, dtype=np.int32)).cuda()
+    grp = None if group_offsets is None else torch.from_numpy(np.ascontiguousarray(group_offsets, dtype=np.int32)).cuda()
     return B.make_params(cfg.n_obj, cfg.n_views, cfg.grid, cfg.heads, cfg.d,
                          cfg.topk if topk is None else topk, cfg.window if window is None else window,
                          seg_offsets=seg, scale=scale, h_kv=cfg.kv_heads, gate_channels=cfg.gate_channels,
-                         window_mode=window_mode, block_count=cnt)
+                         window_mode=window_mode, block_count=cnt, group_offsets=grp)
 
 
 def run_route(B, cfg, pos, cams, want_dist=True):
@@ -50,10 +52,11 @@ def run_route_3d(B, cfg, pos, pos_img, cams, width, prefilter, k_v2v, k_v2i, k_i
     return idx.cpu().numpy(), (d2.cpu().numpy() if want_dist else None)
 
 
-def run_compress(B, cfg, k_bits, v_bits, block_count=None):
-    p = params_for(B, cfg, block_count=block_count)
+def run_compress(B, cfg, k_bits, v_bits, block_count=None, group_offsets=None):
+    p = params_for(B, cfg, block_count=block_count, group_offsets=group_offsets)
     dk, dv = bf16_dev(k_bits), bf16_dev(v_bits)
-    kc = torch.empty((cfg.nb, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device="cuda")
+    n_pairs = cfg.nb if group_offsets is None else len(group_offsets) - 1
+    kc = torch.empty((n_pairs, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device="cuda")
     vc = torch.empty_like(kc)
     B.lsrm_nsa_compress(p, dk, dv, kc, vc)
     torch.cuda.synchronize()
@@ -61,23 +64,24 @@ def run_compress(B, cfg, k_bits, v_bits, block_count=None):
 
 
 def run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets="default", scale=0.0,
-                want_aux=False, window=None, window_mode=0, block_count=None, fused_pack=False):
+                want_aux=False, window=None, window_mode=0, block_count=None, fused_pack=False, group_offsets=None):
     """compress + forward on the device.  Returns dict of numpy results (+ device kc, vc).
     fused_pack: lsrm_nsa_compress_pack, then the forward with kv_packed = 1 (one pass over k and v for both)."""
     topk = idx.shape[1]
     p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window, window_mode=window_mode,
-                   block_count=block_count)
+                   block_count=block_count, group_offsets=group_offsets)
     dq = bf16_dev(q_bits)
     if fused_pack:
         dk, dv = bf16_dev(k_bits), bf16_dev(v_bits)
-        kc = torch.empty((cfg.nb, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device="cuda")
+        n_pairs = cfg.nb if group_offsets is None else len(group_offsets) - 1
+        kc = torch.empty((n_pairs, cfg.kv_heads, cfg.d), dtype=torch.bfloat16, device="cuda")
         vc = torch.empty_like(kc)
         ws = B.alloc_workspace(p, B.LSRM_WS_FORWARD)
         ws.fill_(0xFF)   # NaN patterns: an image the fused pass fails to write shows
         B.lsrm_nsa_compress_pack(p, dk, dv, kc, vc, ws)
         p.kv_packed = 1
     else:
-        dk, dv, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count)
+        dk, dv, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count, group_offsets)
     d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
     d_g = torch.from_numpy(gates).cuda()
     out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
@@ -95,13 +99,13 @@ def run_forward(B, cfg, q_bits, k_bits, v_bits, idx, gates, seg_offsets="default
 
 
 def run_backward(B, cfg, q_bits, k_bits, v_bits, idx, gates, dout_bits, seg_offsets="default", scale=0.0, window=None,
-                 window_mode=0, block_count=None):
+                 window_mode=0, block_count=None, group_offsets=None):
     """compress + forward (saving lse and branch outputs) + backward on the device -> dq, dk, dv as float32 numpy."""
     topk = idx.shape[1]
     p = params_for(B, cfg, seg_offsets=seg_offsets, scale=scale, topk=topk, window=window, window_mode=window_mode,
-                   block_count=block_count)
+                   block_count=block_count, group_offsets=group_offsets)
     dq_in, ddo = bf16_dev(q_bits), bf16_dev(dout_bits)
-    dk_in, dv_in, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count)
+    dk_in, dv_in, kc, vc = run_compress(B, cfg, k_bits, v_bits, block_count, group_offsets)
     d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
     d_g = torch.from_numpy(gates).cuda()
     out = torch.empty((cfg.n, cfg.heads, cfg.d), dtype=torch.bfloat16, device="cuda")
