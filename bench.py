@@ -344,11 +344,14 @@ def main():
     result["roofline_call"] = {"call": "lsrm_nsa_forward", "bound": "mfma", "achieved": round(call_tflops, 3),
                                "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                                "frac": round(call_tflops / BF16_MFMA_PEAK_TFLOPS, 4)}
-    if cfg.d == 32:
-        # At d = 32 a 32 x 32 score tile costs 4 MFMAs but still 1024 exponentials: the softmax arithmetic,
-        # not the matrix pipe, bounds the kernel.  Per score element and head: scale-and-subtract, running
-        # sum, running maximum and the bf16 conversion (4 plain issue slots) plus one exponential (a
-        # quarter-rate instruction: 4 slots).  Peak issue rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+    if cfg.d <= 64:
+        # At d <= 64 the softmax arithmetic, not the matrix pipe, bounds the kernel: a 32 x 32 score tile costs 8 MFMAs
+        # at d = 64 (4 at d = 32) but always 1024 exponentials.  Per score element and head the kernel issues one
+        # fused scale-and-subtract, one exponential (a quarter-rate instruction: 4 issue slots), one add into the row
+        # sum and half a packed bf16 conversion -- 6.5 slots; 8 are charged, the rest being the share of the
+        # per-tile work (operand address updates, overflow test of the optimistic running maximum, masks at the
+        # edges).  Peak issue rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.  At d = 64 the matrix-pipe time at the
+        # bf16 peak is half of the vector-pipe time at this peak, at d = 32 a quarter.
         p_all = cfg.forward_pairs(n_valid)
         slots = 8.0 * cfg.heads * (p_all["cmp"] + p_all["sel"] + p_all["win"])
         peak = 256 * 4 * 16 * 2.4e9 / 1e12
@@ -356,7 +359,8 @@ def main():
         result["roofline"] = {"kernel": "nsa_forward_kernel", "bound": "alu", "achieved": round(ach, 3),
                               "peak": round(peak, 2), "unit": "T fp32 lane-op slots/s", "frac": round(ach / peak, 4),
                               "traffic": None,
-                              "mfma_tflops": round(attn_tflops, 3)}
+                              "mfma_tflops": round(attn_tflops, 3),
+                              "mfma_frac": round(attn_tflops / BF16_MFMA_PEAK_TFLOPS, 4)}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, {"qkv_bits": (q_bits, k_bits, v_bits), "gates": gates}, idx)
     print(json.dumps(result), flush=True)
