@@ -185,6 +185,9 @@ def main():
                     help="routing table: the configs' projected-centroid rule (default) or the four geometric "
                          "selection rules (lsrm_route_blocks_3d: B^i = 4, a quarter of top-k volume blocks, the "
                          "rest image blocks)")
+    ap.add_argument("--serial", action="store_true",
+                    help="routing, pooling/packing and forward on one stream (default: routing on a second stream "
+                         "beside the pooling/packing pass)")
     ap.add_argument("--two-pass", action="store_true",
                     help="lsrm_nsa_compress, then a forward that repacks k and v itself, instead of the default "
                          "lsrm_nsa_compress_pack + forward with kv_packed (one pass over k and v for both)")
@@ -237,11 +240,11 @@ def main():
         d_pos_img = torch.from_numpy(I.make_points_img(cfg, cams)).to(dev)
         ws_route = B.alloc_workspace(p, B.LSRM_WS_ROUTE_3D)
 
-    def route():
+    def route(stream=None):
         if four_rule:
-            B.lsrm_route_blocks_3d(p, r3d, d_pos, d_pos_img, d_cams, d_idx, None, ws_route)
+            B.lsrm_route_blocks_3d(p, r3d, d_pos, d_pos_img, d_cams, d_idx, None, ws_route, stream=stream)
         else:
-            B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route)
+            B.lsrm_route_blocks(p, d_pos, d_cams, d_idx, None, ws_route, stream=stream)
 
     if args.config == 5 or args.backward:
         run_backward_bench(args, cfg, B, I, p, dev, (d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, d_pos, d_cams),
@@ -249,28 +252,36 @@ def main():
         return
 
     n_ev = args.steps
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_ev)]
-    for row in ev:
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(n_ev)]
+    warm_ev = [torch.cuda.Event(enable_timing=True) for _ in range(8)]
+    for row in ev + [warm_ev]:
         for e in row:
             e.record()  # creates the underlying hipEvent handles
+    # Routing (positions and cameras -> table) and pooling/packing (K, V -> pooled pairs and tile images) do not depend
+    # on each other: the step runs routing on a second stream (default priority) beside the pooling/packing pass, and
+    # the forward waits for both.  --serial puts the three calls on one stream.
+    main_stream = torch.cuda.current_stream()
+    side_stream = main_stream if args.serial else torch.cuda.Stream()
 
     def step(i=None):
-        e = ev[i] if i is not None else [None] * 6
-        if i is not None:
-            e[0].record()
-        route()
-        if i is not None:
-            e[1].record()
+        e = ev[i] if i is not None else warm_ev
+        e[0].record(main_stream)
+        if not args.serial:
+            side_stream.wait_event(e[0])  # the previous step's forward has read the routing table
+        e[6].record(side_stream)
+        route(stream=side_stream)
+        e[1].record(side_stream)
         if args.two_pass:
             B.lsrm_nsa_compress(p, d_k, d_v, d_kc, d_vc)
         else:
             B.lsrm_nsa_compress_pack(p, d_k, d_v, d_kc, d_vc, ws_fwd)
-        if i is not None:
-            e[2].record()
+        e[2].record(main_stream)
+        if not args.serial:
+            main_stream.wait_event(e[1])
+        e[7].record(main_stream)
         B.lsrm_nsa_forward(p, d_q, d_k, d_v, d_kc, d_vc, d_idx, d_gates, d_out, None, None, ws_fwd,
                            ev_attn_start=e[3], ev_attn_stop=e[4])
-        if i is not None:
-            e[5].record()
+        e[5].record(main_stream)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -289,9 +300,9 @@ def main():
     wall = time.perf_counter() - t0
 
     ms_step = wall * 1e3 / args.steps
-    ms_route = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    ms_compress = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-    ms_fwd_call = float(np.mean([e[2].elapsed_time(e[5]) for e in ev]))
+    ms_route = float(np.mean([e[6].elapsed_time(e[1]) for e in ev]))
+    ms_compress = float(np.mean([(e[0] if not args.serial else e[1]).elapsed_time(e[2]) for e in ev]))
+    ms_fwd_call = float(np.mean([e[7].elapsed_time(e[5]) for e in ev]))
     ms_attn = float(np.mean([e[3].elapsed_time(e[4]) for e in ev]))
 
     idx = d_idx.cpu().numpy()
@@ -323,6 +334,7 @@ def main():
                            if four_rule else ""),
             "effective_flops": flops,
             "pct_of_bf16_mfma_peak": round(100.0 * value / BF16_MFMA_PEAK_TFLOPS, 2),
+            "streams": "one" if args.serial else "routing on a second stream beside the pooling/packing pass",
         },
         "breakdown_ms": {"route": round(ms_route, 4), "compress": round(ms_compress, 4),
                          "forward_call": round(ms_fwd_call, 4), "attention_kernel": round(ms_attn, 4)},

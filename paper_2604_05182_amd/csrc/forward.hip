@@ -1131,14 +1131,18 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
     static_assert(!(POOL && ROWS_ONLY), "");
     constexpr int K_BYTES = 32 * D * 2, TILE = ROWS_ONLY ? K_BYTES : K_BYTES + D * 64;
     constexpr int CH = D / 8;  // 16-byte chunks per row
-    __shared__ uint16_t vt[64][D + 2];
+    // Both tensors' rows of the block are staged in LDS, so that the images are written in image order (a wavefront
+    // writes 1 KB contiguous per instruction; written straight from the loaded registers, K chunks would go out as
+    // 16-byte pieces 512 bytes apart).  Row pitch D + 16 elements: 16-byte aligned, and the 4 rows x 4 column
+    // groups that 16 lanes address in one transposing load fall in distinct banks.
+    constexpr int PITCH = D + 16;
+    __shared__ __attribute__((aligned(16))) uint16_t kt[64][PITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t vt[ROWS_ONLY ? 1 : 64][PITCH];
     __shared__ float psum[POOL ? 2 : 1][POOL ? 256 / CH : 1][POOL ? D + 1 : 1];  // [k, v][thread group][channel]
     const int64_t blk = blockIdx.x;
     const int head = blockIdx.y;
     const int n_act = count != nullptr ? count[blk] : 64;
     float ak[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, av[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    // K: a permutation of 16-byte chunks.  Source chunk (row t, chunk cc) goes to fragment
-    // ks = cc / 2, lane (hh = cc % 2, r = perm(t % 32)) of tile t / 32.
     // all loads of the thread first (64 CH / 256 chunks of k and as many of v), so that they are in flight together
     constexpr int NIT = 64 * CH / 256;
     uint4 kin[NIT], vin[NIT];
@@ -1159,22 +1163,11 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
         const int e = threadIdx.x + 256 * it;
         const int t = e / CH, cc = e % CH;
         const uint4 kval = kin[it], vval = vin[it];
-        const int64_t tile = blk * 2 + t / 32;
-        if (tile < n_tiles) {
-            const int tt = t % 32;
-            int r = (tt & ~12) | ((tt & 4) << 1) | ((tt & 8) >> 1);
-            if (ROWS_ONLY) r ^= (cc & 1) << 2;
-            *reinterpret_cast<uint4 *>(img + image_index<ROWS_ONLY>(tile, head, h, n_tiles) * TILE + (cc * 32 + r) * 16) = kval;
-        }
+        *reinterpret_cast<uint4 *>(&kt[t][cc * 8]) = kval;
         if (ROWS_ONLY) continue;
-        uint32_t w[4] = {vval.x, vval.y, vval.z, vval.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            vt[t][cc * 8 + 2 * j] = (uint16_t)(w[j] & 0xffffu);
-            vt[t][cc * 8 + 2 * j + 1] = (uint16_t)(w[j] >> 16);
-        }
+        *reinterpret_cast<uint4 *>(&vt[t][cc * 8]) = vval;
         if (POOL) {
-            const uint32_t kw[4] = {kval.x, kval.y, kval.z, kval.w};
+            const uint32_t kw[4] = {kval.x, kval.y, kval.z, kval.w}, w[4] = {vval.x, vval.y, vval.z, vval.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 ak[2 * j] += __uint_as_float(kw[j] << 16);
@@ -1184,7 +1177,6 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
             }
         }
     }
-    if (ROWS_ONLY) return;
     if (POOL) {
         // (every thread keeps one chunk column cc = threadIdx.x % CH: 256 is a multiple of CH)
         const int grp = threadIdx.x / CH, cc = threadIdx.x % CH;
@@ -1195,6 +1187,21 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
         }
     }
     __syncthreads();
+    // K: a permutation of 16-byte chunks.  Chunk q of a tile's K part = fragment ks = cc / 2, lane (hh = cc % 2,
+    // r = q % 32) with cc = q / 32: source row perm(r) of the tile, source chunk cc.
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int e = threadIdx.x + 256 * it;
+        const int half = e / (32 * CH), q = e % (32 * CH);
+        const int cc = q / 32, rr = q % 32;
+        const int r = ROWS_ONLY ? rr ^ ((cc & 1) << 2) : rr;
+        const int tt = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
+        const uint4 kval = *reinterpret_cast<const uint4 *>(&kt[32 * half + tt][cc * 8]);
+        const int64_t tile = blk * 2 + half;
+        if (tile < n_tiles)
+            *reinterpret_cast<uint4 *>(img + image_index<ROWS_ONLY>(tile, head, h, n_tiles) * TILE + q * 16) = kval;
+    }
+    if (ROWS_ONLY) return;
     if (POOL) {
         if (threadIdx.x < 2 * D) {
             const int which = threadIdx.x / D, c = threadIdx.x % D;
@@ -1207,20 +1214,27 @@ __global__ __launch_bounds__(256) void pack_tiles(const uint16_t *__restrict__ k
         }
     }
     // V^T: chunk e of a tile = fragment f = e / 64 (ks2 = f / ND, dt = f % ND), lane = e % 64
-    // (hh = lane / 32, r = lane % 32): channel 32 dt + r, keys 16 ks2 + 8 hh + 0..7.
+    // (hh = lane / 32, r = lane % 32): channel 32 dt + r, keys 16 ks2 + 8 hh + 0..7.  Read with the transposing LDS
+    // load (ds_read_b64_tr_b16: within a group of 16 lanes, lane j receives as element e the 16-bit element j % 4 of
+    // what lane 4 e + j / 4 addressed): lane j of a group addresses row k0 + j / 4, channels c0 + 4 (j % 4) .. + 3, and
+    // receives channel c0 + j of rows k0 .. k0 + 3; two loads give the 8 keys of the chunk.
     constexpr int ND = D / 32;
+    const uint32_t vt_base = (uint32_t)(uintptr_t)&vt[0][0];  // (the low 32 bits of a generic LDS pointer are the LDS address)
     for (int e = threadIdx.x; e < 2 * 2 * ND * 64; e += 256) {
         const int half = e / (2 * ND * 64);
         const int f = (e / 64) % (2 * ND), ln = e % 64;
         const int ks2 = f / ND, dt = f % ND, hh = ln / 32, r = ln % 32;
-        const int ch = 32 * dt + r, t0 = 32 * half + 16 * ks2 + 8 * hh;
+        const int j = ln & 15, c0 = 32 * dt + (r & 16), t0 = 32 * half + 16 * ks2 + 8 * hh;
         const int64_t tile = blk * 2 + half;
+        const uint32_t addr = vt_base + (uint32_t)(((t0 + (j >> 2)) * PITCH + c0 + 4 * (j & 3)) * 2);
+        uint2 lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:%3\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(lo), "=&v"(hi)
+                     : "v"(addr), "n"(4 * PITCH * 2)
+                     : "memory");
         if (tile >= n_tiles) continue;
-        uint32_t w[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = (uint32_t)vt[t0 + 2 * j][ch] | ((uint32_t)vt[t0 + 2 * j + 1][ch] << 16);
         *reinterpret_cast<uint4 *>(img + image_index<ROWS_ONLY>(tile, head, h, n_tiles) * TILE + K_BYTES + (f * 64 + ln) * 16) =
-            make_uint4(w[0], w[1], w[2], w[3]);
+            make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
 }
 
