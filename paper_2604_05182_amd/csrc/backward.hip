@@ -33,6 +33,9 @@
 #include <type_traits>
 #include <utility>
 
+#ifndef LSRM_DKV_INTERLEAVE
+#define LSRM_DKV_INTERLEAVE (D == 128)
+#endif
 constexpr int kBwdNbuf = 2;         // tile buffers of the dQ kernel
 constexpr int kBwdDkvNbuf = 2;      // tile buffers of the dK/dV kernels (three, copies two steps ahead: no faster)
 constexpr int kBwdSplitTarget = 2048;  // pooled-key workgroups aimed at when the query range is split
@@ -206,6 +209,16 @@ template <int ND>
 __device__ __forceinline__ void mfma_tr(f32x16 (&acc)[ND], const char *rows, uint32_t lane_off, const BFrag (&b)[2]) {
     // (the low 32 bits of a generic pointer into LDS are the LDS address)
     mfma_tr_impl<ND>(acc, (uint32_t)(uintptr_t)rows + lane_off, b, std::make_integer_sequence<int, 2 * ND>{});
+}
+
+// f(integral_constant<0>), ..., f(integral_constant<N - 1>), in order
+template <typename F, int... K>
+__device__ __forceinline__ void for_each_index_impl(F &f, std::integer_sequence<int, K...>) {
+    (f(std::integral_constant<int, K>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void for_each_index(F &f) {
+    for_each_index_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 template <int D>
@@ -817,6 +830,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     const int gh0 = MODE == 0 && a.hsplit > 1 ? (int)blockIdx.z * a.hpw : 0;
     const int grp = MODE == 0 && a.hsplit > 1 ? min(a.group, gh0 + a.hpw) - gh0 : a.group;
     constexpr bool VGPR_CHAINS = D == 128;  // (the kernel has one wavefront per SIMD: see mfma_v)
+    constexpr bool INTERLEAVE = LSRM_DKV_INTERLEAVE;
     constexpr int NB = kBwdDkvNbuf;  // tile buffers: the copies run NB - 1 steps ahead of the arithmetic
     constexpr int IPW = G::ROW / 1024;    // copy instructions per wavefront and step (wavefront 0: one more, the table)
     static_assert(NB == 2 || NB == 3, "");
@@ -942,6 +956,143 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
             mfma_tr<ND>(acck, x.buf, tr_off, dsb);
         };
 
+        // The interleaved form of a step (INTERLEAVE).  A wavefront issues in order, and this kernel has one wavefront
+        // per SIMD at d = 128: whatever is to overlap -- vector arithmetic with MFMAs, LDS latency with either -- has to
+        // alternate in the program.  Scheduling barriers fix the order of the pieces:
+        //   reads of the Q rows | S#0, reads of the dout rows and of the table | S#1.. | (all reads have arrived)
+        //   dP#k, each followed by its share of the exponentials (unmasked; edge tiles are fixed up afterwards) and by
+        //     the transposing loads of one dout^T fragment
+        //   dV#i (dout^T P), each followed by its share of dS = P o (dP - D) and by the loads of one Q^T fragment
+        //   dK#i (Q^T dS)
+        // The transposing loads are untracked (see tr_issue): their waits are counted by hand.  Fragment i of dout^T
+        // is needed at dV#i, by when fragments i+1.. of dout^T and 0..i-1 of Q^T (two loads each) have been issued
+        // behind it: at most 14 younger loads whatever i is; Q^T fragment i at dK#i has the 7-i later ones behind it.
+        // The tracked reads (row fragments, table) are all waited for before the first untracked load is issued, so
+        // the compiler's own counted waits never meet loads it does not know of.
+        auto step_interleaved = [&](const char *buf, int tile) {
+            static_assert(!INTERLEAVE || 16 % NS == 0, "");
+            const int q0 = 32 * tile;
+            const bool win = BR == 2 && ((int)key0 - (q0 + 31) < -half_w || (int)key0 + 31 - q0 >= half_w);
+            const bool plain = MODE == 1 ? key0 + 32 <= limit : (!win && n_act == 64);
+            const char *base = buf + row_off;
+            const uint32_t tr_q = (uint32_t)(uintptr_t)buf + tr_off, tr_do = tr_q + G::ROW;
+            f32x16 sc, dp;
+            float lv[16], pr[16];
+            bf16x8 qr[NS], rows[NS];
+#pragma unroll
+            for (int ks = 0; ks < NS; ++ks) qr[ks] = *reinterpret_cast<const bf16x8 *>(base + ks * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (VGPR_CHAINS) {
+                mfma_v_first(sc, qr[0], kB[0]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[0], kB[0], sc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 y = *reinterpret_cast<const f32x4 *>(buf + AUX + 128 + (8 * g + 4 * hh) * 4);
+                const f32x4 z = *reinterpret_cast<const f32x4 *>(buf + AUX + (8 * g + 4 * hh) * 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    dp[4 * g + j] = y[j];
+                    lv[4 * g + j] = z[j];
+                }
+            }
+#pragma unroll
+            for (int ks = 0; ks < NS; ++ks) rows[ks] = *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 1; ks < NS; ++ks) {
+                if constexpr (VGPR_CHAINS)
+                    mfma_v(sc, qr[ks], kB[ks]);
+                else
+                    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[ks], kB[ks], sc, 0, 0, 0);
+            }
+            // every tracked read has arrived (the empty statements make the compiler wait for them here)
+#pragma unroll
+            for (int ks = 0; ks < NS; ++ks) asm volatile("" : "+v"(rows[ks]));
+#pragma unroll
+            for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(lv[i]));
+            asm volatile("" : "+v"(dp));
+            if constexpr (VGPR_CHAINS) mfma_v_settle(sc);
+            __builtin_amdgcn_sched_barrier(0);
+
+            TrFrag fdo[2 * ND], fq[2 * ND];
+            BFrag pb[2], dsb[2];
+            // dP chain with the exponentials; dout^T fragments requested on the way (fragment f after MFMA f * NS / 2ND)
+            constexpr int E = 16 / NS;
+            auto issue_do = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                tr_issue<(I % ND) * 2048 + (I / ND) * 256>(fdo[I], tr_do);
+            };
+            auto issue_q = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                tr_issue<(I % ND) * 2048 + (I / ND) * 256>(fq[I], tr_q);
+            };
+            auto dp_step = [&](auto kc) {
+                constexpr int ks = decltype(kc)::value;
+                if constexpr (VGPR_CHAINS)
+                    mfma_v(dp, rows[ks], vB[ks]);
+                else
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows[ks], vB[ks], dp, 0, 0, 0);
+#pragma unroll
+                for (int e = ks * E; e < (ks + 1) * E; ++e) {
+                    pr[e] = __builtin_amdgcn_exp2f(sc[e] * a.sl2 - lv[e]);
+                    if (e & 1) {
+                        pb[e / 8].u[(e / 2) % 4] = pack_bf16(pr[e - 1], pr[e]);
+                        asm volatile("" : "+v"(pb[e / 8].u[(e / 2) % 4]));
+                    }
+                    asm volatile("" : "+v"(pr[e]));
+                }
+                // NS MFMAs, 2 ND fragments: one fragment behind every (NS / 2ND)-th MFMA (NS = 2 ND * (NS / 2ND))
+                if constexpr (ks % (NS / (2 * ND)) == 0) issue_do(std::integral_constant<int, ks / (NS / (2 * ND))>{});
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for_each_index<NS>(dp_step);
+            if constexpr (VGPR_CHAINS) mfma_v_settle(dp);
+            if (__builtin_expect(!plain, 0)) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    bool ok;
+                    if (MODE == 1) {
+                        ok = key < limit;
+                    } else {
+                        const int qi = q0 + (i % 8) + 8 * hh + 16 * (i / 8);  // the query behind accumulator row i
+                        const int dj = (int)key - qi;
+                        ok = key_active & (!win | ((dj >= -half_w) & (dj < half_w)));
+                    }
+                    pr[i] = ok ? pr[i] : 0.f;
+                }
+                to_b_operand(pr, pb);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // dV with dS; Q^T fragments requested on the way
+            constexpr int EV = 16 / (2 * ND);
+            auto dv_step = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                // younger loads behind dout^T fragment I: its 2 ND - 1 - I successors and the I fragments of Q^T
+                accv[I % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_take<2 * (2 * ND - 1)>(fdo[I]), pb[I / ND].v,
+                                                                       accv[I % ND], 0, 0, 0);
+#pragma unroll
+                for (int e = I * EV; e < (I + 1) * EV; e += 2) {
+                    const float d0 = pr[e] * dp[e], d1 = pr[e + 1] * dp[e + 1];
+                    dsb[e / 8].u[(e / 2) % 4] = pack_bf16(d0, d1);
+                    asm volatile("" : "+v"(dsb[e / 8].u[(e / 2) % 4]));
+                }
+                issue_q(ic);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for_each_index<2 * ND>(dv_step);
+            auto dk_step = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                acck[I % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_take<2 * (2 * ND - 1 - I)>(fq[I]), dsb[I / ND].v,
+                                                                       acck[I % ND], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for_each_index<2 * ND>(dk_step);
+        };
+
         __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
         __syncthreads();  // both wavefronts are done with the buffers (previous segment)
         for (int i = 0; i < NB - 1 && i < U; ++i) {
@@ -970,12 +1121,16 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
             // (dP does not depend on the probabilities, but issuing its MFMAs before the exponentials measured no
             // faster, and its accumulator live across them would cost the third wavefront per SIMD at d <= 64;
             // working on two steps at once at d = 128 was slower: the registers no longer fit)
-            Tile x;
-            ph_scores(x, lds + slot * TILE, tile_fn(t));
-            ph_exp(x);
-            ph_dv(x);
-            ph_dp(x);
-            ph_dk(x);
+            if constexpr (INTERLEAVE) {
+                step_interleaved(lds + slot * TILE, tile_fn(t));
+            } else {
+                Tile x;
+                ph_scores(x, lds + slot * TILE, tile_fn(t));
+                ph_exp(x);
+                ph_dv(x);
+                ph_dp(x);
+                ph_dk(x);
+            }
         }
     };
     if (MODE == 1) {
