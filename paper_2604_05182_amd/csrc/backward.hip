@@ -33,9 +33,6 @@
 #include <type_traits>
 #include <utility>
 
-#ifndef LSRM_DKV_INTERLEAVE
-#define LSRM_DKV_INTERLEAVE (D == 128)
-#endif
 constexpr int kBwdNbuf = 2;         // tile buffers of the dQ kernel
 constexpr int kBwdDkvNbuf = 2;      // tile buffers of the dK/dV kernels (three, copies two steps ahead: no faster)
 constexpr int kBwdSplitTarget = 2048;  // pooled-key workgroups aimed at when the query range is split
@@ -830,7 +827,9 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
     const int gh0 = MODE == 0 && a.hsplit > 1 ? (int)blockIdx.z * a.hpw : 0;
     const int grp = MODE == 0 && a.hsplit > 1 ? min(a.group, gh0 + a.hpw) - gh0 : a.group;
     constexpr bool VGPR_CHAINS = D == 128;  // (the kernel has one wavefront per SIMD: see mfma_v)
-    constexpr bool INTERLEAVE = LSRM_DKV_INTERLEAVE;
+    // the step in its interleaved form (step_interleaved below).  Not at d = 64: there it needs more than the 168
+    // registers of three wavefronts per SIMD, and with two it measured slower (config 5: 1.12 -> 1.25 ms).
+    constexpr bool INTERLEAVE = D != 64;
     constexpr int NB = kBwdDkvNbuf;  // tile buffers: the copies run NB - 1 steps ahead of the arithmetic
     constexpr int IPW = G::ROW / 1024;    // copy instructions per wavefront and step (wavefront 0: one more, the table)
     static_assert(NB == 2 || NB == 3, "");
