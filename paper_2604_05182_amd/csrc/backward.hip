@@ -647,36 +647,80 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
             const char *tile_k = lds + (t & 1) * TILE;
             const char *base = tile_k + row_off;
 
+            // The pieces of the step in a fixed order (a wavefront issues in order: what is to overlap has to alternate
+            // in the program).  K and V row fragments go through one rolling queue of QD registers sets, refilled
+            // behind the MFMA that consumed a set; the score chain, then the dP chain with the tile's exponentials
+            // behind its MFMAs (unmasked; edge tiles are fixed up afterwards); then the transposing loads of K^T are
+            // requested, dS of the first 16-key slab is formed, and the dQ MFMAs run with the second slab's dS
+            // behind the first ones.
+            constexpr int QD = NS < 4 ? NS : 4;
+            bf16x8 fq[QD];
+            auto frag = [&](int i) {  // fragment i of the K rows (i < NS) or of the V rows
+                return *reinterpret_cast<const bf16x8 *>(base + (i < NS ? i * 1024 : G::ROW + (i - NS) * 1024));
+            };
+#pragma unroll
+            for (int i = 0; i < QD; ++i) fq[i] = frag(i);
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[i] = 0.f;
+            __builtin_amdgcn_sched_barrier(0);
+            auto s_step = [&](auto kc) {
+                constexpr int ks = decltype(kc)::value;
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[ks % QD], qf[ks], s, 0, 0, 0);
+                fq[ks % QD] = frag(ks + QD);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for_each_index<NS>(s_step);
+            constexpr int E = 16 / NS;  // exponentials per dP MFMA
+            float pr[16];
+            auto dp_step = [&](auto kc) {
+                constexpr int ks = decltype(kc)::value;
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[ks % QD], dof[ks], ks == 0 ? dp0 : dp, 0, 0, 0);
+                if constexpr (ks + QD < NS) fq[ks % QD] = frag(NS + ks + QD);
 #pragma unroll
-            for (int ks = 0; ks < NS; ++ks)
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(base + ks * 1024), qf[ks], s,
-                                                            0, 0, 0);
-#pragma unroll
-            for (int ks = 0; ks < NS; ++ks)
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    *reinterpret_cast<const bf16x8 *>(base + G::ROW + ks * 1024), dof[ks], ks == 0 ? dp0 : dp, 0, 0, 0);
+                for (int e = ks * E; e < (ks + 1) * E; ++e) {
+                    pr[e] = __builtin_amdgcn_exp2f(s[e] * a.sl2 - lb);
+                    asm volatile("" : "+v"(pr[e]));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for_each_index<NS>(dp_step);
             // with per-channel gates the gradient rows change with the branch: the next branch's are requested
             // once the last dP MFMAs of this one are issued, and have arrived by the wait at the top of the next step
             if (BR < 2 && a.gate_channels && t + 1 == t1 && t + 1 < T) load_dof(t + 1 < tc + ts ? 1 : 2);
-            float ds[16];
+            TrFrag ft[2 * ND];
+            const uint32_t tr_k = (uint32_t)(uintptr_t)tile_k + tr_off;
+            auto issue_tr = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                tr_issue<(I % ND) * 2048 + (I / ND) * 256>(ft[I], tr_k);
+            };
+            for_each_index<2 * ND>(issue_tr);
             if (__builtin_expect(need_mask, 0)) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int j = j0 + 16 * (i / 8) + 8 * hh + (i % 8);
-                    float p = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb);
-                    p = ((j >= lo) & (j < hi)) ? p : 0.f;
-                    ds[i] = p * dp[i];
+                    pr[i] = ((j >= lo) & (j < hi)) ? pr[i] : 0.f;
                 }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(s[i] * a.sl2 - lb) * dp[i];
             }
             BFrag dsb[2];
-            to_b_operand(ds, dsb);
-            mfma_tr<ND>(acc, tile_k, tr_off, dsb);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) dsb[0].u[k] = pack_bf16(pr[2 * k] * dp[2 * k], pr[2 * k + 1] * dp[2 * k + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            constexpr int EQ = 4 / ND > 0 ? 4 / ND : 1;  // bf16 pairs of the second slab's dS per MFMA of the first slab
+            auto dq_step = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                acc[I % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_take<2 * (2 * ND - 1 - I)>(ft[I]), dsb[I / ND].v,
+                                                                      acc[I % ND], 0, 0, 0);
+                if constexpr (I < ND) {
+#pragma unroll
+                    for (int k = 4 + I * EQ; k < 4 + (I + 1) * EQ && k < 8; ++k) {
+                        dsb[1].u[k - 4] = pack_bf16(pr[2 * k] * dp[2 * k], pr[2 * k + 1] * dp[2 * k + 1]);
+                        asm volatile("" : "+v"(dsb[1].u[k - 4]));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            for_each_index<2 * ND>(dq_step);
         }
     };
     // padding slots at the end of a tile's block are no keys: valid keys of the tile, given its block's count
