@@ -638,12 +638,6 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
             __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
             wg_barrier();
             char *nbuf = lds + ((t + 1) & 1) * TILE;
-            if (t + 1 < t1)
-                issue_tile(kimg, vimg, tile_fn(t + 1 - t0), nbuf);
-            else if (t + 1 < T)
-                issue_any(t + 1, nbuf);
-            int j0, lo, hi;
-            const bool need_mask = mask_fn(t - t0, &j0, &lo, &hi);
             const char *tile_k = lds + (t & 1) * TILE;
             const char *base = tile_k + row_off;
 
@@ -660,6 +654,14 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
             };
 #pragma unroll
             for (int i = 0; i < QD; ++i) fq[i] = frag(i);
+            __builtin_amdgcn_sched_barrier(0);
+            // the copies of the next tile: their address arithmetic runs while the first reads land
+            if (t + 1 < t1)
+                issue_tile(kimg, vimg, tile_fn(t + 1 - t0), nbuf);
+            else if (t + 1 < T)
+                issue_any(t + 1, nbuf);
+            int j0, lo, hi;
+            const bool need_mask = mask_fn(t - t0, &j0, &lo, &hi);
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[i] = 0.f;
@@ -1012,7 +1014,7 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
         // behind it: at most 14 younger loads whatever i is; Q^T fragment i at dK#i has the 7-i later ones behind it.
         // The tracked reads (row fragments, table) are all waited for before the first untracked load is issued, so
         // the compiler's own counted waits never meet loads it does not know of.
-        auto step_interleaved = [&](const char *buf, int tile) {
+        auto step_interleaved = [&](const char *buf, int tile, auto issue_next) {
             static_assert(!INTERLEAVE || 16 % NS == 0, "");
             const int q0 = 32 * tile;
             const bool win = BR == 2 && ((int)key0 - (q0 + 31) < -half_w || (int)key0 + 31 - q0 >= half_w);
@@ -1024,6 +1026,8 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
             bf16x8 qr[NS], rows[NS];
 #pragma unroll
             for (int ks = 0; ks < NS; ++ks) qr[ks] = *reinterpret_cast<const bf16x8 *>(base + ks * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_next();  // the copies of the next step's tile: their address arithmetic runs while the reads land
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (VGPR_CHAINS) {
                 mfma_v_first(sc, qr[0], kB[0]);
@@ -1156,17 +1160,19 @@ __global__ __launch_bounds__(128, (D == 128 ? 1 : 3)) void bwd_dkv_kernel(BwdArg
                 __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
             }
             wg_barrier();
-            if (u + NB - 1 < U) {
-                const int fill = slot == 0 ? NB - 1 : slot - 1;  // the buffer of step u - 1 = that of step u + NB - 1
-                issue(t_nxt, gh_nxt, lds + fill * TILE);
-                advance(t_nxt, gh_nxt);
-            }
-            // (dP does not depend on the probabilities, but issuing its MFMAs before the exponentials measured no
-            // faster, and its accumulator live across them would cost the third wavefront per SIMD at d <= 64;
-            // working on two steps at once at d = 128 was slower: the registers no longer fit)
+            auto issue_next = [&]() {
+                if (u + NB - 1 < U) {
+                    const int fill = slot == 0 ? NB - 1 : slot - 1;  // the buffer of step u - 1 = that of step u + NB - 1
+                    issue(t_nxt, gh_nxt, lds + fill * TILE);
+                    advance(t_nxt, gh_nxt);
+                }
+            };
             if constexpr (INTERLEAVE) {
-                step_interleaved(lds + slot * TILE, tile_fn(t));
+                step_interleaved(lds + slot * TILE, tile_fn(t), issue_next);
             } else {
+                // (the plain order: scores, exponentials, dV, dP, dK; at d = 64 the interleaved one does not fit the
+                // registers of three wavefronts per SIMD)
+                issue_next();
                 Tile x;
                 ph_scores(x, lds + slot * TILE, tile_fn(t));
                 ph_exp(x);
