@@ -34,7 +34,7 @@
 #include <utility>
 
 constexpr int kBwdNbuf = 2;         // tile buffers of the dQ kernel
-constexpr int kBwdDkvNbuf = 2;      // tile buffers of the dK/dV kernels (three, copies two steps ahead: no faster)
+constexpr int kBwdDkvNbuf = 2;      // tile buffers of the dK/dV kernels (three, copies two steps ahead: slower, 51 -> 65 ms on the pooled keys at d = 128)
 constexpr int kBwdSplitTarget = 2048;  // pooled-key workgroups aimed at when the query range is split
 
 namespace lsrm {
