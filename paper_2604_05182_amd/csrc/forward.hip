@@ -140,6 +140,7 @@ __device__ __forceinline__ float half_sum(float x) {
 // lgkmcnt bits [11:8]; counters that are not waited for are left at their maxima)
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }            // vmcnt <= n
 constexpr int vm_lgkm_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0070; }          // vmcnt <= n, lgkmcnt == 0
+constexpr int kLgkmOnly = 0xC07F;                                                            // lgkmcnt == 0, vmcnt left alone
 
 // Bare workgroup barrier.  No barrier, fenced or not, waits for global -> LDS copies in flight
 // (they are counted by vmcnt, which a workgroup-scope fence leaves alone), so what must be
@@ -469,7 +470,10 @@ __device__ __forceinline__ void run_shared(WaveCtx<G> &c, int n_steps, int w_lo,
     // step apart: one meets the step's barrier before its MFMA block, the other after it, so
     // one's latency-bound work between blocks coincides with the other's MFMA block.
     const bool lag = G::WAVES == 8 && wave >= 4;
-    __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+    // (LDS reads only: no copy is in flight at the end of a phase, and the stores the previous branch's epilogue has
+    // just issued -- outputs, the gated-sum scratch -- need not have been acknowledged before the first copies of this
+    // phase go out; they are older than those copies, so the counted waits below cover them)
+    __builtin_amdgcn_s_waitcnt(kLgkmOnly);
     wg_barrier();  // every wavefront is done with the slots (previous phase)
     for (int t = 0; t < R && t < n_steps; ++t) issue_shared<G>(c, src(t), slot(t), wave);
     // tiles 0, 1 and 2 must have landed before the first block reads them
@@ -710,7 +714,10 @@ __device__ __forceinline__ void run_own(WaveCtx<G> &c, int n_steps, int my_steps
             }
         }
     };
-    __builtin_amdgcn_s_waitcnt(vm_lgkm_imm(0));
+    // (LDS reads only: no copy is in flight at the end of a phase, and the stores the previous branch's epilogue has
+    // just issued -- outputs, the gated-sum scratch -- need not have been acknowledged before the first copies of this
+    // phase go out; they are older than those copies, so the counted waits below cover them)
+    __builtin_amdgcn_s_waitcnt(kLgkmOnly);
     wg_barrier();  // every wavefront is done with the slots (previous phase)
 #pragma unroll
     for (int tau = 0; tau < NST; ++tau)
