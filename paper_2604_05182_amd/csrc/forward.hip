@@ -113,6 +113,10 @@ struct Geo {
     static constexpr int KQ = 2, VQ = 2;        // operand fragments kept in registers (rolling queues)
     static constexpr int OUT_ROW = 2 * D + 8;   // padded bf16 row of the output staging (bytes)
     static constexpr bool GSUM_REGS = D_ <= 64; // the running gated sum fits the registers beside the accumulators
+    // d = 128: the running gated sum of the first GSUM_LDS_WAVES wavefronts stays in the LDS the ring leaves free
+    // (8 KB each in bf16: 32 of the CU's 160 KB), the others' goes through the scratch buffer in memory
+    static constexpr int GSUM_LDS_WAVES = GSUM_REGS ? 0 : 4;
+    static constexpr int GSUM_LDS_BYTES = 32 * D_ * 2;  // per wavefront
     static constexpr int LDS_BYTES = NSLOT * TILE;
     static_assert(QT == 1 || QT == 2, "");
     static_assert(WAVES % 4 == 0 && WAVES * ROWS * OUT_ROW <= LDS_BYTES, "output staging must fit in the tile slots");
@@ -848,11 +852,22 @@ __device__ __forceinline__ void finish_branch(WaveCtx<G> &c, const FwdArgs &a, i
                         for (int j = 0; j < 4; ++j) c.g[qt][dt][4 * gq + j] = v[j];
                     }
                 } else {
-                    // bf16 pairs in accumulator order: 8 bytes per lane and fragment, fully coalesced
+                    // bf16 pairs in accumulator order: 8 bytes per lane and fragment, fully coalesced; in LDS for the
+                    // first wavefronts of the workgroup (behind the ring), in the scratch buffer for the others
+                    static_assert(G::QT == 1, "");
                     uint2 *slot = reinterpret_cast<uint2 *>(a.gsum) +
                                   ((((row0 >> 5) + qt) * a.h + head) * (G::ND * 4) + dt * 4 + gq) * 64 + lane;
+                    uint2 *slot_lds =
+                        reinterpret_cast<uint2 *>(lds + G::LDS_BYTES + wave * G::GSUM_LDS_BYTES) + (dt * 4 + gq) * 64 + lane;
+                    const bool in_lds = wave < G::GSUM_LDS_WAVES;
                     if (branch > 0) {
-                        const uint2 pv = *slot;
+                        // (address spaces spelled out: one pointer that may be either would become a flat load)
+                        unsigned long long raw;
+                        if (in_lds)
+                            raw = *(const __attribute__((address_space(3))) unsigned long long *)slot_lds;
+                        else
+                            raw = *(const __attribute__((address_space(1))) unsigned long long *)slot;
+                        const uint2 pv = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32));
                         v[0] += __uint_as_float(pv.x << 16);
                         v[1] += __uint_as_float(pv.x & 0xffff0000u);
                         v[2] += __uint_as_float(pv.y << 16);
@@ -862,7 +877,10 @@ __device__ __forceinline__ void finish_branch(WaveCtx<G> &c, const FwdArgs &a, i
                         uint2 w2;
                         w2.x = pack_bf16(v[0], v[1]);
                         w2.y = pack_bf16(v[2], v[3]);
-                        *slot = w2;
+                        if (in_lds)
+                            *slot_lds = w2;
+                        else
+                            *slot = w2;
                     }
                 }
                 if (branch == 2) {
@@ -1325,7 +1343,8 @@ lsrm_status launch_forward_d(const Shape &s, const int32_t *seg_host, int n_seg,
     a.groups_per_head = (s.nb + NP - 1) / NP;
     a.groups_per_xcd = (a.groups_per_head + 7) / 8;
     // dynamic LDS: the tile slots, then 512 bytes per wavefront for compacting a routing row
-    constexpr int kLds = G::LDS_BYTES + G::WAVES * 512;
+    // behind the ring: the routing-row scratch of the selected phase (d <= 64) or the LDS part of the running gated sum
+    constexpr int kLds = G::LDS_BYTES + (G::GSUM_LDS_WAVES > 0 ? G::GSUM_LDS_WAVES * G::GSUM_LDS_BYTES : G::WAVES * 512);
     const bool cnt = a.count != nullptr, wide = s.topk > 64;
     const void *kern = cnt ? (wide ? reinterpret_cast<const void *>(&nsa_forward_kernel<G, true, true>)
                                    : reinterpret_cast<const void *>(&nsa_forward_kernel<G, true, false>))
