@@ -31,7 +31,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per launch of the attention kernel (fetched + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs of this script scaled by the same counters of a plain 1 GiB copy; the readings and the commands are
 # in profiles/nsa_forward_kernel_config4_hbm_traffic.txt.  Only the workloads that were profiled appear.
-MEASURED_HBM_BYTES = {4: 60.6e9 + 5.3e9}
+MEASURED_HBM_BYTES = {4: 56.5e9 + 3.5e9}
 
 
 def cpu_baseline(cfg, arrays, idx, target_seconds=20.0):
