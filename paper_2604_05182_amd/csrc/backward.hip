@@ -486,7 +486,6 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a) {
     constexpr int NS = G::NS, ND = G::ND;
     constexpr int TILE = 2 * G::ROW;     // K rows | V rows (K^T is read out of the K rows, see mfma_tr)
     constexpr int NBUF = kBwdNbuf;  // tile buffers: copies run NBUF - 1 tiles ahead
-    constexpr int IPW = G::ROW / 1024;   // copy instructions per wavefront and tile
     static_assert((G::ROW / 1024) % 2 == 0, "");
     static_assert(2 * 32 * G::OUT_ROW <= NBUF * TILE, "output staging fits in the tile buffers");
     __shared__ __attribute__((aligned(1024))) char lds[NBUF * TILE];
