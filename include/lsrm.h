@@ -16,7 +16,9 @@
  *   - tensors are dense row-major with the shapes given; bf16 is the 16-bit
  *     brain-float bit pattern (uint16_t here);
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
- *     stream) and the call returns without synchronising;
+ *     stream) and the call returns without synchronising; a call enqueues kernel launches only (no memset or
+ *     copy nodes, and event records only where the caller passes events), so calls may be recorded into a HIP
+ *     graph (lsrm_route_blocks_static: after its first call on the device);
  *   - no global state apart from lsrm_route_blocks_static's address lookup; calls may come from any
  *     thread and any device may be current;
  *   - the library allocates no device memory: scratch comes from the caller
