@@ -476,6 +476,21 @@ __device__ __forceinline__ int nth_set_bit(unsigned long long m, int n) {
     return pos;
 }
 
+// The partial gradients of the pooled keys / values, summed over the query ranges in order into range 0's slot,
+// so that the token-key workgroups read one row per pooled pair however many ranges there were.
+__global__ __launch_bounds__(256) void sum_parts(float *__restrict__ part_k, float *__restrict__ part_v, int n_split,
+                                                 int64_t per_split) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= per_split) return;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        float *part = which == 0 ? part_k : part_v;
+        f32x4 acc = *reinterpret_cast<const f32x4 *>(part + i);
+        for (int sp = 1; sp < n_split; ++sp) acc += *reinterpret_cast<const f32x4 *>(part + sp * per_split + i);
+        *reinterpret_cast<f32x4 *>(part + i) = acc;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // dQ: one workgroup (2 wavefronts x 32 query rows) per (query block, head)
 // WIDE: routing rows of 65..128 entries (two per lane of the list holder instead of one).
@@ -1313,14 +1328,36 @@ WsLayout ws_layout(const Shape &s) {
     // pooled keys: enough query ranges to fill the chip
     w.nbp = (s.nbc + 63) / 64 * 64;
     const int wgs = (w.nbp / 64) * s.h_kv;
-    // (more ranges mean more partial sums to write; with grouped-query heads a workgroup's walk is group x as long
-    // and twice as many ranges measured faster, without them slower)
-    const int target = s.h > s.h_kv ? 2 * kBwdSplitTarget : kBwdSplitTarget;
-    int n_split = (target + wgs - 1) / wgs;
-    n_split = n_split < 1 ? 1 : (n_split > 64 ? 64 : n_split);
-    w.tiles_per_split = (int)((nt + n_split - 1) / n_split);
-    w.n_split = (int)((nt + w.tiles_per_split - 1) / (w.tiles_per_split > 0 ? w.tiles_per_split : 1));
-    if (w.n_split < 1) w.n_split = 1;
+    // The query tiles are cut into n ranges, one workgroup per (64 pooled keys, key/value head, range), all equally
+    // long.  The chip runs `slots` of them at a time (256 CUs x the workgroups per CU that the kernel's registers
+    // allow), so the kernel takes ceil(workgroups / slots) rounds of (tiles per range) x (query heads per key/value
+    // head) steps; every range also costs its partial sums, written here and read back by the token-key kernel.
+    // n minimises that: e.g. at 1680 workgroups per range and 512 slots, two ranges run 7 rounds where 6.6 would
+    // do, seven ranges run 23 rounds of a seventh the length (6 % less).
+    {
+        const int slots = 256 * (s.d == 128 ? 2 : s.d == 64 ? 6 : 8);
+        const int grp_q = s.h / s.h_kv;
+        const double range_bytes = (double)w.nbp * s.h_kv * s.d * 4 * 2 * 2;
+        const double step_seconds = 1.1e-6 * s.d / 128, range_steps = range_bytes / 4e12 / step_seconds;
+        double best = 0;
+        int best_n = 1;
+        for (int n = 1; n <= 64; ++n) {
+            const int64_t tiles = ((int64_t)nt + n - 1) / n;
+            if (tiles <= 0) break;
+            const int64_t n_eff = ((int64_t)nt + tiles - 1) / tiles;
+            const int64_t rounds = ((int64_t)wgs * n_eff + slots - 1) / slots;
+            const double cost = (double)rounds * tiles * grp_q + range_steps * n_eff;
+            if (n == 1 || cost < best) {
+                best = cost;
+                best_n = n;
+            }
+        }
+        (void)kBwdSplitTarget;
+        const int n_split = best_n;
+        w.tiles_per_split = (int)((nt + n_split - 1) / n_split);
+        w.n_split = (int)((nt + w.tiles_per_split - 1) / (w.tiles_per_split > 0 ? w.tiles_per_split : 1));
+        if (w.n_split < 1) w.n_split = 1;
+    }
     w.part_k = take((size_t)w.n_split * w.nbp * s.h_kv * s.d * 4);
     w.part_v = take((size_t)w.n_split * w.nbp * s.h_kv * s.d * 4);
     // token keys: with grouped-query heads a workgroup would walk group x as many steps while there are group x
@@ -1408,6 +1445,13 @@ lsrm_status launch_backward_d(const Shape &s, BwdArgs a, const WsLayout &w, char
     hipLaunchKernelGGL((bwd_dkv_kernel<D, 1>), dim3((w.nbp / 64 + 7) / 8 * 8, s.h_kv, w.n_split), dim3(128), DKV_LDS, st,
                        a);
     LSRM_HIP_CHECK(hipGetLastError());
+    if (w.n_split > 1) {
+        const int64_t per_split = (int64_t)w.nbp * s.h_kv * D;
+        hipLaunchKernelGGL(sum_parts, dim3((unsigned)((per_split / 4 + 255) / 256)), dim3(256), 0, st, a.part_k, a.part_v,
+                           w.n_split, per_split);
+        LSRM_HIP_CHECK(hipGetLastError());
+        a.n_split = 1;  // (the kernels below read range 0's slot only)
+    }
     hipLaunchKernelGGL((bwd_dkv_kernel<D, 0>), dim3((s.nb + 7) / 8 * 8, s.h_kv, a.hsplit), dim3(128), DKV_LDS, st, a);
     LSRM_HIP_CHECK(hipGetLastError());
     if (a.hsplit > 1) {  // add up the per-head-range sums, in order, and finish the rows
