@@ -855,8 +855,10 @@ __device__ __forceinline__ void finish_branch(WaveCtx<G> &c, const FwdArgs &a, i
                     // bf16 pairs in accumulator order: 8 bytes per lane and fragment, fully coalesced; in LDS for the
                     // first wavefronts of the workgroup (behind the ring), in the scratch buffer for the others
                     static_assert(G::QT == 1, "");
+                    // (the scratch buffer holds the query tiles of wavefronts GSUM_LDS_WAVES .. WAVES - 1 only)
+                    const int64_t gtile = (row0 / (32 * G::WAVES)) * (G::WAVES - G::GSUM_LDS_WAVES) + (wave - G::GSUM_LDS_WAVES);
                     uint2 *slot = reinterpret_cast<uint2 *>(a.gsum) +
-                                  ((((row0 >> 5) + qt) * a.h + head) * (G::ND * 4) + dt * 4 + gq) * 64 + lane;
+                                  ((gtile * a.h + head) * (G::ND * 4) + dt * 4 + gq) * 64 + lane;
                     uint2 *slot_lds =
                         reinterpret_cast<uint2 *>(lds + G::LDS_BYTES + wave * G::GSUM_LDS_BYTES) + (dt * 4 + gq) * 64 + lane;
                     const bool in_lds = wave < G::GSUM_LDS_WAVES;
@@ -1302,7 +1304,8 @@ WsLayout ws_layout(const Shape &s) {
     w.kvc = off;
     off += align_up((size_t)((s.nbc + 31) / 32) * s.h_kv * tile, 256);
     w.gsum = off;
-    off += s.d == 128 ? align_up((size_t)s.nb * 64 * s.h * s.d * 2, 256) : 0;  // (kept in registers at d <= 64)
+    // (d = 128: bf16, the query tiles of four of a workgroup's eight wavefronts; the others' stay in LDS; in registers at d <= 64)
+    off += s.d == 128 ? align_up((size_t)((s.nb + 3) / 4) * 4 * 32 * s.h * s.d * 2, 256) : 0;
     w.sched = off;
     off += s.d == 128 ? sel_schedule_bytes(s) : 0;
     w.gtab = off;
